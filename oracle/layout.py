@@ -1,0 +1,175 @@
+"""Byte layout of the K/V arena and the Q Cache arena, and resident-byte accounting
+(test infrastructure).
+
+The paper fixes what is stored ("Efficiency Analysis", KV Cache paragraph: a
+lazy layer keeps only its text keys; every layer keeps all values; the Q Cache
+is one layer's worth of visual queries) but not where.  This module states the
+layout the library is specified to use, in closed form, so that cache contents
+can be compared byte for byte:
+
+  K region   layers in order; layer l holds [max_batch][H][capK(l)][D] elements,
+             capK(l) = max_text for a lazy layer, max_seq otherwise.
+  V region   follows the K region; layer l holds [max_batch][H][max_seq][D].
+  meta       follows the V region (256-byte aligned): int32 [4][max_batch] =
+             first token index in the packed prompt, prompt length, vis_start,
+             vis_len of every sequence; total rounded up to 256 bytes.
+  Q arena    [max_batch][H][max_vis][D].
+
+Row maps: V row = position.  K row = position in a normal layer.  In a lazy
+layer positions before the span keep their index, positions after it move
+down by vis_len, and positions inside the span have no row in that layer:
+they resolve to the same position in the block's first layer.
+"""
+import numpy as np
+
+ELEM_BYTES = {"f32": 4, "bf16": 2}
+
+
+def _round_up(x, m):
+    return (x + m - 1) // m * m
+
+
+class ArenaLayout:
+    def __init__(self, n_layers, n_heads, head_dim, dtype, max_batch, max_seq, max_vis, max_text,
+                 lazy_mask):
+        self.N, self.H, self.D = n_layers, n_heads, head_dim
+        self.dtype = dtype
+        self.e = ELEM_BYTES[dtype]
+        self.max_batch, self.max_seq = max_batch, max_seq
+        self.max_vis, self.max_text = max_vis, max_text
+        self.lazy = [int(bool(x)) for x in lazy_mask]
+        assert len(self.lazy) == n_layers and not (n_layers and self.lazy[0])
+
+    def cap_k(self, l):
+        return self.max_text if self.lazy[l] else self.max_seq
+
+    def k_layer_bytes(self, l):
+        return self.max_batch * self.H * self.cap_k(l) * self.D * self.e
+
+    def v_layer_bytes(self):
+        return self.max_batch * self.H * self.max_seq * self.D * self.e
+
+    def off_k(self, l):
+        return sum(self.k_layer_bytes(i) for i in range(l))
+
+    def off_v(self, l):
+        return self.off_k(self.N) + l * self.v_layer_bytes()
+
+    def off_meta(self):
+        return _round_up(self.off_v(self.N), 256)
+
+    def meta_bytes(self):
+        return _round_up(4 * 4 * self.max_batch, 256)
+
+    def kv_arena_bytes(self):
+        return self.off_meta() + self.meta_bytes()
+
+    def q_arena_bytes(self):
+        return self.max_batch * self.H * self.max_vis * self.D * self.e
+
+    def k_offset(self, l, b, h, row):
+        return self.off_k(l) + ((b * self.H + h) * self.cap_k(l) + row) * self.D * self.e
+
+    def v_offset(self, l, b, h, row):
+        return self.off_v(l) + ((b * self.H + h) * self.max_seq + row) * self.D * self.e
+
+    def q_offset(self, b, h, row):
+        return ((b * self.H + h) * self.max_vis + row) * self.D * self.e
+
+    def anchor(self, l):
+        a = l - 1
+        while self.lazy[a]:
+            a -= 1
+        return a
+
+    def locate_k(self, l, b, h, pos, vis_start, vis_len):
+        """(source layer, byte offset in the K/V arena) of the key of `pos` as layer l reads it."""
+        if self.lazy[l] and vis_start <= pos < vis_start + vis_len:
+            a = self.anchor(l)
+            return a, self.k_offset(a, b, h, pos)
+        row = pos
+        if self.lazy[l] and pos >= vis_start + vis_len:
+            row = pos - vis_len
+        return l, self.k_offset(l, b, h, row)
+
+    def locate_v(self, l, b, h, pos):
+        return l, self.v_offset(l, b, h, pos)
+
+
+def encode_rows(x, dtype):
+    """fp64 rows -> raw bytes of the storage type; refuses values the type cannot hold exactly."""
+    x32 = np.ascontiguousarray(x, dtype=np.float32)
+    if not np.array_equal(x32.astype(np.float64), np.asarray(x, dtype=np.float64)):
+        raise ValueError("cache rows are not exactly representable in fp32")
+    if dtype == "f32":
+        return x32.view(np.uint8)
+    bits = x32.view(np.uint32)
+    if np.any(bits & 0xFFFF):
+        raise ValueError("cache rows are not exactly representable in bf16")
+    return (bits >> 16).astype(np.uint16).view(np.uint8)
+
+
+def kv_arena_image(layout, stacks, tok0=None):
+    """Expected bytes of the whole K/V arena given one LazyStackOracle per sequence.
+
+    Unwritten bytes are zero.  `tok0[b]` is the first packed-prompt token index
+    of sequence b (default: prompts packed back to back in batch order).
+    """
+    img = np.zeros(layout.kv_arena_bytes(), dtype=np.uint8)
+    rowb = layout.D * layout.e
+    for b, st in enumerate(stacks):
+        for l in range(layout.N):
+            for h in range(layout.H):
+                kr = st.Kc[l][h]
+                o = layout.k_offset(l, b, h, 0)
+                img[o:o + kr.shape[0] * rowb] = encode_rows(kr, layout.dtype).reshape(-1)
+                vr = st.Vc[l][h]
+                o = layout.v_offset(l, b, h, 0)
+                img[o:o + vr.shape[0] * rowb] = encode_rows(vr, layout.dtype).reshape(-1)
+    meta = np.zeros((4, layout.max_batch), dtype=np.int32)
+    start = 0
+    for b, st in enumerate(stacks):
+        meta[0, b] = start if tok0 is None else tok0[b]
+        meta[1, b] = st.prefill_len
+        meta[2, b] = st.s
+        meta[3, b] = st.Vn
+        start += st.prefill_len
+    o = layout.off_meta()
+    img[o:o + meta.nbytes] = meta.view(np.uint8).reshape(-1)
+    return img
+
+
+def q_arena_image(layout, stacks):
+    img = np.zeros(layout.q_arena_bytes(), dtype=np.uint8)
+    rowb = layout.D * layout.e
+    for b, st in enumerate(stacks):
+        if st.q_owner < 0:
+            continue
+        for h in range(layout.H):
+            o = layout.q_offset(b, h, 0)
+            img[o:o + st.Vn * rowb] = encode_rows(st.Qc[h], layout.dtype).reshape(-1)
+    return img
+
+
+def resident_bytes(layout, stacks):
+    """Bytes actually occupied by cached rows: dict(k_bytes, v_bytes, q_bytes, tokens)."""
+    per_row = layout.H * layout.D * layout.e
+    k = v = q = tokens = 0
+    for st in stacks:
+        rk, rv, rq = st.resident_rows()
+        k += rk * per_row
+        v += rv * per_row
+        q += rq * per_row
+        tokens += st.len if st.len else st.prefill_len
+    return {"k_bytes": k, "v_bytes": v, "q_bytes": q, "tokens": tokens}
+
+
+def standard_kv_bytes(layout, lens):
+    """K + V bytes of the same sequences without lazy layers (every layer keeps every row)."""
+    return 2 * layout.N * sum(lens) * layout.H * layout.D * layout.e
+
+
+def vla_kv_saving_closed_form(n_layers, n_lazy, vis_len, text_len):
+    """"Efficiency Analysis", KV Cache paragraph: |V|/(|V|+|T|) * n/(2N), as an exact fraction."""
+    from fractions import Fraction
+    return Fraction(vis_len, vis_len + text_len) * Fraction(n_lazy, 2 * n_layers)
