@@ -1,0 +1,171 @@
+/*
+ * qcache.h - C ABI of the Lazy Attention / Q Cache attention library for AMD MI355X (gfx950).
+ *
+ * The library implements the per-layer decoder attention of a multimodal LLM under
+ * Visual Lazy Attention (VLA): ordinary layers compute causal softmax attention
+ * (paper Eq. 1 for prefill, Eq. 2 for decode); lazy layers inherit the queries and keys
+ * of the visual-token span from the first layer of their lazy block through the
+ * layer-shared Q Cache (paper Eq. 7 for prefill, Eq. 8 for decode; Q Cache definition at
+ * the end of the "Lazy Attention" subsection) and therefore keep only their text keys
+ * ("Efficiency Analysis", KV Cache paragraph).
+ *
+ * Conventions common to every entry point
+ *   - Every pointer is tagged below as HOST or DEVICE memory.  The caller owns all device
+ *     memory (arenas, Q/K/V/O tensors, workspace) and the stream; the library owns only the
+ *     host-side handles.  `stream` is a hipStream_t passed as void* (NULL = default stream).
+ *   - Compute entry points are asynchronous on `stream`; host metadata is updated at call time.
+ *   - Every call returns a qc_status and never throws or aborts.  Arguments are validated
+ *     before anything is launched or changed: on any status other than QC_OK no cache state
+ *     (host or device) has changed.  qc_last_error() returns a text for the calling thread's
+ *     most recent failure.
+ *   - Handles are not thread-safe; use one stream at a time per handle pair.
+ *   - Layers must be visited in order 0..n_layers-1 within a prefill pass and within each
+ *     decode step: that order is what makes "the Q Cache updates as the block changes"
+ *     well defined.
+ *   - Multi-head attention with as many K/V heads as query heads; head h of a lazy layer
+ *     inherits from head h of its block's first layer.
+ *   - Each sequence has one contiguous visual span [vis_start, vis_start + vis_len) at its
+ *     true token positions; text may precede and follow it; generated tokens are text.
+ */
+#ifndef QCACHE_H
+#define QCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  QC_OK = 0,
+  QC_EINVAL = 1,    /* null pointer, bad shape/dtype/stride, span out of range, lazy flag differs from
+                       the configured mask, layer 0 marked lazy */
+  QC_EORDER = 2,    /* layer called out of sequence; decode before prefill has finished; lazy layer
+                       while the Q Cache belongs to another block */
+  QC_ECAPACITY = 3, /* sequence, text-row or batch capacity exceeded; arena or workspace too small */
+  QC_EDEVICE = 4    /* a HIP call failed (launch error, or an earlier asynchronous fault surfacing) */
+} qc_status;
+
+typedef enum { QC_F32 = 0, QC_BF16 = 1 } qc_dtype;
+
+enum { QC_K = 0, QC_V = 1 };
+
+/* Static description of the decoder stack and cache capacities.
+ * lazy_mask: HOST, n_layers bytes, non-zero = lazy layer; copied by the create calls.  Layer 0
+ * must be 0.  The first layer of the block a lazy layer l belongs to (its "anchor", l_c in the
+ * paper) is the nearest preceding layer whose flag is 0.
+ * max_seq  : most positions (prompt + generated) any sequence may reach.
+ * max_vis  : most visual tokens in any sequence.
+ * max_text : most text rows (prompt text + generated) any sequence may reach; this is the row
+ *            capacity of a lazy layer's K cache, which is what makes its allocation smaller.
+ * head_dim : 64 or 128.  dtype: element type of Q/K/V/O and of all caches. */
+typedef struct qc_config {
+  int32_t n_layers;
+  int32_t n_heads;
+  int32_t head_dim;
+  int32_t dtype; /* qc_dtype */
+  int32_t max_batch;
+  int32_t max_seq;
+  int32_t max_vis;
+  int32_t max_text;
+  const uint8_t* lazy_mask;
+} qc_config;
+
+typedef struct qc_kvcache qc_kvcache; /* opaque host objects: metadata only */
+typedef struct qc_qcache qc_qcache;
+
+/* Resident-byte accounting ("Efficiency Analysis", KV Cache paragraph): bytes of cache rows that
+ * currently hold data, not capacity.  k_bytes = sum over sequences and layers of
+ * (len - lazy[l]*vis_len) * H * D * e; v_bytes = sum of n_layers * len * H * D * e; q_bytes = sum
+ * of vis_len * H * D * e once a layer has written the Q Cache (0 before).  tokens = sum of len. */
+typedef struct qc_stats_t {
+  int64_t k_bytes;
+  int64_t v_bytes;
+  int64_t q_bytes;
+  int64_t tokens;
+  int32_t batch;
+  int32_t q_owner;     /* layer whose visual queries the Q Cache holds, -1 if none */
+  int32_t generated;   /* decode steps completed since prefill */
+  int32_t next_layer;  /* layer the next qc_prefill / qc_decode call must name */
+} qc_stats_t;
+
+/* ---- sizes ------------------------------------------------------------------------------------
+ * Exact byte sizes of the caller-allocated device buffers; 0 if the configuration is invalid.
+ * K/V arena layout (all offsets in bytes, e = element size):
+ *   K region: layers in order, layer l is [max_batch][n_heads][capK(l)][head_dim],
+ *             capK(l) = max_text if lazy else max_seq;
+ *   V region: layers in order, each [max_batch][n_heads][max_seq][head_dim];
+ *   meta    : at the next multiple of 256: int32 [4][max_batch] = {first packed token index,
+ *             prompt length, vis_start, vis_len} per sequence, padded to a multiple of 256 bytes.
+ * Q arena: [max_batch][n_heads][max_vis][head_dim] (one layer's worth, visual rows only).
+ * Decode workspace: split partial results, fp32. */
+size_t qc_kv_arena_bytes(const qc_config* cfg);
+size_t qc_q_arena_bytes(const qc_config* cfg);
+size_t qc_decode_workspace_bytes(const qc_config* cfg);
+
+/* ---- handles ----------------------------------------------------------------------------------
+ * cfg: HOST.  dev_arena: DEVICE, 256-byte aligned, at least the size reported above (else
+ * QC_ECAPACITY); it stays owned by the caller and must outlive the handle.  *out receives a new
+ * handle on QC_OK.  The create calls touch no device memory and make no HIP call. */
+qc_status qc_kvcache_create(const qc_config* cfg, void* dev_arena, size_t arena_bytes, qc_kvcache** out);
+qc_status qc_qcache_create(const qc_config* cfg, void* dev_arena, size_t arena_bytes, qc_qcache** out);
+void qc_kvcache_destroy(qc_kvcache* kv);
+void qc_qcache_destroy(qc_qcache* qc);
+
+/* Start a new batch of `batch` sequences (1..max_batch): lengths 0, Q Cache unowned.
+ * vis_start, vis_len: HOST, `batch` entries each (vis_len may be 0: pure-text sequence).
+ * zero_fill != 0 additionally clears both arenas on `stream` (fill kernel), so that bytes never
+ * written stay zero and whole-arena comparisons are meaningful; with 0 the call is host-only. */
+qc_status qc_reset(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* vis_start,
+                   const int32_t* vis_len, int32_t zero_fill, void* stream);
+
+/* ---- prefill: one layer over the packed prompts (paper Eq. 1; Eq. 7 in a lazy layer) -----------
+ * q, k, v, out: DEVICE, element (token t, head h, dim d) at t*token_stride + h*head_stride + d
+ *   (strides in elements, shared by all four tensors; head_stride >= head_dim, 16-byte aligned
+ *   rows).  Sequence b owns tokens cu_seqlens[b] .. cu_seqlens[b+1]-1.
+ * cu_seqlens: HOST, batch+1 entries, cu_seqlens[0] = 0.  vis_start, vis_len: HOST, must repeat
+ *   the values given to qc_reset.  is_lazy must equal the configured flag of `layer`.
+ * softmax_scale: 0 selects 1/sqrt(head_dim).
+ * Effects, ordinary layer: out = causal softmax attention of (q, k, v); all k and v rows are
+ *   stored; if layer+1 is lazy the span rows of q are stored in the Q Cache, which now belongs
+ *   to `layer`.
+ * Effects, lazy layer: span rows of q are taken from the Q Cache and span rows of k from the
+ *   anchor layer's K cache (the span rows of the q and k arguments are never read and may be
+ *   left unwritten by the caller); attention as above with the layer's own v; only text rows of
+ *   k are stored (compacted: positions after the span move down by vis_len), all rows of v. */
+qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_lazy, const void* q,
+                     const void* k, const void* v, void* out, const int32_t* cu_seqlens,
+                     int64_t token_stride, int64_t head_stride, const int32_t* vis_start,
+                     const int32_t* vis_len, float softmax_scale, void* stream);
+
+/* ---- decode: one generated token per sequence through one layer (paper Eq. 2; Eq. 8 if lazy) ---
+ * q, k, v, out: DEVICE, [batch][n_heads][head_dim] contiguous.
+ * The new k row is appended at row len (ordinary layer) or len - vis_len (lazy layer), the new
+ * v row at row len; the query attends positions 0..len, where a lazy layer reads the span
+ * positions from its anchor layer's K cache.  The Q Cache is neither read nor written (the
+ * decode query is a text token); qc may be NULL.  After layer n_layers-1 every length grows by 1.
+ * workspace: DEVICE, at least qc_decode_workspace_bytes(cfg), contents undefined between calls. */
+qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_lazy, const void* q,
+                    const void* k, const void* v, void* out, const int32_t* vis_start,
+                    const int32_t* vis_len, float softmax_scale, void* workspace,
+                    size_t workspace_bytes, void* stream);
+
+/* ---- bookkeeping queries (host only, no HIP call) ---------------------------------------------- */
+qc_status qc_stats(const qc_kvcache* kv, const qc_qcache* qc, qc_stats_t* out);
+/* Rows of layer `layer` currently resident, summed over the batch. */
+qc_status qc_layer_rows(const qc_kvcache* kv, int32_t layer, int64_t* rows_k, int64_t* rows_v);
+qc_status qc_seq_len(const qc_kvcache* kv, int32_t b, int32_t* len);
+/* Where layer `layer` reads the key (which = QC_K) or value (QC_V) of position `pos` of head h of
+ * sequence b: *src_layer is `layer` itself, or the anchor layer for a span position of a lazy
+ * layer; *byte_offset is the offset of that row in the K/V arena.  pos must be < max_seq. */
+qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t b, int32_t h,
+                    int32_t pos, int32_t* src_layer, int64_t* byte_offset);
+
+const char* qc_status_str(qc_status s);
+const char* qc_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QCACHE_H */

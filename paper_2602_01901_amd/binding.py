@@ -1,0 +1,191 @@
+"""ctypes binding of libqcache.so: same names as include/qcache.h, argument marshalling only.
+
+Tensors are passed as torch tensors (their data_ptr() is taken) or as raw integer device
+addresses; host integer arrays as Python sequences.  Every step of the attention path runs
+inside the library's kernels.  If the library has not been built, importing works but the
+first call raises: there is no fallback implementation.
+"""
+import ctypes
+import os
+from ctypes import POINTER, byref, c_char_p, c_float, c_int32, c_int64, c_size_t, c_uint8, c_void_p
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libqcache.so")
+
+QC_OK, QC_EINVAL, QC_EORDER, QC_ECAPACITY, QC_EDEVICE = range(5)
+QC_F32, QC_BF16 = 0, 1
+QC_K, QC_V = 0, 1
+DTYPE_CODE = {"f32": QC_F32, "bf16": QC_BF16}
+
+
+class qc_config(ctypes.Structure):
+    _fields_ = [("n_layers", c_int32), ("n_heads", c_int32), ("head_dim", c_int32), ("dtype", c_int32),
+                ("max_batch", c_int32), ("max_seq", c_int32), ("max_vis", c_int32), ("max_text", c_int32),
+                ("lazy_mask", POINTER(c_uint8))]
+
+
+class qc_stats_t(ctypes.Structure):
+    _fields_ = [("k_bytes", c_int64), ("v_bytes", c_int64), ("q_bytes", c_int64), ("tokens", c_int64),
+                ("batch", c_int32), ("q_owner", c_int32), ("generated", c_int32), ("next_layer", c_int32)]
+
+
+class QcError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("%s: %s" % (status_str(status), message))
+        self.status = status
+
+
+_PROTOTYPES = {
+    "qc_kv_arena_bytes": (c_size_t, [POINTER(qc_config)]),
+    "qc_q_arena_bytes": (c_size_t, [POINTER(qc_config)]),
+    "qc_decode_workspace_bytes": (c_size_t, [POINTER(qc_config)]),
+    "qc_kvcache_create": (c_int32, [POINTER(qc_config), c_void_p, c_size_t, POINTER(c_void_p)]),
+    "qc_qcache_create": (c_int32, [POINTER(qc_config), c_void_p, c_size_t, POINTER(c_void_p)]),
+    "qc_kvcache_destroy": (None, [c_void_p]),
+    "qc_qcache_destroy": (None, [c_void_p]),
+    "qc_reset": (c_int32, [c_void_p, c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32), c_int32, c_void_p]),
+    "qc_prefill": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+                             POINTER(c_int32), c_int64, c_int64, POINTER(c_int32), POINTER(c_int32), c_float,
+                             c_void_p]),
+    "qc_decode": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+                            POINTER(c_int32), POINTER(c_int32), c_float, c_void_p, c_size_t, c_void_p]),
+    "qc_stats": (c_int32, [c_void_p, c_void_p, POINTER(qc_stats_t)]),
+    "qc_layer_rows": (c_int32, [c_void_p, c_int32, POINTER(c_int64), POINTER(c_int64)]),
+    "qc_seq_len": (c_int32, [c_void_p, c_int32, POINTER(c_int32)]),
+    "qc_locate": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, POINTER(c_int32),
+                            POINTER(c_int64)]),
+    "qc_status_str": (c_char_p, [c_int32]),
+    "qc_last_error": (c_char_p, []),
+}
+EXPORTED = tuple(_PROTOTYPES)
+
+_lib = None
+
+
+def load_library():
+    """Load libqcache.so (once) and set the prototypes.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libqcache.so is missing: build it with __graft_entry__.build() or "
+                               "python -m paper_2602_01901_amd.build (there is no fallback path)")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _PROTOTYPES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _i32(seq):
+    if seq is None:
+        return None
+    seq = [int(v) for v in seq]
+    return (c_int32 * max(len(seq), 1))(*seq)
+
+
+def _check(status):
+    if status != QC_OK:
+        raise QcError(status, qc_last_error())
+    return status
+
+
+def status_str(status):
+    return load_library().qc_status_str(int(status)).decode()
+
+
+qc_status_str = status_str
+
+
+def qc_last_error():
+    return load_library().qc_last_error().decode()
+
+
+def make_config(n_layers, n_heads, head_dim, dtype, max_batch, max_seq, max_vis, max_text, lazy_mask):
+    """Returns a qc_config; the mask buffer is kept alive by the returned object."""
+    mask = (c_uint8 * max(len(lazy_mask), 1))(*[int(bool(x)) for x in lazy_mask])
+    cfg = qc_config(n_layers, n_heads, head_dim, DTYPE_CODE.get(dtype, dtype), max_batch, max_seq, max_vis,
+                    max_text, ctypes.cast(mask, POINTER(c_uint8)))
+    cfg._mask_keepalive = mask
+    return cfg
+
+
+def qc_kv_arena_bytes(cfg):
+    return load_library().qc_kv_arena_bytes(byref(cfg))
+
+
+def qc_q_arena_bytes(cfg):
+    return load_library().qc_q_arena_bytes(byref(cfg))
+
+
+def qc_decode_workspace_bytes(cfg):
+    return load_library().qc_decode_workspace_bytes(byref(cfg))
+
+
+def qc_kvcache_create(cfg, dev_arena, arena_bytes):
+    out = c_void_p()
+    _check(load_library().qc_kvcache_create(byref(cfg), _ptr(dev_arena), arena_bytes, byref(out)))
+    return out
+
+
+def qc_qcache_create(cfg, dev_arena, arena_bytes):
+    out = c_void_p()
+    _check(load_library().qc_qcache_create(byref(cfg), _ptr(dev_arena), arena_bytes, byref(out)))
+    return out
+
+
+def qc_kvcache_destroy(kv):
+    load_library().qc_kvcache_destroy(kv)
+
+
+def qc_qcache_destroy(qc):
+    load_library().qc_qcache_destroy(qc)
+
+
+def qc_reset(kv, qc, batch, vis_start, vis_len, zero_fill=1, stream=None):
+    return _check(load_library().qc_reset(kv, qc, batch, _i32(vis_start), _i32(vis_len), int(zero_fill), stream))
+
+
+def qc_prefill(kv, qc, layer, is_lazy, q, k, v, out, cu_seqlens, token_stride, head_stride, vis_start, vis_len,
+               softmax_scale=0.0, stream=None):
+    return _check(load_library().qc_prefill(kv, qc, layer, int(is_lazy), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
+                                           _i32(cu_seqlens), token_stride, head_stride, _i32(vis_start),
+                                           _i32(vis_len), softmax_scale, stream))
+
+
+def qc_decode(kv, qc, layer, is_lazy, q, k, v, out, vis_start, vis_len, softmax_scale, workspace,
+              workspace_bytes, stream=None):
+    return _check(load_library().qc_decode(kv, qc, layer, int(is_lazy), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
+                                          _i32(vis_start), _i32(vis_len), softmax_scale, _ptr(workspace),
+                                          workspace_bytes, stream))
+
+
+def qc_stats(kv, qc):
+    st = qc_stats_t()
+    _check(load_library().qc_stats(kv, qc, byref(st)))
+    return {name: getattr(st, name) for name, _ in qc_stats_t._fields_}
+
+
+def qc_layer_rows(kv, layer):
+    rk, rv = c_int64(), c_int64()
+    _check(load_library().qc_layer_rows(kv, layer, byref(rk), byref(rv)))
+    return rk.value, rv.value
+
+
+def qc_seq_len(kv, b):
+    n = c_int32()
+    _check(load_library().qc_seq_len(kv, b, byref(n)))
+    return n.value
+
+
+def qc_locate(kv, which, layer, b, h, pos):
+    src, off = c_int32(), c_int64()
+    _check(load_library().qc_locate(kv, which, layer, b, h, pos, byref(src), byref(off)))
+    return src.value, off.value

@@ -1,0 +1,448 @@
+// Host side of the C ABI declared in include/qcache.h: validation, lazy-block bookkeeping,
+// arena address arithmetic and kernel dispatch.  All arithmetic of the method runs in the
+// kernels; this file only decides which rows live where (integers).
+#include "qcache.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "qc_internal.h"
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+qc_status fail(qc_status s, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return s;
+}
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+struct Config {
+  int32_t N = 0, H = 0, D = 0, dtype = 0;
+  int32_t max_batch = 0, max_seq = 0, max_vis = 0, max_text = 0;
+  std::vector<uint8_t> lazy;
+  std::vector<int32_t> anchor;  // anchor[l] = first layer of l's block (l itself if not lazy)
+
+  int e() const { return dtype == QC_BF16 ? 2 : 4; }
+  int64_t cap_k(int l) const { return lazy[l] ? max_text : max_seq; }
+  int64_t k_layer_bytes(int l) const { return (int64_t)max_batch * H * cap_k(l) * D * e(); }
+  int64_t v_layer_bytes() const { return (int64_t)max_batch * H * max_seq * D * e(); }
+  int64_t off_k(int l) const {
+    int64_t o = 0;
+    for (int i = 0; i < l; ++i) o += k_layer_bytes(i);
+    return o;
+  }
+  int64_t off_v(int l) const { return off_k(N) + (int64_t)l * v_layer_bytes(); }
+  int64_t off_meta() const { return round_up(off_v(N), 256); }
+  int64_t meta_bytes() const { return round_up((int64_t)qc::META_ROWS * 4 * max_batch, 256); }
+  int64_t kv_bytes() const { return off_meta() + meta_bytes(); }
+  int64_t q_bytes() const { return (int64_t)max_batch * H * max_vis * D * e(); }
+  int64_t row_bytes() const { return (int64_t)D * e(); }
+  bool same(const Config& o) const {
+    return N == o.N && H == o.H && D == o.D && dtype == o.dtype && max_batch == o.max_batch &&
+           max_seq == o.max_seq && max_vis == o.max_vis && max_text == o.max_text && lazy == o.lazy;
+  }
+};
+
+// Smallest key chunk a decode workgroup takes; fixes the workspace size.
+constexpr int kMinChunkKeys = 64;
+
+bool parse_config(const qc_config* c, Config* out) {
+  if (!c || !c->lazy_mask) return false;
+  if (c->n_layers < 1 || c->n_heads < 1 || c->max_batch < 1 || c->max_seq < 1 || c->max_vis < 0 ||
+      c->max_text < 0)
+    return false;
+  if (c->head_dim != 64 && c->head_dim != 128) return false;
+  if (c->dtype != QC_F32 && c->dtype != QC_BF16) return false;
+  if (c->max_vis > c->max_seq || c->max_text > c->max_seq) return false;
+  if (c->lazy_mask[0]) return false;
+  out->N = c->n_layers;
+  out->H = c->n_heads;
+  out->D = c->head_dim;
+  out->dtype = c->dtype;
+  out->max_batch = c->max_batch;
+  out->max_seq = c->max_seq;
+  out->max_vis = c->max_vis;
+  out->max_text = c->max_text;
+  out->lazy.assign(c->lazy_mask, c->lazy_mask + c->n_layers);
+  for (auto& f : out->lazy) f = f ? 1 : 0;
+  out->anchor.resize(out->N);
+  for (int l = 0; l < out->N; ++l) out->anchor[l] = out->lazy[l] ? out->anchor[l - 1] : l;
+  return true;
+}
+
+enum Phase { PH_EMPTY = 0, PH_RESET = 1, PH_PREFILL = 2, PH_READY = 3, PH_DECODE = 4 };
+
+}  // namespace
+
+struct qc_kvcache {
+  Config cfg;
+  char* arena = nullptr;
+  int phase = PH_EMPTY;
+  int32_t batch = 0;
+  int32_t next_layer = 0;
+  int32_t generated = 0;
+  std::vector<int32_t> vis_start, vis_len, len0, tok0;
+};
+
+struct qc_qcache {
+  Config cfg;
+  char* arena = nullptr;
+  int32_t owner = -1;
+};
+
+extern "C" {
+
+const char* qc_status_str(qc_status s) {
+  switch (s) {
+    case QC_OK: return "QC_OK";
+    case QC_EINVAL: return "QC_EINVAL";
+    case QC_EORDER: return "QC_EORDER";
+    case QC_ECAPACITY: return "QC_ECAPACITY";
+    case QC_EDEVICE: return "QC_EDEVICE";
+  }
+  return "QC_UNKNOWN";
+}
+
+const char* qc_last_error(void) { return g_err; }
+
+size_t qc_kv_arena_bytes(const qc_config* cfg) {
+  Config c;
+  return parse_config(cfg, &c) ? (size_t)c.kv_bytes() : 0;
+}
+
+size_t qc_q_arena_bytes(const qc_config* cfg) {
+  Config c;
+  return parse_config(cfg, &c) ? (size_t)c.q_bytes() : 0;
+}
+
+size_t qc_decode_workspace_bytes(const qc_config* cfg) {
+  Config c;
+  if (!parse_config(cfg, &c)) return 0;
+  int64_t chunks = (c.max_seq + kMinChunkKeys - 1) / kMinChunkKeys;
+  return (size_t)((int64_t)c.max_batch * c.H * chunks * (c.D + 2) * 4);
+}
+
+qc_status qc_kvcache_create(const qc_config* cfg, void* dev_arena, size_t arena_bytes, qc_kvcache** out) {
+  if (!out) return fail(QC_EINVAL, "qc_kvcache_create: out is null");
+  *out = nullptr;
+  Config c;
+  if (!parse_config(cfg, &c)) return fail(QC_EINVAL, "qc_kvcache_create: invalid configuration");
+  if (!dev_arena || ((uintptr_t)dev_arena & 255)) return fail(QC_EINVAL, "qc_kvcache_create: arena null or not 256-byte aligned");
+  if ((int64_t)arena_bytes < c.kv_bytes())
+    return fail(QC_ECAPACITY, "qc_kvcache_create: arena holds %zu bytes, %lld needed", arena_bytes, (long long)c.kv_bytes());
+  qc_kvcache* kv = new (std::nothrow) qc_kvcache;
+  if (!kv) return fail(QC_ECAPACITY, "qc_kvcache_create: out of host memory");
+  kv->cfg = c;
+  kv->arena = (char*)dev_arena;
+  *out = kv;
+  return QC_OK;
+}
+
+qc_status qc_qcache_create(const qc_config* cfg, void* dev_arena, size_t arena_bytes, qc_qcache** out) {
+  if (!out) return fail(QC_EINVAL, "qc_qcache_create: out is null");
+  *out = nullptr;
+  Config c;
+  if (!parse_config(cfg, &c)) return fail(QC_EINVAL, "qc_qcache_create: invalid configuration");
+  if (c.q_bytes() > 0 && (!dev_arena || ((uintptr_t)dev_arena & 255)))
+    return fail(QC_EINVAL, "qc_qcache_create: arena null or not 256-byte aligned");
+  if ((int64_t)arena_bytes < c.q_bytes())
+    return fail(QC_ECAPACITY, "qc_qcache_create: arena holds %zu bytes, %lld needed", arena_bytes, (long long)c.q_bytes());
+  qc_qcache* q = new (std::nothrow) qc_qcache;
+  if (!q) return fail(QC_ECAPACITY, "qc_qcache_create: out of host memory");
+  q->cfg = c;
+  q->arena = (char*)dev_arena;
+  *out = q;
+  return QC_OK;
+}
+
+void qc_kvcache_destroy(qc_kvcache* kv) { delete kv; }
+void qc_qcache_destroy(qc_qcache* qc) { delete qc; }
+
+qc_status qc_reset(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* vis_start,
+                   const int32_t* vis_len, int32_t zero_fill, void* stream) {
+  if (!kv || !qc) return fail(QC_EINVAL, "qc_reset: null handle");
+  if (!kv->cfg.same(qc->cfg)) return fail(QC_EINVAL, "qc_reset: K/V cache and Q Cache were created with different configurations");
+  if (!vis_start || !vis_len) return fail(QC_EINVAL, "qc_reset: null span arrays");
+  const Config& c = kv->cfg;
+  if (batch < 1) return fail(QC_EINVAL, "qc_reset: batch %d", batch);
+  if (batch > c.max_batch) return fail(QC_ECAPACITY, "qc_reset: batch %d exceeds max_batch %d", batch, c.max_batch);
+  for (int b = 0; b < batch; ++b) {
+    if (vis_start[b] < 0 || vis_len[b] < 0) return fail(QC_EINVAL, "qc_reset: negative span for sequence %d", b);
+    if (vis_len[b] > c.max_vis) return fail(QC_ECAPACITY, "qc_reset: sequence %d has %d visual tokens, max_vis %d", b, vis_len[b], c.max_vis);
+    if ((int64_t)vis_start[b] + vis_len[b] > c.max_seq) return fail(QC_ECAPACITY, "qc_reset: span of sequence %d exceeds max_seq", b);
+  }
+  if (zero_fill) {
+    hipError_t e = qc::launch_fill_zero(kv->arena, (size_t)c.kv_bytes(), (hipStream_t)stream);
+    if (e == hipSuccess && c.q_bytes() > 0) e = qc::launch_fill_zero(qc->arena, (size_t)c.q_bytes(), (hipStream_t)stream);
+    if (e != hipSuccess) return fail(QC_EDEVICE, "qc_reset: %s", hipGetErrorString(e));
+  }
+  kv->batch = batch;
+  kv->vis_start.assign(vis_start, vis_start + batch);
+  kv->vis_len.assign(vis_len, vis_len + batch);
+  kv->len0.assign(batch, 0);
+  kv->tok0.assign(batch, 0);
+  kv->phase = PH_RESET;
+  kv->next_layer = 0;
+  kv->generated = 0;
+  qc->owner = -1;
+  return QC_OK;
+}
+
+static qc::LayerView make_view(const qc_kvcache* kv, const qc_qcache* qc, int layer) {
+  const Config& c = kv->cfg;
+  qc::LayerView lv;
+  lv.k_own = kv->arena + c.off_k(layer);
+  lv.v_own = kv->arena + c.off_v(layer);
+  lv.cap_k = (int32_t)c.cap_k(layer);
+  lv.cap_v = c.max_seq;
+  int a = c.anchor[layer];
+  lv.k_anchor = c.lazy[layer] ? kv->arena + c.off_k(a) : nullptr;
+  lv.cap_k_anchor = (int32_t)c.cap_k(a);
+  lv.q_cache = qc ? qc->arena : nullptr;
+  lv.cap_q = c.max_vis;
+  lv.meta = (const int32_t*)(kv->arena + c.off_meta());
+  lv.max_batch = c.max_batch;
+  return lv;
+}
+
+static qc_status check_spans(const char* who, const qc_kvcache* kv, const int32_t* vis_start, const int32_t* vis_len) {
+  if (!vis_start || !vis_len) return fail(QC_EINVAL, "%s: null span arrays", who);
+  for (int b = 0; b < kv->batch; ++b)
+    if (vis_start[b] != kv->vis_start[b] || vis_len[b] != kv->vis_len[b])
+      return fail(QC_EINVAL, "%s: span of sequence %d differs from the one given to qc_reset", who, b);
+  return QC_OK;
+}
+
+qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_lazy, const void* q,
+                     const void* k, const void* v, void* out, const int32_t* cu_seqlens,
+                     int64_t token_stride, int64_t head_stride, const int32_t* vis_start,
+                     const int32_t* vis_len, float softmax_scale, void* stream) {
+  if (!kv || !qc) return fail(QC_EINVAL, "qc_prefill: null handle");
+  const Config& c = kv->cfg;
+  if (!c.same(qc->cfg)) return fail(QC_EINVAL, "qc_prefill: handles were created with different configurations");
+  if (layer < 0 || layer >= c.N) return fail(QC_EINVAL, "qc_prefill: layer %d out of range", layer);
+  if ((is_lazy != 0) != (c.lazy[layer] != 0)) return fail(QC_EINVAL, "qc_prefill: is_lazy=%d contradicts the configured mask for layer %d", is_lazy, layer);
+  if (!q || !k || !v || !out || !cu_seqlens) return fail(QC_EINVAL, "qc_prefill: null tensor or cu_seqlens");
+  const int e = c.e();
+  if (head_stride < c.D || token_stride < c.D || (head_stride * e) % 16 || (token_stride * e) % 16)
+    return fail(QC_EINVAL, "qc_prefill: strides must be >= head_dim and keep rows 16-byte aligned");
+  if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15)
+    return fail(QC_EINVAL, "qc_prefill: tensors must be 16-byte aligned");
+  if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return fail(QC_EINVAL, "qc_prefill: bad softmax_scale");
+  if (kv->phase != PH_RESET && kv->phase != PH_PREFILL)
+    return fail(QC_EORDER, "qc_prefill: no prefill pass is open (call qc_reset first)");
+  if (layer != kv->next_layer) return fail(QC_EORDER, "qc_prefill: expected layer %d, got %d", kv->next_layer, layer);
+  if (qc_status s = check_spans("qc_prefill", kv, vis_start, vis_len)) return s;
+  if (cu_seqlens[0] != 0) return fail(QC_EINVAL, "qc_prefill: cu_seqlens[0] must be 0");
+  int32_t max_len = 0;
+  for (int b = 0; b < kv->batch; ++b) {
+    int64_t len = (int64_t)cu_seqlens[b + 1] - cu_seqlens[b];
+    if (len < 1) return fail(QC_EINVAL, "qc_prefill: sequence %d is empty", b);
+    if (kv->vis_start[b] + kv->vis_len[b] > len) return fail(QC_EINVAL, "qc_prefill: span of sequence %d exceeds its %lld tokens", b, (long long)len);
+    if (len > c.max_seq) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld tokens, max_seq %d", b, (long long)len, c.max_seq);
+    if (len - kv->vis_len[b] > c.max_text) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld text tokens, max_text %d", b, (long long)(len - kv->vis_len[b]), c.max_text);
+    if (layer > 0 && (len != kv->len0[b] || cu_seqlens[b] != kv->tok0[b]))
+      return fail(QC_EINVAL, "qc_prefill: cu_seqlens changed between layers");
+    if (len > max_len) max_len = (int32_t)len;
+  }
+  if (c.lazy[layer] && qc->owner != c.anchor[layer])
+    return fail(QC_EORDER, "qc_prefill: Q Cache belongs to layer %d, layer %d inherits from %d", qc->owner, layer, c.anchor[layer]);
+
+  hipStream_t st = (hipStream_t)stream;
+  qc::LayerView lv = make_view(kv, qc, layer);
+  if (layer == 0) {
+    for (int first = 0; first < kv->batch; first += qc::MetaChunk::N) {
+      qc::MetaChunk mc;
+      memset(&mc, 0, sizeof(mc));
+      int count = kv->batch - first < qc::MetaChunk::N ? kv->batch - first : qc::MetaChunk::N;
+      for (int i = 0; i < count; ++i) {
+        int b = first + i;
+        mc.v[qc::META_TOK0][i] = cu_seqlens[b];
+        mc.v[qc::META_LEN0][i] = cu_seqlens[b + 1] - cu_seqlens[b];
+        mc.v[qc::META_VIS_START][i] = kv->vis_start[b];
+        mc.v[qc::META_VIS_LEN][i] = kv->vis_len[b];
+      }
+      hipError_t e2 = qc::launch_meta_upload((int32_t*)(kv->arena + c.off_meta()), c.max_batch, first, count, mc, st);
+      if (e2 != hipSuccess) return fail(QC_EDEVICE, "qc_prefill: metadata upload: %s", hipGetErrorString(e2));
+    }
+  }
+  qc::PrefillArgs a;
+  a.lv = lv;
+  a.q = q; a.k = k; a.v = v; a.out = out;
+  a.token_stride = token_stride;
+  a.head_stride = head_stride;
+  a.batch = kv->batch; a.n_heads = c.H; a.head_dim = c.D;
+  a.is_lazy = c.lazy[layer];
+  a.write_q = (!c.lazy[layer] && layer + 1 < c.N && c.lazy[layer + 1]) ? 1 : 0;
+  a.max_len = max_len;
+  a.scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)c.D);
+  hipError_t err = qc::launch_prefill(a, c.dtype, st);
+  if (err != hipSuccess) return fail(QC_EDEVICE, "qc_prefill: %s", hipGetErrorString(err));
+
+  if (layer == 0)
+    for (int b = 0; b < kv->batch; ++b) {
+      kv->tok0[b] = cu_seqlens[b];
+      kv->len0[b] = cu_seqlens[b + 1] - cu_seqlens[b];
+    }
+  if (a.write_q) qc->owner = layer;
+  kv->next_layer = layer + 1;
+  kv->phase = PH_PREFILL;
+  if (kv->next_layer == c.N) {
+    kv->phase = PH_READY;
+    kv->next_layer = 0;
+  }
+  return QC_OK;
+}
+
+qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_lazy, const void* q,
+                    const void* k, const void* v, void* out, const int32_t* vis_start,
+                    const int32_t* vis_len, float softmax_scale, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+  (void)qc;  // Visual Lazy Attention never touches the Q Cache while decoding
+  if (!kv) return fail(QC_EINVAL, "qc_decode: null handle");
+  const Config& c = kv->cfg;
+  if (layer < 0 || layer >= c.N) return fail(QC_EINVAL, "qc_decode: layer %d out of range", layer);
+  if ((is_lazy != 0) != (c.lazy[layer] != 0)) return fail(QC_EINVAL, "qc_decode: is_lazy=%d contradicts the configured mask for layer %d", is_lazy, layer);
+  if (!q || !k || !v || !out || !workspace) return fail(QC_EINVAL, "qc_decode: null tensor or workspace");
+  if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out | (uintptr_t)workspace) & 15)
+    return fail(QC_EINVAL, "qc_decode: tensors and workspace must be 16-byte aligned");
+  if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return fail(QC_EINVAL, "qc_decode: bad softmax_scale");
+  if (kv->phase != PH_READY && kv->phase != PH_DECODE) return fail(QC_EORDER, "qc_decode: prefill has not finished");
+  if (layer != kv->next_layer) return fail(QC_EORDER, "qc_decode: expected layer %d, got %d", kv->next_layer, layer);
+  if (qc_status s = check_spans("qc_decode", kv, vis_start, vis_len)) return s;
+  int32_t max_len = 0;
+  int64_t total = 0;
+  for (int b = 0; b < kv->batch; ++b) {
+    int64_t len = (int64_t)kv->len0[b] + kv->generated;
+    if (len + 1 > c.max_seq) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld positions, max_seq %d", b, (long long)(len + 1), c.max_seq);
+    if (len + 1 - kv->vis_len[b] > c.max_text) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld text rows, max_text %d", b, (long long)(len + 1 - kv->vis_len[b]), c.max_text);
+    if (len > max_len) max_len = (int32_t)len;
+    total += len + 1;
+  }
+  // Split the key axis so that roughly kTargetGroups workgroups are in flight.
+  constexpr int64_t kTargetGroups = 2048;
+  int64_t per = (total * c.H + kTargetGroups - 1) / kTargetGroups;
+  int32_t chunk = (int32_t)round_up(per < kMinChunkKeys ? kMinChunkKeys : per, kMinChunkKeys);
+  int32_t max_chunks = (max_len + 1 + chunk - 1) / chunk;
+  size_t need = (size_t)kv->batch * c.H * max_chunks * (c.D + 2) * 4;
+  if (workspace_bytes < need) return fail(QC_ECAPACITY, "qc_decode: workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+
+  qc::DecodeArgs a;
+  a.lv = make_view(kv, nullptr, layer);
+  a.q = q; a.k = k; a.v = v; a.out = out;
+  a.workspace = (float*)workspace;
+  a.batch = kv->batch; a.n_heads = c.H; a.head_dim = c.D;
+  a.is_lazy = c.lazy[layer];
+  a.generated = kv->generated;
+  a.max_len = max_len;
+  a.chunk_keys = chunk;
+  a.max_chunks = max_chunks;
+  a.scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)c.D);
+  hipError_t err = qc::launch_decode(a, c.dtype, (hipStream_t)stream);
+  if (err != hipSuccess) return fail(QC_EDEVICE, "qc_decode: %s", hipGetErrorString(err));
+
+  kv->next_layer = layer + 1;
+  kv->phase = PH_DECODE;
+  if (kv->next_layer == c.N) {
+    kv->next_layer = 0;
+    kv->generated += 1;
+    kv->phase = PH_READY;
+  }
+  return QC_OK;
+}
+
+// Rows resident in `layer` for sequence b, given how far the current pass has come.
+static void rows_of(const qc_kvcache* kv, int layer, int b, int64_t* rk, int64_t* rv) {
+  const Config& c = kv->cfg;
+  int64_t len = 0;
+  switch (kv->phase) {
+    case PH_EMPTY:
+    case PH_RESET: len = 0; break;
+    case PH_PREFILL: len = layer < kv->next_layer ? kv->len0[b] : 0; break;
+    case PH_READY: len = (int64_t)kv->len0[b] + kv->generated; break;
+    case PH_DECODE: len = (int64_t)kv->len0[b] + kv->generated + (layer < kv->next_layer ? 1 : 0); break;
+  }
+  *rv = len;
+  *rk = len ? len - (c.lazy[layer] ? kv->vis_len[b] : 0) : 0;
+}
+
+qc_status qc_stats(const qc_kvcache* kv, const qc_qcache* qc, qc_stats_t* out) {
+  if (!kv || !out) return fail(QC_EINVAL, "qc_stats: null argument");
+  const Config& c = kv->cfg;
+  memset(out, 0, sizeof(*out));
+  const int64_t per_row = (int64_t)c.H * c.D * c.e();
+  for (int b = 0; b < kv->batch; ++b) {
+    for (int l = 0; l < c.N; ++l) {
+      int64_t rk, rv;
+      rows_of(kv, l, b, &rk, &rv);
+      out->k_bytes += rk * per_row;
+      out->v_bytes += rv * per_row;
+    }
+    if (qc && qc->owner >= 0) out->q_bytes += (int64_t)kv->vis_len[b] * per_row;
+    if (kv->phase == PH_PREFILL) out->tokens += kv->len0[b];
+    else if (kv->phase >= PH_READY) out->tokens += (int64_t)kv->len0[b] + kv->generated;
+  }
+  out->batch = kv->batch;
+  out->q_owner = qc ? qc->owner : -1;
+  out->generated = kv->generated;
+  out->next_layer = kv->next_layer;
+  return QC_OK;
+}
+
+qc_status qc_layer_rows(const qc_kvcache* kv, int32_t layer, int64_t* rows_k, int64_t* rows_v) {
+  if (!kv || !rows_k || !rows_v) return fail(QC_EINVAL, "qc_layer_rows: null argument");
+  if (layer < 0 || layer >= kv->cfg.N) return fail(QC_EINVAL, "qc_layer_rows: layer %d out of range", layer);
+  *rows_k = *rows_v = 0;
+  for (int b = 0; b < kv->batch; ++b) {
+    int64_t rk, rv;
+    rows_of(kv, layer, b, &rk, &rv);
+    *rows_k += rk;
+    *rows_v += rv;
+  }
+  return QC_OK;
+}
+
+qc_status qc_seq_len(const qc_kvcache* kv, int32_t b, int32_t* len) {
+  if (!kv || !len) return fail(QC_EINVAL, "qc_seq_len: null argument");
+  if (b < 0 || b >= kv->batch) return fail(QC_EINVAL, "qc_seq_len: sequence %d out of range", b);
+  *len = kv->phase >= PH_READY ? kv->len0[b] + kv->generated : 0;
+  return QC_OK;
+}
+
+qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t b, int32_t h,
+                    int32_t pos, int32_t* src_layer, int64_t* byte_offset) {
+  if (!kv || !src_layer || !byte_offset) return fail(QC_EINVAL, "qc_locate: null argument");
+  const Config& c = kv->cfg;
+  if (which != QC_K && which != QC_V) return fail(QC_EINVAL, "qc_locate: which must be QC_K or QC_V");
+  if (layer < 0 || layer >= c.N || b < 0 || b >= kv->batch || h < 0 || h >= c.H || pos < 0 || pos >= c.max_seq)
+    return fail(QC_EINVAL, "qc_locate: index out of range");
+  const int64_t rb = c.row_bytes();
+  if (which == QC_V) {
+    *src_layer = layer;
+    *byte_offset = c.off_v(layer) + (((int64_t)b * c.H + h) * c.max_seq + pos) * rb;
+    return QC_OK;
+  }
+  const int32_t s = kv->vis_start[b], vn = kv->vis_len[b];
+  int src = layer;
+  int64_t row = pos;
+  if (c.lazy[layer]) {
+    if (pos >= s && pos < s + vn) src = c.anchor[layer];
+    else if (pos >= s + vn) row = pos - vn;
+  }
+  if (row >= c.cap_k(src)) return fail(QC_ECAPACITY, "qc_locate: position %d has no row within the layer's capacity", pos);
+  *src_layer = src;
+  *byte_offset = c.off_k(src) + (((int64_t)b * c.H + h) * c.cap_k(src) + row) * rb;
+  return QC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,186 @@
+// Decode attention for one generated token per sequence (paper Eq. 2; Eq. 8 in a lazy layer).
+//
+// The kernel is bound by HBM bandwidth: every cached K and V row of a (sequence, head) pair is
+// streamed exactly once.  The key axis is cut into chunks; one workgroup takes one chunk of one
+// (sequence, head).  A row (head_dim elements) is covered by a group of 16-byte lanes, so a wave
+// reads whole consecutive rows with one load instruction per lane.  Each group keeps its own
+// running softmax (max, sum, weighted V) in fp32; groups are merged through LDS at the end of the
+// chunk and chunks are merged by a second, tiny kernel in fixed order (bitwise reproducible).
+//
+// Lazy layers differ only in where a key row comes from: positions before the visual span and
+// after it are the layer's own (compacted) rows, positions inside it are rows of the block's
+// first layer.  The new token's k/v are taken from the call's inputs, appended to the caches by
+// the one group that owns that position.
+#include "qc_device.h"
+
+namespace qc {
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
+  constexpr int EPL = ElemTraits<T>::kPer16;  // elements per lane (16 bytes)
+  constexpr int LPR = D / EPL;                // lanes per row
+  constexpr int GPW = 64 / LPR;               // row groups per wave
+  constexpr int GROUPS = 4 * GPW;             // row groups per workgroup
+  constexpr int U = 4;                        // rows in flight per group
+  constexpr int ROWB = D * (int)sizeof(T);
+
+  const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const SeqMeta sm = load_meta(a.lv, b);
+  const int len = sm.len0 + a.generated;  // position of the new token
+  const int kbeg = chunk * a.chunk_keys;
+  if (kbeg > len) return;
+  const int kend = min(kbeg + a.chunk_keys, len + 1);
+  const int s = sm.vis_start, e = sm.vis_start + sm.vis_len;
+  const bool lazy = a.is_lazy != 0;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int li = lane % LPR, gid = wave * GPW + lane / LPR;
+  const int64_t bh = (int64_t)b * a.n_heads + h;
+
+  char* kown = a.lv.k_own + bh * a.lv.cap_k * ROWB + li * 16;
+  const char* kanc = lazy ? a.lv.k_anchor + bh * a.lv.cap_k_anchor * ROWB + li * 16 : nullptr;
+  char* vown = a.lv.v_own + bh * a.lv.cap_v * ROWB + li * 16;
+  const char* knew = (const char*)a.k + bh * ROWB + li * 16;
+  const char* vnew = (const char*)a.v + bh * ROWB + li * 16;
+
+  float qf[EPL];
+  {
+    const uint4 raw = *(const uint4*)((const char*)a.q + bh * ROWB + li * 16);
+    unpack16(raw, qf, (T*)nullptr);
+    const float c = a.scale * kLog2e;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) qf[i] *= c;
+  }
+
+  float m = -INFINITY, l = 0.f;
+  float acc[EPL];
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+
+  for (int r0 = kbeg + gid; r0 < kend; r0 += GROUPS * U) {
+    uint4 kr[U], vr[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int pos = r0 + u * GROUPS;
+      kr[u] = make_uint4(0, 0, 0, 0);
+      vr[u] = make_uint4(0, 0, 0, 0);
+      if (pos < kend) {
+        if (pos == len) {  // the token being decoded: read the inputs, append to the caches
+          kr[u] = *(const uint4*)knew;
+          vr[u] = *(const uint4*)vnew;
+          const int krow = lazy ? len - sm.vis_len : len;
+          *(uint4*)(kown + (int64_t)krow * ROWB) = kr[u];
+          *(uint4*)(vown + (int64_t)len * ROWB) = vr[u];
+        } else {
+          const char* kp;
+          if (lazy && pos >= s) kp = pos < e ? kanc + (int64_t)pos * ROWB : kown + (int64_t)(pos - sm.vis_len) * ROWB;
+          else kp = kown + (int64_t)pos * ROWB;
+          kr[u] = *(const uint4*)kp;
+          vr[u] = *(const uint4*)(vown + (int64_t)pos * ROWB);
+        }
+      }
+    }
+    float sc[U];
+    float mt = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[EPL];
+      unpack16(kr[u], kf, (T*)nullptr);
+      float d = 0.f;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) d = fmaf(qf[i], kf[i], d);
+      d = group_sum<LPR>(d);
+      sc[u] = (r0 + u * GROUPS < kend) ? d : -INFINITY;
+      mt = fmaxf(mt, sc[u]);
+    }
+    const float mn = fmaxf(m, mt);  // finite: the first row of every iteration is valid
+    const float alpha = __builtin_amdgcn_exp2f(m - mn);
+    l *= alpha;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[i] *= alpha;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float p = __builtin_amdgcn_exp2f(sc[u] - mn);
+      l += p;
+      float vf[EPL];
+      unpack16(vr[u], vf, (T*)nullptr);
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) acc[i] = fmaf(p, vf[i], acc[i]);
+    }
+    m = mn;
+  }
+
+  __shared__ float s_acc[GROUPS][D];
+  __shared__ float s_m[GROUPS], s_l[GROUPS];
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) s_acc[gid][li * EPL + i] = acc[i];
+  if (li == 0) {
+    s_m[gid] = m;
+    s_l[gid] = l;
+  }
+  __syncthreads();
+  const int d = threadIdx.x;
+  if (d < D) {
+    float M = -INFINITY;
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g) M = fmaxf(M, s_m[g]);
+    float o = 0.f, lsum = 0.f;
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g) {
+      const float w = __builtin_amdgcn_exp2f(s_m[g] - M);  // 0 for groups that saw no row
+      o = fmaf(w, s_acc[g][d], o);
+      lsum = fmaf(w, s_l[g], lsum);
+    }
+    if (a.max_chunks == 1) {
+      store_elem((T*)a.out + bh * D + d, o / lsum);
+    } else {
+      float* w = a.workspace + (bh * a.max_chunks + chunk) * (D + 2);
+      w[d] = o;
+      if (d == 0) {
+        w[D] = M;
+        w[D + 1] = lsum;
+      }
+    }
+  }
+}
+
+// Merge the chunk partials of one (sequence, head) in chunk order.
+template <typename T, int D>
+__global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
+  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+  const int len = a.lv.meta[META_LEN0 * a.lv.max_batch + b] + a.generated;
+  const int n = (len + a.chunk_keys) / a.chunk_keys;  // ceil((len + 1) / chunk_keys)
+  const int64_t bh = (int64_t)b * a.n_heads + h;
+  const float* w = a.workspace + bh * a.max_chunks * (D + 2);
+  float M = -INFINITY;
+  for (int c = 0; c < n; ++c) M = fmaxf(M, w[c * (D + 2) + D]);
+  float o = 0.f, l = 0.f;
+  for (int c = 0; c < n; ++c) {
+    const float f = __builtin_amdgcn_exp2f(w[c * (D + 2) + D] - M);
+    o = fmaf(f, w[c * (D + 2) + d], o);
+    l = fmaf(f, w[c * (D + 2) + D + 1], l);
+  }
+  store_elem((T*)a.out + bh * D + d, o / l);
+}
+
+template <typename T, int D> static hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t stream) {
+  dim3 grid(a.max_chunks, a.n_heads, a.batch);
+  hipLaunchKernelGGL((decode_split_kernel<T, D>), grid, dim3(256), 0, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || a.max_chunks == 1) return e;
+  hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(a.n_heads, a.batch), dim3(D), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t stream) {
+  if (dtype == 0) {
+    if (a.head_dim == 64) return launch_decode_t<float, 64>(a, stream);
+    if (a.head_dim == 128) return launch_decode_t<float, 128>(a, stream);
+  } else {
+    if (a.head_dim == 64) return launch_decode_t<bf16_t, 64>(a, stream);
+    if (a.head_dim == 128) return launch_decode_t<bf16_t, 128>(a, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace qc

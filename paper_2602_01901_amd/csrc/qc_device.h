@@ -1,0 +1,95 @@
+// Device-side helpers shared by the kernels: element types, 16-byte vector access,
+// wave64 / sub-wave reductions on DPP, per-sequence metadata access.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qc_internal.h"
+
+namespace qc {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+typedef __bf16 bf16_t;
+
+template <typename T> struct ElemTraits;
+template <> struct ElemTraits<float> {
+  static constexpr int kPer16 = 4;
+};
+template <> struct ElemTraits<bf16_t> {
+  static constexpr int kPer16 = 8;
+};
+
+// 16 bytes of T -> floats.
+__device__ __forceinline__ void unpack16(const uint4& raw, float (&f)[4], float*) {
+  f[0] = __uint_as_float(raw.x);
+  f[1] = __uint_as_float(raw.y);
+  f[2] = __uint_as_float(raw.z);
+  f[3] = __uint_as_float(raw.w);
+}
+__device__ __forceinline__ void unpack16(const uint4& raw, float (&f)[8], bf16_t*) {
+  f[0] = __uint_as_float(raw.x << 16);
+  f[1] = __uint_as_float(raw.x & 0xffff0000u);
+  f[2] = __uint_as_float(raw.y << 16);
+  f[3] = __uint_as_float(raw.y & 0xffff0000u);
+  f[4] = __uint_as_float(raw.z << 16);
+  f[5] = __uint_as_float(raw.z & 0xffff0000u);
+  f[6] = __uint_as_float(raw.w << 16);
+  f[7] = __uint_as_float(raw.w & 0xffff0000u);
+}
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return (float)x; }
+// Round-to-nearest-even conversions to the storage type.
+__device__ __forceinline__ void store_elem(float* p, float x) { *p = x; }
+__device__ __forceinline__ void store_elem(bf16_t* p, float x) { *p = (bf16_t)x; }
+
+// ---- DPP lane exchange (row = 16 lanes) -----------------------------------
+template <int kCtrl> __device__ __forceinline__ float dpp_move(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), kCtrl, 0xf, 0xf, false));
+}
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7 - i within each 8
+constexpr int kDppMirror = 0x140;      // lane i <-> 15 - i within each 16
+
+__device__ __forceinline__ float swap32(float x) {  // value held by lane ^ 32
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
+  return __int_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
+
+// Sum over aligned groups of kLanes consecutive lanes; every lane receives the total.
+template <int kLanes> __device__ __forceinline__ float group_sum(float x) {
+  static_assert(kLanes == 8 || kLanes == 16 || kLanes == 32 || kLanes == 64, "group size");
+  x += dpp_move<kDppXor1>(x);
+  x += dpp_move<kDppXor2>(x);
+  x += dpp_move<kDppHalfMirror>(x);
+  if (kLanes >= 16) x += dpp_move<kDppMirror>(x);
+  if (kLanes >= 32) x += __shfl_xor(x, 16);
+  if (kLanes >= 64) x += __shfl_xor(x, 32);
+  return x;
+}
+template <int kLanes> __device__ __forceinline__ float group_max(float x) {
+  static_assert(kLanes == 8 || kLanes == 16 || kLanes == 32 || kLanes == 64, "group size");
+  x = fmaxf(x, dpp_move<kDppXor1>(x));
+  x = fmaxf(x, dpp_move<kDppXor2>(x));
+  x = fmaxf(x, dpp_move<kDppHalfMirror>(x));
+  if (kLanes >= 16) x = fmaxf(x, dpp_move<kDppMirror>(x));
+  if (kLanes >= 32) x = fmaxf(x, __shfl_xor(x, 16));
+  if (kLanes >= 64) x = fmaxf(x, __shfl_xor(x, 32));
+  return x;
+}
+
+struct SeqMeta {
+  int32_t tok0, len0, vis_start, vis_len;
+};
+__device__ __forceinline__ SeqMeta load_meta(const LayerView& lv, int b) {
+  SeqMeta m;
+  m.tok0 = lv.meta[META_TOK0 * lv.max_batch + b];
+  m.len0 = lv.meta[META_LEN0 * lv.max_batch + b];
+  m.vis_start = lv.meta[META_VIS_START * lv.max_batch + b];
+  m.vis_len = lv.meta[META_VIS_LEN * lv.max_batch + b];
+  return m;
+}
+
+}  // namespace qc

@@ -1,0 +1,68 @@
+// Internal interface between the host-side C ABI (qc_api.cpp) and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qc {
+
+// Per-sequence metadata rows in the arena's meta region: meta[row * max_batch + b].
+enum { META_TOK0 = 0, META_LEN0 = 1, META_VIS_START = 2, META_VIS_LEN = 3, META_ROWS = 4 };
+
+// Device addresses of everything one layer call touches.  Cache regions are
+// [batch][head][cap][D] with the element type of the configuration.
+struct LayerView {
+  char* k_own;            // this layer's K rows
+  char* v_own;            // this layer's V rows
+  const char* k_anchor;   // K rows of the block's first layer (lazy layers only, else nullptr)
+  char* q_cache;          // Q Cache rows (nullptr if the call neither reads nor writes it)
+  const int32_t* meta;    // int32 [META_ROWS][max_batch]
+  int32_t cap_k;          // row capacity per (b, h) of k_own
+  int32_t cap_v;
+  int32_t cap_k_anchor;
+  int32_t cap_q;
+  int32_t max_batch;
+};
+
+struct PrefillArgs {
+  LayerView lv;
+  const void* q;
+  const void* k;
+  const void* v;
+  void* out;
+  int64_t token_stride;   // elements
+  int64_t head_stride;    // elements
+  int32_t batch, n_heads, head_dim;
+  int32_t is_lazy;        // substitute span rows of q/k, store text rows of k only
+  int32_t write_q;        // store span rows of q into the Q Cache
+  int32_t max_len;        // longest prompt in the batch
+  float scale;            // softmax scale (already resolved, > 0)
+};
+
+struct DecodeArgs {
+  LayerView lv;
+  const void* q;          // [batch][H][D]
+  const void* k;
+  const void* v;
+  void* out;
+  float* workspace;       // [batch][H][max_chunks][D + 2] partial (o, m, l)
+  int32_t batch, n_heads, head_dim;
+  int32_t is_lazy;
+  int32_t generated;      // decode steps completed before this one: len_b = len0_b + generated
+  int32_t max_len;        // longest len_b in the batch (before this step)
+  int32_t chunk_keys;     // key positions per workgroup
+  int32_t max_chunks;     // ceil((max_len + 1) / chunk_keys)
+  float scale;
+};
+
+struct MetaChunk {        // by-value payload of the metadata upload kernel
+  enum { N = 64 };
+  int32_t v[META_ROWS][N];
+};
+
+hipError_t launch_fill_zero(void* dev, size_t bytes, hipStream_t stream);
+hipError_t launch_meta_upload(int32_t* meta_dev, int32_t max_batch, int32_t first, int32_t count,
+                              const MetaChunk& chunk, hipStream_t stream);
+hipError_t launch_prefill(const PrefillArgs& a, int dtype, hipStream_t stream);
+hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t stream);
+
+}  // namespace qc

@@ -1,0 +1,83 @@
+"""Device-memory plumbing around the C ABI: arenas, workspace and handles for one decoder stack.
+
+PyTorch is used for allocation and for the current stream only.  Every call forwards to the
+library; nothing is computed here.
+"""
+import torch
+
+from . import binding as B
+
+_TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+class Session:
+    def __init__(self, n_layers, n_heads, head_dim, dtype, lazy_mask, max_batch, max_seq, max_vis, max_text,
+                 device="cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("the Lazy Attention library needs a GPU; there is no CPU path")
+        B.load_library()
+        self.device = torch.device(device)
+        self.dtype = dtype
+        self.torch_dtype = _TORCH_DTYPE[dtype]
+        self.n_layers, self.n_heads, self.head_dim = n_layers, n_heads, head_dim
+        self.lazy_mask = [int(bool(x)) for x in lazy_mask]
+        self.cfg = B.make_config(n_layers, n_heads, head_dim, dtype, max_batch, max_seq, max_vis, max_text,
+                                 self.lazy_mask)
+        self.kv_bytes = B.qc_kv_arena_bytes(self.cfg)
+        self.q_bytes = B.qc_q_arena_bytes(self.cfg)
+        self.ws_bytes = B.qc_decode_workspace_bytes(self.cfg)
+        if self.kv_bytes == 0:
+            raise B.QcError(B.QC_EINVAL, "invalid configuration")
+        self.kv_arena = torch.empty(self.kv_bytes, dtype=torch.uint8, device=self.device)
+        self.q_arena = torch.empty(max(self.q_bytes, 256), dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=self.device)
+        self.kv = B.qc_kvcache_create(self.cfg, self.kv_arena, self.kv_bytes)
+        self.qc = B.qc_qcache_create(self.cfg, self.q_arena, self.q_bytes)
+        self.vis_start = self.vis_len = None
+        self.batch = 0
+
+    @classmethod
+    def for_workload(cls, w, device="cuda:0"):
+        return cls(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.lazy_mask, w.batch, w.max_seq, w.max_vis,
+                   w.max_text, device=device)
+
+    def _stream(self):
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    def reset(self, vis_start, vis_len, zero_fill=True):
+        self.vis_start, self.vis_len = list(vis_start), list(vis_len)
+        self.batch = len(self.vis_start)
+        B.qc_reset(self.kv, self.qc, self.batch, self.vis_start, self.vis_len, int(zero_fill), self._stream())
+
+    def prefill(self, layer, q, k, v, cu_seqlens, out=None, softmax_scale=0.0):
+        """q, k, v: [tokens, H, D] tensors sharing strides.  Returns out."""
+        if out is None:
+            out = torch.empty_like(q)
+        assert q.stride() == k.stride() == v.stride() == out.stride() and q.stride(2) == 1
+        B.qc_prefill(self.kv, self.qc, layer, self.lazy_mask[layer], q, k, v, out, cu_seqlens, q.stride(0),
+                     q.stride(1), self.vis_start, self.vis_len, softmax_scale, self._stream())
+        return out
+
+    def decode(self, layer, q, k, v, out=None, softmax_scale=0.0):
+        """q, k, v: contiguous [B, H, D] tensors.  Returns out."""
+        if out is None:
+            out = torch.empty_like(q)
+        assert q.is_contiguous() and k.is_contiguous() and v.is_contiguous() and out.is_contiguous()
+        B.qc_decode(self.kv, self.qc, layer, self.lazy_mask[layer], q, k, v, out, self.vis_start, self.vis_len,
+                    softmax_scale, self.workspace, self.ws_bytes, self._stream())
+        return out
+
+    def stats(self):
+        return B.qc_stats(self.kv, self.qc)
+
+    def close(self):
+        if self.kv is not None:
+            B.qc_kvcache_destroy(self.kv)
+            B.qc_qcache_destroy(self.qc)
+            self.kv = self.qc = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,88 @@
+"""Drive the same seeded workload through the HIP library and through the CPU oracle."""
+import numpy as np
+import torch
+
+import workloads
+from oracle import layout as olayout
+from oracle.lazy_stack import LazyStackOracle
+
+TOL = {"f32": 1e-4, "bf16": 3e-2}   # max-abs-error bars for outputs (fp32 / bf16 storage)
+
+
+def oracle_layout(w):
+    return olayout.ArenaLayout(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.batch, w.max_seq, w.max_vis,
+                               w.max_text, w.lazy_mask)
+
+
+def new_oracles(w, heads=None):
+    H = w.n_heads if heads is None else len(heads)
+    return [LazyStackOracle(w.n_layers, H, w.head_dim, w.lazy_mask, w.vis_start[b], w.vis_len[b])
+            for b in range(w.batch)]
+
+
+def oracle_prefill_layer(w, stacks, layer, q, k, v):
+    """q, k, v: torch tensors [tokens, H, D] (any device).  Returns fp64 [tokens, H, D]."""
+    q64, k64, v64 = (workloads.to_f64(t) for t in (q, k, v))
+    cu = w.cu_seqlens
+    outs = [stacks[b].prefill(layer, q64[cu[b]:cu[b + 1]], k64[cu[b]:cu[b + 1]], v64[cu[b]:cu[b + 1]])
+            for b in range(w.batch)]
+    return np.concatenate(outs, axis=0)
+
+
+def oracle_decode_layer(w, stacks, layer, q, k, v):
+    q64, k64, v64 = (workloads.to_f64(t) for t in (q, k, v))
+    return np.stack([stacks[b].decode(layer, q64[b], k64[b], v64[b]) for b in range(w.batch)], axis=0)
+
+
+def max_abs_err(gpu_tensor, ref64):
+    return float(np.max(np.abs(workloads.to_f64(gpu_tensor) - ref64)))
+
+
+def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=True):
+    """Prefill every layer then `decode_steps` decode steps on both sides; returns worst errors.
+
+    With poison_span the span rows of q and k handed to lazy layers hold NaN on the GPU side
+    (the oracle gets the clean tensors): lazy layers must never read them.
+    """
+    dev = session.device
+    stacks = new_oracles(w)
+    session.reset(w.vis_start, w.vis_len, zero_fill=True)
+    worst_p = worst_d = 0.0
+    for l in range(w.n_layers):
+        q, k, v = workloads.prefill_qkv(w, l)
+        ref = oracle_prefill_layer(w, stacks, l, q, k, v)
+        qg, kg, vg = q.to(dev), k.to(dev), v.to(dev)
+        if poison_span and w.lazy_mask[l]:
+            cu = w.cu_seqlens
+            for b in range(w.batch):
+                s, e = cu[b] + w.vis_start[b], cu[b] + w.vis_start[b] + w.vis_len[b]
+                qg[s:e] = float("nan")
+                kg[s:e] = float("nan")
+        out = session.prefill(l, qg, kg, vg, w.cu_seqlens)
+        err = max_abs_err(out, ref)
+        assert np.isfinite(err), "layer %d produced non-finite output" % l
+        worst_p = max(worst_p, err)
+    for t in range(decode_steps):
+        for l in range(w.n_layers):
+            q, k, v = workloads.decode_qkv(w, l, t)
+            ref = oracle_decode_layer(w, stacks, l, q, k, v)
+            out = session.decode(l, q.to(dev), k.to(dev), v.to(dev))
+            err = max_abs_err(out, ref)
+            assert np.isfinite(err)
+            worst_d = max(worst_d, err)
+    torch.cuda.synchronize()
+    if check_arena:
+        lay = oracle_layout(w)
+        want_kv = olayout.kv_arena_image(lay, stacks)
+        got_kv = session.kv_arena.cpu().numpy()
+        assert got_kv.shape == want_kv.shape
+        assert np.array_equal(got_kv, want_kv), "K/V arena differs from the oracle's image"
+        want_q = olayout.q_arena_image(lay, stacks)
+        got_q = session.q_arena.cpu().numpy()[: lay.q_arena_bytes()]
+        assert np.array_equal(got_q, want_q), "Q Cache arena differs from the oracle's image"
+        res = olayout.resident_bytes(lay, stacks)
+        st = session.stats()
+        for key in ("k_bytes", "v_bytes", "q_bytes", "tokens"):
+            assert st[key] == res[key], key
+        assert st["q_owner"] == stacks[0].q_owner
+    return worst_p, worst_d

@@ -1,0 +1,174 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+its size formulas and row map agree with the oracle's layout bit for bit, and every validation
+path returns its status before anything is launched (no GPU is touched here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2602_01901_amd as P
+from paper_2602_01901_amd import binding as B
+from oracle.layout import ArenaLayout
+import workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # a non-null, aligned address that is never dereferenced on the host
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "qcache.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(P.LIB_PATH)
+    names = header_functions()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.EXPORTED) == names, "binding and header must declare the same entry points"
+
+
+CONFIGS = [(4, 8, 64, "f32", 1, 192, 144, 48, [0, 0, 1, 1]),
+           (3, 2, 128, "bf16", 5, 77, 30, 50, [0, 1, 0]),
+           (6, 3, 64, "bf16", 2, 40, 40, 40, [0, 1, 1, 1, 0, 1])]
+
+
+@pytest.mark.parametrize("c", CONFIGS)
+def test_arena_sizes_match_oracle_layout(c):
+    cfg = P.make_config(*c)
+    lay = ArenaLayout(*c)
+    assert B.qc_kv_arena_bytes(cfg) == lay.kv_arena_bytes()
+    assert B.qc_q_arena_bytes(cfg) == lay.q_arena_bytes()
+    assert B.qc_decode_workspace_bytes(cfg) > 0
+
+
+def test_benchmark_configs_sizes_match_oracle_layout():
+    for i in range(5):
+        w = workloads.config(i)
+        c = (w.n_layers, w.n_heads, w.head_dim, w.dtype, w.batch, w.max_seq, w.max_vis, w.max_text, w.lazy_mask)
+        assert B.qc_kv_arena_bytes(P.make_config(*c)) == ArenaLayout(*c).kv_arena_bytes()
+
+
+def test_invalid_configs_report_zero_bytes_and_einval():
+    bad = [(4, 8, 96, "f32", 1, 10, 5, 5, [0, 0, 1, 1]),      # head_dim
+           (4, 8, 64, "f32", 1, 10, 5, 5, [1, 0, 1, 1]),      # layer 0 lazy
+           (4, 8, 64, "f32", 0, 10, 5, 5, [0, 0, 1, 1]),      # max_batch
+           (4, 8, 64, 7, 1, 10, 5, 5, [0, 0, 1, 1]),          # dtype
+           (4, 8, 64, "f32", 1, 10, 11, 5, [0, 0, 1, 1])]     # max_vis > max_seq
+    for c in bad:
+        cfg = P.make_config(*c)
+        assert B.qc_kv_arena_bytes(cfg) == 0
+        with pytest.raises(P.QcError) as e:
+            B.qc_kvcache_create(cfg, FAKE, 1 << 40)
+        assert e.value.status == B.QC_EINVAL
+
+
+def make_handles(c):
+    cfg = P.make_config(*c)
+    kv = B.qc_kvcache_create(cfg, FAKE, B.qc_kv_arena_bytes(cfg))
+    qc = B.qc_qcache_create(cfg, FAKE, B.qc_q_arena_bytes(cfg))
+    return cfg, kv, qc
+
+
+def test_create_rejects_small_or_misaligned_arena():
+    cfg = P.make_config(*CONFIGS[0])
+    with pytest.raises(P.QcError) as e:
+        B.qc_kvcache_create(cfg, FAKE, B.qc_kv_arena_bytes(cfg) - 1)
+    assert e.value.status == B.QC_ECAPACITY
+    with pytest.raises(P.QcError) as e:
+        B.qc_kvcache_create(cfg, FAKE + 8, B.qc_kv_arena_bytes(cfg))
+    assert e.value.status == B.QC_EINVAL
+    with pytest.raises(P.QcError) as e:
+        B.qc_qcache_create(cfg, FAKE, 16)
+    assert e.value.status == B.QC_ECAPACITY
+
+
+@pytest.mark.parametrize("c", CONFIGS[1:])
+def test_locate_matches_oracle_row_map(c):
+    cfg, kv, qc = make_handles(c)
+    lay = ArenaLayout(*c)
+    N, H, batch, max_seq = c[0], c[1], c[4], c[5]
+    vis_start = [(3 * b) % 7 for b in range(batch)]
+    vis_len = [min(c[6], 5 + 4 * b) for b in range(batch)]
+    B.qc_reset(kv, qc, batch, vis_start, vis_len, zero_fill=0)
+    for l in range(N):
+        for b in range(batch):
+            for h in (0, H - 1):
+                for pos in range(max_seq):
+                    src, off = lay.locate_k(l, b, h, pos, vis_start[b], vis_len[b])
+                    row = (off - lay.k_offset(src, b, h, 0)) // (lay.D * lay.e)
+                    if row >= lay.cap_k(src):
+                        with pytest.raises(P.QcError):
+                            B.qc_locate(kv, B.QC_K, l, b, h, pos)
+                    else:
+                        assert B.qc_locate(kv, B.QC_K, l, b, h, pos) == (src, off)
+                    assert B.qc_locate(kv, B.QC_V, l, b, h, pos) == lay.locate_v(l, b, h, pos)
+    st = B.qc_stats(kv, qc)
+    assert st["k_bytes"] == st["v_bytes"] == st["q_bytes"] == st["tokens"] == 0
+    assert st["q_owner"] == -1 and st["batch"] == batch
+    B.qc_kvcache_destroy(kv)
+    B.qc_qcache_destroy(qc)
+
+
+def test_reset_validation():
+    c = CONFIGS[1]
+    cfg, kv, qc = make_handles(c)
+    with pytest.raises(P.QcError) as e:
+        B.qc_reset(kv, qc, 6, [0] * 6, [1] * 6, 0)
+    assert e.value.status == B.QC_ECAPACITY
+    with pytest.raises(P.QcError) as e:
+        B.qc_reset(kv, qc, 1, [0], [31], 0)           # more visual tokens than max_vis
+    assert e.value.status == B.QC_ECAPACITY
+    with pytest.raises(P.QcError) as e:
+        B.qc_reset(kv, qc, 1, [-1], [3], 0)
+    assert e.value.status == B.QC_EINVAL
+    with pytest.raises(P.QcError) as e:
+        B.qc_reset(kv, qc, 0, [], [], 0)
+    assert e.value.status == B.QC_EINVAL
+    other = P.make_config(3, 2, 128, "bf16", 5, 77, 30, 49, [0, 1, 0])
+    qc2 = B.qc_qcache_create(other, FAKE, B.qc_q_arena_bytes(other))
+    with pytest.raises(P.QcError) as e:
+        B.qc_reset(kv, qc2, 1, [0], [3], 0)
+    assert e.value.status == B.QC_EINVAL
+
+
+def test_prefill_and_decode_validation_happens_before_any_launch():
+    c = CONFIGS[1]  # 3 layers, mask [0,1,0], H=2, D=128, bf16, max_batch 5, max_seq 77, max_vis 30, max_text 50
+    cfg, kv, qc = make_handles(c)
+    H, D = 2, 128
+    args = dict(q=FAKE, k=FAKE, v=FAKE, out=FAKE, token_stride=H * D, head_stride=D)
+
+    def prefill(layer, lazy, cu, vs, vl, **kw):
+        a = dict(args)
+        a.update(kw)
+        return B.qc_prefill(kv, qc, layer, lazy, a["q"], a["k"], a["v"], a["out"], cu, a["token_stride"],
+                            a["head_stride"], vs, vl)
+
+    def expect(status, fn, *a, **kw):
+        with pytest.raises(P.QcError) as e:
+            fn(*a, **kw)
+        assert e.value.status == status, (P.status_str(e.value.status), str(e.value))
+
+    expect(B.QC_EORDER, prefill, 0, 0, [0, 40], [4], [20])              # before qc_reset
+    B.qc_reset(kv, qc, 1, [4], [20], 0)
+    expect(B.QC_EORDER, prefill, 1, 1, [0, 40], [4], [20])              # layer 1 first
+    expect(B.QC_EINVAL, prefill, 0, 1, [0, 40], [4], [20])              # flag contradicts mask
+    expect(B.QC_EINVAL, prefill, 3, 0, [0, 40], [4], [20])              # layer out of range
+    expect(B.QC_EINVAL, prefill, 0, 0, [0, 40], [5], [20])              # span differs from reset
+    expect(B.QC_EINVAL, prefill, 0, 0, [1, 40], [4], [20])              # cu_seqlens[0] != 0
+    expect(B.QC_EINVAL, prefill, 0, 0, [0, 20], [4], [20])              # span exceeds the sequence
+    expect(B.QC_ECAPACITY, prefill, 0, 0, [0, 78], [4], [20])           # longer than max_seq
+    expect(B.QC_ECAPACITY, prefill, 0, 0, [0, 71], [4], [20])           # 51 text rows > max_text
+    expect(B.QC_EINVAL, prefill, 0, 0, [0, 40], [4], [20], q=0)         # null tensor
+    expect(B.QC_EINVAL, prefill, 0, 0, [0, 40], [4], [20], k=FAKE + 2)  # misaligned
+    expect(B.QC_EINVAL, prefill, 0, 0, [0, 40], [4], [20], head_stride=64)
+    expect(B.QC_EINVAL, prefill, 0, 0, [0, 40], [4], [20], token_stride=H * D + 1)
+    ws = B.qc_decode_workspace_bytes(cfg)
+    expect(B.QC_EORDER, B.qc_decode, kv, qc, 0, 0, FAKE, FAKE, FAKE, FAKE, [4], [20], 0.0, FAKE, ws)
+    st = B.qc_stats(kv, qc)
+    assert st["next_layer"] == 0 and st["tokens"] == 0 and st["q_owner"] == -1, "failed calls change nothing"
+    assert "prefill has not finished" in B.qc_last_error()
+    assert B.qc_status_str(B.QC_ECAPACITY) == "QC_ECAPACITY"
