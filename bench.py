@@ -1,0 +1,296 @@
+#!/usr/bin/env python3
+"""Benchmark of the Lazy Attention / Q Cache attention stack on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: reset the caches,
+prefill every layer of the stack (ordinary and lazy layers in order), then run the workload's
+decode steps, each of which visits every layer.  Inputs are seeded N(0,1) tensors resident in
+HBM before the timed region starts; every call goes through the C ABI (qc_prefill / qc_decode).
+
+The headline line is measured on the LLaVA-1.5-7B-shaped configuration (batch 1).  Because that
+shape is launch/latency bound on a 256-CU part, the same JSON line also carries, under
+"workloads", the batched-decode configuration (HBM roofline) and the high-resolution prefill
+configuration (MFMA roofline), each timed in this same run.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def prefill_flops_per_layer(w):
+    """4*D flops per attended (query, key) pair: sum_b H * 4*D * L_b(L_b+1)/2."""
+    return sum(w.n_heads * 4 * w.head_dim * L * (L + 1) // 2 for L in w.seq_len)
+
+
+def decode_bytes_per_layer(w, generated):
+    """K and V rows streamed once plus q,k,v in, o out, k,v appended: sum_b (2*(L_b+1)+6)*H*D*e."""
+    return sum((2 * (L + generated + 1) + 6) * w.n_heads * w.head_dim * w.elem_bytes for L in w.seq_len)
+
+
+class Runner:
+    """Holds resident inputs for one workload and drives the library."""
+
+    def __init__(self, w, decode_steps, distinct_decode_inputs=8):
+        import torch
+        import paper_2602_01901_amd as P
+        import workloads
+        self.torch, self.w = torch, w
+        self.decode_steps = decode_steps
+        self.sess = P.Session.for_workload(w)
+        dev = self.sess.device
+        self.pre = [workloads.prefill_qkv(w, l, device=dev) for l in range(w.n_layers)]
+        self.out_pre = torch.empty_like(self.pre[0][0])
+        nd = max(1, min(distinct_decode_inputs, decode_steps))
+        self.dec = [[workloads.decode_qkv(w, l, t, device=dev) for l in range(w.n_layers)] for t in range(nd)]
+        self.out_dec = torch.empty_like(self.dec[0][0][0])
+        torch.cuda.synchronize()
+
+    def prefill_stack(self, per_call_events=None):
+        w, s = self.w, self.sess
+        s.reset(w.vis_start, w.vis_len, zero_fill=False)
+        for l in range(w.n_layers):
+            q, k, v = self.pre[l]
+            if per_call_events is not None:
+                e0, e1 = (self.torch.cuda.Event(enable_timing=True) for _ in range(2))
+                e0.record()
+            s.prefill(l, q, k, v, w.cu_seqlens, out=self.out_pre)
+            if per_call_events is not None:
+                e1.record()
+                per_call_events.append((e0, e1))
+
+    def decode_steps_run(self, steps, per_call_events=None):
+        w, s = self.w, self.sess
+        for t in range(steps):
+            row = self.dec[t % len(self.dec)]
+            for l in range(w.n_layers):
+                q, k, v = row[l]
+                if per_call_events is not None:
+                    e0, e1 = (self.torch.cuda.Event(enable_timing=True) for _ in range(2))
+                    e0.record()
+                s.decode(l, q, k, v, out=self.out_dec)
+                if per_call_events is not None:
+                    e1.record()
+                    per_call_events.append((e0, e1))
+
+    def step(self):
+        self.prefill_stack()
+        self.decode_steps_run(self.decode_steps)
+
+
+def timed(torch, fn, reps):
+    """Wall-clock seconds per repetition, synchronised on both sides, plus HIP-event time."""
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / reps
+    return wall, e0.elapsed_time(e1) * 1e-3 / reps
+
+
+def mean_event_ms(events):
+    return sum(a.elapsed_time(b) for a, b in events) / max(len(events), 1)
+
+
+def bench_cfg2(args):
+    import torch
+    import workloads
+    w = workloads.config(1)
+    r = Runner(w, w.decode_steps)
+    log("cfg2: warmup %d" % args.warmup)
+    for _ in range(args.warmup):
+        r.step()
+    torch.cuda.synchronize()
+    # whole steps
+    wall, _ = timed(torch, r.step, args.steps)
+    # split of the same step into its two phases (extra passes, not part of `value`)
+    pre_wall, pre_ev = timed(torch, r.prefill_stack, max(args.steps, 3))
+    r.prefill_stack()
+    dec_wall, dec_ev = timed(torch, lambda: r.decode_steps_run(w.decode_steps), 1)
+    stats = r.sess.stats()
+    # per-launch durations with HIP events around single calls
+    r.prefill_stack()
+    ev = []
+    r.decode_steps_run(w.decode_steps, per_call_events=ev)
+    torch.cuda.synchronize()
+    call_ms = mean_event_ms(ev)
+    mean_bytes = sum(decode_bytes_per_layer(w, g) for g in range(w.decode_steps)) / w.decode_steps
+    achieved = mean_bytes / (call_ms * 1e-3) / 1e9
+    pf = prefill_flops_per_layer(w) * w.n_layers
+    res = {
+        "ms_per_step": wall * 1e3,
+        "decode_tokens_per_s": w.batch * w.decode_steps / dec_ev,
+        "decode_ms_per_token_step": dec_ev / w.decode_steps * 1e3,
+        "prefill_ms": pre_ev * 1e3,
+        "prefill_tflops": pf / pre_ev / 1e12,
+        "k_cache_bytes_per_token": stats["k_bytes"] / stats["tokens"],
+        "k_cache_bytes_per_token_standard": w.n_layers * w.n_heads * w.head_dim * w.elem_bytes,
+        "roofline": {"bound": "hbm", "kernel": "decode layer call (split + merge)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "avg_launch_us": call_ms * 1e3, "algorithmic_bytes_per_launch": mean_bytes},
+    }
+    del r
+    torch.cuda.empty_cache()
+    return w, res
+
+
+def bench_decode_batched(args):
+    """Batch-32 decode (HBM-bound): caches filled by an untimed prefill, then timed decode steps."""
+    import torch
+    import workloads
+    w = workloads.config(2)
+    steps = args.decode_batched_steps
+    r = Runner(w, steps, distinct_decode_inputs=4)
+    r.prefill_stack()
+    r.decode_steps_run(2)
+    torch.cuda.synchronize()
+    g0 = r.sess.stats()["generated"]
+    _, ev_s = timed(torch, lambda: r.decode_steps_run(steps), 1)
+    ev = []
+    g1 = r.sess.stats()["generated"]
+    r.decode_steps_run(4, per_call_events=ev)
+    torch.cuda.synchronize()
+    call_ms = mean_event_ms(ev)
+    bytes_call = sum(decode_bytes_per_layer(w, g1 + t) for t in range(4)) / 4
+    bytes_step = sum(decode_bytes_per_layer(w, g0 + t) for t in range(steps)) / steps * w.n_layers
+    stats = r.sess.stats()
+    achieved = bytes_call / (call_ms * 1e-3) / 1e9
+    res = {
+        "workload": w.name, "batch": w.batch, "decode_steps_timed": steps,
+        "decode_tokens_per_s": w.batch * steps / ev_s,
+        "decode_ms_per_step": ev_s / steps * 1e3,
+        "stack_GBps": bytes_step / (ev_s / steps) / 1e9,
+        "k_cache_bytes_per_token": stats["k_bytes"] / stats["tokens"],
+        "roofline": {"bound": "hbm", "kernel": "decode layer call (split + merge)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "avg_launch_us": call_ms * 1e3, "algorithmic_bytes_per_launch": bytes_call},
+    }
+    del r
+    torch.cuda.empty_cache()
+    return res
+
+
+def bench_prefill_highres(args):
+    """Batch-8, 3008-token prefill (MFMA-bound)."""
+    import torch
+    import workloads
+    w = workloads.config(3)
+    r = Runner(w, 0)
+    r.prefill_stack()
+    torch.cuda.synchronize()
+    reps = args.prefill_reps
+    _, ev_s = timed(torch, r.prefill_stack, reps)
+    ev = []
+    r.prefill_stack(per_call_events=ev)
+    torch.cuda.synchronize()
+    call_ms = mean_event_ms(ev)
+    flops_layer = prefill_flops_per_layer(w)
+    stats = r.sess.stats()
+    achieved = flops_layer / (call_ms * 1e-3) / 1e12
+    res = {
+        "workload": w.name, "batch": w.batch, "seq_len": w.seq_len[0],
+        "prefill_ms": ev_s * 1e3, "prefill_tflops": flops_layer * w.n_layers / ev_s / 1e12,
+        "k_cache_bytes_per_token": stats["k_bytes"] / stats["tokens"],
+        "roofline": {"bound": "mfma", "kernel": "prefill layer call (cache write + attention)", "achieved": achieved,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": None, "avg_launch_us": call_ms * 1e3, "algorithmic_flops_per_launch": flops_layer},
+    }
+    del r
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(budget_s=20.0):
+    """The fp64 oracle on the host cores, on a bounded sample of the headline workload."""
+    import torch
+    import workloads
+    from stack_runner import new_oracles, oracle_decode_layer, oracle_prefill_layer
+    w = workloads.config(1)
+    stacks = new_oracles(w)
+    inputs = [workloads.prefill_qkv(w, l) for l in range(w.n_layers)]
+    t0 = time.perf_counter()
+    for l in range(w.n_layers):
+        oracle_prefill_layer(w, stacks, l, *inputs[l])
+    t_pre = time.perf_counter() - t0
+    steps = 0
+    t1 = time.perf_counter()
+    while steps < w.decode_steps and (time.perf_counter() - t1) < budget_s:
+        for l in range(w.n_layers):
+            oracle_decode_layer(w, stacks, l, *workloads.decode_qkv(w, l, steps))
+        steps += 1
+    t_dec = time.perf_counter() - t1
+    return {"value": w.batch * steps / t_dec, "unit": "tokens/s", "cores": torch.get_num_threads(),
+            "kind": "oracle",
+            "sample": "%s: full 32-layer prefill (%.2f s, %.4f TFLOP/s fp64) then %d decode steps of 32 layers"
+                      % (w.name, t_pre, prefill_flops_per_layer(w) * w.n_layers / t_pre / 1e12, steps),
+            "prefill_s": t_pre}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--decode-batched-steps", type=int, default=16)
+    ap.add_argument("--prefill-reps", type=int, default=3)
+    ap.add_argument("--skip-extra", action="store_true", help="headline workload only")
+    ap.add_argument("--skip-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (nothing in the attention path needs a collective); "
+                 "use --gpus 1")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the library has no CPU path")
+    import paper_2602_01901_amd as P
+    P.load_library()
+
+    w, r = bench_cfg2(args)
+    log("cfg2 done: %.1f tok/s decode, prefill %.2f TFLOP/s" % (r["decode_tokens_per_s"], r["prefill_tflops"]))
+    extra = {}
+    if not args.skip_extra:
+        extra["decode_batched"] = bench_decode_batched(args)
+        log("cfg3 done: %.1f tok/s, %.0f GB/s" % (extra["decode_batched"]["decode_tokens_per_s"],
+                                                 extra["decode_batched"]["roofline"]["achieved"]))
+        extra["prefill_highres"] = bench_prefill_highres(args)
+        log("cfg4 done: %.1f TFLOP/s" % extra["prefill_highres"]["prefill_tflops"])
+    cpu = None if args.skip_cpu else cpu_baseline()
+    line = {
+        "metric": "decode_tokens_per_s", "value": r["decode_tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "layers": w.n_layers, "heads": w.n_heads, "head_dim": w.head_dim,
+                   "batch": w.batch, "visual_tokens": w.vis_len[0], "text_tokens": w.seq_len[0] - w.vis_len[0],
+                   "decode_steps": w.decode_steps, "lazy_layers": w.n_lazy,
+                   "step": "reset + 32-layer prefill + 256 decode steps x 32 layers"},
+        "prefill_tflops": r["prefill_tflops"], "prefill_ms": r["prefill_ms"],
+        "decode_ms_per_token_step": r["decode_ms_per_token_step"],
+        "k_cache_bytes_per_token": r["k_cache_bytes_per_token"],
+        "k_cache_bytes_per_token_standard": r["k_cache_bytes_per_token_standard"],
+        "roofline": r["roofline"],
+        "cpu_baseline": cpu,
+        "workloads": extra,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -186,7 +186,7 @@ hipError_t launch_prefill(const PrefillArgs& a, int dtype, hipStream_t stream) {
     if (a.head_dim == 128) return launch_prefill_simple_t<float, 128>(a, stream);
   } else {
     if (a.head_dim == 64) return launch_prefill_simple_t<bf16_t, 64>(a, stream);
-    if (a.head_dim == 128) return launch_prefill_simple_t<bf16_t, 128>(a, stream);
+    if (a.head_dim == 128) return launch_prefill_mfma_bf16_d128(a, stream);
   }
   return hipErrorInvalidValue;
 }
