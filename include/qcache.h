@@ -123,7 +123,8 @@ qc_status qc_reset(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* 
 /* ---- prefill: one layer over the packed prompts (paper Eq. 1; Eq. 7 in a lazy layer) -----------
  * q, k, v, out: DEVICE, element (token t, head h, dim d) at t*token_stride + h*head_stride + d
  *   (strides in elements, shared by all four tensors; head_stride >= head_dim, 16-byte aligned
- *   rows).  Sequence b owns tokens cu_seqlens[b] .. cu_seqlens[b+1]-1.
+ *   rows; the rows of one sequence must span less than 2 GiB: len * token_stride * e < 2^31).
+ *   Sequence b owns tokens cu_seqlens[b] .. cu_seqlens[b+1]-1.
  * cu_seqlens: HOST, batch+1 entries, cu_seqlens[0] = 0.  vis_start, vis_len: HOST, must repeat
  *   the values given to qc_reset.  is_lazy must equal the configured flag of `layer`.
  * softmax_scale: 0 selects 1/sqrt(head_dim).

@@ -255,6 +255,8 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
       return fail(QC_EINVAL, "qc_prefill: cu_seqlens changed between layers");
     if (len > max_len) max_len = (int32_t)len;
   }
+  if ((int64_t)max_len * token_stride * e >= ((int64_t)1 << 31))
+    return fail(QC_EINVAL, "qc_prefill: one sequence spans %lld bytes of the input tensors, the limit is 2 GiB", (long long)((int64_t)max_len * token_stride * e));
   if (c.lazy[layer] && qc->owner != c.anchor[layer])
     return fail(QC_EORDER, "qc_prefill: Q Cache belongs to layer %d, layer %d inherits from %d", qc->owner, layer, c.anchor[layer]);
 

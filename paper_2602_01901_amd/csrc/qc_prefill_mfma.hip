@@ -34,25 +34,60 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 
 namespace pf {
 constexpr int BM = 128, BN = 64, D = 128;
-constexpr int KSTRIDE = 272;  // bytes per K row in LDS: 256 + 16, 16-byte reads of 16 rows hit 64 distinct banks
-constexpr int VSTRIDE = 320;  // bytes per V row in LDS: 256 + 64, the 4-row transposing reads hit distinct banks
-constexpr int KTILE = BN * KSTRIDE;
-constexpr int VTILE = BN * VSTRIDE;
-constexpr int LDS_BYTES = 2 * (KTILE + VTILE);
+constexpr int ROWB = D * 2;            // bytes per row
+constexpr int TILE = BN * ROWB;        // one K or V tile in LDS (no padding; XOR-swizzled 16-byte chunks)
+constexpr int LDS_BYTES = 4 * TILE;    // K0 K1 V0 V1
 constexpr float kRescaleThreshold = 8.0f;  // log2 units
 }  // namespace pf
+
+// LDS layout.  A tile row is 16 chunks of 16 bytes.  K rows store logical chunk c at physical
+// chunk c ^ (row & 15): the 16-byte operand reads of 16 consecutive rows then cover all 64 banks.
+// V rows store chunk c at c ^ ((row & 3) << 2): the 4-row transposing reads hit 4 distinct
+// quarter-rows.  Tiles are filled by global_load_lds_dwordx4 (each lane's 16 bytes land at
+// consecutive LDS addresses), so the swizzle is applied on the global side: lane i of an
+// instruction that fills rows r0..r0+3 fetches logical chunk (i % 16) ^ swz(row).
 
 hipError_t launch_cache_write_bf16_d128(const PrefillArgs& a, hipStream_t stream);
 
 __device__ __forceinline__ const char* pf_q_row(const PrefillArgs& a, const SeqMeta& sm, int64_t bh, int h, int pos) {
   if (a.is_lazy && pos >= sm.vis_start && pos < sm.vis_start + sm.vis_len)
-    return a.lv.q_cache + (bh * a.lv.cap_q + (pos - sm.vis_start)) * (pf::D * 2);
+    return a.lv.q_cache + (bh * a.lv.cap_q + (pos - sm.vis_start)) * pf::ROWB;
   return (const char*)a.q + ((int64_t)(sm.tok0 + pos) * a.token_stride + (int64_t)h * a.head_stride) * 2;
 }
 __device__ __forceinline__ const char* pf_k_row(const PrefillArgs& a, const SeqMeta& sm, int64_t bh, int h, int pos) {
   if (a.is_lazy && pos >= sm.vis_start && pos < sm.vis_start + sm.vis_len)
-    return a.lv.k_anchor + (bh * a.lv.cap_k_anchor + pos) * (pf::D * 2);
+    return a.lv.k_anchor + (bh * a.lv.cap_k_anchor + pos) * pf::ROWB;
   return (const char*)a.k + ((int64_t)(sm.tok0 + pos) * a.token_stride + (int64_t)h * a.head_stride) * 2;
+}
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void global_void;
+
+// One global_load_lds_dwordx4: lane i's 16 bytes go to LDS byte offset lds_off + 16*i (lds_off is
+// wave-uniform and travels in M0).  Issued as inline asm so that the compiler does not tie later
+// LDS reads of the OTHER buffer to these loads; the kernel waits for them itself (vmcnt(0)) before
+// the barrier that publishes the tile.
+__device__ __forceinline__ void async_copy16(const char* src, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_off) : "memory", "m0");
+}
+// Same with a wave-uniform 64-bit base in SGPRs and a 32-bit per-lane byte offset.
+__device__ __forceinline__ void async_copy16_sv(const char* sbase, uint32_t voff, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_off) : "memory", "m0");
+}
+// Pin a wave-uniform pointer into scalar registers.
+__device__ __forceinline__ const char* uniform_ptr(const char* p) {
+  const uint64_t v = (uint64_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const char*)(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ uint32_t lds_offset_of(const char* p) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+}
+__device__ __forceinline__ bf16x8 lds_read_tr8(const char* p0, const char* p1) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p0));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p1));
+  const s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v8);
 }
 
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a, int n_qt, int xcd_map) {
@@ -89,14 +124,9 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a, int
   // ---- Q fragments (B operand of S^T = K Q^T): query qi, dims ks*16 + hf*8 .. +8
   bf16x8 qf[8];
   {
-    const bool ok = qi < len;
-    const char* qp = ok ? pf_q_row(a, sm, bh, h, qi) : nullptr;
+    const char* qp = pf_q_row(a, sm, bh, h, min(qi, len - 1));
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      uint4 raw = make_uint4(0, 0, 0, 0);
-      if (ok) raw = *(const uint4*)(qp + (ks * 16 + hf * 8) * 2);
-      qf[ks] = __builtin_bit_cast(bf16x8, raw);
-    }
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + (ks * 16 + hf * 8) * 2));
   }
 
   f32x16 o[4];
@@ -106,61 +136,95 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a, int
     for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
   float m = -INFINITY, lsum = 0.f;
 
-  // ---- tile loader: thread -> (row = tid/16 + 16p, 16-byte chunk = tid%16)
-  const int lrow = tid >> 4, lchunk = tid & 15;
+  // ---- tile loader: wave w fills rows w*16 + p*4 + lane/16, p = 0..3, of the K and V tiles
   const int n_tiles = min((len + BN - 1) / BN, (q0 + BM + BN - 1) / BN);
-  const int64_t v_head_off = (int64_t)h * a.head_stride * 2 + lchunk * 16;
-  uint4 kreg[4], vreg[4];
+  const int lrow = wave * 16 + (lane >> 4), lchunk = lane & 15;
+  const uint32_t lds_base = lds_offset_of(lds);
+  // Fast path (tile fully inside the sequence and taken from one source): a wave-uniform 64-bit
+  // base that already includes the tile offset, plus per-lane 32-bit offsets fixed for the kernel.
+  const uint32_t ts2 = (uint32_t)(a.token_stride * 2);
+  const char* kin_base = uniform_ptr((const char*)a.k + ((int64_t)sm.tok0 * a.token_stride + (int64_t)h * a.head_stride) * 2);
+  const char* vin_base = uniform_ptr((const char*)a.v + ((int64_t)sm.tok0 * a.token_stride + (int64_t)h * a.head_stride) * 2);
+  const char* kanc_base = uniform_ptr(a.is_lazy ? a.lv.k_anchor + bh * a.lv.cap_k_anchor * ROWB : nullptr);
+  uint32_t off_kin[4], off_kanc[4], off_v[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int r = lrow + 4 * p;
+    off_kin[p] = r * ts2 + ((lchunk ^ (r & 15)) * 16);
+    off_kanc[p] = r * ROWB + ((lchunk ^ (r & 15)) * 16);
+    off_v[p] = r * ts2 + ((lchunk ^ ((r & 3) << 2)) * 16);
+  }
+  const int span_lo = a.is_lazy ? sm.vis_start : 0, span_hi = a.is_lazy ? sm.vis_start + sm.vis_len : 0;
   auto load_tile = [&](int t) {
-    const int k0 = t * BN;
+    const uint32_t kb = __builtin_amdgcn_readfirstlane(lds_base + (t & 1) * TILE + wave * 16 * ROWB);
+    const uint32_t vb = kb + 2 * TILE;
+    const int k0 = __builtin_amdgcn_readfirstlane(t * BN);
+    const bool inside = k0 >= span_lo && k0 + BN <= span_hi;
+    const bool outside = k0 + BN <= span_lo || k0 >= span_hi;
+    if (k0 + BN <= len && (inside || outside)) {
+      const char* vsrc = vin_base + (uint64_t)k0 * ts2;
+      if (inside) {
+        const char* ksrc = kanc_base + (uint64_t)k0 * ROWB;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int pos = k0 + lrow + 16 * p;
-      kreg[p] = make_uint4(0, 0, 0, 0);
-      vreg[p] = make_uint4(0, 0, 0, 0);
-      if (pos < len) {
-        kreg[p] = *(const uint4*)(pf_k_row(a, sm, bh, h, pos) + lchunk * 16);
-        vreg[p] = *(const uint4*)((const char*)a.v + (int64_t)(sm.tok0 + pos) * a.token_stride * 2 + v_head_off);
+        for (int p = 0; p < 4; ++p) {
+          async_copy16_sv(ksrc, off_kanc[p], kb + p * 4 * ROWB);
+          async_copy16_sv(vsrc, off_v[p], vb + p * 4 * ROWB);
+        }
+      } else {
+        const char* ksrc = kin_base + (uint64_t)k0 * ts2;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          async_copy16_sv(ksrc, off_kin[p], kb + p * 4 * ROWB);
+          async_copy16_sv(vsrc, off_v[p], vb + p * 4 * ROWB);
+        }
       }
-    }
-  };
-  auto store_tile = [&](int buf) {
-    char* kb = lds + buf * KTILE;
-    char* vb = lds + 2 * KTILE + buf * VTILE;
+    } else {  // ragged last tile or a tile straddling a span boundary: per-row addresses
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int r = lrow + 16 * p;
-      *(uint4*)(kb + r * KSTRIDE + lchunk * 16) = kreg[p];
-      *(uint4*)(vb + r * VSTRIDE + lchunk * 16) = vreg[p];
+      for (int p = 0; p < 4; ++p) {
+        const int r = lrow + 4 * p;
+        const int pos = min(k0 + r, len - 1);  // rows past the end repeat the last row; their scores are masked
+        async_copy16(pf_k_row(a, sm, bh, h, pos) + ((lchunk ^ (r & 15)) * 16), kb + p * 4 * ROWB);
+        async_copy16(vin_base + (int64_t)pos * ts2 + ((lchunk ^ ((r & 3) << 2)) * 16), vb + p * 4 * ROWB);
+      }
     }
   };
 
   load_tile(0);
-  store_tile(0);
+  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the tile has landed in LDS
   __syncthreads();
 
-  // per-lane LDS offsets that do not depend on the tile
-  const int k_rd = l32 * KSTRIDE + hf * 16;                                    // + jb*32*KSTRIDE + ks*32
-  const int v_rd = (hf * 4 + ((lane & 15) >> 2)) * VSTRIDE + (((l32 >> 4) * 16) + 4 * (lane & 3)) * 2;
+  // per-lane LDS read offsets that do not depend on the tile
+  int k_off[8];  // K fragment of k-step ks: row l32 (+32 jb), logical chunk ks*2 + hf
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) k_off[ks] = l32 * ROWB + (((ks * 2 + hf) ^ (l32 & 15)) * 16);
+  const int vq = (lane & 15) >> 2;
+  const int v_base = (hf * 4 + vq) * ROWB + (l32 >> 4) * 32 + (lane & 3) * 8;
+  int v_off[4];  // V fragment of output block db: chunk group db ^ (row & 3)
+#pragma unroll
+  for (int db = 0; db < 4; ++db) v_off[db] = v_base + ((db ^ vq) * 64);
 
   for (int t = 0; t < n_tiles; ++t) {
-    const bool more = t + 1 < n_tiles;
-    if (more) load_tile(t + 1);
+    if (t + 1 < n_tiles) load_tile(t + 1);
     const int k0 = t * BN;
     if (k0 <= wrow0 + 31) {  // wave-uniform: otherwise every key of the tile is above the diagonal
-      const char* kb = lds + (t & 1) * KTILE;
-      const char* vb = lds + 2 * KTILE + (t & 1) * VTILE;
+      const char* kb = lds + (t & 1) * TILE;
+      const char* vb = lds + 2 * TILE + (t & 1) * TILE;
       f32x16 s[2];
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[jb][r] = 0.f;
+      {  // S^T = K Q^T, K fragments prefetched 4 MFMAs ahead
+        bf16x8 kf[4];
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
+        for (int i = 0; i < 4; ++i) kf[i] = *(const bf16x8*)(kb + k_off[i >> 1] + (i & 1) * 32 * ROWB);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
-        for (int jb = 0; jb < 2; ++jb) {
-          const bf16x8 kf = *(const bf16x8*)(kb + k_rd + jb * 32 * KSTRIDE + ks * 32);
-          s[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[jb], 0, 0, 0);
+        for (int i = 0; i < 16; ++i) {
+          s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i & 3], qf[i >> 1], s[i & 1], 0, 0, 0);
+          if (i + 4 < 16) kf[i & 3] = *(const bf16x8*)(kb + k_off[(i + 4) >> 1] + ((i + 4) & 1) * 32 * ROWB);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA ...
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // ... then the LDS read four steps ahead
         }
       }
       // accumulator register r of block jb holds key k0 + jb*32 + (r/4)*8 + hf*4 + r%4 for query qi
@@ -203,19 +267,21 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a, int
         }
       // O^T += V^T P^T: k-step kk covers keys k0 + kk*16 .. +15; lane half hf supplies keys
       // {hf*4 .. +3} and {8 + hf*4 .. +3} of that run, exactly the keys its P registers hold.
+      {
+        bf16x8 vf[4];
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
+        for (int i = 0; i < 4; ++i) vf[i] = lds_read_tr8(vb + v_off[i & 3] + (i >> 2) * 16 * ROWB, vb + v_off[i & 3] + ((i >> 2) * 16 + 8) * ROWB);
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const char* vp = vb + v_rd + kk * 16 * VSTRIDE + db * 64;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp + 8 * VSTRIDE));
-          const s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v8), pb[kk], o[db], 0, 0, 0);
+        for (int i = 0; i < 16; ++i) {
+          o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i & 3], pb[i >> 2], o[i & 3], 0, 0, 0);
+          if (i + 4 < 16) vf[i & 3] = lds_read_tr8(vb + v_off[i & 3] + ((i + 4) >> 2) * 16 * ROWB, vb + v_off[i & 3] + (((i + 4) >> 2) * 16 + 8) * ROWB);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
       }
     }
-    if (more) store_tile((t + 1) & 1);
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): next tile has landed
     __syncthreads();
   }
 
