@@ -176,9 +176,6 @@ template <typename T, int D> hipError_t launch_prefill_simple_t(const PrefillArg
 }
 
 hipError_t launch_prefill_mfma_bf16_d128(const PrefillArgs& a, hipStream_t stream);
-hipError_t launch_cache_write_bf16_d128(const PrefillArgs& a, hipStream_t stream) {
-  return launch_cache_write_t<bf16_t, 128>(a, stream);
-}
 
 hipError_t launch_prefill(const PrefillArgs& a, int dtype, hipStream_t stream) {
   if (dtype == 0) {

@@ -1,0 +1,115 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The whole tensors are too large for the fp64 oracle, so a few (sequence, head) pairs are run
+through oracle instances of their own (heads are independent) and compared on sampled query
+rows; the cache rows of those heads are compared bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_01901_amd as P
+from paper_2602_01901_amd import binding as B
+import workloads
+from oracle.lazy_stack import LazyStackOracle
+from stack_runner import TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_rows(w, b, rng, extra=6):
+    L, s, vn = w.seq_len[b], w.vis_start[b], w.vis_len[b]
+    rows = {0, 1, L - 1, L - 2, max(s - 1, 0), s, min(s + 1, L - 1), s + vn - 1, min(s + vn, L - 1), 63, 64, 127, 128, 255, 256}
+    rows |= set(int(x) for x in rng.integers(0, L, size=extra))
+    return sorted(r for r in rows if 0 <= r < L)
+
+
+def head_slice(t, w, b, h):
+    cu = w.cu_seqlens
+    return workloads.to_f64(t[cu[b]:cu[b + 1], h:h + 1, :])
+
+
+def arena_rows(sess, which, layer, b, h, pos_list):
+    """Cache rows as the library locates them, as raw int16/int32 words."""
+    rowb = sess.head_dim * (2 if sess.dtype == "bf16" else 4)
+    out = []
+    for pos in pos_list:
+        src, off = B.qc_locate(sess.kv, which, layer, b, h, pos)
+        out.append(sess.kv_arena[off:off + rowb].clone())
+    return torch.stack(out).cpu().numpy()
+
+
+def run_sampled(w, n_layers, pairs, decode_steps=0, seed=0):
+    rng = np.random.default_rng(seed)
+    sess = P.Session.for_workload(w)
+    sess.reset(w.vis_start, w.vis_len, zero_fill=False)
+    oracles = {p: LazyStackOracle(w.n_layers, 1, w.head_dim, w.lazy_mask, w.vis_start[p[0]], w.vis_len[p[0]])
+               for p in pairs}
+    rows = {p: sample_rows(w, p[0], rng) for p in pairs}
+    worst = 0.0
+    cu = w.cu_seqlens
+    for l in range(n_layers):
+        q, k, v = workloads.prefill_qkv(w, l, device="cuda")
+        out = sess.prefill(l, q, k, v, w.cu_seqlens)
+        for (b, h) in pairs:
+            ref = oracles[(b, h)].prefill(l, head_slice(q, w, b, h), head_slice(k, w, b, h), head_slice(v, w, b, h),
+                                          rows=rows[(b, h)])
+            got = workloads.to_f64(out[cu[b]:cu[b + 1], h, :][rows[(b, h)]])
+            err = float(np.max(np.abs(got - ref[:, 0, :])))
+            assert np.isfinite(err)
+            worst = max(worst, err)
+            # cache rows: bit-exact copies of the inputs, at the rows the library reports
+            pos = rows[(b, h)]
+            want_v = v[cu[b]:cu[b + 1], h, :][pos].contiguous().view(torch.uint8).cpu().numpy()
+            assert np.array_equal(arena_rows(sess, B.QC_V, l, b, h, pos), want_v)
+            st = oracles[(b, h)]
+            src_rows = [st.k_source(l, p_) for p_ in pos]
+            got_k = arena_rows(sess, B.QC_K, l, b, h, pos)
+            for n, (src, row) in enumerate(src_rows):
+                want = st.Kc[src][0, row].astype(np.float32)
+                gotf = torch.from_numpy(got_k[n].copy()).view(torch.bfloat16 if w.dtype == "bf16" else torch.float32)
+                assert np.array_equal(gotf.float().numpy(), want), (l, b, h, pos[n])
+        del q, k, v, out
+    assert n_layers == w.n_layers or decode_steps == 0
+    for t in range(decode_steps):
+        for l in range(w.n_layers):
+            q, k, v = workloads.decode_qkv(w, l, t, device="cuda")
+            out = sess.decode(l, q, k, v)
+            for (b, h) in pairs:
+                ref = oracles[(b, h)].decode(l, workloads.to_f64(q[b, h:h + 1]), workloads.to_f64(k[b, h:h + 1]),
+                                             workloads.to_f64(v[b, h:h + 1]))
+                err = float(np.max(np.abs(workloads.to_f64(out[b, h]) - ref[0])))
+                assert np.isfinite(err)
+                worst = max(worst, err)
+    torch.cuda.synchronize()
+    return worst, sess
+
+
+def test_cfg4_highres_prefill_sampled():
+    """Batch 8 x 3008 tokens (2880 visual), 32 heads: the 256-row prefill kernel, first 8 layers
+    (two ordinary layers, then two blocks of one ordinary + two lazy layers)."""
+    w = workloads.config(3)
+    worst, sess = run_sampled(w, 8, [(0, 0), (3, 17), (7, 31)])
+    print("cfg4 sampled max abs err %.3g" % worst, flush=True)
+    assert worst <= TOL["bf16"]
+    rk, rv = B.qc_layer_rows(sess.kv, 3)
+    assert rv == 8 * 3008 and rk == 8 * 128   # a lazy layer keeps text keys only
+
+
+def test_cfg3_batched_decode_sampled():
+    """Batch 32 with unequal lengths: full 32-layer prefill then 3 decode steps, sampled heads."""
+    w = workloads.config(2)
+    worst, sess = run_sampled(w, w.n_layers, [(0, 5), (13, 0), (31, 31)], decode_steps=3)
+    print("cfg3 sampled max abs err %.3g" % worst, flush=True)
+    assert worst <= TOL["bf16"]
+    st = sess.stats()
+    want_k = sum((L + 3 - lz * 576) for L in w.seq_len for lz in w.lazy_mask) * 32 * 128 * 2
+    assert st["k_bytes"] == want_k and st["tokens"] == sum(w.seq_len) + 3 * 32
+
+
+def test_cfg5_video_shape_sampled():
+    """13B-shaped video workload: 40 heads, 4864-token prompts; first 5 layers of prefill."""
+    w = workloads.config(4)
+    worst, _ = run_sampled(w, 5, [(0, 39), (3, 7)])
+    print("cfg5 sampled max abs err %.3g" % worst, flush=True)
+    assert worst <= TOL["bf16"]
