@@ -32,6 +32,16 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def measured_traffic(key):
+    """HBM bytes per launch from committed rocprofv3 --pmc runs (profiles/hbm_traffic.json), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(key, {}).get("bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
 def prefill_flops_per_layer(w):
     """4*D flops per attended (query, key) pair: sum_b H * 4*D * L_b(L_b+1)/2."""
     return sum(w.n_heads * 4 * w.head_dim * L * (L + 1) // 2 for L in w.seq_len)
@@ -60,36 +70,41 @@ class Runner:
         self.out_dec = torch.empty_like(self.dec[0][0][0])
         torch.cuda.synchronize()
 
-    def prefill_stack(self, per_call_events=None):
+    def prefill_stack(self):
         w, s = self.w, self.sess
         s.reset(w.vis_start, w.vis_len, zero_fill=False)
         for l in range(w.n_layers):
             q, k, v = self.pre[l]
-            if per_call_events is not None:
-                e0, e1 = (self.torch.cuda.Event(enable_timing=True) for _ in range(2))
-                e0.record()
             s.prefill(l, q, k, v, w.cu_seqlens, out=self.out_pre)
-            if per_call_events is not None:
-                e1.record()
-                per_call_events.append((e0, e1))
 
-    def decode_steps_run(self, steps, per_call_events=None):
+    def decode_steps_run(self, steps):
         w, s = self.w, self.sess
+        stream = self.torch.cuda.current_stream(s.device).cuda_stream
         for t in range(steps):
             row = self.dec[t % len(self.dec)]
             for l in range(w.n_layers):
                 q, k, v = row[l]
-                if per_call_events is not None:
-                    e0, e1 = (self.torch.cuda.Event(enable_timing=True) for _ in range(2))
-                    e0.record()
-                s.decode(l, q, k, v, out=self.out_dec)
-                if per_call_events is not None:
-                    e1.record()
-                    per_call_events.append((e0, e1))
+                s.decode(l, q, k, v, out=self.out_dec, stream=stream)
 
     def step(self):
         self.prefill_stack()
         self.decode_steps_run(self.decode_steps)
+
+    def kernel_times(self, fn):
+        """Run fn with the library's per-kernel HIP-event timing on; returns
+        {"prefill": (avg_us, launches), "decode": (avg_us, launches)} for its dominant kernels."""
+        from paper_2602_01901_amd import binding as B
+        B.qc_timing_enable(self.sess.kv, 1)
+        B.qc_timing_read(self.sess.kv, 0)
+        B.qc_timing_read(self.sess.kv, 1)
+        fn()
+        self.torch.cuda.synchronize()
+        out = {}
+        for name, which in (("prefill", 0), ("decode", 1)):
+            ms, n = B.qc_timing_read(self.sess.kv, which)
+            out[name] = (ms * 1e3 / n if n else 0.0, n)
+        B.qc_timing_enable(self.sess.kv, 0)
+        return out
 
 
 def timed(torch, fn, reps):
@@ -104,10 +119,6 @@ def timed(torch, fn, reps):
     torch.cuda.synchronize()
     wall = (time.perf_counter() - t0) / reps
     return wall, e0.elapsed_time(e1) * 1e-3 / reps
-
-
-def mean_event_ms(events):
-    return sum(a.elapsed_time(b) for a, b in events) / max(len(events), 1)
 
 
 def bench_cfg2(args):
@@ -126,14 +137,19 @@ def bench_cfg2(args):
     r.prefill_stack()
     dec_wall, dec_ev = timed(torch, lambda: r.decode_steps_run(w.decode_steps), 1)
     stats = r.sess.stats()
-    # per-launch durations with HIP events around single calls
-    r.prefill_stack()
-    ev = []
-    r.decode_steps_run(w.decode_steps, per_call_events=ev)
-    torch.cuda.synchronize()
-    call_ms = mean_event_ms(ev)
+    # per-launch duration of the dominant kernels: HIP events recorded by the library on the launch
+    # stream around the kernel itself, over one more whole step
+    stats_prefill = {}
+
+    def one_step():
+        r.prefill_stack()
+        stats_prefill.update(r.sess.stats())
+        r.decode_steps_run(w.decode_steps)
+    kt = r.kernel_times(one_step)
+    dec_us, dec_n = kt["decode"]
+    pre_us, pre_n = kt["prefill"]
     mean_bytes = sum(decode_bytes_per_layer(w, g) for g in range(w.decode_steps)) / w.decode_steps
-    achieved = mean_bytes / (call_ms * 1e-3) / 1e9
+    achieved = mean_bytes / (dec_us * 1e-6) / 1e9
     pf = prefill_flops_per_layer(w) * w.n_layers
     res = {
         "ms_per_step": wall * 1e3,
@@ -143,9 +159,13 @@ def bench_cfg2(args):
         "prefill_tflops": pf / pre_ev / 1e12,
         "k_cache_bytes_per_token": stats["k_bytes"] / stats["tokens"],
         "k_cache_bytes_per_token_standard": w.n_layers * w.n_heads * w.head_dim * w.elem_bytes,
-        "roofline": {"bound": "hbm", "kernel": "decode layer call (split + merge)", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "avg_launch_us": call_ms * 1e3, "algorithmic_bytes_per_launch": mean_bytes},
+        "k_cache_bytes_per_token_after_prefill": stats_prefill["k_bytes"] / stats_prefill["tokens"],
+        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<bf16,128>", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic("decode_cfg2"),
+                     "avg_launch_us": dec_us, "launches_timed": dec_n, "algorithmic_bytes_per_launch": mean_bytes},
+        "prefill_kernel": {"kernel": "prefill_mfma_kernel<4,2>", "avg_launch_us": pre_us, "launches_timed": pre_n,
+                           "tflops": prefill_flops_per_layer(w) / (pre_us * 1e-6) / 1e12 if pre_us else None},
     }
     del r
     torch.cuda.empty_cache()
@@ -164,24 +184,23 @@ def bench_decode_batched(args):
     torch.cuda.synchronize()
     g0 = r.sess.stats()["generated"]
     _, ev_s = timed(torch, lambda: r.decode_steps_run(steps), 1)
-    ev = []
     g1 = r.sess.stats()["generated"]
-    r.decode_steps_run(4, per_call_events=ev)
-    torch.cuda.synchronize()
-    call_ms = mean_event_ms(ev)
+    kt = r.kernel_times(lambda: r.decode_steps_run(4))
+    call_us, call_n = kt["decode"]
     bytes_call = sum(decode_bytes_per_layer(w, g1 + t) for t in range(4)) / 4
     bytes_step = sum(decode_bytes_per_layer(w, g0 + t) for t in range(steps)) / steps * w.n_layers
     stats = r.sess.stats()
-    achieved = bytes_call / (call_ms * 1e-3) / 1e9
+    achieved = bytes_call / (call_us * 1e-6) / 1e9
     res = {
         "workload": w.name, "batch": w.batch, "decode_steps_timed": steps,
         "decode_tokens_per_s": w.batch * steps / ev_s,
         "decode_ms_per_step": ev_s / steps * 1e3,
         "stack_GBps": bytes_step / (ev_s / steps) / 1e9,
         "k_cache_bytes_per_token": stats["k_bytes"] / stats["tokens"],
-        "roofline": {"bound": "hbm", "kernel": "decode layer call (split + merge)", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "avg_launch_us": call_ms * 1e3, "algorithmic_bytes_per_launch": bytes_call},
+        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<bf16,128> (no split at this batch: whole layer call)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic("decode_cfg3"), "avg_launch_us": call_us, "launches_timed": call_n,
+                     "algorithmic_bytes_per_launch": bytes_call},
     }
     del r
     torch.cuda.empty_cache()
@@ -198,20 +217,19 @@ def bench_prefill_highres(args):
     torch.cuda.synchronize()
     reps = args.prefill_reps
     _, ev_s = timed(torch, r.prefill_stack, reps)
-    ev = []
-    r.prefill_stack(per_call_events=ev)
-    torch.cuda.synchronize()
-    call_ms = mean_event_ms(ev)
+    kt = r.kernel_times(r.prefill_stack)
+    call_us, call_n = kt["prefill"]
     flops_layer = prefill_flops_per_layer(w)
     stats = r.sess.stats()
-    achieved = flops_layer / (call_ms * 1e-3) / 1e12
+    achieved = flops_layer / (call_us * 1e-6) / 1e12
     res = {
         "workload": w.name, "batch": w.batch, "seq_len": w.seq_len[0],
         "prefill_ms": ev_s * 1e3, "prefill_tflops": flops_layer * w.n_layers / ev_s / 1e12,
         "k_cache_bytes_per_token": stats["k_bytes"] / stats["tokens"],
-        "roofline": {"bound": "mfma", "kernel": "prefill layer call (cache write + attention)", "achieved": achieved,
-                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": None, "avg_launch_us": call_ms * 1e3, "algorithmic_flops_per_launch": flops_layer},
+        "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel<4,2> (attention + fused cache writes: whole layer call)",
+                     "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic("prefill_cfg4"),
+                     "avg_launch_us": call_us, "launches_timed": call_n, "algorithmic_flops_per_launch": flops_layer},
     }
     del r
     torch.cuda.empty_cache()
@@ -284,8 +302,10 @@ def main():
         "prefill_tflops": r["prefill_tflops"], "prefill_ms": r["prefill_ms"],
         "decode_ms_per_token_step": r["decode_ms_per_token_step"],
         "k_cache_bytes_per_token": r["k_cache_bytes_per_token"],
+        "k_cache_bytes_per_token_after_prefill": r["k_cache_bytes_per_token_after_prefill"],
         "k_cache_bytes_per_token_standard": r["k_cache_bytes_per_token_standard"],
         "roofline": r["roofline"],
+        "prefill_kernel": r["prefill_kernel"],
         "cpu_baseline": cpu,
         "workloads": extra,
     }

@@ -163,6 +163,16 @@ qc_status qc_seq_len(const qc_kvcache* kv, int32_t b, int32_t* len);
 qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t b, int32_t h,
                     int32_t pos, int32_t* src_layer, int64_t* byte_offset);
 
+/* ---- optional instrumentation ------------------------------------------------------------------
+ * While enabled, qc_prefill and qc_decode record a pair of HIP events on the call's stream around
+ * their dominant kernel (prefill: the attention kernel; decode: the kernel that streams the caches,
+ * not the small merge pass).  qc_timing_read waits for the recorded events of one kind (which = 0
+ * prefill, 1 decode), returns the sum of their durations and the number of launches, and starts
+ * over.  At most 16384 launches are kept between reads; further ones are not timed.  Event
+ * creation allocates: leave this off on paths that must not. */
+qc_status qc_timing_enable(qc_kvcache* kv, int32_t enable);
+qc_status qc_timing_read(qc_kvcache* kv, int32_t which, double* total_ms, int64_t* launches);
+
 const char* qc_status_str(qc_status s);
 const char* qc_last_error(void);
 

@@ -53,6 +53,8 @@ _PROTOTYPES = {
     "qc_seq_len": (c_int32, [c_void_p, c_int32, POINTER(c_int32)]),
     "qc_locate": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, POINTER(c_int32),
                             POINTER(c_int64)]),
+    "qc_timing_enable": (c_int32, [c_void_p, c_int32]),
+    "qc_timing_read": (c_int32, [c_void_p, c_int32, POINTER(ctypes.c_double), POINTER(c_int64)]),
     "qc_status_str": (c_char_p, [c_int32]),
     "qc_last_error": (c_char_p, []),
 }
@@ -189,3 +191,14 @@ def qc_locate(kv, which, layer, b, h, pos):
     src, off = c_int32(), c_int64()
     _check(load_library().qc_locate(kv, which, layer, b, h, pos, byref(src), byref(off)))
     return src.value, off.value
+
+
+def qc_timing_enable(kv, enable):
+    return _check(load_library().qc_timing_enable(kv, int(enable)))
+
+
+def qc_timing_read(kv, which):
+    """(total milliseconds, launches) of the dominant kernel since the last read; which: 0 prefill, 1 decode."""
+    ms, n = ctypes.c_double(), c_int64()
+    _check(load_library().qc_timing_read(kv, which, byref(ms), byref(n)))
+    return ms.value, n.value

@@ -92,6 +92,8 @@ struct qc_kvcache {
   int32_t next_layer = 0;
   int32_t generated = 0;
   std::vector<int32_t> vis_start, vis_len, len0, tok0;
+  bool timing = false;
+  qc::KernelTimer prefill_timer, decode_timer;
 };
 
 struct qc_qcache {
@@ -288,7 +290,7 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
   a.write_q = (!c.lazy[layer] && layer + 1 < c.N && c.lazy[layer + 1]) ? 1 : 0;
   a.max_len = max_len;
   a.scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)c.D);
-  hipError_t err = qc::launch_prefill(a, c.dtype, st);
+  hipError_t err = qc::launch_prefill(a, c.dtype, st, kv->timing ? &kv->prefill_timer : nullptr);
   if (err != hipSuccess) return fail(QC_EDEVICE, "qc_prefill: %s", hipGetErrorString(err));
 
   if (layer == 0)
@@ -323,17 +325,20 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   if (layer != kv->next_layer) return fail(QC_EORDER, "qc_decode: expected layer %d, got %d", kv->next_layer, layer);
   if (qc_status s = check_spans("qc_decode", kv, vis_start, vis_len)) return s;
   int32_t max_len = 0;
-  int64_t total = 0;
   for (int b = 0; b < kv->batch; ++b) {
     int64_t len = (int64_t)kv->len0[b] + kv->generated;
     if (len + 1 > c.max_seq) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld positions, max_seq %d", b, (long long)(len + 1), c.max_seq);
     if (len + 1 - kv->vis_len[b] > c.max_text) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld text rows, max_text %d", b, (long long)(len + 1 - kv->vis_len[b]), c.max_text);
     if (len > max_len) max_len = (int32_t)len;
-    total += len + 1;
   }
-  // Split the key axis so that roughly kTargetGroups workgroups are in flight.
-  constexpr int64_t kTargetGroups = 2048;
-  int64_t per = (total * c.H + kTargetGroups - 1) / kTargetGroups;
+  // Split the key axis only as far as needed to give every CU a few workgroups: each extra chunk
+  // costs a partial result and the merge pass.  With many (sequence, head) pairs there is no split
+  // and the kernel writes the output directly.
+  constexpr int64_t kTargetGroups = 1024;
+  const int64_t pairs = (int64_t)kv->batch * c.H;
+  int64_t want = (kTargetGroups + pairs - 1) / pairs;
+  if (want < 1) want = 1;
+  int64_t per = (max_len + 1 + want - 1) / want;
   int32_t chunk = (int32_t)round_up(per < kMinChunkKeys ? kMinChunkKeys : per, kMinChunkKeys);
   int32_t max_chunks = (max_len + 1 + chunk - 1) / chunk;
   size_t need = (size_t)kv->batch * c.H * max_chunks * (c.D + 2) * 4;
@@ -350,7 +355,7 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   a.chunk_keys = chunk;
   a.max_chunks = max_chunks;
   a.scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)c.D);
-  hipError_t err = qc::launch_decode(a, c.dtype, (hipStream_t)stream);
+  hipError_t err = qc::launch_decode(a, c.dtype, (hipStream_t)stream, kv->timing ? &kv->decode_timer : nullptr);
   if (err != hipSuccess) return fail(QC_EDEVICE, "qc_decode: %s", hipGetErrorString(err));
 
   kv->next_layer = layer + 1;
@@ -398,6 +403,20 @@ qc_status qc_stats(const qc_kvcache* kv, const qc_qcache* qc, qc_stats_t* out) {
   out->q_owner = qc ? qc->owner : -1;
   out->generated = kv->generated;
   out->next_layer = kv->next_layer;
+  return QC_OK;
+}
+
+qc_status qc_timing_enable(qc_kvcache* kv, int32_t enable) {
+  if (!kv) return fail(QC_EINVAL, "qc_timing_enable: null handle");
+  kv->timing = enable != 0;
+  return QC_OK;
+}
+
+qc_status qc_timing_read(qc_kvcache* kv, int32_t which, double* total_ms, int64_t* launches) {
+  if (!kv || !total_ms || !launches) return fail(QC_EINVAL, "qc_timing_read: null argument");
+  if (which != 0 && which != 1) return fail(QC_EINVAL, "qc_timing_read: which must be 0 (prefill) or 1 (decode)");
+  hipError_t e = (which == 0 ? kv->prefill_timer : kv->decode_timer).read(total_ms, launches);
+  if (e != hipSuccess) return fail(QC_EDEVICE, "qc_timing_read: %s", hipGetErrorString(e));
   return QC_OK;
 }
 

@@ -15,6 +15,14 @@
 
 namespace qc {
 
+// Cache rows are read once per step: load them with the non-temporal hint (measurably faster HBM
+// streaming than ordinary loads on this part).
+__device__ __forceinline__ uint4 stream_load16(const char* p) {
+  typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+  const u32x4 t = __builtin_nontemporal_load((const u32x4*)p);
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
   constexpr int EPL = ElemTraits<T>::kPer16;  // elements per lane (16 bytes)
@@ -75,8 +83,8 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
           const char* kp;
           if (lazy && pos >= s) kp = pos < e ? kanc + (int64_t)pos * ROWB : kown + (int64_t)(pos - sm.vis_len) * ROWB;
           else kp = kown + (int64_t)pos * ROWB;
-          kr[u] = *(const uint4*)kp;
-          vr[u] = *(const uint4*)(vown + (int64_t)pos * ROWB);
+          kr[u] = stream_load16(kp);
+          vr[u] = stream_load16(vown + (int64_t)pos * ROWB);
         }
       }
     }
@@ -144,7 +152,8 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
   }
 }
 
-// Merge the chunk partials of one (sequence, head) in chunk order.
+// Merge the chunk partials of one (sequence, head) in chunk order.  Loads are issued in batches of
+// eight chunks so that their latencies overlap; the arithmetic order is fixed (bitwise reproducible).
 template <typename T, int D>
 __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
   const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
@@ -152,33 +161,54 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
   const int n = (len + a.chunk_keys) / a.chunk_keys;  // ceil((len + 1) / chunk_keys)
   const int64_t bh = (int64_t)b * a.n_heads + h;
   const float* w = a.workspace + bh * a.max_chunks * (D + 2);
+  constexpr int G = 8;
   float M = -INFINITY;
-  for (int c = 0; c < n; ++c) M = fmaxf(M, w[c * (D + 2) + D]);
+  for (int c0 = 0; c0 < n; c0 += G) {
+    float mv[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) mv[g] = (c0 + g < n) ? w[(c0 + g) * (D + 2) + D] : -INFINITY;
+#pragma unroll
+    for (int g = 0; g < G; ++g) M = fmaxf(M, mv[g]);
+  }
   float o = 0.f, l = 0.f;
-  for (int c = 0; c < n; ++c) {
-    const float f = __builtin_amdgcn_exp2f(w[c * (D + 2) + D] - M);
-    o = fmaf(f, w[c * (D + 2) + d], o);
-    l = fmaf(f, w[c * (D + 2) + D + 1], l);
+  for (int c0 = 0; c0 < n; c0 += G) {
+    float mv[G], lv[G], ov[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const bool ok = c0 + g < n;
+      const float* p = w + (ok ? c0 + g : 0) * (D + 2);
+      mv[g] = ok ? p[D] : -INFINITY;
+      lv[g] = p[D + 1];
+      ov[g] = p[d];
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float f = __builtin_amdgcn_exp2f(mv[g] - M);  // 0 for slots past the last chunk
+      o = fmaf(f, ov[g], o);
+      l = fmaf(f, lv[g], l);
+    }
   }
   store_elem((T*)a.out + bh * D + d, o / l);
 }
 
-template <typename T, int D> static hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t stream) {
+template <typename T, int D> static hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t stream, KernelTimer* timer) {
   dim3 grid(a.max_chunks, a.n_heads, a.batch);
+  if (timer) timer->begin(stream);
   hipLaunchKernelGGL((decode_split_kernel<T, D>), grid, dim3(256), 0, stream, a);
+  if (timer) timer->end(stream);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.max_chunks == 1) return e;
   hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(a.n_heads, a.batch), dim3(D), 0, stream, a);
   return hipGetLastError();
 }
 
-hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t stream) {
+hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t stream, KernelTimer* timer) {
   if (dtype == 0) {
-    if (a.head_dim == 64) return launch_decode_t<float, 64>(a, stream);
-    if (a.head_dim == 128) return launch_decode_t<float, 128>(a, stream);
+    if (a.head_dim == 64) return launch_decode_t<float, 64>(a, stream, timer);
+    if (a.head_dim == 128) return launch_decode_t<float, 128>(a, stream, timer);
   } else {
-    if (a.head_dim == 64) return launch_decode_t<bf16_t, 64>(a, stream);
-    if (a.head_dim == 128) return launch_decode_t<bf16_t, 128>(a, stream);
+    if (a.head_dim == 64) return launch_decode_t<bf16_t, 64>(a, stream, timer);
+    if (a.head_dim == 128) return launch_decode_t<bf16_t, 128>(a, stream, timer);
   }
   return hipErrorInvalidValue;
 }

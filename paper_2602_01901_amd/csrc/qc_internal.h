@@ -3,6 +3,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <utility>
+#include <vector>
+
 namespace qc {
 
 // Per-sequence metadata rows in the arena's meta region: meta[row * max_batch + b].
@@ -59,10 +62,54 @@ struct MetaChunk {        // by-value payload of the metadata upload kernel
   int32_t v[META_ROWS][N];
 };
 
+// Optional instrumentation: HIP events recorded on the call's stream around the dominant kernel
+// of a layer call (prefill: the attention kernel; decode: the streaming kernel, not the merge).
+struct KernelTimer {
+  static constexpr size_t kMaxPairs = 16384;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
+  size_t used = 0;
+  int64_t dropped = 0;
+  bool open = false;
+  void begin(hipStream_t s) {
+    open = false;
+    if (used == pool.size()) {
+      if (pool.size() >= kMaxPairs) { ++dropped; return; }
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess) { ++dropped; return; }
+      if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); ++dropped; return; }
+      pool.emplace_back(a, b);
+    }
+    open = hipEventRecord(pool[used].first, s) == hipSuccess;
+  }
+  void end(hipStream_t s) {
+    if (open && hipEventRecord(pool[used].second, s) == hipSuccess) ++used;
+    open = false;
+  }
+  // Waits for the recorded events, sums their durations and starts over.
+  hipError_t read(double* total_ms, int64_t* launches) {
+    *total_ms = 0.0;
+    *launches = 0;
+    for (size_t i = 0; i < used; ++i) {
+      hipError_t e = hipEventSynchronize(pool[i].second);
+      float ms = 0.f;
+      if (e == hipSuccess) e = hipEventElapsedTime(&ms, pool[i].first, pool[i].second);
+      if (e != hipSuccess) { used = 0; return e; }
+      *total_ms += ms;
+      ++*launches;
+    }
+    used = 0;
+    dropped = 0;
+    return hipSuccess;
+  }
+  ~KernelTimer() {
+    for (auto& p : pool) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
+  }
+};
+
 hipError_t launch_fill_zero(void* dev, size_t bytes, hipStream_t stream);
 hipError_t launch_meta_upload(int32_t* meta_dev, int32_t max_batch, int32_t first, int32_t count,
                               const MetaChunk& chunk, hipStream_t stream);
-hipError_t launch_prefill(const PrefillArgs& a, int dtype, hipStream_t stream);
-hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t stream);
+hipError_t launch_prefill(const PrefillArgs& a, int dtype, hipStream_t stream, KernelTimer* timer);
+hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t stream, KernelTimer* timer);
 
 }  // namespace qc

@@ -517,7 +517,7 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillArgs a,
   }
 }
 
-template <int NW, int STAGES, bool PIPE> static hipError_t launch_variant(const PrefillArgs& a, hipStream_t stream) {
+template <int NW, int STAGES, bool PIPE> static hipError_t launch_variant(const PrefillArgs& a, hipStream_t stream, KernelTimer* timer) {
   static bool attr_set = false;
   constexpr int lds_bytes = STAGES * pf::STAGE + (PIPE ? 1024 : 0);  // + scratch kilobyte for idle load slots
   if (!attr_set) {
@@ -527,17 +527,19 @@ template <int NW, int STAGES, bool PIPE> static hipError_t launch_variant(const 
   }
   const int n_qt = (a.max_len + NW * 32 - 1) / (NW * 32);
   const int nbh = a.batch * a.n_heads;
+  if (timer) timer->begin(stream);
   hipLaunchKernelGGL((prefill_mfma_kernel<NW, STAGES, PIPE>), dim3(n_qt * nbh), dim3(NW * 64), lds_bytes, stream, a, n_qt, (nbh % 8 == 0) ? 1 : 0);
+  if (timer) timer->end(stream);
   return hipGetLastError();
 }
 
-hipError_t launch_prefill_mfma_bf16_d128(const PrefillArgs& a, hipStream_t stream) {
+hipError_t launch_prefill_mfma_bf16_d128(const PrefillArgs& a, hipStream_t stream, KernelTimer* timer) {
   // 128-row workgroups, two per CU, measure fastest at every benchmark shape; the 256-row
   // software-pipelined variant (launch_variant<8, 4, true>) is kept for shapes where K/V traffic
   // from L2 dominates (very long prompts with few heads in flight per XCD).
   const int64_t wg256 = (int64_t)((a.max_len + 255) / 256) * a.batch * a.n_heads;
-  if (a.max_len >= 32768 && wg256 >= 1024) return launch_variant<8, 4, true>(a, stream);
-  return launch_variant<4, 2, false>(a, stream);
+  if (a.max_len >= 32768 && wg256 >= 1024) return launch_variant<8, 4, true>(a, stream, timer);
+  return launch_variant<4, 2, false>(a, stream, timer);
 }
 
 }  // namespace qc

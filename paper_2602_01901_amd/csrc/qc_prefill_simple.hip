@@ -167,23 +167,25 @@ template <typename T, int D> hipError_t launch_cache_write_t(const PrefillArgs& 
   return hipGetLastError();
 }
 
-template <typename T, int D> hipError_t launch_prefill_simple_t(const PrefillArgs& a, hipStream_t stream) {
+template <typename T, int D> hipError_t launch_prefill_simple_t(const PrefillArgs& a, hipStream_t stream, KernelTimer* timer) {
   hipError_t e = launch_cache_write_t<T, D>(a, stream);
   if (e != hipSuccess) return e;
   dim3 grid((a.max_len + 15) / 16, a.n_heads, a.batch);
+  if (timer) timer->begin(stream);
   hipLaunchKernelGGL((prefill_simple_kernel<T, D>), grid, dim3(256), 0, stream, a);
+  if (timer) timer->end(stream);
   return hipGetLastError();
 }
 
-hipError_t launch_prefill_mfma_bf16_d128(const PrefillArgs& a, hipStream_t stream);
+hipError_t launch_prefill_mfma_bf16_d128(const PrefillArgs& a, hipStream_t stream, KernelTimer* timer);
 
-hipError_t launch_prefill(const PrefillArgs& a, int dtype, hipStream_t stream) {
+hipError_t launch_prefill(const PrefillArgs& a, int dtype, hipStream_t stream, KernelTimer* timer) {
   if (dtype == 0) {
-    if (a.head_dim == 64) return launch_prefill_simple_t<float, 64>(a, stream);
-    if (a.head_dim == 128) return launch_prefill_simple_t<float, 128>(a, stream);
+    if (a.head_dim == 64) return launch_prefill_simple_t<float, 64>(a, stream, timer);
+    if (a.head_dim == 128) return launch_prefill_simple_t<float, 128>(a, stream, timer);
   } else {
-    if (a.head_dim == 64) return launch_prefill_simple_t<bf16_t, 64>(a, stream);
-    if (a.head_dim == 128) return launch_prefill_mfma_bf16_d128(a, stream);
+    if (a.head_dim == 64) return launch_prefill_simple_t<bf16_t, 64>(a, stream, timer);
+    if (a.head_dim == 128) return launch_prefill_mfma_bf16_d128(a, stream, timer);
   }
   return hipErrorInvalidValue;
 }

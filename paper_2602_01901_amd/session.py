@@ -35,6 +35,8 @@ class Session:
         self.qc = B.qc_qcache_create(self.cfg, self.q_arena, self.q_bytes)
         self.vis_start = self.vis_len = None
         self.batch = 0
+        self._lib = B.load_library()
+        self._ws_ptr = self.workspace.data_ptr()
 
     @classmethod
     def for_workload(cls, w, device="cuda:0"):
@@ -47,6 +49,8 @@ class Session:
     def reset(self, vis_start, vis_len, zero_fill=True):
         self.vis_start, self.vis_len = list(vis_start), list(vis_len)
         self.batch = len(self.vis_start)
+        # marshalled once per batch: the span arrays every later call repeats
+        self._vs_c, self._vl_c = B._i32(self.vis_start), B._i32(self.vis_len)
         B.qc_reset(self.kv, self.qc, self.batch, self.vis_start, self.vis_len, int(zero_fill), self._stream())
 
     def prefill(self, layer, q, k, v, cu_seqlens, out=None, softmax_scale=0.0):
@@ -58,13 +62,17 @@ class Session:
                      q.stride(1), self.vis_start, self.vis_len, softmax_scale, self._stream())
         return out
 
-    def decode(self, layer, q, k, v, out=None, softmax_scale=0.0):
-        """q, k, v: contiguous [B, H, D] tensors.  Returns out."""
+    def decode(self, layer, q, k, v, out=None, softmax_scale=0.0, stream=None):
+        """q, k, v: contiguous [B, H, D] tensors.  Returns out.  `stream` (a raw hipStream_t value)
+        defaults to torch's current stream; tight loops may pass it to skip the lookup."""
         if out is None:
             out = torch.empty_like(q)
         assert q.is_contiguous() and k.is_contiguous() and v.is_contiguous() and out.is_contiguous()
-        B.qc_decode(self.kv, self.qc, layer, self.lazy_mask[layer], q, k, v, out, self.vis_start, self.vis_len,
-                    softmax_scale, self.workspace, self.ws_bytes, self._stream())
+        status = self._lib.qc_decode(self.kv, self.qc, layer, self.lazy_mask[layer], q.data_ptr(), k.data_ptr(),
+                                     v.data_ptr(), out.data_ptr(), self._vs_c, self._vl_c, softmax_scale,
+                                     self._ws_ptr, self.ws_bytes, self._stream() if stream is None else stream)
+        if status != B.QC_OK:
+            raise B.QcError(status, B.qc_last_error())
         return out
 
     def stats(self):

@@ -113,3 +113,13 @@ def test_cfg5_video_shape_sampled():
     worst, _ = run_sampled(w, 5, [(0, 39), (3, 7)])
     print("cfg5 sampled max abs err %.3g" % worst, flush=True)
     assert worst <= TOL["bf16"]
+
+
+def test_long_prompt_uses_pipelined_256_row_kernel():
+    """One 32768-token prompt (32000 visual), 8 heads: long enough for the 256-row, software-pipelined
+    prefill variant; an ordinary layer then a lazy one, sampled rows."""
+    w = workloads.custom("long", 2, 8, 128, "bf16", [256], [32000], [32768], 0, [0, 1])
+    worst, sess = run_sampled(w, 2, [(0, 0), (0, 7)])
+    print("long prompt sampled max abs err %.3g" % worst, flush=True)
+    assert worst <= TOL["bf16"]
+    assert B.qc_layer_rows(sess.kv, 1) == (768, 32768)
