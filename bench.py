@@ -271,6 +271,10 @@ def main():
     ap.add_argument("--prefill-reps", type=int, default=3)
     ap.add_argument("--skip-extra", action="store_true", help="headline workload only")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--only", choices=["decode_batched", "prefill_highres"],
+                    help="profiling aid: run just this extra workload and print its object")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="profiling aid: run plain 1 GiB device copies (known HBM traffic) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (nothing in the attention path needs a collective); "
@@ -280,6 +284,21 @@ def main():
         sys.exit("bench.py: no GPU visible; the library has no CPU path")
     import paper_2602_01901_amd as P
     P.load_library()
+
+    if args.copy_calibration:
+        # 1 GiB read + 1 GiB written per launch: the yardstick for the FETCH_SIZE / WRITE_SIZE counters
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read_per_launch": 1 << 30, "bytes_written_per_launch": 1 << 30,
+                                               "launches": 5}}))
+        return
+    if args.only:
+        fn = {"decode_batched": bench_decode_batched, "prefill_highres": bench_prefill_highres}[args.only]
+        print(json.dumps({args.only: fn(args)}))
+        return
 
     w, r = bench_cfg2(args)
     log("cfg2 done: %.1f tok/s decode, prefill %.2f TFLOP/s" % (r["decode_tokens_per_s"], r["prefill_tflops"]))
