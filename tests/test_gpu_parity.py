@@ -106,3 +106,77 @@ def test_capacity_and_order_errors_on_device_handles():
         s.decode(0, dq, dk, dv)          # would be position 22 > max_seq
     assert e.value.status == P.binding.QC_ECAPACITY
     assert s.stats()["tokens"] == 21
+
+
+def test_more_than_64_sequences():
+    """Per-sequence metadata is uploaded 64 sequences per launch: 70 short sequences of mixed shape."""
+    B = 70
+    lens = [20 + (7 * b) % 50 for b in range(B)]
+    vlen = [min(lens[b] - 3, (5 * b) % 30) for b in range(B)]
+    vstart = [min(2, lens[b] - vlen[b]) for b in range(B)]
+    w = workloads.custom("b70", 3, 2, 64, "f32", vstart, vlen, lens, 2, [0, 1, 1])
+    ep, ed = run_full_parity(w, 2, session_for(w))
+    assert ep <= TOL["f32"] and ed <= TOL["f32"]
+
+
+def test_decode_many_chunks_merge():
+    """Batch 1, 2 heads, 2100-token context: 33 split chunks, so the merge pass loops over several
+    batches of partials; the lazy layer's three key segments each span many chunks."""
+    w = workloads.custom("chunks", 3, 2, 128, "bf16", [300], [1500], [2100], 3, [0, 1, 0])
+    ep, ed = run_full_parity(w, 3, session_for(w))
+    print("many chunks: decode %.3g" % ed, flush=True)
+    assert ep <= TOL["bf16"] and ed <= TOL["bf16"]
+
+
+def test_strided_inputs_and_custom_scale():
+    """Q/K/V as slices of one fused [tokens, 3, H, D'] projection output (token and head strides
+    larger than the packed ones) and a caller-supplied softmax scale."""
+    import numpy as np
+    from stack_runner import new_oracles, max_abs_err
+    w = workloads.custom("strided", 2, 4, 128, "bf16", [10, 0], [120, 64], [300, 130], 1, [0, 1])
+    s = session_for(w)
+    s.reset(w.vis_start, w.vis_len)
+    scale = 0.05
+    stacks = new_oracles(w)
+    for st in stacks:
+        st.scale = scale
+    cu = w.cu_seqlens
+    for l in range(w.n_layers):
+        q, k, v = workloads.prefill_qkv(w, l)
+        fused = torch.zeros(w.total_tokens, 3, w.n_heads, 160, dtype=torch.bfloat16, device="cuda")
+        fused[:, 0, :, :128], fused[:, 1, :, :128], fused[:, 2, :, :128] = q.cuda(), k.cuda(), v.cuda()
+        outbuf = torch.zeros_like(fused)
+        qs, ks, vs, os_ = fused[:, 0, :, :128], fused[:, 1, :, :128], fused[:, 2, :, :128], outbuf[:, 0, :, :128]
+        assert qs.stride() == (3 * w.n_heads * 160, 160, 1)
+        s.prefill(l, qs, ks, vs, w.cu_seqlens, out=os_, softmax_scale=scale)
+        q64, k64, v64 = (workloads.to_f64(t) for t in (q, k, v))
+        for b in range(w.batch):
+            ref = stacks[b].prefill(l, q64[cu[b]:cu[b + 1]], k64[cu[b]:cu[b + 1]], v64[cu[b]:cu[b + 1]])
+            assert max_abs_err(os_[cu[b]:cu[b + 1]], ref) <= TOL["bf16"]
+        assert float(outbuf[:, 1:].abs().max()) == 0.0 and float(outbuf[:, 0, :, 128:].abs().max()) == 0.0
+    for l in range(w.n_layers):
+        q, k, v = workloads.decode_qkv(w, l, 0)
+        out = s.decode(l, q.cuda(), k.cuda(), v.cuda(), softmax_scale=scale)
+        q64, k64, v64 = (workloads.to_f64(t) for t in (q, k, v))
+        ref = np.stack([stacks[b].decode(l, q64[b], k64[b], v64[b]) for b in range(w.batch)])
+        assert max_abs_err(out, ref) <= TOL["bf16"]
+
+
+def test_kernel_timing_counts_launches():
+    w = workloads.custom("timing", 2, 2, 128, "bf16", [4], [100], [200], 2, [0, 1])
+    s = session_for(w)
+    B = P.binding
+    B.qc_timing_enable(s.kv, 1)
+    s.reset(w.vis_start, w.vis_len)
+    for l in range(2):
+        q, k, v = (t.cuda() for t in workloads.prefill_qkv(w, l))
+        s.prefill(l, q, k, v, w.cu_seqlens)
+    for t in range(2):
+        for l in range(2):
+            q, k, v = (x.cuda() for x in workloads.decode_qkv(w, l, t))
+            s.decode(l, q, k, v)
+    ms_p, n_p = B.qc_timing_read(s.kv, 0)
+    ms_d, n_d = B.qc_timing_read(s.kv, 1)
+    assert (n_p, n_d) == (2, 4) and ms_p > 0 and ms_d > 0
+    assert B.qc_timing_read(s.kv, 1) == (0.0, 0)
+    B.qc_timing_enable(s.kv, 0)

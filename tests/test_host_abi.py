@@ -172,3 +172,14 @@ def test_prefill_and_decode_validation_happens_before_any_launch():
     assert st["next_layer"] == 0 and st["tokens"] == 0 and st["q_owner"] == -1, "failed calls change nothing"
     assert "prefill has not finished" in B.qc_last_error()
     assert B.qc_status_str(B.QC_ECAPACITY) == "QC_ECAPACITY"
+
+
+def test_timing_api_validation():
+    cfg, kv, qc = make_handles(CONFIGS[0])
+    assert B.qc_timing_enable(kv, 0) == B.QC_OK
+    with pytest.raises(P.QcError) as e:
+        B.qc_timing_read(kv, 2)
+    assert e.value.status == B.QC_EINVAL
+    assert B.qc_timing_read(kv, 0) == (0.0, 0)      # nothing recorded, no HIP call needed
+    with pytest.raises(P.QcError):
+        B.qc_timing_enable(None, 1)
