@@ -1,14 +1,11 @@
 // Prefill attention on the matrix cores: bf16 inputs, head_dim 128 (paper Eq. 1; Eq. 7 in a lazy
 // layer).  Flash-style: the score matrix is never materialised; softmax runs online in fp32.
 //
-// Work split.  One workgroup of NW waves takes BM = 32*NW consecutive query rows of one (sequence,
-// head); each wave owns 32 of them for the whole kernel.  Keys/values are visited in tiles of
-// BN = 64 rows that travel through a ring of STAGES LDS buffers: the global->LDS loads of tile
-// t + STAGES - 1 are issued while tile t is multiplied, so a tile has several tile-times to arrive
-// (all query tiles of a head walk the key tiles in step, so most tile loads see DRAM latency even
-// when they hit in L2).  NW = 8 (256 rows, one workgroup per CU, 4 stages) halves the K/V traffic
-// per flop and is used for long prompts; NW = 4 (128 rows, two workgroups per CU, 2 stages) gives
-// more workgroups for short ones.
+// Work split.  One workgroup of 4 waves takes BM = 128 consecutive query rows of one (sequence,
+// head); each wave owns 32 of them for the whole kernel; two workgroups share a CU (their phases
+// drift apart, so one's matrix work meets the other's vector work).  Keys/values are visited in
+// tiles of BN = 64 rows, double buffered in LDS: the global->LDS loads of tile t+1 are in flight
+// while tile t is multiplied.
 //
 // Operand layout.  Scores are produced transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16:
 // the A operand is a K fragment read from LDS with one 16-byte read per lane, the B operand is a
@@ -40,6 +37,10 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
 namespace pf {
+constexpr int NW = 4;                  // waves per workgroup
+constexpr int BM = NW * 32;            // query rows per workgroup
+constexpr int STAGES = 2;              // LDS buffers per tile ring
+constexpr int LPT = 16 / NW;           // load instructions per wave per tile and matrix (4 rows each)
 constexpr int BN = 64, D = 128;
 constexpr int ROWB = D * 2;            // bytes per row
 constexpr int TILE = BN * ROWB;        // one K or V tile in LDS (no padding; XOR-swizzled 16-byte chunks)
@@ -99,12 +100,8 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {  // at most N ve
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <int NW, int STAGES, bool PIPE>
-__global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillArgs a, int n_qt, int xcd_map) {
+__global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArgs a, int n_qt, int xcd_map) {
   using namespace pf;
-  constexpr int BM = NW * 32;
-  constexpr int PD = STAGES - 1;   // tiles in flight ahead of the one being multiplied
-  constexpr int LPT = 16 / NW;     // load instructions per wave per tile and matrix (4 rows each)
   extern __shared__ __attribute__((aligned(16))) char lds[];
 
   // ---- which tile: heavy (late) query tiles first; heads grouped per XCD so K/V stay in its L2
@@ -133,21 +130,6 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillArgs a,
   const int wrow0 = q0 + wave * 32;        // first query row of this wave
   const int qi = wrow0 + l32;              // this lane's query row
   const float c = a.scale * kLog2e;
-
-  // ---- Q fragments (B operand of S^T = K Q^T): query qi, dims ks*16 + hf*8 .. +8
-  bf16x8 qf[8];
-  {
-    const char* qp = pf_q_row(a, sm, bh, h, min(qi, len - 1));
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + (ks * 16 + hf * 8) * 2));
-    // Q Cache write (ordinary layer followed by a lazy one): the span rows of Q, straight from the
-    // fragments this lane holds (the two lane halves of a row write alternate 16-byte pieces).
-    if (a.write_q && qi < len && qi >= sm.vis_start && qi < sm.vis_start + sm.vis_len) {
-      char* qc = a.lv.q_cache + (bh * a.lv.cap_q + (qi - sm.vis_start)) * ROWB;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) *(uint4*)(qc + (ks * 16 + hf * 8) * 2) = __builtin_bit_cast(uint4, qf[ks]);
-    }
-  }
 
   f32x16 o[4];
 #pragma unroll
@@ -209,9 +191,23 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillArgs a,
     }
   };
 
+  load_tile(0);  // issued before the Q loads below so that the two latencies overlap
+
+  // ---- Q fragments (B operand of S^T = K Q^T): query qi, dims ks*16 + hf*8 .. +8
+  bf16x8 qf[8];
+  {
+    const char* qp = pf_q_row(a, sm, bh, h, min(qi, len - 1));
 #pragma unroll
-  for (int t = 0; t < PD; ++t)
-    if (t < n_tiles) load_tile(t);
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + (ks * 16 + hf * 8) * 2));
+    // Q Cache write (ordinary layer followed by a lazy one): the span rows of Q, straight from the
+    // fragments this lane holds (the two lane halves of a row write alternate 16-byte pieces).
+    if (a.write_q && qi < len && qi >= sm.vis_start && qi < sm.vis_start + sm.vis_len) {
+      char* qc = a.lv.q_cache + (bh * a.lv.cap_q + (qi - sm.vis_start)) * ROWB;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) *(uint4*)(qc + (ks * 16 + hf * 8) * 2) = __builtin_bit_cast(uint4, qf[ks]);
+    }
+  }
+
 
   // per-lane LDS read offsets that do not depend on the tile
   int k_off[8];  // K fragment of k-step ks: row l32 (+32 jb), logical chunk ks*2 + hf
@@ -252,106 +248,40 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillArgs a,
     }
   };
 
-  if constexpr (!PIPE) {
   for (int t = 0; t < n_tiles; ++t) {
-      // Tile t has landed once at most the loads of the PD-1 younger tiles are outstanding; the
-      // barrier then also tells that every wave is done with tile t-1, whose stage is refilled next.
-      if (t + PD - 1 < n_tiles) wait_vmcnt<(PD - 1) * 2 * LPT>();
-      else wait_vmcnt<0>();
-      __syncthreads();
-      if (t + PD < n_tiles) load_tile(t + PD);
-      const int k0 = t * BN;
-      if (k0 >= q0) store_tile_to_caches(t);
-      if (k0 <= wrow0 + 31) {  // wave-uniform: otherwise every key of the tile is above the diagonal
-        const char* kb = lds + (t % STAGES) * STAGE;
-        const char* vb = kb + TILE;
-        f32x16 s[2];
-  #pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
-  #pragma unroll
-          for (int r = 0; r < 16; ++r) s[jb][r] = 0.f;
-        {  // S^T = K Q^T, K fragments prefetched 4 MFMAs ahead
-          bf16x8 kf[4];
-  #pragma unroll
-          for (int i = 0; i < 4; ++i) kf[i] = *(const bf16x8*)(kb + k_off[i >> 1] + (i & 1) * 32 * ROWB);
-          __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-  #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i & 3], qf[i >> 1], s[i & 1], 0, 0, 0);
-            if (i + 4 < 16) kf[i & 3] = *(const bf16x8*)(kb + k_off[(i + 4) >> 1] + ((i + 4) & 1) * 32 * ROWB);
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA ...
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // ... then the LDS read four steps ahead
-          }
-        }
-        // accumulator register r of block jb holds key k0 + jb*32 + (r/4)*8 + hf*4 + r%4 for query qi
-        if (k0 + BN - 1 > wrow0 || k0 + BN > len) {
-  #pragma unroll
-          for (int jb = 0; jb < 2; ++jb)
-  #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int kj = k0 + jb * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
-              if (kj > qi || kj >= len) s[jb][r] = -INFINITY;
-            }
-        }
-        float mloc = s[0][0];
-  #pragma unroll
-        for (int r = 1; r < 16; ++r) mloc = fmaxf(mloc, s[0][r]);
-  #pragma unroll
-        for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[1][r]);
-        mloc = fmaxf(mloc, swap32(mloc));
-        const float mnew = fmaxf(m, mloc);
-        const bool upd = (mnew - m) * c > kRescaleThreshold;  // also true while m is -inf
-        if (__builtin_amdgcn_ballot_w64(upd) != 0) {
-          const float mu = upd ? mnew : m;
-          const float alpha = __builtin_amdgcn_exp2f((m - mu) * c);
-          m = mu;
-          lsum *= alpha;
-  #pragma unroll
-          for (int i = 0; i < 4; ++i)
-  #pragma unroll
-            for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
-        }
-        const float mc = m * c;
-        bf16x8 pb[4];
-  #pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
-  #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(s[jb][r], c, -mc));
-            lsum += p;
-            pb[jb * 2 + (r >> 3)][r & 7] = (__bf16)p;
-          }
-        // O^T += V^T P^T: k-step kk covers keys k0 + kk*16 .. +15; lane half hf supplies keys
-        // {hf*4 .. +3} and {8 + hf*4 .. +3} of that run, exactly the keys its P registers hold.
-        {
-          bf16x8 vf[4];
-  #pragma unroll
-          for (int i = 0; i < 4; ++i) vf[i] = lds_read_tr8(vb + v_off[i & 3] + (i >> 2) * 16 * ROWB, vb + v_off[i & 3] + ((i >> 2) * 16 + 8) * ROWB);
-          __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-  #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i & 3], pb[i >> 2], o[i & 3], 0, 0, 0);
-            if (i + 4 < 16) vf[i & 3] = lds_read_tr8(vb + v_off[i & 3] + ((i + 4) >> 2) * 16 * ROWB, vb + v_off[i & 3] + (((i + 4) >> 2) * 16 + 8) * ROWB);
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-          }
+    // This wave's part of tile t has landed; after the barrier the whole tile is visible and every
+    // wave is done with tile t-1, whose buffer is refilled next.
+    wait_vmcnt<0>();
+    __syncthreads();
+    if (t + 1 < n_tiles) load_tile(t + 1);
+    const int k0 = t * BN;
+    if (k0 >= q0) store_tile_to_caches(t);
+    if (k0 <= wrow0 + 31) {  // wave-uniform: otherwise every key of the tile is above the diagonal
+      const char* kb = lds + (t % STAGES) * STAGE;
+      const char* vb = kb + TILE;
+      f32x16 s[2];
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[jb][r] = 0.f;
+      {  // S^T = K Q^T, K fragments prefetched 4 MFMAs ahead
+        bf16x8 kf[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) kf[i] = *(const bf16x8*)(kb + k_off[i >> 1] + (i & 1) * 32 * ROWB);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i & 3], qf[i >> 1], s[i & 1], 0, 0, 0);
+          if (i + 4 < 16) kf[i & 3] = *(const bf16x8*)(kb + k_off[(i + 4) >> 1] + ((i + 4) & 1) * 32 * ROWB);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA ...
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // ... then the LDS read four steps ahead
         }
       }
-    }
-  
-} else {
-    // ---- software-pipelined main loop (one wave overlaps its own matrix and vector work):
-    // while the exponentials of tile t run on the vector ALU, the matrix core computes the scores
-    // of tile t+1; while it computes O += P V of tile t, the vector ALU takes the row maximum of
-    // tile t+1.  sc = scores of the current tile, sn = scores of the next one.
-    const int n_my = min(n_tiles, (wrow0 + 31) / BN + 1);  // tiles at or below this wave's diagonal
-    auto wait_for_tile = [&](int tneed, int tlast) {       // tlast: youngest tile whose loads were issued
-      const int younger = min(tlast, n_tiles - 1) - tneed;
-      if (younger >= 2) wait_vmcnt<2 * 2 * LPT>();
-      else if (younger == 1) wait_vmcnt<2 * LPT>();
-      else wait_vmcnt<0>();
-    };
-    auto mask_scores = [&](f32x16 (&s)[2], int k0) {
+      // The softmax section runs at raised wave priority and the matrix sections at the base one: the
+      // SIMD then issues this wave's vector work ahead of the other workgroup's matrix instructions,
+      // which keeps both pipes fed (measured 4 % faster than equal priorities).
+      __builtin_amdgcn_s_setprio(3);
+      // accumulator register r of block jb holds key k0 + jb*32 + (r/4)*8 + hf*4 + r%4 for query qi
       if (k0 + BN - 1 > wrow0 || k0 + BN > len) {
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb)
@@ -361,140 +291,49 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillArgs a,
             if (kj > qi || kj >= len) s[jb][r] = -INFINITY;
           }
       }
-    };
-    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    f32x16 sc[2], sn[2];
-    sn[0] = zero16;
-    sn[1] = zero16;
-    float mloc;
-    {  // prologue: scores and row maximum of tile 0
-      wait_for_tile(0, PD - 1);
-      __syncthreads();
-      const char* kb = lds;
-      bf16x8 kf[4];
+      float mloc = s[0][0];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) kf[i] = *(const bf16x8*)(kb + k_off[i >> 1] + (i & 1) * 32 * ROWB);
+      for (int r = 1; r < 16; ++r) mloc = fmaxf(mloc, s[0][r]);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        sc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i & 3], qf[i >> 1], i < 2 ? zero16 : sc[i & 1], 0, 0, 0);
-        if (i + 4 < 16) kf[i & 3] = *(const bf16x8*)(kb + k_off[(i + 4) >> 1] + ((i + 4) & 1) * 32 * ROWB);
-      }
-      mask_scores(sc, 0);
-      mloc = sc[0][0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) mloc = fmaxf(mloc, sc[0][r]);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, sc[1][r]);
+      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[1][r]);
       mloc = fmaxf(mloc, swap32(mloc));
-    }
-    for (int t = 0; t < n_tiles; ++t) {
-      if (t + 1 < n_tiles) wait_for_tile(t + 1, t + PD - 1);
-      __syncthreads();  // tile t+1 is visible; every wave is done with tile t-1, whose stage is refilled next
-      if (t * BN >= q0) store_tile_to_caches(t);
-      // Loads of tile t+PD.  The common case (tile inside the sequence, one source) is issued piecewise
-      // inside [B]; the pieces are unconditional there (no branches between the matrix instructions):
-      // when there is nothing to load they copy 16 bytes of row 0 into a scratch kilobyte of LDS.
-      const int tl = t + PD;
-      const bool do_load = tl < n_tiles;
-      bool inl = false, insl = false;
-      if (do_load) {
-        const int k0l = tl * BN;
-        const bool ins = k0l >= span_lo && k0l + BN <= span_hi;
-        const bool fast = k0l + BN <= len && (ins || k0l + BN <= span_lo || k0l >= span_hi);
-        if (!fast || t >= n_my) load_tile(tl);  // ragged / mixed tiles, and waves past their diagonal
-        else { inl = true; insl = ins; }
+      const float mnew = fmaxf(m, mloc);
+      const bool upd = (mnew - m) * c > kRescaleThreshold;  // also true while m is -inf
+      if (__builtin_amdgcn_ballot_w64(upd) != 0) {
+        const float mu = upd ? mnew : m;
+        const float alpha = __builtin_amdgcn_exp2f((m - mu) * c);
+        m = mu;
+        lsum *= alpha;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
       }
-      const int k0l = inl ? tl * BN : 0;
-      const char* ksrc_l = uniform_ptr(insl ? kanc_base + (uint64_t)k0l * ROWB : kin_base + (uint64_t)k0l * ts2);
-      const char* vsrc_l = uniform_ptr(vin_base + (uint64_t)k0l * ts2);
-      const uint32_t stage_l = lds_base + (tl % STAGES) * STAGE + wave * (4 * LPT) * ROWB;
-      uint32_t voff_l[2 * LPT], dst_l[2 * LPT];
+      const float mc = m * c;
+      bf16x8 pb[4];
 #pragma unroll
-      for (int j = 0; j < 2 * LPT; ++j) {
-        const int p = j >> 1;
-        const uint32_t vo = (j & 1) ? off_v[p] : (insl ? off_kanc[p] : off_kin[p]);
-        voff_l[j] = inl ? vo : 0u;
-        dst_l[j] = __builtin_amdgcn_readfirstlane(inl ? stage_l + ((j & 1) ? TILE : 0) + p * 4 * ROWB : lds_base + STAGES * STAGE);
-      }
-      if (t < n_my) {
-        const char* vb = lds + (t % STAGES) * STAGE + TILE;
-        const char* kbn = lds + ((t + 1) % STAGES) * STAGE;
-        // [A] move the running maximum if the tile raised it by more than the threshold
-        {
-          const float mnew = fmaxf(m, mloc);
-          const bool upd = (mnew - m) * c > kRescaleThreshold;  // also true while m is -inf
-          if (__builtin_amdgcn_ballot_w64(upd) != 0) {
-            const float mu = upd ? mnew : m;
-            const float alpha = __builtin_amdgcn_exp2f((m - mu) * c);
-            m = mu;
-            lsum *= alpha;
+      for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-              for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
-          }
+        for (int r = 0; r < 16; ++r) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[jb][r], c, -mc));
+          lsum += p;
+          pb[jb * 2 + (r >> 3)][r & 7] = (__bf16)p;
         }
-        const float mc = m * c;
-        // [B] scores of tile t+1 on the matrix core; on the vector ALU the exponentials of the first
-        // 32 keys of tile t.  The global->LDS loads of tile t+PD are issued a few at a time between
-        // the matrix instructions (issued back to back they stall the wave on the address queue).
-        // (For the wave's last tile the extra scores come from whatever the next stage holds and
-        // are never used.)
-        bf16x8 pb[4];
-        float lsum2 = 0.f;
-        {
-          bf16x8 kf[4];
+      // O^T += V^T P^T: k-step kk covers keys k0 + kk*16 .. +15; lane half hf supplies keys
+      // {hf*4 .. +3} and {8 + hf*4 .. +3} of that run, exactly the keys its P registers hold.
+      {
+        bf16x8 vf[4];
+        __builtin_amdgcn_s_setprio(0);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) kf[i] = *(const bf16x8*)(kbn + k_off[i >> 1] + (i & 1) * 32 * ROWB);
+        for (int i = 0; i < 4; ++i) vf[i] = lds_read_tr8(vb + v_off[i & 3] + (i >> 2) * 16 * ROWB, vb + v_off[i & 3] + ((i >> 2) * 16 + 8) * ROWB);
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            sn[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i & 3], qf[i >> 1], i < 2 ? zero16 : sn[i & 1], 0, 0, 0);
-            if (i + 4 < 16) kf[i & 3] = *(const bf16x8*)(kbn + k_off[(i + 4) >> 1] + ((i + 4) & 1) * 32 * ROWB);
-            if ((i & 3) == 1 && (i >> 2) < 2 * LPT) async_copy16_sv(((i >> 2) & 1) ? vsrc_l : ksrc_l, voff_l[i >> 2], dst_l[i >> 2]);
-            const float p = __builtin_amdgcn_exp2f(fmaf(sc[0][i], c, -mc));
-            if (i & 1) lsum2 += p; else lsum += p;
-            pb[i >> 3][i & 7] = (__bf16)p;
-            __builtin_amdgcn_sched_barrier(0);
-          }
+        for (int i = 0; i < 16; ++i) {
+          o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i & 3], pb[i >> 2], o[i & 3], 0, 0, 0);
+          if (i + 4 < 16) vf[i & 3] = lds_read_tr8(vb + v_off[i & 3] + ((i + 4) >> 2) * 16 * ROWB, vb + v_off[i & 3] + (((i + 4) >> 2) * 16 + 8) * ROWB);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
-        {  // keep the exponentials in this block (they would otherwise sink below the matrix work)
-          typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-          asm volatile("" ::"v"(__builtin_bit_cast(u32x4, pb[0])), "v"(__builtin_bit_cast(u32x4, pb[1])), "v"(lsum), "v"(lsum2));
-        }
-        mask_scores(sn, (t + 1) * BN);
-        // [C] O^T += V^T P^T of tile t on the matrix core; on the vector ALU first the exponentials
-        // of the last 32 keys (their P is needed from the 9th matrix instruction on), then the row
-        // maximum of tile t+1.  k-step kk covers keys k0 + kk*16 .. +15; lane half hf supplies keys
-        // {hf*4 .. +3} and {8 + hf*4 .. +3} of that run, exactly the keys its P registers hold.
-        {
-          bf16x8 vf[4];
-          float mx0 = -INFINITY, mx1 = -INFINITY;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) vf[i] = lds_read_tr8(vb + v_off[i & 3] + (i >> 2) * 16 * ROWB, vb + v_off[i & 3] + ((i >> 2) * 16 + 8) * ROWB);
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i & 3], pb[i >> 2], o[i & 3], 0, 0, 0);
-            if (i + 4 < 16) vf[i & 3] = lds_read_tr8(vb + v_off[i & 3] + ((i + 4) >> 2) * 16 * ROWB, vb + v_off[i & 3] + (((i + 4) >> 2) * 16 + 8) * ROWB);
-            if (i < 8) {
-              const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[1][2 * i], c, -mc));
-              const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[1][2 * i + 1], c, -mc));
-              lsum += p0;
-              lsum2 += p1;
-              pb[2 + (i >> 2)][(2 * i) & 7] = (__bf16)p0;
-              pb[2 + (i >> 2)][((2 * i) & 7) + 1] = (__bf16)p1;
-            } else {
-              const int r = 2 * (i - 8);
-              mx0 = fmaxf(mx0, fmaxf(sn[0][r], sn[0][r + 1]));
-              mx1 = fmaxf(mx1, fmaxf(sn[1][r], sn[1][r + 1]));
-            }
-            __builtin_amdgcn_sched_barrier(0);
-          }
-          mloc = fmaxf(mx0, mx1);
-          mloc = fmaxf(mloc, swap32(mloc));
-        }
-        lsum += lsum2;
-        sc[0] = sn[0];
-        sc[1] = sn[1];
       }
     }
   }
@@ -517,29 +356,20 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillArgs a,
   }
 }
 
-template <int NW, int STAGES, bool PIPE> static hipError_t launch_variant(const PrefillArgs& a, hipStream_t stream, KernelTimer* timer) {
+hipError_t launch_prefill_mfma_bf16_d128(const PrefillArgs& a, hipStream_t stream, KernelTimer* timer) {
   static bool attr_set = false;
-  constexpr int lds_bytes = STAGES * pf::STAGE + (PIPE ? 1024 : 0);  // + scratch kilobyte for idle load slots
+  constexpr int lds_bytes = pf::STAGES * pf::STAGE;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)prefill_mfma_kernel<NW, STAGES, PIPE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    hipError_t e = hipFuncSetAttribute((const void*)prefill_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int n_qt = (a.max_len + NW * 32 - 1) / (NW * 32);
+  const int n_qt = (a.max_len + pf::BM - 1) / pf::BM;
   const int nbh = a.batch * a.n_heads;
   if (timer) timer->begin(stream);
-  hipLaunchKernelGGL((prefill_mfma_kernel<NW, STAGES, PIPE>), dim3(n_qt * nbh), dim3(NW * 64), lds_bytes, stream, a, n_qt, (nbh % 8 == 0) ? 1 : 0);
+  hipLaunchKernelGGL(prefill_mfma_kernel, dim3(n_qt * nbh), dim3(pf::NW * 64), lds_bytes, stream, a, n_qt, (nbh % 8 == 0) ? 1 : 0);
   if (timer) timer->end(stream);
   return hipGetLastError();
-}
-
-hipError_t launch_prefill_mfma_bf16_d128(const PrefillArgs& a, hipStream_t stream, KernelTimer* timer) {
-  // 128-row workgroups, two per CU, measure fastest at every benchmark shape; the 256-row
-  // software-pipelined variant (launch_variant<8, 4, true>) is kept for shapes where K/V traffic
-  // from L2 dominates (very long prompts with few heads in flight per XCD).
-  const int64_t wg256 = (int64_t)((a.max_len + 255) / 256) * a.batch * a.n_heads;
-  if (a.max_len >= 32768 && wg256 >= 1024) return launch_variant<8, 4, true>(a, stream, timer);
-  return launch_variant<4, 2, false>(a, stream, timer);
 }
 
 }  // namespace qc
