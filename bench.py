@@ -164,7 +164,7 @@ def bench_cfg2(args):
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic("decode_cfg2"),
                      "avg_launch_us": dec_us, "launches_timed": dec_n, "algorithmic_bytes_per_launch": mean_bytes},
-        "prefill_kernel": {"kernel": "prefill_mfma_kernel<4,2>", "avg_launch_us": pre_us, "launches_timed": pre_n,
+        "prefill_kernel": {"kernel": "prefill_mfma_kernel", "avg_launch_us": pre_us, "launches_timed": pre_n,
                            "tflops": prefill_flops_per_layer(w) / (pre_us * 1e-6) / 1e12 if pre_us else None},
     }
     del r
@@ -207,11 +207,11 @@ def bench_decode_batched(args):
     return res
 
 
-def bench_prefill_highres(args):
-    """Batch-8, 3008-token prefill (MFMA-bound)."""
+def bench_prefill_highres(args, w=None, traffic_key="prefill_cfg4", layers=None):
+    """Batch-8, 3008-token prefill (MFMA-bound); also used for the other prefill shapes."""
     import torch
     import workloads
-    w = workloads.config(3)
+    w = w or workloads.config(3)
     r = Runner(w, 0)
     r.prefill_stack()
     torch.cuda.synchronize()
@@ -226,14 +226,56 @@ def bench_prefill_highres(args):
         "workload": w.name, "batch": w.batch, "seq_len": w.seq_len[0],
         "prefill_ms": ev_s * 1e3, "prefill_tflops": flops_layer * w.n_layers / ev_s / 1e12,
         "k_cache_bytes_per_token": stats["k_bytes"] / stats["tokens"],
-        "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel<4,2> (attention + fused cache writes: whole layer call)",
+        "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel (attention + fused cache writes: whole layer call)",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic("prefill_cfg4"),
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic(traffic_key),
                      "avg_launch_us": call_us, "launches_timed": call_n, "algorithmic_flops_per_launch": flops_layer},
     }
     del r
     torch.cuda.empty_cache()
     return res
+
+
+def bench_video(args):
+    """13B-shaped video workload (batch 4, 4864-token prompts, 40 heads): prefill, then decode steps."""
+    import torch
+    import workloads
+    w = workloads.config(4)
+    steps = 8
+    r = Runner(w, steps, distinct_decode_inputs=2)
+    r.prefill_stack()
+    torch.cuda.synchronize()
+    _, pre_s = timed(torch, r.prefill_stack, 1)
+    kp = r.kernel_times(r.prefill_stack)["prefill"]
+    r.decode_steps_run(2)
+    torch.cuda.synchronize()
+    _, dec_s = timed(torch, lambda: r.decode_steps_run(steps), 1)
+    g = r.sess.stats()["generated"]
+    kd = r.kernel_times(lambda: r.decode_steps_run(2))["decode"]
+    flops_layer = prefill_flops_per_layer(w)
+    bytes_call = sum(decode_bytes_per_layer(w, g + t) for t in range(2)) / 2
+    stats = r.sess.stats()
+    res = {
+        "workload": w.name, "batch": w.batch, "seq_len": w.seq_len[0], "layers": w.n_layers, "heads": w.n_heads,
+        "prefill_ms": pre_s * 1e3, "prefill_tflops": flops_layer * w.n_layers / pre_s / 1e12,
+        "prefill_kernel_avg_us": kp[0], "prefill_kernel_tflops": flops_layer / (kp[0] * 1e-6) / 1e12,
+        "decode_tokens_per_s": w.batch * steps / dec_s, "decode_ms_per_step": dec_s / steps * 1e3,
+        "decode_kernel_avg_us": kd[0], "decode_kernel_GBps": bytes_call / (kd[0] * 1e-6) / 1e9,
+        "decode_note": "7 key chunks per (sequence, head): the figure is the streaming kernel, the merge pass is extra",
+        "k_cache_bytes_per_token": stats["k_bytes"] / stats["tokens"],
+        "k_cache_bytes_per_token_standard": w.n_layers * w.n_heads * w.head_dim * w.elem_bytes,
+    }
+    del r
+    torch.cuda.empty_cache()
+    return res
+
+
+def bench_prefill_long(args):
+    """One 32768-token prompt (32000 visual tokens), 7B head shape, 4 layers with one lazy block: the
+    prefill kernel's steady state, where per-workgroup fixed costs are amortised over 257 key tiles."""
+    import workloads
+    w = workloads.custom("extra_long_prompt_32k_b1", 4, 32, 128, "bf16", [256], [32000], [32768], 0, [0, 0, 1, 1])
+    return bench_prefill_highres(args, w=w, traffic_key="prefill_long")
 
 
 def cpu_baseline(budget_s=20.0):
@@ -309,6 +351,11 @@ def main():
                                                  extra["decode_batched"]["roofline"]["achieved"]))
         extra["prefill_highres"] = bench_prefill_highres(args)
         log("cfg4 done: %.1f TFLOP/s" % extra["prefill_highres"]["prefill_tflops"])
+        extra["video_13b"] = bench_video(args)
+        log("cfg5 done: prefill %.1f TFLOP/s, decode %.1f tok/s" % (extra["video_13b"]["prefill_tflops"],
+                                                                 extra["video_13b"]["decode_tokens_per_s"]))
+        extra["prefill_long_32k"] = bench_prefill_long(args)
+        log("32k prompt done: %.1f TFLOP/s" % extra["prefill_long_32k"]["prefill_tflops"])
     cpu = None if args.skip_cpu else cpu_baseline()
     line = {
         "metric": "decode_tokens_per_s", "value": r["decode_tokens_per_s"], "unit": "tokens/s",
