@@ -355,6 +355,13 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   a.chunk_keys = chunk;
   a.max_chunks = max_chunks;
   a.scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)c.D);
+  a.inline_meta = kv->batch <= qc::DecodeArgs::kInlineSeqs ? 1 : 0;
+  for (int b = 0; b < qc::DecodeArgs::kInlineSeqs; ++b) {
+    const bool ok = a.inline_meta && b < kv->batch;
+    a.len0_inline[b] = ok ? kv->len0[b] : 0;
+    a.vis_start_inline[b] = ok ? kv->vis_start[b] : 0;
+    a.vis_len_inline[b] = ok ? kv->vis_len[b] : 0;
+  }
   hipError_t err = qc::launch_decode(a, c.dtype, (hipStream_t)stream, kv->timing ? &kv->decode_timer : nullptr);
   if (err != hipSuccess) return fail(QC_EDEVICE, "qc_decode: %s", hipGetErrorString(err));
 

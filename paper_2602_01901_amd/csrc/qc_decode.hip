@@ -23,6 +23,19 @@ __device__ __forceinline__ uint4 stream_load16(const char* p) {
   return make_uint4(t.x, t.y, t.z, t.w);
 }
 
+// Per-sequence integers: from the kernel arguments for small batches, else from the arena's meta region.
+__device__ __forceinline__ SeqMeta decode_meta(const DecodeArgs& a, int b) {
+  if (a.inline_meta) {
+    SeqMeta m;
+    m.tok0 = 0;
+    m.len0 = a.len0_inline[b];
+    m.vis_start = a.vis_start_inline[b];
+    m.vis_len = a.vis_len_inline[b];
+    return m;
+  }
+  return load_meta(a.lv, b);
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
   constexpr int EPL = ElemTraits<T>::kPer16;  // elements per lane (16 bytes)
@@ -33,7 +46,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
   constexpr int ROWB = D * (int)sizeof(T);
 
   const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  const SeqMeta sm = load_meta(a.lv, b);
+  const SeqMeta sm = decode_meta(a, b);
   const int len = sm.len0 + a.generated;  // position of the new token
   const int kbeg = chunk * a.chunk_keys;
   if (kbeg > len) return;
@@ -152,25 +165,19 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
   }
 }
 
-// Merge the chunk partials of one (sequence, head) in chunk order.  Loads are issued in batches of
-// eight chunks so that their latencies overlap; the arithmetic order is fixed (bitwise reproducible).
+// Merge the chunk partials of one (sequence, head) in chunk order.  Partials are loaded in batches
+// of 16 chunks (all loads of a batch are independent, so their latencies overlap); within a batch
+// the usual running (max, sum) update is applied chunk by chunk in a fixed order, so results are
+// bitwise reproducible.
 template <typename T, int D>
 __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
   const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
-  const int len = a.lv.meta[META_LEN0 * a.lv.max_batch + b] + a.generated;
+  const int len = decode_meta(a, b).len0 + a.generated;
   const int n = (len + a.chunk_keys) / a.chunk_keys;  // ceil((len + 1) / chunk_keys)
   const int64_t bh = (int64_t)b * a.n_heads + h;
   const float* w = a.workspace + bh * a.max_chunks * (D + 2);
-  constexpr int G = 8;
-  float M = -INFINITY;
-  for (int c0 = 0; c0 < n; c0 += G) {
-    float mv[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) mv[g] = (c0 + g < n) ? w[(c0 + g) * (D + 2) + D] : -INFINITY;
-#pragma unroll
-    for (int g = 0; g < G; ++g) M = fmaxf(M, mv[g]);
-  }
-  float o = 0.f, l = 0.f;
+  constexpr int G = 16;
+  float M = -INFINITY, o = 0.f, l = 0.f;
   for (int c0 = 0; c0 < n; c0 += G) {
     float mv[G], lv[G], ov[G];
 #pragma unroll
@@ -181,12 +188,19 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
       lv[g] = p[D + 1];
       ov[g] = p[d];
     }
+    float Mb = M;
+#pragma unroll
+    for (int g = 0; g < G; ++g) Mb = fmaxf(Mb, mv[g]);
+    const float keep = __builtin_amdgcn_exp2f(M - Mb);  // 0 on the first batch (M = -inf)
+    o *= keep;
+    l *= keep;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      const float f = __builtin_amdgcn_exp2f(mv[g] - M);  // 0 for slots past the last chunk
+      const float f = __builtin_amdgcn_exp2f(mv[g] - Mb);  // 0 for slots past the last chunk
       o = fmaf(f, ov[g], o);
       l = fmaf(f, lv[g], l);
     }
+    M = Mb;
   }
   store_elem((T*)a.out + bh * D + d, o / l);
 }
