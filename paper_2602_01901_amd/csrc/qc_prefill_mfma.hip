@@ -70,15 +70,23 @@ typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
 
 // One global_load_lds_dwordx4: lane i's 16 bytes go to LDS byte offset lds_off + 16*i (lds_off is
-// wave-uniform and travels in M0).  Issued as inline asm so that the compiler does not tie later
-// LDS reads of the OTHER buffer to these loads; the kernel waits for them itself (vmcnt(0)) before
-// the barrier that publishes the tile.
+// wave-uniform and travels in M0, which is saved and restored around the instruction).  Issued as
+// inline asm so that the compiler does not tie later LDS reads of the OTHER buffer to these
+// loads; the kernel waits for them itself (vmcnt(0)) before the barrier that publishes the tile.
 __device__ __forceinline__ void async_copy16(const char* src, uint32_t lds_off) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_off) : "memory", "m0");
+  uint32_t saved_m0;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(saved_m0)
+               : "v"(src), "s"(lds_off)
+               : "memory");
 }
 // Same with a wave-uniform 64-bit base in SGPRs and a 32-bit per-lane byte offset.
 __device__ __forceinline__ void async_copy16_sv(const char* sbase, uint32_t voff, uint32_t lds_off) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_off) : "memory", "m0");
+  uint32_t saved_m0;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+               : "=&s"(saved_m0)
+               : "v"(voff), "s"(sbase), "s"(lds_off)
+               : "memory");
 }
 // Pin a wave-uniform pointer into scalar registers.
 __device__ __forceinline__ const char* uniform_ptr(const char* p) {

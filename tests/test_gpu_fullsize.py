@@ -115,9 +115,9 @@ def test_cfg5_video_shape_sampled():
     assert worst <= TOL["bf16"]
 
 
-def test_long_prompt_uses_pipelined_256_row_kernel():
-    """One 32768-token prompt (32000 visual), 8 heads: long enough for the 256-row, software-pipelined
-    prefill variant; an ordinary layer then a lazy one, sampled rows."""
+def test_long_prompt_32k():
+    """One 32768-token prompt (32000 visual), 8 heads: 256 query tiles per head and key walks of up to
+    512 tiles; an ordinary layer then a lazy one, sampled rows."""
     w = workloads.custom("long", 2, 8, 128, "bf16", [256], [32000], [32768], 0, [0, 1])
     worst, sess = run_sampled(w, 2, [(0, 0), (0, 7)])
     print("long prompt sampled max abs err %.3g" % worst, flush=True)
