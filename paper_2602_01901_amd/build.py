@@ -25,10 +25,7 @@ def hipcc():
     return exe
 
 
-def build_library(verbose=False, extra_flags=()):
-    """Compile every source into libqcache.so (always recompiles)."""
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = [hipcc()] + HIPCC_FLAGS + list(extra_flags) + ["-I", os.path.join(ROOT, "include"), "-I", CSRC] + srcs + ["-o", LIB_PATH + ".tmp"]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -37,6 +34,24 @@ def build_library(verbose=False, extra_flags=()):
         raise RuntimeError("hipcc failed:\n" + "\n".join(lines))
     if verbose and lines:
         print("\n".join(lines))
+
+
+def build_library(verbose=False, extra_flags=()):
+    """Compile every source (in parallel) and link libqcache.so; always recompiles."""
+    from concurrent.futures import ThreadPoolExecutor
+    objdir = os.path.join(PKG_DIR, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"] + list(extra_flags) + [
+        "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    objs = []
+    jobs = []
+    for src in SOURCES:
+        obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
+        objs.append(obj)
+        jobs.append([hipcc()] + compile_flags + ["-c", os.path.join(CSRC, src), "-o", obj])
+    with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1, 8)) as pool:
+        list(pool.map(lambda c: _run(c, verbose), jobs))
+    _run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB_PATH + ".tmp"], verbose)
     os.replace(LIB_PATH + ".tmp", LIB_PATH)
     return LIB_PATH
 

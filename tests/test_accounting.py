@@ -1,0 +1,55 @@
+"""CPU checks of the byte/flop accounting that bench.py reports: the formulas of the scope table
+evaluated on the benchmark configurations, and the K-cache bytes per token the layout predicts."""
+import os
+import sys
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+
+import bench
+import workloads
+from oracle import layout
+from oracle.lazy_stack import LazyStackOracle
+
+
+def k_bytes_per_token_after_prefill(w):
+    """Resident K bytes / tokens, from row counts only: sum_b sum_l (L_b - lazy[l]*Vn_b) * H * D * e."""
+    rows = sum(L - lz * v for L, v in zip(w.seq_len, w.vis_len) for lz in w.lazy_mask)
+    return rows * w.n_heads * w.head_dim * w.elem_bytes / sum(w.seq_len)
+
+
+def test_k_cache_bytes_per_token_predictions():
+    want = {0: 851968 / 176, 1: 122060.8, 3: 113119.319, 4: 176774.737}
+    for i, val in want.items():
+        got = k_bytes_per_token_after_prefill(workloads.config(i))
+        assert abs(got - val) < 1e-2, (i, got)
+    w = workloads.config(1)
+    assert w.n_layers * w.n_heads * w.head_dim * w.elem_bytes == 262144
+
+
+def test_row_count_formula_matches_oracle_state():
+    w = workloads.custom("acc", 5, 2, 4, "bf16", [3, 0], [6, 4], [15, 9], 0, [0, 1, 1, 0, 1])
+    stacks = [LazyStackOracle(w.n_layers, w.n_heads, w.head_dim, w.lazy_mask, w.vis_start[b], w.vis_len[b])
+              for b in range(w.batch)]
+    for b, st in enumerate(stacks):
+        z = np.zeros((w.seq_len[b], w.n_heads, w.head_dim))
+        for l in range(w.n_layers):
+            st.prefill(l, z, z, z, rows=[0])
+    lay = layout.ArenaLayout(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.batch, w.max_seq, w.max_vis,
+                             w.max_text, w.lazy_mask)
+    res = layout.resident_bytes(lay, stacks)
+    assert res["k_bytes"] / res["tokens"] == k_bytes_per_token_after_prefill(w)
+
+
+def test_prefill_flops_and_decode_bytes_of_the_benchmark_shapes():
+    assert bench.prefill_flops_per_layer(workloads.config(1)) == 32 * 4 * 128 * 640 * 641 // 2        # 3.36 GFLOP
+    assert round(bench.prefill_flops_per_layer(workloads.config(3)) / 1e9, 1) == 593.2
+    w5 = workloads.config(4)
+    assert bench.prefill_flops_per_layer(w5) == sum(40 * 512 * L * (L + 1) // 2 for L in w5.seq_len)
+    w = workloads.config(1)
+    assert bench.decode_bytes_per_layer(w, 0) == (2 * 641 + 6) * 32 * 128 * 2                         # 10.6 MB
+    # a lazy layer reads as many bytes as an ordinary one (its visual keys come from another buffer)
+    assert bench.decode_bytes_per_layer(workloads.config(2), 5) == sum(
+        (2 * (L + 6) + 6) * 32 * 128 * 2 for L in workloads.config(2).seq_len)
