@@ -19,6 +19,12 @@ Row maps: V row = position.  K row = position in a normal layer.  In a lazy
 layer positions before the span keep their index, positions after it move
 down by vis_len, and positions inside the span have no row in that layer:
 they resolve to the same position in the block's first layer.
+
+Global Lazy Attention (mode "gla"; Eq. 5/6 and the sentence after Eq. 6: a lazy
+layer stores no K rows, the Q Cache holds the queries of every token): capK(l) = 0
+for a lazy layer, every key position of a lazy layer resolves to the same
+position in the block's first layer, and the Q arena is
+[max_batch][H][max_seq][D] with row = position.
 """
 import numpy as np
 
@@ -31,7 +37,9 @@ def _round_up(x, m):
 
 class ArenaLayout:
     def __init__(self, n_layers, n_heads, head_dim, dtype, max_batch, max_seq, max_vis, max_text,
-                 lazy_mask):
+                 lazy_mask, mode="vla"):
+        assert mode in ("vla", "gla")
+        self.mode = mode
         self.N, self.H, self.D = n_layers, n_heads, head_dim
         self.dtype = dtype
         self.e = ELEM_BYTES[dtype]
@@ -41,7 +49,12 @@ class ArenaLayout:
         assert len(self.lazy) == n_layers and not (n_layers and self.lazy[0])
 
     def cap_k(self, l):
-        return self.max_text if self.lazy[l] else self.max_seq
+        if not self.lazy[l]:
+            return self.max_seq
+        return self.max_text if self.mode == "vla" else 0
+
+    def cap_q(self):
+        return self.max_vis if self.mode == "vla" else self.max_seq
 
     def k_layer_bytes(self, l):
         return self.max_batch * self.H * self.cap_k(l) * self.D * self.e
@@ -65,7 +78,7 @@ class ArenaLayout:
         return self.off_meta() + self.meta_bytes()
 
     def q_arena_bytes(self):
-        return self.max_batch * self.H * self.max_vis * self.D * self.e
+        return self.max_batch * self.H * self.cap_q() * self.D * self.e
 
     def k_offset(self, l, b, h, row):
         return self.off_k(l) + ((b * self.H + h) * self.cap_k(l) + row) * self.D * self.e
@@ -74,7 +87,7 @@ class ArenaLayout:
         return self.off_v(l) + ((b * self.H + h) * self.max_seq + row) * self.D * self.e
 
     def q_offset(self, b, h, row):
-        return ((b * self.H + h) * self.max_vis + row) * self.D * self.e
+        return ((b * self.H + h) * self.cap_q() + row) * self.D * self.e
 
     def anchor(self, l):
         a = l - 1
@@ -84,6 +97,9 @@ class ArenaLayout:
 
     def locate_k(self, l, b, h, pos, vis_start, vis_len):
         """(source layer, byte offset in the K/V arena) of the key of `pos` as layer l reads it."""
+        if self.lazy[l] and self.mode == "gla":
+            a = self.anchor(l)
+            return a, self.k_offset(a, b, h, pos)
         if self.lazy[l] and vis_start <= pos < vis_start + vis_len:
             a = self.anchor(l)
             return a, self.k_offset(a, b, h, pos)
@@ -110,7 +126,7 @@ def encode_rows(x, dtype):
 
 
 def kv_arena_image(layout, stacks, tok0=None):
-    """Expected bytes of the whole K/V arena given one LazyStackOracle per sequence.
+    """Expected bytes of the whole K/V arena given one stack oracle (of the layout's mode) per sequence.
 
     Unwritten bytes are zero.  `tok0[b]` is the first packed-prompt token index
     of sequence b (default: prompts packed back to back in batch order).
@@ -147,7 +163,7 @@ def q_arena_image(layout, stacks):
             continue
         for h in range(layout.H):
             o = layout.q_offset(b, h, 0)
-            img[o:o + st.Vn * rowb] = encode_rows(st.Qc[h], layout.dtype).reshape(-1)
+            img[o:o + st.Qc.shape[1] * rowb] = encode_rows(st.Qc[h], layout.dtype).reshape(-1)
     return img
 
 
@@ -173,3 +189,15 @@ def vla_kv_saving_closed_form(n_layers, n_lazy, vis_len, text_len):
     """"Efficiency Analysis", KV Cache paragraph: |V|/(|V|+|T|) * n/(2N), as an exact fraction."""
     from fractions import Fraction
     return Fraction(vis_len, vis_len + text_len) * Fraction(n_lazy, 2 * n_layers)
+
+
+def gla_kv_saving_closed_form(n_layers, n_lazy):
+    """"Efficiency Analysis", KV Cache paragraph: GLA saves n/(2N) of the KV cache, as an exact fraction."""
+    from fractions import Fraction
+    return Fraction(n_lazy, 2 * n_layers)
+
+
+def q_cache_share_closed_form(n_layers):
+    """Same paragraph: a Q Cache that holds every token is 1/(2N) of a standard KV cache."""
+    from fractions import Fraction
+    return Fraction(1, 2 * n_layers)
