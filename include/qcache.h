@@ -26,6 +26,13 @@
  *     inherits from head h of its block's first layer.
  *   - Each sequence has one contiguous visual span [vis_start, vis_start + vis_len) at its
  *     true token positions; text may precede and follow it; generated tokens are text.
+ *
+ * Global Lazy Attention (GLA, qc_config.mode = QC_GLA; paper Eq. 5 for prefill, Eq. 6 for decode)
+ * is the paper's coarser variant: a lazy layer inherits the queries and keys of EVERY token from
+ * the first layer of its block, computes none of its own and stores no K rows; only its values are
+ * its own.  The Q Cache then holds one row per token position (prompt and generated).  Where GLA
+ * changes an entry point's behaviour the comment of that entry point says so; everything else
+ * (state machine, layouts of the ordinary layers, error behaviour) is shared with VLA.
  */
 #ifndef QCACHE_H
 #define QCACHE_H
@@ -48,6 +55,7 @@ typedef enum {
 } qc_status;
 
 typedef enum { QC_F32 = 0, QC_BF16 = 1 } qc_dtype;
+typedef enum { QC_VLA = 0, QC_GLA = 1 } qc_mode;
 
 enum { QC_K = 0, QC_V = 1 };
 
@@ -59,7 +67,9 @@ enum { QC_K = 0, QC_V = 1 };
  * max_vis  : most visual tokens in any sequence.
  * max_text : most text rows (prompt text + generated) any sequence may reach; this is the row
  *            capacity of a lazy layer's K cache, which is what makes its allocation smaller.
- * head_dim : 64 or 128.  dtype: element type of Q/K/V/O and of all caches. */
+ * head_dim : 64 or 128.  dtype: element type of Q/K/V/O and of all caches.
+ * mode     : QC_VLA or QC_GLA.  Under QC_GLA max_vis and max_text size nothing (a lazy layer has
+ *            no K rows, the Q Cache has max_seq rows) but must still be valid (0..max_seq). */
 typedef struct qc_config {
   int32_t n_layers;
   int32_t n_heads;
@@ -69,6 +79,8 @@ typedef struct qc_config {
   int32_t max_seq;
   int32_t max_vis;
   int32_t max_text;
+  int32_t mode;     /* qc_mode */
+  int32_t reserved; /* must be 0 */
   const uint8_t* lazy_mask;
 } qc_config;
 
@@ -78,7 +90,10 @@ typedef struct qc_qcache qc_qcache;
 /* Resident-byte accounting ("Efficiency Analysis", KV Cache paragraph): bytes of cache rows that
  * currently hold data, not capacity.  k_bytes = sum over sequences and layers of
  * (len - lazy[l]*vis_len) * H * D * e; v_bytes = sum of n_layers * len * H * D * e; q_bytes = sum
- * of vis_len * H * D * e once a layer has written the Q Cache (0 before).  tokens = sum of len. */
+ * of vis_len * H * D * e once a layer has written the Q Cache (0 before).  tokens = sum of len.
+ * Under QC_GLA a lazy layer contributes no k_bytes, and q_bytes counts one row per position the
+ * Q Cache holds: len rows, plus the row of the token being decoded once a block's first layer
+ * has stored its query in the current step. */
 typedef struct qc_stats_t {
   int64_t k_bytes;
   int64_t v_bytes;
@@ -99,6 +114,8 @@ typedef struct qc_stats_t {
  *   meta    : at the next multiple of 256: int32 [4][max_batch] = {first packed token index,
  *             prompt length, vis_start, vis_len} per sequence, padded to a multiple of 256 bytes.
  * Q arena: [max_batch][n_heads][max_vis][head_dim] (one layer's worth, visual rows only).
+ * Under QC_GLA: capK(l) = 0 for a lazy layer, and the Q arena is
+ *   [max_batch][n_heads][max_seq][head_dim] with row = token position.
  * Decode workspace: split partial results, fp32. */
 size_t qc_kv_arena_bytes(const qc_config* cfg);
 size_t qc_q_arena_bytes(const qc_config* cfg);
@@ -134,7 +151,11 @@ qc_status qc_reset(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* 
  * Effects, lazy layer: span rows of q are taken from the Q Cache and span rows of k from the
  *   anchor layer's K cache (the span rows of the q and k arguments are never read and may be
  *   left unwritten by the caller); attention as above with the layer's own v; only text rows of
- *   k are stored (compacted: positions after the span move down by vis_len), all rows of v. */
+ *   k are stored (compacted: positions after the span move down by vis_len), all rows of v.
+ * Under QC_GLA (paper Eq. 5) an ordinary layer followed by a lazy one stores every row of q in the
+ *   Q Cache; a lazy layer takes every row of q from the Q Cache and every row of k from the K cache
+ *   of its block's first layer, stores all rows of v and nothing else; its q and k arguments are
+ *   ignored and may be NULL. */
 qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_lazy, const void* q,
                      const void* k, const void* v, void* out, const int32_t* cu_seqlens,
                      int64_t token_stride, int64_t head_stride, const int32_t* vis_start,
@@ -146,7 +167,13 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
  * v row at row len; the query attends positions 0..len, where a lazy layer reads the span
  * positions from its anchor layer's K cache.  The Q Cache is neither read nor written (the
  * decode query is a text token); qc may be NULL.  After layer n_layers-1 every length grows by 1.
- * workspace: DEVICE, at least qc_decode_workspace_bytes(cfg), contents undefined between calls. */
+ * workspace: DEVICE, at least qc_decode_workspace_bytes(cfg), contents undefined between calls.
+ * Under QC_GLA (paper Eq. 6) qc is required.  An ordinary layer followed by a lazy one also stores
+ *   its query at row len of the Q Cache, which from then on belongs to it.  A lazy layer attends
+ *   with that row and with the K cache of its block's first layer (rows 0..len, the last one
+ *   appended by that layer earlier in the same step, on the same stream), appends only its v row;
+ *   its q and k arguments are ignored and may be NULL.  QC_EORDER if the Q Cache belongs to
+ *   another block. */
 qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_lazy, const void* q,
                     const void* k, const void* v, void* out, const int32_t* vis_start,
                     const int32_t* vis_len, float softmax_scale, void* workspace,
@@ -159,7 +186,8 @@ qc_status qc_layer_rows(const qc_kvcache* kv, int32_t layer, int64_t* rows_k, in
 qc_status qc_seq_len(const qc_kvcache* kv, int32_t b, int32_t* len);
 /* Where layer `layer` reads the key (which = QC_K) or value (QC_V) of position `pos` of head h of
  * sequence b: *src_layer is `layer` itself, or the anchor layer for a span position of a lazy
- * layer; *byte_offset is the offset of that row in the K/V arena.  pos must be < max_seq. */
+ * layer; *byte_offset is the offset of that row in the K/V arena.  pos must be < max_seq.
+ * Under QC_GLA every key position of a lazy layer resolves to the block's first layer. */
 qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t b, int32_t h,
                     int32_t pos, int32_t* src_layer, int64_t* byte_offset);
 

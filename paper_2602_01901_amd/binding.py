@@ -14,13 +14,15 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libqcache.s
 QC_OK, QC_EINVAL, QC_EORDER, QC_ECAPACITY, QC_EDEVICE = range(5)
 QC_F32, QC_BF16 = 0, 1
 QC_K, QC_V = 0, 1
+QC_VLA, QC_GLA = 0, 1
 DTYPE_CODE = {"f32": QC_F32, "bf16": QC_BF16}
+MODE_CODE = {"vla": QC_VLA, "gla": QC_GLA}
 
 
 class qc_config(ctypes.Structure):
     _fields_ = [("n_layers", c_int32), ("n_heads", c_int32), ("head_dim", c_int32), ("dtype", c_int32),
                 ("max_batch", c_int32), ("max_seq", c_int32), ("max_vis", c_int32), ("max_text", c_int32),
-                ("lazy_mask", POINTER(c_uint8))]
+                ("mode", c_int32), ("reserved", c_int32), ("lazy_mask", POINTER(c_uint8))]
 
 
 class qc_stats_t(ctypes.Structure):
@@ -110,11 +112,12 @@ def qc_last_error():
     return load_library().qc_last_error().decode()
 
 
-def make_config(n_layers, n_heads, head_dim, dtype, max_batch, max_seq, max_vis, max_text, lazy_mask):
+def make_config(n_layers, n_heads, head_dim, dtype, max_batch, max_seq, max_vis, max_text, lazy_mask,
+                mode="vla"):
     """Returns a qc_config; the mask buffer is kept alive by the returned object."""
     mask = (c_uint8 * max(len(lazy_mask), 1))(*[int(bool(x)) for x in lazy_mask])
     cfg = qc_config(n_layers, n_heads, head_dim, DTYPE_CODE.get(dtype, dtype), max_batch, max_seq, max_vis,
-                    max_text, ctypes.cast(mask, POINTER(c_uint8)))
+                    max_text, MODE_CODE.get(mode, mode), 0, ctypes.cast(mask, POINTER(c_uint8)))
     cfg._mask_keepalive = mask
     return cfg
 

@@ -29,11 +29,16 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 struct Config {
   int32_t N = 0, H = 0, D = 0, dtype = 0;
   int32_t max_batch = 0, max_seq = 0, max_vis = 0, max_text = 0;
+  int32_t mode = QC_VLA;
   std::vector<uint8_t> lazy;
   std::vector<int32_t> anchor;  // anchor[l] = first layer of l's block (l itself if not lazy)
 
   int e() const { return dtype == QC_BF16 ? 2 : 4; }
-  int64_t cap_k(int l) const { return lazy[l] ? max_text : max_seq; }
+  bool gla() const { return mode == QC_GLA; }
+  int64_t cap_k(int l) const { return lazy[l] ? (gla() ? 0 : max_text) : max_seq; }
+  int64_t cap_q() const { return gla() ? max_seq : max_vis; }
+  // An ordinary layer stores queries in the Q Cache exactly when the next layer is lazy.
+  bool writes_q(int l) const { return !lazy[l] && l + 1 < N && lazy[l + 1]; }
   int64_t k_layer_bytes(int l) const { return (int64_t)max_batch * H * cap_k(l) * D * e(); }
   int64_t v_layer_bytes() const { return (int64_t)max_batch * H * max_seq * D * e(); }
   int64_t off_k(int l) const {
@@ -45,11 +50,12 @@ struct Config {
   int64_t off_meta() const { return round_up(off_v(N), 256); }
   int64_t meta_bytes() const { return round_up((int64_t)qc::META_ROWS * 4 * max_batch, 256); }
   int64_t kv_bytes() const { return off_meta() + meta_bytes(); }
-  int64_t q_bytes() const { return (int64_t)max_batch * H * max_vis * D * e(); }
+  int64_t q_bytes() const { return (int64_t)max_batch * H * cap_q() * D * e(); }
   int64_t row_bytes() const { return (int64_t)D * e(); }
   bool same(const Config& o) const {
     return N == o.N && H == o.H && D == o.D && dtype == o.dtype && max_batch == o.max_batch &&
-           max_seq == o.max_seq && max_vis == o.max_vis && max_text == o.max_text && lazy == o.lazy;
+           max_seq == o.max_seq && max_vis == o.max_vis && max_text == o.max_text && mode == o.mode &&
+           lazy == o.lazy;
   }
 };
 
@@ -63,6 +69,7 @@ bool parse_config(const qc_config* c, Config* out) {
     return false;
   if (c->head_dim != 64 && c->head_dim != 128) return false;
   if (c->dtype != QC_F32 && c->dtype != QC_BF16) return false;
+  if ((c->mode != QC_VLA && c->mode != QC_GLA) || c->reserved != 0) return false;
   if (c->max_vis > c->max_seq || c->max_text > c->max_seq) return false;
   if (c->lazy_mask[0]) return false;
   out->N = c->n_layers;
@@ -73,6 +80,7 @@ bool parse_config(const qc_config* c, Config* out) {
   out->max_seq = c->max_seq;
   out->max_vis = c->max_vis;
   out->max_text = c->max_text;
+  out->mode = c->mode;
   out->lazy.assign(c->lazy_mask, c->lazy_mask + c->n_layers);
   for (auto& f : out->lazy) f = f ? 1 : 0;
   out->anchor.resize(out->N);
@@ -180,7 +188,7 @@ qc_status qc_reset(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* 
   if (batch > c.max_batch) return fail(QC_ECAPACITY, "qc_reset: batch %d exceeds max_batch %d", batch, c.max_batch);
   for (int b = 0; b < batch; ++b) {
     if (vis_start[b] < 0 || vis_len[b] < 0) return fail(QC_EINVAL, "qc_reset: negative span for sequence %d", b);
-    if (vis_len[b] > c.max_vis) return fail(QC_ECAPACITY, "qc_reset: sequence %d has %d visual tokens, max_vis %d", b, vis_len[b], c.max_vis);
+    if (!c.gla() && vis_len[b] > c.max_vis) return fail(QC_ECAPACITY, "qc_reset: sequence %d has %d visual tokens, max_vis %d", b, vis_len[b], c.max_vis);
     if ((int64_t)vis_start[b] + vis_len[b] > c.max_seq) return fail(QC_ECAPACITY, "qc_reset: span of sequence %d exceeds max_seq", b);
   }
   if (zero_fill) {
@@ -211,7 +219,7 @@ static qc::LayerView make_view(const qc_kvcache* kv, const qc_qcache* qc, int la
   lv.k_anchor = c.lazy[layer] ? kv->arena + c.off_k(a) : nullptr;
   lv.cap_k_anchor = (int32_t)c.cap_k(a);
   lv.q_cache = qc ? qc->arena : nullptr;
-  lv.cap_q = c.max_vis;
+  lv.cap_q = (int32_t)c.cap_q();
   lv.meta = (const int32_t*)(kv->arena + c.off_meta());
   lv.max_batch = c.max_batch;
   return lv;
@@ -234,7 +242,10 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
   if (!c.same(qc->cfg)) return fail(QC_EINVAL, "qc_prefill: handles were created with different configurations");
   if (layer < 0 || layer >= c.N) return fail(QC_EINVAL, "qc_prefill: layer %d out of range", layer);
   if ((is_lazy != 0) != (c.lazy[layer] != 0)) return fail(QC_EINVAL, "qc_prefill: is_lazy=%d contradicts the configured mask for layer %d", is_lazy, layer);
-  if (!q || !k || !v || !out || !cu_seqlens) return fail(QC_EINVAL, "qc_prefill: null tensor or cu_seqlens");
+  // Global Lazy Attention: a lazy layer has no q and k of its own, the two arguments are ignored.
+  const bool qk_unused = c.gla() && c.lazy[layer];
+  if (qk_unused) q = k = nullptr;
+  if ((!qk_unused && (!q || !k)) || !v || !out || !cu_seqlens) return fail(QC_EINVAL, "qc_prefill: null tensor or cu_seqlens");
   const int e = c.e();
   if (head_stride < c.D || token_stride < c.D || (head_stride * e) % 16 || (token_stride * e) % 16)
     return fail(QC_EINVAL, "qc_prefill: strides must be >= head_dim and keep rows 16-byte aligned");
@@ -252,7 +263,7 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
     if (len < 1) return fail(QC_EINVAL, "qc_prefill: sequence %d is empty", b);
     if (kv->vis_start[b] + kv->vis_len[b] > len) return fail(QC_EINVAL, "qc_prefill: span of sequence %d exceeds its %lld tokens", b, (long long)len);
     if (len > c.max_seq) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld tokens, max_seq %d", b, (long long)len, c.max_seq);
-    if (len - kv->vis_len[b] > c.max_text) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld text tokens, max_text %d", b, (long long)(len - kv->vis_len[b]), c.max_text);
+    if (!c.gla() && len - kv->vis_len[b] > c.max_text) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld text tokens, max_text %d", b, (long long)(len - kv->vis_len[b]), c.max_text);
     if (layer > 0 && (len != kv->len0[b] || cu_seqlens[b] != kv->tok0[b]))
       return fail(QC_EINVAL, "qc_prefill: cu_seqlens changed between layers");
     if (len > max_len) max_len = (int32_t)len;
@@ -287,7 +298,8 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
   a.head_stride = head_stride;
   a.batch = kv->batch; a.n_heads = c.H; a.head_dim = c.D;
   a.is_lazy = c.lazy[layer];
-  a.write_q = (!c.lazy[layer] && layer + 1 < c.N && c.lazy[layer + 1]) ? 1 : 0;
+  a.write_q = c.writes_q(layer) ? 1 : 0;
+  a.inherit_all = c.gla() ? 1 : 0;
   a.max_len = max_len;
   a.scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)c.D);
   hipError_t err = qc::launch_prefill(a, c.dtype, st, kv->timing ? &kv->prefill_timer : nullptr);
@@ -312,12 +324,18 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
                     const void* k, const void* v, void* out, const int32_t* vis_start,
                     const int32_t* vis_len, float softmax_scale, void* workspace,
                     size_t workspace_bytes, void* stream) {
-  (void)qc;  // Visual Lazy Attention never touches the Q Cache while decoding
   if (!kv) return fail(QC_EINVAL, "qc_decode: null handle");
   const Config& c = kv->cfg;
+  // Visual Lazy Attention never touches the Q Cache while decoding; Global Lazy Attention does.
+  if (c.gla()) {
+    if (!qc) return fail(QC_EINVAL, "qc_decode: Global Lazy Attention needs the Q Cache handle");
+    if (!c.same(qc->cfg)) return fail(QC_EINVAL, "qc_decode: handles were created with different configurations");
+  }
   if (layer < 0 || layer >= c.N) return fail(QC_EINVAL, "qc_decode: layer %d out of range", layer);
   if ((is_lazy != 0) != (c.lazy[layer] != 0)) return fail(QC_EINVAL, "qc_decode: is_lazy=%d contradicts the configured mask for layer %d", is_lazy, layer);
-  if (!q || !k || !v || !out || !workspace) return fail(QC_EINVAL, "qc_decode: null tensor or workspace");
+  const bool qk_unused = c.gla() && c.lazy[layer];
+  if (qk_unused) q = k = nullptr;
+  if ((!qk_unused && (!q || !k)) || !v || !out || !workspace) return fail(QC_EINVAL, "qc_decode: null tensor or workspace");
   if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out | (uintptr_t)workspace) & 15)
     return fail(QC_EINVAL, "qc_decode: tensors and workspace must be 16-byte aligned");
   if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return fail(QC_EINVAL, "qc_decode: bad softmax_scale");
@@ -328,9 +346,11 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   for (int b = 0; b < kv->batch; ++b) {
     int64_t len = (int64_t)kv->len0[b] + kv->generated;
     if (len + 1 > c.max_seq) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld positions, max_seq %d", b, (long long)(len + 1), c.max_seq);
-    if (len + 1 - kv->vis_len[b] > c.max_text) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld text rows, max_text %d", b, (long long)(len + 1 - kv->vis_len[b]), c.max_text);
+    if (!c.gla() && len + 1 - kv->vis_len[b] > c.max_text) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld text rows, max_text %d", b, (long long)(len + 1 - kv->vis_len[b]), c.max_text);
     if (len > max_len) max_len = (int32_t)len;
   }
+  if (qk_unused && qc->owner != c.anchor[layer])
+    return fail(QC_EORDER, "qc_decode: Q Cache belongs to layer %d, layer %d inherits from %d", qc->owner, layer, c.anchor[layer]);
   // Split the key axis only as far as needed to give every CU a few workgroups: each extra chunk
   // costs a partial result and the merge pass.  With many (sequence, head) pairs there is no split
   // and the kernel writes the output directly.
@@ -345,11 +365,13 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   if (workspace_bytes < need) return fail(QC_ECAPACITY, "qc_decode: workspace holds %zu bytes, %zu needed", workspace_bytes, need);
 
   qc::DecodeArgs a;
-  a.lv = make_view(kv, nullptr, layer);
+  a.lv = make_view(kv, c.gla() ? qc : nullptr, layer);
   a.q = q; a.k = k; a.v = v; a.out = out;
   a.workspace = (float*)workspace;
   a.batch = kv->batch; a.n_heads = c.H; a.head_dim = c.D;
   a.is_lazy = c.lazy[layer];
+  a.inherit_all = c.gla() ? 1 : 0;
+  a.write_q = (c.gla() && c.writes_q(layer)) ? 1 : 0;
   a.generated = kv->generated;
   a.max_len = max_len;
   a.chunk_keys = chunk;
@@ -365,6 +387,7 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   hipError_t err = qc::launch_decode(a, c.dtype, (hipStream_t)stream, kv->timing ? &kv->decode_timer : nullptr);
   if (err != hipSuccess) return fail(QC_EDEVICE, "qc_decode: %s", hipGetErrorString(err));
 
+  if (a.write_q) qc->owner = layer;
   kv->next_layer = layer + 1;
   kv->phase = PH_DECODE;
   if (kv->next_layer == c.N) {
@@ -387,7 +410,8 @@ static void rows_of(const qc_kvcache* kv, int layer, int b, int64_t* rk, int64_t
     case PH_DECODE: len = (int64_t)kv->len0[b] + kv->generated + (layer < kv->next_layer ? 1 : 0); break;
   }
   *rv = len;
-  *rk = len ? len - (c.lazy[layer] ? kv->vis_len[b] : 0) : 0;
+  if (c.gla()) *rk = c.lazy[layer] ? 0 : len;
+  else *rk = len ? len - (c.lazy[layer] ? kv->vis_len[b] : 0) : 0;
 }
 
 qc_status qc_stats(const qc_kvcache* kv, const qc_qcache* qc, qc_stats_t* out) {
@@ -402,7 +426,16 @@ qc_status qc_stats(const qc_kvcache* kv, const qc_qcache* qc, qc_stats_t* out) {
       out->k_bytes += rk * per_row;
       out->v_bytes += rv * per_row;
     }
-    if (qc && qc->owner >= 0) out->q_bytes += (int64_t)kv->vis_len[b] * per_row;
+    if (qc && qc->owner >= 0) {
+      int64_t q_rows = kv->vis_len[b];
+      if (c.gla()) {  // one row per position; the row of the token in flight once a block's first layer has run
+        q_rows = (int64_t)kv->len0[b] + kv->generated;
+        if (kv->phase == PH_DECODE)
+          for (int l = 0; l < kv->next_layer; ++l)
+            if (c.writes_q(l)) { q_rows += 1; break; }
+      }
+      out->q_bytes += q_rows * per_row;
+    }
     if (kv->phase == PH_PREFILL) out->tokens += kv->len0[b];
     else if (kv->phase >= PH_READY) out->tokens += (int64_t)kv->len0[b] + kv->generated;
   }
@@ -464,7 +497,7 @@ qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t 
   int src = layer;
   int64_t row = pos;
   if (c.lazy[layer]) {
-    if (pos >= s && pos < s + vn) src = c.anchor[layer];
+    if (c.gla() || (pos >= s && pos < s + vn)) src = c.anchor[layer];
     else if (pos >= s + vn) row = pos - vn;
   }
   if (row >= c.cap_k(src)) return fail(QC_ECAPACITY, "qc_locate: position %d has no row within the layer's capacity", pos);

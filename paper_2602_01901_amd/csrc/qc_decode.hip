@@ -11,6 +11,11 @@
 // after it are the layer's own (compacted) rows, positions inside it are rows of the block's
 // first layer.  The new token's k/v are taken from the call's inputs, appended to the caches by
 // the one group that owns that position.
+//
+// Global Lazy Attention (Eq. 6): a lazy layer reads its query from row `len` of the Q Cache and
+// every key, the new token's included, from the block's first layer (which appended that row in
+// an earlier launch of the same step); it appends its v row only.  The first layer of a block
+// also stores its query at row `len` of the Q Cache.
 #include "qc_device.h"
 
 namespace qc {
@@ -53,6 +58,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
   const int kend = min(kbeg + a.chunk_keys, len + 1);
   const int s = sm.vis_start, e = sm.vis_start + sm.vis_len;
   const bool lazy = a.is_lazy != 0;
+  const bool all_inherited = lazy && a.inherit_all != 0;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int li = lane % LPR, gid = wave * GPW + lane / LPR;
@@ -65,8 +71,12 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
   const char* vnew = (const char*)a.v + bh * ROWB + li * 16;
 
   float qf[EPL];
+  uint4 qraw;
   {
-    const uint4 raw = *(const uint4*)((const char*)a.q + bh * ROWB + li * 16);
+    const char* qsrc = all_inherited ? a.lv.q_cache + (bh * a.lv.cap_q + len) * ROWB + li * 16
+                                     : (const char*)a.q + bh * ROWB + li * 16;
+    qraw = *(const uint4*)qsrc;
+    const uint4 raw = qraw;
     unpack16(raw, qf, (T*)nullptr);
     const float c = a.scale * kLog2e;
 #pragma unroll
@@ -87,14 +97,20 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
       vr[u] = make_uint4(0, 0, 0, 0);
       if (pos < kend) {
         if (pos == len) {  // the token being decoded: read the inputs, append to the caches
-          kr[u] = *(const uint4*)knew;
           vr[u] = *(const uint4*)vnew;
-          const int krow = lazy ? len - sm.vis_len : len;
-          *(uint4*)(kown + (int64_t)krow * ROWB) = kr[u];
           *(uint4*)(vown + (int64_t)len * ROWB) = vr[u];
+          if (all_inherited) {
+            kr[u] = stream_load16(kanc + (int64_t)len * ROWB);
+          } else {
+            kr[u] = *(const uint4*)knew;
+            const int krow = lazy ? len - sm.vis_len : len;
+            *(uint4*)(kown + (int64_t)krow * ROWB) = kr[u];
+            if (a.write_q) *(uint4*)(a.lv.q_cache + (bh * a.lv.cap_q + len) * ROWB + li * 16) = qraw;
+          }
         } else {
           const char* kp;
-          if (lazy && pos >= s) kp = pos < e ? kanc + (int64_t)pos * ROWB : kown + (int64_t)(pos - sm.vis_len) * ROWB;
+          if (all_inherited) kp = kanc + (int64_t)pos * ROWB;
+          else if (lazy && pos >= s) kp = pos < e ? kanc + (int64_t)pos * ROWB : kown + (int64_t)(pos - sm.vis_len) * ROWB;
           else kp = kown + (int64_t)pos * ROWB;
           kr[u] = stream_load16(kp);
           vr[u] = stream_load16(vown + (int64_t)pos * ROWB);

@@ -83,12 +83,13 @@ template <int kLanes> __device__ __forceinline__ float group_max(float x) {
 struct SeqMeta {
   int32_t tok0, len0, vis_start, vis_len;
 };
-__device__ __forceinline__ SeqMeta load_meta(const LayerView& lv, int b) {
+// With inherit_all (Global Lazy Attention) the span a lazy layer inherits is the whole prompt.
+__device__ __forceinline__ SeqMeta load_meta(const LayerView& lv, int b, int inherit_all = 0) {
   SeqMeta m;
   m.tok0 = lv.meta[META_TOK0 * lv.max_batch + b];
   m.len0 = lv.meta[META_LEN0 * lv.max_batch + b];
-  m.vis_start = lv.meta[META_VIS_START * lv.max_batch + b];
-  m.vis_len = lv.meta[META_VIS_LEN * lv.max_batch + b];
+  m.vis_start = inherit_all ? 0 : lv.meta[META_VIS_START * lv.max_batch + b];
+  m.vis_len = inherit_all ? m.len0 : lv.meta[META_VIS_LEN * lv.max_batch + b];
   return m;
 }
 

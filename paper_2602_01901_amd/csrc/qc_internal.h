@@ -37,6 +37,7 @@ struct PrefillArgs {
   int32_t batch, n_heads, head_dim;
   int32_t is_lazy;        // substitute span rows of q/k, store text rows of k only
   int32_t write_q;        // store span rows of q into the Q Cache
+  int32_t inherit_all;    // Global Lazy Attention: the inherited span is the whole prompt, [0, len)
   int32_t max_len;        // longest prompt in the batch
   float scale;            // softmax scale (already resolved, > 0)
 };
@@ -50,6 +51,9 @@ struct DecodeArgs {
   float* workspace;       // [batch][H][max_chunks][D + 2] partial (o, m, l)
   int32_t batch, n_heads, head_dim;
   int32_t is_lazy;
+  int32_t inherit_all;    // Global Lazy Attention: a lazy layer takes its query from row len of the Q
+                          // Cache and every key (the new token's too) from the block's first layer
+  int32_t write_q;        // store the query at row len of the Q Cache (first layer of a GLA block)
   int32_t generated;      // decode steps completed before this one: len_b = len0_b + generated
   int32_t max_len;        // longest len_b in the batch (before this step)
   int32_t chunk_keys;     // key positions per workgroup

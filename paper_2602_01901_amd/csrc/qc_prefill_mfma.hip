@@ -127,7 +127,7 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
     }
   }
   const int b = bhi / a.n_heads, h = bhi % a.n_heads;
-  const SeqMeta sm = load_meta(a.lv, b);
+  const SeqMeta sm = load_meta(a.lv, b, a.inherit_all);
   const int len = sm.len0;
   const int q0 = qt * BM;
   if (q0 >= len) return;

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void prefill_simple_kernel(PrefillArgs a) {
   __shared__ float Ps[4][RPW][BK];
 
   const int h = blockIdx.y, b = blockIdx.z;
-  const SeqMeta sm = load_meta(a.lv, b);
+  const SeqMeta sm = load_meta(a.lv, b, a.inherit_all);
   const int len = sm.len0;
   const int q0 = blockIdx.x * BQ;
   if (q0 >= len) return;
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256) void prefill_cache_write_kernel(PrefillArgs a)
   constexpr int CPR = D / EPL;
   constexpr int ROWS = 256 / CPR * 4;
   const int h = blockIdx.y, b = blockIdx.z;
-  const SeqMeta sm = load_meta(a.lv, b);
+  const SeqMeta sm = load_meta(a.lv, b, a.inherit_all);
   const int r0 = blockIdx.x * ROWS;
   if (r0 >= sm.len0) return;
   const int64_t bh = (int64_t)b * a.n_heads + h;

@@ -12,7 +12,7 @@ _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 class Session:
     def __init__(self, n_layers, n_heads, head_dim, dtype, lazy_mask, max_batch, max_seq, max_vis, max_text,
-                 device="cuda:0"):
+                 device="cuda:0", mode="vla"):
         if not torch.cuda.is_available():
             raise RuntimeError("the Lazy Attention library needs a GPU; there is no CPU path")
         B.load_library()
@@ -21,8 +21,9 @@ class Session:
         self.torch_dtype = _TORCH_DTYPE[dtype]
         self.n_layers, self.n_heads, self.head_dim = n_layers, n_heads, head_dim
         self.lazy_mask = [int(bool(x)) for x in lazy_mask]
+        self.mode = mode
         self.cfg = B.make_config(n_layers, n_heads, head_dim, dtype, max_batch, max_seq, max_vis, max_text,
-                                 self.lazy_mask)
+                                 self.lazy_mask, mode=mode)
         self.kv_bytes = B.qc_kv_arena_bytes(self.cfg)
         self.q_bytes = B.qc_q_arena_bytes(self.cfg)
         self.ws_bytes = B.qc_decode_workspace_bytes(self.cfg)
@@ -39,9 +40,9 @@ class Session:
         self._ws_ptr = self.workspace.data_ptr()
 
     @classmethod
-    def for_workload(cls, w, device="cuda:0"):
+    def for_workload(cls, w, device="cuda:0", mode="vla"):
         return cls(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.lazy_mask, w.batch, w.max_seq, w.max_vis,
-                   w.max_text, device=device)
+                   w.max_text, device=device, mode=mode)
 
     def _stream(self):
         return torch.cuda.current_stream(self.device).cuda_stream
@@ -54,21 +55,27 @@ class Session:
         B.qc_reset(self.kv, self.qc, self.batch, self.vis_start, self.vis_len, int(zero_fill), self._stream())
 
     def prefill(self, layer, q, k, v, cu_seqlens, out=None, softmax_scale=0.0):
-        """q, k, v: [tokens, H, D] tensors sharing strides.  Returns out."""
+        """q, k, v: [tokens, H, D] tensors sharing strides.  Returns out.  In "gla" mode a lazy
+        layer has no q and k: pass None for both."""
         if out is None:
-            out = torch.empty_like(q)
-        assert q.stride() == k.stride() == v.stride() == out.stride() and q.stride(2) == 1
-        B.qc_prefill(self.kv, self.qc, layer, self.lazy_mask[layer], q, k, v, out, cu_seqlens, q.stride(0),
-                     q.stride(1), self.vis_start, self.vis_len, softmax_scale, self._stream())
+            out = torch.empty_like(v)
+        for t in (q, k, out):
+            assert t is None or t.stride() == v.stride()
+        assert v.stride(2) == 1
+        B.qc_prefill(self.kv, self.qc, layer, self.lazy_mask[layer], q, k, v, out, cu_seqlens, v.stride(0),
+                     v.stride(1), self.vis_start, self.vis_len, softmax_scale, self._stream())
         return out
 
     def decode(self, layer, q, k, v, out=None, softmax_scale=0.0, stream=None):
         """q, k, v: contiguous [B, H, D] tensors.  Returns out.  `stream` (a raw hipStream_t value)
-        defaults to torch's current stream; tight loops may pass it to skip the lookup."""
+        defaults to torch's current stream; tight loops may pass it to skip the lookup.  In "gla" mode a
+        lazy layer has no q and k: pass None for both."""
         if out is None:
-            out = torch.empty_like(q)
-        assert q.is_contiguous() and k.is_contiguous() and v.is_contiguous() and out.is_contiguous()
-        status = self._lib.qc_decode(self.kv, self.qc, layer, self.lazy_mask[layer], q.data_ptr(), k.data_ptr(),
+            out = torch.empty_like(v)
+        assert v.is_contiguous() and out.is_contiguous()
+        assert (q is None or q.is_contiguous()) and (k is None or k.is_contiguous())
+        status = self._lib.qc_decode(self.kv, self.qc, layer, self.lazy_mask[layer],
+                                     None if q is None else q.data_ptr(), None if k is None else k.data_ptr(),
                                      v.data_ptr(), out.data_ptr(), self._vs_c, self._vl_c, softmax_scale,
                                      self._ws_ptr, self.ws_bytes, self._stream() if stream is None else stream)
         if status != B.QC_OK:

@@ -4,18 +4,22 @@ import torch
 
 import workloads
 from oracle import layout as olayout
+from oracle.global_lazy_stack import GlobalLazyStackOracle
 from oracle.lazy_stack import LazyStackOracle
 
 TOL = {"f32": 1e-4, "bf16": 3e-2}   # max-abs-error bars for outputs (fp32 / bf16 storage)
 
 
-def oracle_layout(w):
+def oracle_layout(w, mode="vla"):
     return olayout.ArenaLayout(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.batch, w.max_seq, w.max_vis,
-                               w.max_text, w.lazy_mask)
+                               w.max_text, w.lazy_mask, mode=mode)
 
 
-def new_oracles(w, heads=None):
+def new_oracles(w, heads=None, mode="vla"):
     H = w.n_heads if heads is None else len(heads)
+    if mode == "gla":
+        return [GlobalLazyStackOracle(w.n_layers, H, w.head_dim, w.lazy_mask, vis_start=w.vis_start[b],
+                                      vis_len=w.vis_len[b]) for b in range(w.batch)]
     return [LazyStackOracle(w.n_layers, H, w.head_dim, w.lazy_mask, w.vis_start[b], w.vis_len[b])
             for b in range(w.batch)]
 
@@ -42,17 +46,23 @@ def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=Tru
     """Prefill every layer then `decode_steps` decode steps on both sides; returns worst errors.
 
     With poison_span the span rows of q and k handed to lazy layers hold NaN on the GPU side
-    (the oracle gets the clean tensors): lazy layers must never read them.
+    (the oracle gets the clean tensors): lazy layers must never read them.  A session in "gla"
+    mode is checked against the Global Lazy Attention oracle; its lazy layers get no q and k at
+    all (None), or, with poison_span, tensors that are NaN everywhere.
     """
     dev = session.device
-    stacks = new_oracles(w)
+    mode = session.mode
+    gla = mode == "gla"
+    stacks = new_oracles(w, mode=mode)
     session.reset(w.vis_start, w.vis_len, zero_fill=True)
     worst_p = worst_d = 0.0
     for l in range(w.n_layers):
         q, k, v = workloads.prefill_qkv(w, l)
         ref = oracle_prefill_layer(w, stacks, l, q, k, v)
         qg, kg, vg = q.to(dev), k.to(dev), v.to(dev)
-        if poison_span and w.lazy_mask[l]:
+        if gla and w.lazy_mask[l]:
+            qg, kg = (qg * float("nan"), kg * float("nan")) if poison_span else (None, None)
+        elif poison_span and w.lazy_mask[l]:
             cu = w.cu_seqlens
             for b in range(w.batch):
                 s, e = cu[b] + w.vis_start[b], cu[b] + w.vis_start[b] + w.vis_len[b]
@@ -66,13 +76,16 @@ def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=Tru
         for l in range(w.n_layers):
             q, k, v = workloads.decode_qkv(w, l, t)
             ref = oracle_decode_layer(w, stacks, l, q, k, v)
-            out = session.decode(l, q.to(dev), k.to(dev), v.to(dev))
+            qg, kg = q.to(dev), k.to(dev)
+            if gla and w.lazy_mask[l]:
+                qg, kg = (qg * float("nan"), kg * float("nan")) if poison_span else (None, None)
+            out = session.decode(l, qg, kg, v.to(dev))
             err = max_abs_err(out, ref)
             assert np.isfinite(err)
             worst_d = max(worst_d, err)
     torch.cuda.synchronize()
     if check_arena:
-        lay = oracle_layout(w)
+        lay = oracle_layout(w, mode)
         want_kv = olayout.kv_arena_image(lay, stacks)
         got_kv = session.kv_arena.cpu().numpy()
         assert got_kv.shape == want_kv.shape

@@ -183,3 +183,53 @@ def test_timing_api_validation():
     assert B.qc_timing_read(kv, 0) == (0.0, 0)      # nothing recorded, no HIP call needed
     with pytest.raises(P.QcError):
         B.qc_timing_enable(None, 1)
+
+
+# ---------------------------------------------------------------------------
+# Global Lazy Attention mode
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("c", CONFIGS)
+def test_gla_arena_sizes_and_row_map_match_oracle_layout(c):
+    cfg = P.make_config(*c, mode="gla")
+    lay = ArenaLayout(*c, mode="gla")
+    assert B.qc_kv_arena_bytes(cfg) == lay.kv_arena_bytes()
+    assert B.qc_q_arena_bytes(cfg) == lay.q_arena_bytes()
+    assert B.qc_kv_arena_bytes(cfg) < B.qc_kv_arena_bytes(P.make_config(*c))
+    kv = B.qc_kvcache_create(cfg, FAKE, B.qc_kv_arena_bytes(cfg))
+    qc = B.qc_qcache_create(cfg, FAKE, B.qc_q_arena_bytes(cfg))
+    N, H, batch, max_seq = c[0], c[1], c[4], c[5]
+    B.qc_reset(kv, qc, batch, [1] * batch, [2] * batch, zero_fill=0)
+    for l in range(N):
+        for pos in (0, 1, 2, 3, max_seq - 1):
+            want = lay.locate_k(l, batch - 1, H - 1, pos, 1, 2)
+            assert B.qc_locate(kv, B.QC_K, l, batch - 1, H - 1, pos) == want
+            assert want[0] == (lay.anchor(l) if c[8][l] else l)
+    B.qc_kvcache_destroy(kv)
+    B.qc_qcache_destroy(qc)
+
+
+def test_gla_config_and_call_validation():
+    c = CONFIGS[1]  # mask [0,1,0]
+    bad = P.make_config(*c, mode=2)
+    assert B.qc_kv_arena_bytes(bad) == 0
+    cfg = P.make_config(*c, mode="gla")
+    kv = B.qc_kvcache_create(cfg, FAKE, B.qc_kv_arena_bytes(cfg))
+    qc = B.qc_qcache_create(cfg, FAKE, B.qc_q_arena_bytes(cfg))
+    vla_cfg = P.make_config(*c)
+    qc_vla = B.qc_qcache_create(vla_cfg, FAKE, B.qc_q_arena_bytes(vla_cfg))
+    with pytest.raises(P.QcError) as e:
+        B.qc_reset(kv, qc_vla, 1, [0], [3], 0)        # the two handles disagree on the mode
+    assert e.value.status == B.QC_EINVAL
+    B.qc_reset(kv, qc, 1, [0], [40], 0)               # more visual tokens than max_vis: no limit under GLA
+    H, D = 2, 128
+    with pytest.raises(P.QcError) as e:               # an ordinary layer still needs q and k
+        B.qc_prefill(kv, qc, 0, 0, None, FAKE, FAKE, FAKE, [0, 60], H * D, D, [0], [40])
+    assert e.value.status == B.QC_EINVAL
+    with pytest.raises(P.QcError) as e:               # decode before prefill, and without the Q Cache handle
+        B.qc_decode(kv, None, 0, 0, FAKE, FAKE, FAKE, FAKE, [0], [40], 0.0, FAKE, 1 << 20)
+    assert e.value.status == B.QC_EINVAL
+    with pytest.raises(P.QcError) as e:
+        B.qc_decode(kv, qc, 0, 0, FAKE, FAKE, FAKE, FAKE, [0], [40], 0.0, FAKE, 1 << 20)
+    assert e.value.status == B.QC_EORDER
+    st = B.qc_stats(kv, qc)
+    assert st["next_layer"] == 0 and st["q_owner"] == -1
