@@ -116,7 +116,8 @@ typedef struct qc_stats_t {
  * Q arena: [max_batch][n_heads][max_vis][head_dim] (one layer's worth, visual rows only).
  * Under QC_GLA: capK(l) = 0 for a lazy layer, and the Q arena is
  *   [max_batch][n_heads][max_seq][head_dim] with row = token position.
- * Decode workspace: split partial results, fp32. */
+ * Decode workspace: split partial results, fp32; under QC_GLA followed by one fp32 score per
+ *   position, [max_batch][n_heads][max_seq]. */
 size_t qc_kv_arena_bytes(const qc_config* cfg);
 size_t qc_q_arena_bytes(const qc_config* cfg);
 size_t qc_decode_workspace_bytes(const qc_config* cfg);
@@ -169,11 +170,14 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
  * decode query is a text token); qc may be NULL.  After layer n_layers-1 every length grows by 1.
  * workspace: DEVICE, at least qc_decode_workspace_bytes(cfg), contents undefined between calls.
  * Under QC_GLA (paper Eq. 6) qc is required.  An ordinary layer followed by a lazy one also stores
- *   its query at row len of the Q Cache, which from then on belongs to it.  A lazy layer attends
- *   with that row and with the K cache of its block's first layer (rows 0..len, the last one
- *   appended by that layer earlier in the same step, on the same stream), appends only its v row;
- *   its q and k arguments are ignored and may be NULL.  QC_EORDER if the Q Cache belongs to
- *   another block. */
+ *   its query at row len of the Q Cache, which from then on belongs to it, and its scaled scores
+ *   q.k of positions 0..len in the workspace.  A lazy layer attends with that query and with the
+ *   K cache of its block's first layer, that is with exactly those scores: it reads them back
+ *   instead of the keys (the product of Eq. 6 is formed once per block), streams only its own V
+ *   cache and appends only its v row; its q and k arguments are ignored and may be NULL.  The
+ *   layers of a block must therefore be given the same workspace on the same stream (QC_EINVAL
+ *   otherwise), and nothing else may write to it between them.  QC_EORDER if the Q Cache belongs
+ *   to another block. */
 qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_lazy, const void* q,
                     const void* k, const void* v, void* out, const int32_t* vis_start,
                     const int32_t* vis_len, float softmax_scale, void* workspace,

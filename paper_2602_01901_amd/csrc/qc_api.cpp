@@ -102,6 +102,7 @@ struct qc_kvcache {
   std::vector<int32_t> vis_start, vis_len, len0, tok0;
   bool timing = false;
   qc::KernelTimer prefill_timer, decode_timer;
+  const void* score_workspace = nullptr;  // workspace the current block's scores were written to (GLA)
 };
 
 struct qc_qcache {
@@ -135,11 +136,18 @@ size_t qc_q_arena_bytes(const qc_config* cfg) {
   return parse_config(cfg, &c) ? (size_t)c.q_bytes() : 0;
 }
 
+// Decode workspace: the split partials, then (Global Lazy Attention only) one float per position
+// of every (sequence, head): the scaled scores of the block whose first layer ran last.
+static int64_t partial_bytes(const Config& c) {
+  int64_t chunks = (c.max_seq + kMinChunkKeys - 1) / kMinChunkKeys;
+  return (int64_t)c.max_batch * c.H * chunks * (c.D + 2) * 4;
+}
+static int64_t score_bytes(const Config& c) { return c.gla() ? (int64_t)c.max_batch * c.H * c.max_seq * 4 : 0; }
+
 size_t qc_decode_workspace_bytes(const qc_config* cfg) {
   Config c;
   if (!parse_config(cfg, &c)) return 0;
-  int64_t chunks = (c.max_seq + kMinChunkKeys - 1) / kMinChunkKeys;
-  return (size_t)((int64_t)c.max_batch * c.H * chunks * (c.D + 2) * 4);
+  return (size_t)(partial_bytes(c) + score_bytes(c));
 }
 
 qc_status qc_kvcache_create(const qc_config* cfg, void* dev_arena, size_t arena_bytes, qc_kvcache** out) {
@@ -204,6 +212,7 @@ qc_status qc_reset(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* 
   kv->phase = PH_RESET;
   kv->next_layer = 0;
   kv->generated = 0;
+  kv->score_workspace = nullptr;
   qc->owner = -1;
   return QC_OK;
 }
@@ -362,7 +371,10 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   int32_t chunk = (int32_t)round_up(per < kMinChunkKeys ? kMinChunkKeys : per, kMinChunkKeys);
   int32_t max_chunks = (max_len + 1 + chunk - 1) / chunk;
   size_t need = (size_t)kv->batch * c.H * max_chunks * (c.D + 2) * 4;
+  if (c.gla()) need = (size_t)(partial_bytes(c) + score_bytes(c));
   if (workspace_bytes < need) return fail(QC_ECAPACITY, "qc_decode: workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+  if (qk_unused && kv->score_workspace != workspace)
+    return fail(QC_EINVAL, "qc_decode: layer %d needs the workspace its block's first layer was called with", layer);
 
   qc::DecodeArgs a;
   a.lv = make_view(kv, c.gla() ? qc : nullptr, layer);
@@ -372,6 +384,10 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   a.is_lazy = c.lazy[layer];
   a.inherit_all = c.gla() ? 1 : 0;
   a.write_q = (c.gla() && c.writes_q(layer)) ? 1 : 0;
+  a.scores = c.gla() ? (float*)((char*)workspace + partial_bytes(c)) : nullptr;
+  a.score_stride = c.max_seq;
+  a.store_scores = a.write_q;
+  a.use_scores = qk_unused ? 1 : 0;
   a.generated = kv->generated;
   a.max_len = max_len;
   a.chunk_keys = chunk;
@@ -387,7 +403,10 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   hipError_t err = qc::launch_decode(a, c.dtype, (hipStream_t)stream, kv->timing ? &kv->decode_timer : nullptr);
   if (err != hipSuccess) return fail(QC_EDEVICE, "qc_decode: %s", hipGetErrorString(err));
 
-  if (a.write_q) qc->owner = layer;
+  if (a.write_q) {
+    qc->owner = layer;
+    kv->score_workspace = workspace;
+  }
   kv->next_layer = layer + 1;
   kv->phase = PH_DECODE;
   if (kv->next_layer == c.N) {

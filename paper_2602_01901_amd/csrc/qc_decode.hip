@@ -12,10 +12,12 @@
 // first layer.  The new token's k/v are taken from the call's inputs, appended to the caches by
 // the one group that owns that position.
 //
-// Global Lazy Attention (Eq. 6): a lazy layer reads its query from row `len` of the Q Cache and
-// every key, the new token's included, from the block's first layer (which appended that row in
-// an earlier launch of the same step); it appends its v row only.  The first layer of a block
-// also stores its query at row `len` of the Q Cache.
+// Global Lazy Attention (Eq. 6): a lazy layer attends with the query and the keys of its block's
+// first layer, so its scores q.k are the ones that layer computed earlier in the same step.  The
+// first layer of a block therefore stores its scaled scores (one float per position) next to the
+// split partials and its query at row `len` of the Q Cache; a lazy layer (SHARED instantiation)
+// reads those scores instead of any key row: it streams V only, half the bytes, and gets
+// bit-identical scores.  It appends its v row only.
 #include "qc_device.h"
 
 namespace qc {
@@ -41,7 +43,7 @@ __device__ __forceinline__ SeqMeta decode_meta(const DecodeArgs& a, int b) {
   return load_meta(a.lv, b);
 }
 
-template <typename T, int D>
+template <typename T, int D, bool SHARED>
 __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
   constexpr int EPL = ElemTraits<T>::kPer16;  // elements per lane (16 bytes)
   constexpr int LPR = D / EPL;                // lanes per row
@@ -58,7 +60,6 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
   const int kend = min(kbeg + a.chunk_keys, len + 1);
   const int s = sm.vis_start, e = sm.vis_start + sm.vis_len;
   const bool lazy = a.is_lazy != 0;
-  const bool all_inherited = lazy && a.inherit_all != 0;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int li = lane % LPR, gid = wave * GPW + lane / LPR;
@@ -70,14 +71,13 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
   const char* knew = (const char*)a.k + bh * ROWB + li * 16;
   const char* vnew = (const char*)a.v + bh * ROWB + li * 16;
 
+  float* score_row = (SHARED || a.store_scores) ? a.scores + bh * a.score_stride : nullptr;
+
   float qf[EPL];
-  uint4 qraw;
-  {
-    const char* qsrc = all_inherited ? a.lv.q_cache + (bh * a.lv.cap_q + len) * ROWB + li * 16
-                                     : (const char*)a.q + bh * ROWB + li * 16;
-    qraw = *(const uint4*)qsrc;
-    const uint4 raw = qraw;
-    unpack16(raw, qf, (T*)nullptr);
+  uint4 qraw = make_uint4(0, 0, 0, 0);
+  if (!SHARED) {
+    qraw = *(const uint4*)((const char*)a.q + bh * ROWB + li * 16);
+    unpack16(qraw, qf, (T*)nullptr);
     const float c = a.scale * kLog2e;
 #pragma unroll
     for (int i = 0; i < EPL; ++i) qf[i] *= c;
@@ -90,44 +90,51 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
 
   for (int r0 = kbeg + gid; r0 < kend; r0 += GROUPS * U) {
     uint4 kr[U], vr[U];
+    float sc[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int pos = r0 + u * GROUPS;
       kr[u] = make_uint4(0, 0, 0, 0);
       vr[u] = make_uint4(0, 0, 0, 0);
+      sc[u] = -INFINITY;
       if (pos < kend) {
+        if (SHARED) sc[u] = score_row[pos];
         if (pos == len) {  // the token being decoded: read the inputs, append to the caches
           vr[u] = *(const uint4*)vnew;
           *(uint4*)(vown + (int64_t)len * ROWB) = vr[u];
-          if (all_inherited) {
-            kr[u] = stream_load16(kanc + (int64_t)len * ROWB);
-          } else {
+          if (!SHARED) {
             kr[u] = *(const uint4*)knew;
             const int krow = lazy ? len - sm.vis_len : len;
             *(uint4*)(kown + (int64_t)krow * ROWB) = kr[u];
             if (a.write_q) *(uint4*)(a.lv.q_cache + (bh * a.lv.cap_q + len) * ROWB + li * 16) = qraw;
           }
         } else {
-          const char* kp;
-          if (all_inherited) kp = kanc + (int64_t)pos * ROWB;
-          else if (lazy && pos >= s) kp = pos < e ? kanc + (int64_t)pos * ROWB : kown + (int64_t)(pos - sm.vis_len) * ROWB;
-          else kp = kown + (int64_t)pos * ROWB;
-          kr[u] = stream_load16(kp);
+          if (!SHARED) {
+            const char* kp;
+            if (lazy && pos >= s) kp = pos < e ? kanc + (int64_t)pos * ROWB : kown + (int64_t)(pos - sm.vis_len) * ROWB;
+            else kp = kown + (int64_t)pos * ROWB;
+            kr[u] = stream_load16(kp);
+          }
           vr[u] = stream_load16(vown + (int64_t)pos * ROWB);
         }
       }
     }
-    float sc[U];
     float mt = -INFINITY;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float kf[EPL];
-      unpack16(kr[u], kf, (T*)nullptr);
-      float d = 0.f;
+      if (!SHARED) {
+        float kf[EPL];
+        unpack16(kr[u], kf, (T*)nullptr);
+        float d = 0.f;
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) d = fmaf(qf[i], kf[i], d);
-      d = group_sum<LPR>(d);
-      sc[u] = (r0 + u * GROUPS < kend) ? d : -INFINITY;
+        for (int i = 0; i < EPL; ++i) d = fmaf(qf[i], kf[i], d);
+        d = group_sum<LPR>(d);
+        const int pos = r0 + u * GROUPS;
+        if (pos < kend) {
+          sc[u] = d;
+          if (a.store_scores && li == 0) score_row[pos] = d;
+        }
+      }
       mt = fmaxf(mt, sc[u]);
     }
     const float mn = fmaxf(m, mt);  // finite: the first row of every iteration is valid
@@ -224,7 +231,8 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
 template <typename T, int D> static hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t stream, KernelTimer* timer) {
   dim3 grid(a.max_chunks, a.n_heads, a.batch);
   if (timer) timer->begin(stream);
-  hipLaunchKernelGGL((decode_split_kernel<T, D>), grid, dim3(256), 0, stream, a);
+  if (a.use_scores) hipLaunchKernelGGL((decode_split_kernel<T, D, true>), grid, dim3(256), 0, stream, a);
+  else hipLaunchKernelGGL((decode_split_kernel<T, D, false>), grid, dim3(256), 0, stream, a);
   if (timer) timer->end(stream);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.max_chunks == 1) return e;

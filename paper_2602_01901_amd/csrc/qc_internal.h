@@ -49,10 +49,13 @@ struct DecodeArgs {
   const void* v;
   void* out;
   float* workspace;       // [batch][H][max_chunks][D + 2] partial (o, m, l)
+  float* scores;          // [batch][H][score_stride] scaled scores of the current step (GLA), else nullptr
+  int32_t score_stride;   // floats per (sequence, head) in `scores`
+  int32_t store_scores;   // first layer of a GLA block: write the score of every position
+  int32_t use_scores;     // lazy GLA layer: take the scores from `scores` instead of reading keys
   int32_t batch, n_heads, head_dim;
   int32_t is_lazy;
-  int32_t inherit_all;    // Global Lazy Attention: a lazy layer takes its query from row len of the Q
-                          // Cache and every key (the new token's too) from the block's first layer
+  int32_t inherit_all;    // Global Lazy Attention: a lazy layer shares query and keys of the block's first layer
   int32_t write_q;        // store the query at row len of the Q Cache (first layer of a GLA block)
   int32_t generated;      // decode steps completed before this one: len_b = len0_b + generated
   int32_t max_len;        // longest len_b in the batch (before this step)

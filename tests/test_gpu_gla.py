@@ -94,3 +94,34 @@ def test_gla_order_error_when_the_q_cache_belongs_to_another_block():
         s.decode(3, None, None, v)
     assert e.value.status == B.QC_EORDER
     torch.cuda.synchronize()
+
+
+def test_gla_lazy_decode_reads_no_key_rows():
+    """Between a block's first layer and its lazy layers the whole K region is overwritten with NaN
+    bit patterns: the lazy layers must give the same bits as in an untouched twin session, because
+    they reuse the block's scores and stream only their own V rows."""
+    w = workloads.custom("gla_nokeys", 3, 2, 128, "bf16", [2], [100], [333], 2, [0, 1, 1])
+    sessions = [gla_session(w), gla_session(w)]
+    for s in sessions:
+        s.reset(w.vis_start, w.vis_len)
+        for l in range(w.n_layers):
+            q, k, v = (t.cuda() for t in workloads.prefill_qkv(w, l))
+            s.prefill(l, None if w.lazy_mask[l] else q, None if w.lazy_mask[l] else k, v, w.cu_seqlens)
+    k_region_bytes = B.qc_locate(sessions[0].kv, B.QC_V, 0, 0, 0, 0)[1]   # the V region starts where K ends
+    for t in range(2):
+        outs = []
+        for i, s in enumerate(sessions):
+            q, k, v = (x.cuda() for x in workloads.decode_qkv(w, 0, t))
+            acc = [s.decode(0, q, k, v).clone()]
+            saved = None
+            if i == 1:
+                saved = s.kv_arena[:k_region_bytes].clone()
+                s.kv_arena[:k_region_bytes] = 0xFF
+            for l in (1, 2):
+                acc.append(s.decode(l, None, None, workloads.decode_qkv(w, l, t)[2].cuda()).clone())
+            if saved is not None:
+                s.kv_arena[:k_region_bytes] = saved
+            outs.append(acc)
+        for a, b in zip(*outs):
+            assert torch.isfinite(a.float()).all() and torch.equal(a, b)
+    torch.cuda.synchronize()
