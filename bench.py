@@ -55,13 +55,15 @@ def decode_bytes_per_layer(w, generated):
 class Runner:
     """Holds resident inputs for one workload and drives the library."""
 
-    def __init__(self, w, decode_steps, distinct_decode_inputs=8):
+    def __init__(self, w, decode_steps, distinct_decode_inputs=8, mode="vla"):
         import torch
         import paper_2602_01901_amd as P
         import workloads
         self.torch, self.w = torch, w
         self.decode_steps = decode_steps
-        self.sess = P.Session.for_workload(w)
+        self.sess = P.Session.for_workload(w, mode=mode)
+        # Global Lazy Attention: a lazy layer has no q and k of its own
+        self.no_qk = [mode == "gla" and bool(f) for f in w.lazy_mask]
         dev = self.sess.device
         self.pre = [workloads.prefill_qkv(w, l, device=dev) for l in range(w.n_layers)]
         self.out_pre = torch.empty_like(self.pre[0][0])
@@ -75,6 +77,8 @@ class Runner:
         s.reset(w.vis_start, w.vis_len, zero_fill=False)
         for l in range(w.n_layers):
             q, k, v = self.pre[l]
+            if self.no_qk[l]:
+                q = k = None
             s.prefill(l, q, k, v, w.cu_seqlens, out=self.out_pre)
 
     def decode_steps_run(self, steps):
@@ -84,6 +88,8 @@ class Runner:
             row = self.dec[t % len(self.dec)]
             for l in range(w.n_layers):
                 q, k, v = row[l]
+                if self.no_qk[l]:
+                    q = k = None
                 s.decode(l, q, k, v, out=self.out_dec, stream=stream)
 
     def step(self):
@@ -97,10 +103,11 @@ class Runner:
         B.qc_timing_enable(self.sess.kv, 1)
         B.qc_timing_read(self.sess.kv, 0)
         B.qc_timing_read(self.sess.kv, 1)
+        B.qc_timing_read(self.sess.kv, 2)
         fn()
         self.torch.cuda.synchronize()
         out = {}
-        for name, which in (("prefill", 0), ("decode", 1)):
+        for name, which in (("prefill", 0), ("decode", 1), ("decode_shared", 2)):
             ms, n = B.qc_timing_read(self.sess.kv, which)
             out[name] = (ms * 1e3 / n if n else 0.0, n)
         B.qc_timing_enable(self.sess.kv, 0)
@@ -207,12 +214,62 @@ def bench_decode_batched(args):
     return res
 
 
-def bench_prefill_highres(args, w=None, traffic_key="prefill_cfg4", layers=None):
+def gla_shared_decode_bytes_per_layer(w, generated):
+    """Lazy layer under Global Lazy Attention: V rows and one fp32 score per position streamed once,
+    v in, o out, v appended: sum_b ((L_b+1+3)*D*e + (L_b+1)*4) * H."""
+    return sum(((L + generated + 4) * w.head_dim * w.elem_bytes + (L + generated + 1) * 4) * w.n_heads
+               for L in w.seq_len)
+
+
+def bench_gla_decode_batched(args):
+    """The batched-decode configuration under Global Lazy Attention: lazy layers reuse the scores of
+    their block's first layer and stream only their V cache."""
+    import torch
+    import workloads
+    w = workloads.config(2)
+    steps = args.decode_batched_steps
+    r = Runner(w, steps, distinct_decode_inputs=4, mode="gla")
+    r.prefill_stack()
+    r.decode_steps_run(2)
+    torch.cuda.synchronize()
+    g0 = r.sess.stats()["generated"]
+    _, ev_s = timed(torch, lambda: r.decode_steps_run(steps), 1)
+    g1 = r.sess.stats()["generated"]
+    kt = r.kernel_times(lambda: r.decode_steps_run(4))
+    sh_us, sh_n = kt["decode_shared"]
+    od_us, od_n = kt["decode"]
+    sh_bytes = sum(gla_shared_decode_bytes_per_layer(w, g1 + t) for t in range(4)) / 4
+    od_bytes = sum(decode_bytes_per_layer(w, g1 + t) for t in range(4)) / 4
+    n_lazy = w.n_lazy
+    step_bytes = sum((w.n_layers - n_lazy) * decode_bytes_per_layer(w, g0 + t) +
+                     n_lazy * gla_shared_decode_bytes_per_layer(w, g0 + t) for t in range(steps)) / steps
+    stats = r.sess.stats()
+    achieved = sh_bytes / (sh_us * 1e-6) / 1e9
+    res = {
+        "workload": w.name + " (GLA)", "batch": w.batch, "decode_steps_timed": steps,
+        "decode_tokens_per_s": w.batch * steps / ev_s,
+        "decode_ms_per_step": ev_s / steps * 1e3,
+        "stack_GBps": step_bytes / (ev_s / steps) / 1e9,
+        "k_cache_bytes_per_token": stats["k_bytes"] / stats["tokens"],
+        "q_cache_bytes_per_token": stats["q_bytes"] / stats["tokens"],
+        "ordinary_layer_kernel": {"avg_launch_us": od_us, "launches_timed": od_n,
+                                  "GBps": od_bytes / (od_us * 1e-6) / 1e9 if od_us else None},
+        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<bf16,128,shared scores> (lazy layers: whole layer call)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic("gla_decode_cfg3"), "avg_launch_us": sh_us, "launches_timed": sh_n,
+                     "algorithmic_bytes_per_launch": sh_bytes},
+    }
+    del r
+    torch.cuda.empty_cache()
+    return res
+
+
+def bench_prefill_highres(args, w=None, traffic_key="prefill_cfg4", layers=None, mode="vla"):
     """Batch-8, 3008-token prefill (MFMA-bound); also used for the other prefill shapes."""
     import torch
     import workloads
     w = w or workloads.config(3)
-    r = Runner(w, 0)
+    r = Runner(w, 0, mode=mode)
     r.prefill_stack()
     torch.cuda.synchronize()
     reps = args.prefill_reps
@@ -223,7 +280,7 @@ def bench_prefill_highres(args, w=None, traffic_key="prefill_cfg4", layers=None)
     stats = r.sess.stats()
     achieved = flops_layer / (call_us * 1e-6) / 1e12
     res = {
-        "workload": w.name, "batch": w.batch, "seq_len": w.seq_len[0],
+        "workload": w.name + (" (GLA)" if mode == "gla" else ""), "batch": w.batch, "seq_len": w.seq_len[0],
         "prefill_ms": ev_s * 1e3, "prefill_tflops": flops_layer * w.n_layers / ev_s / 1e12,
         "k_cache_bytes_per_token": stats["k_bytes"] / stats["tokens"],
         "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel (attention + fused cache writes: whole layer call)",
@@ -313,7 +370,7 @@ def main():
     ap.add_argument("--prefill-reps", type=int, default=3)
     ap.add_argument("--skip-extra", action="store_true", help="headline workload only")
     ap.add_argument("--skip-cpu", action="store_true")
-    ap.add_argument("--only", choices=["decode_batched", "prefill_highres"],
+    ap.add_argument("--only", choices=["decode_batched", "prefill_highres", "gla_decode_batched"],
                     help="profiling aid: run just this extra workload and print its object")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profiling aid: run plain 1 GiB device copies (known HBM traffic) and exit")
@@ -338,7 +395,8 @@ def main():
                                                "launches": 5}}))
         return
     if args.only:
-        fn = {"decode_batched": bench_decode_batched, "prefill_highres": bench_prefill_highres}[args.only]
+        fn = {"decode_batched": bench_decode_batched, "prefill_highres": bench_prefill_highres,
+              "gla_decode_batched": bench_gla_decode_batched}[args.only]
         print(json.dumps({args.only: fn(args)}))
         return
 
@@ -356,6 +414,11 @@ def main():
                                                                  extra["video_13b"]["decode_tokens_per_s"]))
         extra["prefill_long_32k"] = bench_prefill_long(args)
         log("32k prompt done: %.1f TFLOP/s" % extra["prefill_long_32k"]["prefill_tflops"])
+        extra["gla_decode_batched"] = bench_gla_decode_batched(args)
+        log("GLA cfg3 done: %.1f tok/s, lazy layers %.0f GB/s" % (extra["gla_decode_batched"]["decode_tokens_per_s"],
+                                                                 extra["gla_decode_batched"]["roofline"]["achieved"]))
+        extra["gla_prefill_highres"] = bench_prefill_highres(args, traffic_key="gla_prefill_cfg4", mode="gla")
+        log("GLA cfg4 done: %.1f TFLOP/s" % extra["gla_prefill_highres"]["prefill_tflops"])
     cpu = None if args.skip_cpu else cpu_baseline()
     line = {
         "metric": "decode_tokens_per_s", "value": r["decode_tokens_per_s"], "unit": "tokens/s",

@@ -116,8 +116,8 @@ typedef struct qc_stats_t {
  * Q arena: [max_batch][n_heads][max_vis][head_dim] (one layer's worth, visual rows only).
  * Under QC_GLA: capK(l) = 0 for a lazy layer, and the Q arena is
  *   [max_batch][n_heads][max_seq][head_dim] with row = token position.
- * Decode workspace: split partial results, fp32; under QC_GLA followed by one fp32 score per
- *   position, [max_batch][n_heads][max_seq]. */
+ * Decode workspace: split partial results, fp32; under QC_GLA followed (256-byte aligned) by one
+ *   fp32 score per position, [max_batch][n_heads][max_seq rounded up to a multiple of 8]. */
 size_t qc_kv_arena_bytes(const qc_config* cfg);
 size_t qc_q_arena_bytes(const qc_config* cfg);
 size_t qc_decode_workspace_bytes(const qc_config* cfg);
@@ -199,8 +199,9 @@ qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t 
  * While enabled, qc_prefill and qc_decode record a pair of HIP events on the call's stream around
  * their dominant kernel (prefill: the attention kernel; decode: the kernel that streams the caches,
  * not the small merge pass).  qc_timing_read waits for the recorded events of one kind (which = 0
- * prefill, 1 decode), returns the sum of their durations and the number of launches, and starts
- * over.  At most 16384 launches are kept between reads; further ones are not timed.  Event
+ * prefill, 1 decode, 2 decode calls of lazy layers under QC_GLA, which run the score-sharing
+ * variant of the kernel and are not counted under 1), returns the sum of their durations and the
+ * number of launches, and starts over.  At most 16384 launches are kept between reads; further ones are not timed.  Event
  * creation allocates: leave this off on paths that must not. */
 qc_status qc_timing_enable(qc_kvcache* kv, int32_t enable);
 qc_status qc_timing_read(qc_kvcache* kv, int32_t which, double* total_ms, int64_t* launches);

@@ -201,7 +201,8 @@ def qc_timing_enable(kv, enable):
 
 
 def qc_timing_read(kv, which):
-    """(total milliseconds, launches) of the dominant kernel since the last read; which: 0 prefill, 1 decode."""
+    """(total milliseconds, launches) of the dominant kernel since the last read; which: 0 prefill, 1 decode,
+    2 decode calls of lazy layers in "gla" mode."""
     ms, n = ctypes.c_double(), c_int64()
     _check(load_library().qc_timing_read(kv, which, byref(ms), byref(n)))
     return ms.value, n.value

@@ -101,7 +101,7 @@ struct qc_kvcache {
   int32_t generated = 0;
   std::vector<int32_t> vis_start, vis_len, len0, tok0;
   bool timing = false;
-  qc::KernelTimer prefill_timer, decode_timer;
+  qc::KernelTimer prefill_timer, decode_timer, decode_shared_timer;
   const void* score_workspace = nullptr;  // workspace the current block's scores were written to (GLA)
 };
 
@@ -138,11 +138,15 @@ size_t qc_q_arena_bytes(const qc_config* cfg) {
 
 // Decode workspace: the split partials, then (Global Lazy Attention only) one float per position
 // of every (sequence, head): the scaled scores of the block whose first layer ran last.
+// The score rows are read and written 16 bytes at a time in runs of 8 positions: the row stride is
+// max_seq rounded up to 8 floats and the region starts 256-byte aligned.
 static int64_t partial_bytes(const Config& c) {
   int64_t chunks = (c.max_seq + kMinChunkKeys - 1) / kMinChunkKeys;
-  return (int64_t)c.max_batch * c.H * chunks * (c.D + 2) * 4;
+  int64_t b = (int64_t)c.max_batch * c.H * chunks * (c.D + 2) * 4;
+  return c.gla() ? round_up(b, 256) : b;
 }
-static int64_t score_bytes(const Config& c) { return c.gla() ? (int64_t)c.max_batch * c.H * c.max_seq * 4 : 0; }
+static int64_t score_stride(const Config& c) { return round_up(c.max_seq, 8); }
+static int64_t score_bytes(const Config& c) { return c.gla() ? (int64_t)c.max_batch * c.H * score_stride(c) * 4 : 0; }
 
 size_t qc_decode_workspace_bytes(const qc_config* cfg) {
   Config c;
@@ -385,7 +389,7 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   a.inherit_all = c.gla() ? 1 : 0;
   a.write_q = (c.gla() && c.writes_q(layer)) ? 1 : 0;
   a.scores = c.gla() ? (float*)((char*)workspace + partial_bytes(c)) : nullptr;
-  a.score_stride = c.max_seq;
+  a.score_stride = (int32_t)score_stride(c);
   a.store_scores = a.write_q;
   a.use_scores = qk_unused ? 1 : 0;
   a.generated = kv->generated;
@@ -400,7 +404,8 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
     a.vis_start_inline[b] = ok ? kv->vis_start[b] : 0;
     a.vis_len_inline[b] = ok ? kv->vis_len[b] : 0;
   }
-  hipError_t err = qc::launch_decode(a, c.dtype, (hipStream_t)stream, kv->timing ? &kv->decode_timer : nullptr);
+  qc::KernelTimer* timer = !kv->timing ? nullptr : (a.use_scores ? &kv->decode_shared_timer : &kv->decode_timer);
+  hipError_t err = qc::launch_decode(a, c.dtype, (hipStream_t)stream, timer);
   if (err != hipSuccess) return fail(QC_EDEVICE, "qc_decode: %s", hipGetErrorString(err));
 
   if (a.write_q) {
@@ -473,8 +478,9 @@ qc_status qc_timing_enable(qc_kvcache* kv, int32_t enable) {
 
 qc_status qc_timing_read(qc_kvcache* kv, int32_t which, double* total_ms, int64_t* launches) {
   if (!kv || !total_ms || !launches) return fail(QC_EINVAL, "qc_timing_read: null argument");
-  if (which != 0 && which != 1) return fail(QC_EINVAL, "qc_timing_read: which must be 0 (prefill) or 1 (decode)");
-  hipError_t e = (which == 0 ? kv->prefill_timer : kv->decode_timer).read(total_ms, launches);
+  if (which < 0 || which > 2) return fail(QC_EINVAL, "qc_timing_read: which must be 0 (prefill), 1 (decode) or 2 (decode, score-sharing lazy layers)");
+  qc::KernelTimer& t = which == 0 ? kv->prefill_timer : which == 1 ? kv->decode_timer : kv->decode_shared_timer;
+  hipError_t e = t.read(total_ms, launches);
   if (e != hipSuccess) return fail(QC_EDEVICE, "qc_timing_read: %s", hipGetErrorString(e));
   return QC_OK;
 }

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
   constexpr int LPR = D / EPL;                // lanes per row
   constexpr int GPW = 64 / LPR;               // row groups per wave
   constexpr int GROUPS = 4 * GPW;             // row groups per workgroup
-  constexpr int U = 4;                        // rows in flight per group
+  constexpr int U = SHARED ? 8 : 4;           // rows in flight per group
   constexpr int ROWB = D * (int)sizeof(T);
 
   const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -91,6 +91,11 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
   for (int r0 = kbeg + gid; r0 < kend; r0 += GROUPS * U) {
     uint4 kr[U], vr[U];
     float sc[U];
+    float mine = -INFINITY;
+    if (SHARED) {  // lane li < U of a group fetches the score of the group's row u = li; broadcast below
+      const int pos = r0 + li * GROUPS;
+      if (li < U && pos < kend) mine = score_row[pos];
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int pos = r0 + u * GROUPS;
@@ -98,7 +103,6 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
       vr[u] = make_uint4(0, 0, 0, 0);
       sc[u] = -INFINITY;
       if (pos < kend) {
-        if (SHARED) sc[u] = score_row[pos];
         if (pos == len) {  // the token being decoded: read the inputs, append to the caches
           vr[u] = *(const uint4*)vnew;
           *(uint4*)(vown + (int64_t)len * ROWB) = vr[u];
@@ -122,7 +126,9 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
     float mt = -INFINITY;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if (!SHARED) {
+      if (SHARED) {
+        sc[u] = group_broadcast<LPR>(mine, u);
+      } else {
         float kf[EPL];
         unpack16(kr[u], kf, (T*)nullptr);
         float d = 0.f;

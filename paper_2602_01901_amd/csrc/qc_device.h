@@ -69,6 +69,10 @@ template <int kLanes> __device__ __forceinline__ float group_sum(float x) {
   if (kLanes >= 64) x += __shfl_xor(x, 32);
   return x;
 }
+// Value held by lane `src` (0 .. kLanes-1) of the caller's aligned group of kLanes lanes.
+template <int kLanes> __device__ __forceinline__ float group_broadcast(float x, int src) {
+  return __shfl(x, src, kLanes);
+}
 template <int kLanes> __device__ __forceinline__ float group_max(float x) {
   static_assert(kLanes == 8 || kLanes == 16 || kLanes == 32 || kLanes == 64, "group size");
   x = fmaxf(x, dpp_move<kDppXor1>(x));

@@ -11,6 +11,7 @@ import torch
 import paper_2602_01901_amd as P
 from paper_2602_01901_amd import binding as B
 import workloads
+from oracle.global_lazy_stack import GlobalLazyStackOracle
 from oracle.lazy_stack import LazyStackOracle
 from stack_runner import TOL
 
@@ -39,18 +40,23 @@ def arena_rows(sess, which, layer, b, h, pos_list):
     return torch.stack(out).cpu().numpy()
 
 
-def run_sampled(w, n_layers, pairs, decode_steps=0, seed=0):
+def run_sampled(w, n_layers, pairs, decode_steps=0, seed=0, mode="vla"):
     rng = np.random.default_rng(seed)
-    sess = P.Session.for_workload(w)
+    gla = mode == "gla"
+    sess = P.Session.for_workload(w, mode=mode)
     sess.reset(w.vis_start, w.vis_len, zero_fill=False)
-    oracles = {p: LazyStackOracle(w.n_layers, 1, w.head_dim, w.lazy_mask, w.vis_start[p[0]], w.vis_len[p[0]])
-               for p in pairs}
+    if gla:
+        oracles = {p: GlobalLazyStackOracle(w.n_layers, 1, w.head_dim, w.lazy_mask) for p in pairs}
+    else:
+        oracles = {p: LazyStackOracle(w.n_layers, 1, w.head_dim, w.lazy_mask, w.vis_start[p[0]], w.vis_len[p[0]])
+                   for p in pairs}
     rows = {p: sample_rows(w, p[0], rng) for p in pairs}
     worst = 0.0
     cu = w.cu_seqlens
     for l in range(n_layers):
         q, k, v = workloads.prefill_qkv(w, l, device="cuda")
-        out = sess.prefill(l, q, k, v, w.cu_seqlens)
+        no_qk = gla and w.lazy_mask[l]
+        out = sess.prefill(l, None if no_qk else q, None if no_qk else k, v, w.cu_seqlens)
         for (b, h) in pairs:
             ref = oracles[(b, h)].prefill(l, head_slice(q, w, b, h), head_slice(k, w, b, h), head_slice(v, w, b, h),
                                           rows=rows[(b, h)])
@@ -63,7 +69,10 @@ def run_sampled(w, n_layers, pairs, decode_steps=0, seed=0):
             want_v = v[cu[b]:cu[b + 1], h, :][pos].contiguous().view(torch.uint8).cpu().numpy()
             assert np.array_equal(arena_rows(sess, B.QC_V, l, b, h, pos), want_v)
             st = oracles[(b, h)]
-            src_rows = [st.k_source(l, p_) for p_ in pos]
+            if gla:   # every key of a lazy layer is the block's first layer's
+                src_rows = [(st.first_layer_of_block(l) if w.lazy_mask[l] else l, p_) for p_ in pos]
+            else:
+                src_rows = [st.k_source(l, p_) for p_ in pos]
             got_k = arena_rows(sess, B.QC_K, l, b, h, pos)
             for n, (src, row) in enumerate(src_rows):
                 want = st.Kc[src][0, row].astype(np.float32)
@@ -74,7 +83,8 @@ def run_sampled(w, n_layers, pairs, decode_steps=0, seed=0):
     for t in range(decode_steps):
         for l in range(w.n_layers):
             q, k, v = workloads.decode_qkv(w, l, t, device="cuda")
-            out = sess.decode(l, q, k, v)
+            no_qk = gla and w.lazy_mask[l]
+            out = sess.decode(l, None if no_qk else q, None if no_qk else k, v)
             for (b, h) in pairs:
                 ref = oracles[(b, h)].decode(l, workloads.to_f64(q[b, h:h + 1]), workloads.to_f64(k[b, h:h + 1]),
                                              workloads.to_f64(v[b, h:h + 1]))
@@ -123,3 +133,27 @@ def test_long_prompt_32k():
     print("long prompt sampled max abs err %.3g" % worst, flush=True)
     assert worst <= TOL["bf16"]
     assert B.qc_layer_rows(sess.kv, 1) == (768, 32768)
+
+
+def test_gla_cfg4_highres_prefill_sampled():
+    """Global Lazy Attention at batch 8 x 3008 tokens: every row of a lazy layer comes from the Q Cache and
+    from the K cache of its block's first layer; first 8 layers."""
+    w = workloads.config(3)
+    worst, sess = run_sampled(w, 8, [(0, 0), (3, 17), (7, 31)], mode="gla")
+    print("gla cfg4 sampled max abs err %.3g" % worst, flush=True)
+    assert worst <= TOL["bf16"]
+    assert B.qc_layer_rows(sess.kv, 3) == (0, 8 * 3008)   # a lazy layer keeps no keys at all
+
+
+def test_gla_cfg3_batched_decode_sampled():
+    """Global Lazy Attention, batch 32 with unequal lengths: full prefill then 3 decode steps in which the
+    lazy layers reuse their block's scores."""
+    w = workloads.config(2)
+    worst, sess = run_sampled(w, w.n_layers, [(0, 5), (13, 0), (31, 31)], decode_steps=3, mode="gla")
+    print("gla cfg3 sampled max abs err %.3g" % worst, flush=True)
+    assert worst <= TOL["bf16"]
+    st = sess.stats()
+    per_row = 32 * 128 * 2
+    tokens = sum(w.seq_len) + 3 * 32
+    assert st["tokens"] == tokens
+    assert st["k_bytes"] == (w.n_layers - w.n_lazy) * tokens * per_row and st["q_bytes"] == tokens * per_row

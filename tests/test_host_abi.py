@@ -178,9 +178,10 @@ def test_timing_api_validation():
     cfg, kv, qc = make_handles(CONFIGS[0])
     assert B.qc_timing_enable(kv, 0) == B.QC_OK
     with pytest.raises(P.QcError) as e:
-        B.qc_timing_read(kv, 2)
+        B.qc_timing_read(kv, 3)
     assert e.value.status == B.QC_EINVAL
     assert B.qc_timing_read(kv, 0) == (0.0, 0)      # nothing recorded, no HIP call needed
+    assert B.qc_timing_read(kv, 2) == (0.0, 0)
     with pytest.raises(P.QcError):
         B.qc_timing_enable(None, 1)
 
