@@ -264,6 +264,54 @@ def bench_gla_decode_batched(args):
     return res
 
 
+def bench_selection(args):
+    """Lazy-block selection statistics (Eq. 3) at the batched 7B shape with every layer ordinary: the
+    head-averaged last-row attention of all 32 layers, then the 31 adjacent-layer similarities."""
+    import torch
+    import workloads
+    from paper_2602_01901_amd import binding as B
+    base = workloads.config(2)
+    w = workloads.custom("extra_selection_b32", base.n_layers, base.n_heads, base.head_dim, "bf16", base.vis_start,
+                         base.vis_len, base.seq_len, 0, [0] * base.n_layers)
+    r = Runner(w, 0)
+    r.prefill_stack()
+    s = r.sess
+    ws = torch.empty(B.qc_select_workspace_bytes(s.cfg), dtype=torch.uint8, device=s.device)
+    stride = max(w.seq_len)
+    probs = torch.zeros((w.n_layers, w.batch, stride), dtype=torch.float32, device=s.device)
+    cu = w.cu_seqlens
+    q_last = [torch.stack([r.pre[l][0][cu[b + 1] - 1] for b in range(w.batch)]).contiguous() for l in range(w.n_layers)]
+    js = torch.empty(w.batch, dtype=torch.float32, device=s.device)
+    sim = torch.empty(w.n_layers - 1, dtype=torch.float32, device=s.device)
+
+    def rows():
+        for l in range(w.n_layers):
+            B.qc_last_row_attention(s.kv, l, q_last[l], probs[l], stride, 0.0, ws, ws.numel())
+
+    def sims():
+        for l in range(w.n_layers - 1):
+            B.qc_attention_similarity(probs[l], probs[l + 1], stride, w.batch, w.seq_len, js, sim[l:l + 1])
+    rows()
+    sims()
+    _, rows_s = timed(torch, rows, 3)
+    _, sims_s = timed(torch, sims, 3)
+    k_bytes = sum(w.seq_len) * w.n_heads * w.head_dim * w.elem_bytes          # per layer: every key row once
+    score_bytes = 2 * sum(w.seq_len) * w.n_heads * 4                          # scores written, then read back
+    adjacent = [float(x) for x in sim.cpu()]
+    res = {
+        "workload": w.name, "batch": w.batch, "layers": w.n_layers,
+        "last_row_attention_us_per_layer": rows_s / w.n_layers * 1e6,
+        "last_row_attention_GBps": (k_bytes + score_bytes) / (rows_s / w.n_layers) / 1e9,
+        "similarity_us_per_layer_pair": sims_s / (w.n_layers - 1) * 1e6,
+        "similarity_min": min(adjacent), "similarity_max": max(adjacent),
+        "note": "independent random layers: every adjacent pair is equally dissimilar; offline analysis, two tiny "
+                "launches per layer, latency-bound",
+    }
+    del r
+    torch.cuda.empty_cache()
+    return res
+
+
 def bench_prefill_highres(args, w=None, traffic_key="prefill_cfg4", layers=None, mode="vla"):
     """Batch-8, 3008-token prefill (MFMA-bound); also used for the other prefill shapes."""
     import torch
@@ -370,7 +418,7 @@ def main():
     ap.add_argument("--prefill-reps", type=int, default=3)
     ap.add_argument("--skip-extra", action="store_true", help="headline workload only")
     ap.add_argument("--skip-cpu", action="store_true")
-    ap.add_argument("--only", choices=["decode_batched", "prefill_highres", "gla_decode_batched"],
+    ap.add_argument("--only", choices=["decode_batched", "prefill_highres", "gla_decode_batched", "selection"],
                     help="profiling aid: run just this extra workload and print its object")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profiling aid: run plain 1 GiB device copies (known HBM traffic) and exit")
@@ -396,7 +444,7 @@ def main():
         return
     if args.only:
         fn = {"decode_batched": bench_decode_batched, "prefill_highres": bench_prefill_highres,
-              "gla_decode_batched": bench_gla_decode_batched}[args.only]
+              "gla_decode_batched": bench_gla_decode_batched, "selection": bench_selection}[args.only]
         print(json.dumps({args.only: fn(args)}))
         return
 
@@ -419,6 +467,8 @@ def main():
                                                                  extra["gla_decode_batched"]["roofline"]["achieved"]))
         extra["gla_prefill_highres"] = bench_prefill_highres(args, traffic_key="gla_prefill_cfg4", mode="gla")
         log("GLA cfg4 done: %.1f TFLOP/s" % extra["gla_prefill_highres"]["prefill_tflops"])
+        extra["selection"] = bench_selection(args)
+        log("selection done: %.1f us per layer" % extra["selection"]["last_row_attention_us_per_layer"])
     cpu = None if args.skip_cpu else cpu_baseline()
     line = {
         "metric": "decode_tokens_per_s", "value": r["decode_tokens_per_s"], "unit": "tokens/s",

@@ -195,6 +195,34 @@ qc_status qc_seq_len(const qc_kvcache* kv, int32_t b, int32_t* len);
 qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t b, int32_t h,
                     int32_t pos, int32_t* src_layer, int64_t* byte_offset);
 
+/* ---- lazy-block selection (paper Eq. 3 and Eq. 4; offline analysis, not part of serving) ---------
+ * Run the model with a mask of zeros (every layer ordinary), and after the prefill pass ask every
+ * layer for the last row of its attention matrix:
+ * qc_last_row_attention: probs[b][pos], pos = 0..len_b-1, = mean over heads of
+ *   Softmax(q_last[b][h] . K^layer[b][h][0..len_b-1] * scale) (the paper averages over heads; base of
+ *   the softmax as in qc_prefill, softmax_scale 0 selects 1/sqrt(head_dim)).
+ *   q_last: DEVICE, [batch][n_heads][head_dim], element type of the configuration: the query of each
+ *   sequence's last token at `layer`.  probs: DEVICE, fp32, row b starts at b*probs_stride
+ *   (probs_stride >= longest sequence); entries at and beyond len_b are not written.
+ *   workspace: DEVICE, at least qc_select_workspace_bytes(cfg).  Requires a finished prefill pass
+ *   (QC_EORDER otherwise) and an ordinary `layer` (QC_EINVAL: a lazy layer does not hold all its keys).
+ * qc_attention_similarity: js_out[i] = JS(probs_m row i, probs_n row i) over lens[i] entries, in bits
+ *   (JS = (KL(p||m) + KL(q||m))/2, m = (p+q)/2, terms with zero probability contribute zero), and
+ *   *s_out = their mean over the n_samples rows = S(l_m, l_n) of Eq. 3.  probs_m, probs_n, js_out,
+ *   s_out: DEVICE fp32; lens: HOST, n_samples entries, each 1..stride.
+ * qc_lazy_mask_from_similarity (host only): Eq. 4.  adjacent[i] = S(l_i, l_i+1), i = 0..n_layers-2;
+ *   layer i >= 1 becomes lazy exactly when adjacent[i-1] < eps, so that blocks are the maximal runs
+ *   whose adjacent pairs all stay below eps and every block starts with an ordinary layer.
+ *   0 < eps <= 1 (QC_EINVAL otherwise).  adjacent, mask_out: HOST. */
+size_t qc_select_workspace_bytes(const qc_config* cfg);
+qc_status qc_last_row_attention(qc_kvcache* kv, int32_t layer, const void* q_last, float* probs,
+                                int64_t probs_stride, float softmax_scale, void* workspace,
+                                size_t workspace_bytes, void* stream);
+qc_status qc_attention_similarity(const float* probs_m, const float* probs_n, int64_t stride,
+                                  int32_t n_samples, const int32_t* lens, float* js_out, float* s_out,
+                                  void* stream);
+qc_status qc_lazy_mask_from_similarity(const float* adjacent, int32_t n_layers, float eps, uint8_t* mask_out);
+
 /* ---- optional instrumentation ------------------------------------------------------------------
  * While enabled, qc_prefill and qc_decode record a pair of HIP events on the call's stream around
  * their dominant kernel (prefill: the attention kernel; decode: the kernel that streams the caches,

@@ -55,6 +55,12 @@ _PROTOTYPES = {
     "qc_seq_len": (c_int32, [c_void_p, c_int32, POINTER(c_int32)]),
     "qc_locate": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, POINTER(c_int32),
                             POINTER(c_int64)]),
+    "qc_select_workspace_bytes": (c_size_t, [POINTER(qc_config)]),
+    "qc_last_row_attention": (c_int32, [c_void_p, c_int32, c_void_p, c_void_p, c_int64, c_float, c_void_p, c_size_t,
+                                        c_void_p]),
+    "qc_attention_similarity": (c_int32, [c_void_p, c_void_p, c_int64, c_int32, POINTER(c_int32), c_void_p, c_void_p,
+                                          c_void_p]),
+    "qc_lazy_mask_from_similarity": (c_int32, [POINTER(c_float), c_int32, c_float, POINTER(c_uint8)]),
     "qc_timing_enable": (c_int32, [c_void_p, c_int32]),
     "qc_timing_read": (c_int32, [c_void_p, c_int32, POINTER(ctypes.c_double), POINTER(c_int64)]),
     "qc_status_str": (c_char_p, [c_int32]),
@@ -194,6 +200,30 @@ def qc_locate(kv, which, layer, b, h, pos):
     src, off = c_int32(), c_int64()
     _check(load_library().qc_locate(kv, which, layer, b, h, pos, byref(src), byref(off)))
     return src.value, off.value
+
+
+def qc_select_workspace_bytes(cfg):
+    return load_library().qc_select_workspace_bytes(byref(cfg))
+
+
+def qc_last_row_attention(kv, layer, q_last, probs, probs_stride, softmax_scale, workspace, workspace_bytes,
+                          stream=None):
+    return _check(load_library().qc_last_row_attention(kv, layer, _ptr(q_last), _ptr(probs), probs_stride,
+                                                      softmax_scale, _ptr(workspace), workspace_bytes, stream))
+
+
+def qc_attention_similarity(probs_m, probs_n, stride, n_samples, lens, js_out, s_out, stream=None):
+    return _check(load_library().qc_attention_similarity(_ptr(probs_m), _ptr(probs_n), stride, n_samples,
+                                                        _i32(lens), _ptr(js_out), _ptr(s_out), stream))
+
+
+def qc_lazy_mask_from_similarity(adjacent, eps):
+    """Eq. 4 on the host: list of flags, one per layer (len(adjacent) + 1 layers)."""
+    n = len(adjacent) + 1
+    adj = (c_float * max(len(adjacent), 1))(*[float(x) for x in adjacent])
+    out = (c_uint8 * n)()
+    _check(load_library().qc_lazy_mask_from_similarity(adj, n, eps, out))
+    return [int(x) for x in out]
 
 
 def qc_timing_enable(kv, enable):

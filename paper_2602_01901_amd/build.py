@@ -8,7 +8,8 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libqcache.so")
 
-SOURCES = ["qc_api.cpp", "qc_util.hip", "qc_decode.hip", "qc_prefill_simple.hip", "qc_prefill_mfma.hip"]
+SOURCES = ["qc_api.cpp", "qc_util.hip", "qc_decode.hip", "qc_prefill_simple.hip", "qc_prefill_mfma.hip",
+           "qc_select.hip"]
 
 # Packed fp32 instructions are kept out of the generated code on purpose.
 HIPCC_FLAGS = [

@@ -470,6 +470,80 @@ qc_status qc_stats(const qc_kvcache* kv, const qc_qcache* qc, qc_stats_t* out) {
   return QC_OK;
 }
 
+// ---- lazy-block selection (Eq. 3 / Eq. 4) --------------------------------------------------------
+static int64_t select_score_stride(const Config& c) { return round_up(c.max_seq, 4); }
+
+size_t qc_select_workspace_bytes(const qc_config* cfg) {
+  Config c;
+  if (!parse_config(cfg, &c)) return 0;
+  return (size_t)round_up((int64_t)c.max_batch * c.H * (select_score_stride(c) + 2) * 4, 256);
+}
+
+qc_status qc_last_row_attention(qc_kvcache* kv, int32_t layer, const void* q_last, float* probs,
+                                int64_t probs_stride, float softmax_scale, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+  if (!kv) return fail(QC_EINVAL, "qc_last_row_attention: null handle");
+  const Config& c = kv->cfg;
+  if (layer < 0 || layer >= c.N) return fail(QC_EINVAL, "qc_last_row_attention: layer %d out of range", layer);
+  if (c.lazy[layer]) return fail(QC_EINVAL, "qc_last_row_attention: layer %d is lazy and does not hold all of its keys", layer);
+  if (!q_last || !probs || !workspace) return fail(QC_EINVAL, "qc_last_row_attention: null tensor or workspace");
+  if (((uintptr_t)q_last | (uintptr_t)workspace) & 15) return fail(QC_EINVAL, "qc_last_row_attention: q_last and workspace must be 16-byte aligned");
+  if ((uintptr_t)probs & 3) return fail(QC_EINVAL, "qc_last_row_attention: probs must be 4-byte aligned");
+  if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return fail(QC_EINVAL, "qc_last_row_attention: bad softmax_scale");
+  if (kv->phase != PH_READY) return fail(QC_EORDER, "qc_last_row_attention: needs a finished prefill pass and no decode step in flight");
+  int32_t max_len = 0;
+  for (int b = 0; b < kv->batch; ++b) {
+    int32_t len = kv->len0[b] + kv->generated;
+    if (len > max_len) max_len = len;
+  }
+  if (probs_stride < max_len) return fail(QC_EINVAL, "qc_last_row_attention: probs_stride %lld is shorter than the longest sequence (%d)", (long long)probs_stride, max_len);
+  const int64_t need = round_up((int64_t)c.max_batch * c.H * (select_score_stride(c) + 2) * 4, 256);
+  if ((int64_t)workspace_bytes < need) return fail(QC_ECAPACITY, "qc_last_row_attention: workspace holds %zu bytes, %lld needed", workspace_bytes, (long long)need);
+  qc::SelectArgs a;
+  a.lv = make_view(kv, nullptr, layer);
+  a.q_last = q_last;
+  a.scores = (float*)workspace;
+  a.row_stats = (float*)workspace + (int64_t)c.max_batch * c.H * select_score_stride(c);
+  a.probs = probs;
+  a.probs_stride = probs_stride;
+  a.score_stride = (int32_t)select_score_stride(c);
+  a.batch = kv->batch; a.n_heads = c.H; a.head_dim = c.D;
+  a.generated = kv->generated;
+  a.scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)c.D);
+  hipError_t e = qc::launch_last_row_attention(a, c.dtype, max_len, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(QC_EDEVICE, "qc_last_row_attention: %s", hipGetErrorString(e));
+  return QC_OK;
+}
+
+qc_status qc_attention_similarity(const float* probs_m, const float* probs_n, int64_t stride,
+                                  int32_t n_samples, const int32_t* lens, float* js_out, float* s_out,
+                                  void* stream) {
+  if (!probs_m || !probs_n || !lens || !js_out || !s_out) return fail(QC_EINVAL, "qc_attention_similarity: null argument");
+  if (n_samples < 1 || stride < 1) return fail(QC_EINVAL, "qc_attention_similarity: needs at least one sample and a positive stride");
+  if (((uintptr_t)probs_m | (uintptr_t)probs_n | (uintptr_t)js_out | (uintptr_t)s_out) & 3) return fail(QC_EINVAL, "qc_attention_similarity: pointers must be 4-byte aligned");
+  for (int i = 0; i < n_samples; ++i)
+    if (lens[i] < 1 || lens[i] > stride) return fail(QC_EINVAL, "qc_attention_similarity: length of sample %d out of range", i);
+  for (int first = 0; first < n_samples; first += qc::JsChunk::N) {
+    qc::JsChunk ch;
+    memset(&ch, 0, sizeof(ch));
+    const int count = n_samples - first < qc::JsChunk::N ? n_samples - first : qc::JsChunk::N;
+    for (int i = 0; i < count; ++i) ch.len[i] = lens[first + i];
+    hipError_t e = qc::launch_js(probs_m, probs_n, stride, first, count, ch, js_out, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(QC_EDEVICE, "qc_attention_similarity: %s", hipGetErrorString(e));
+  }
+  hipError_t e = qc::launch_mean(js_out, n_samples, s_out, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(QC_EDEVICE, "qc_attention_similarity: %s", hipGetErrorString(e));
+  return QC_OK;
+}
+
+qc_status qc_lazy_mask_from_similarity(const float* adjacent, int32_t n_layers, float eps, uint8_t* mask_out) {
+  if (!mask_out || n_layers < 1 || (n_layers > 1 && !adjacent)) return fail(QC_EINVAL, "qc_lazy_mask_from_similarity: null argument or no layers");
+  if (!(eps > 0.0f) || !(eps <= 1.0f)) return fail(QC_EINVAL, "qc_lazy_mask_from_similarity: eps must lie in (0, 1]");
+  mask_out[0] = 0;
+  for (int i = 1; i < n_layers; ++i) mask_out[i] = adjacent[i - 1] < eps ? 1 : 0;
+  return QC_OK;
+}
+
 qc_status qc_timing_enable(qc_kvcache* kv, int32_t enable) {
   if (!kv) return fail(QC_EINVAL, "qc_timing_enable: null handle");
   kv->timing = enable != 0;

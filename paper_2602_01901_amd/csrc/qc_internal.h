@@ -71,6 +71,24 @@ struct DecodeArgs {
   int32_t vis_len_inline[kInlineSeqs];
 };
 
+struct SelectArgs {       // last-row attention of one ordinary layer (lazy-block selection, Eq. 3)
+  LayerView lv;
+  const void* q_last;     // [batch][H][D]: query of each sequence's last token
+  float* scores;          // workspace: [batch][H][score_stride]
+  float* row_stats;       // workspace: [batch][H][2] = (max, sum) of each score row
+  float* probs;           // out: [batch][probs_stride], positions 0..len-1
+  int64_t probs_stride;
+  int32_t score_stride;
+  int32_t batch, n_heads, head_dim;
+  int32_t generated;
+  float scale;
+};
+
+struct JsChunk {          // by-value payload of the similarity kernel: row lengths of up to N samples
+  enum { N = 64 };
+  int32_t len[N];
+};
+
 struct MetaChunk {        // by-value payload of the metadata upload kernel
   enum { N = 64 };
   int32_t v[META_ROWS][N];
@@ -125,5 +143,9 @@ hipError_t launch_meta_upload(int32_t* meta_dev, int32_t max_batch, int32_t firs
                               const MetaChunk& chunk, hipStream_t stream);
 hipError_t launch_prefill(const PrefillArgs& a, int dtype, hipStream_t stream, KernelTimer* timer);
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t stream, KernelTimer* timer);
+hipError_t launch_last_row_attention(const SelectArgs& a, int dtype, int max_len, hipStream_t stream);
+hipError_t launch_js(const float* pm, const float* pn, int64_t stride, int first, int count, const JsChunk& c,
+                     float* js_out, hipStream_t stream);
+hipError_t launch_mean(const float* x, int n, float* out, hipStream_t stream);
 
 }  // namespace qc

@@ -234,3 +234,40 @@ def test_gla_config_and_call_validation():
     assert e.value.status == B.QC_EORDER
     st = B.qc_stats(kv, qc)
     assert st["next_layer"] == 0 and st["q_owner"] == -1
+
+
+# ---------------------------------------------------------------------------
+# lazy-block selection: host-only part and validation
+# ---------------------------------------------------------------------------
+def test_lazy_mask_from_similarity_matches_oracle():
+    import numpy as np
+    from oracle import selection
+    rng = np.random.default_rng(5)
+    for _ in range(30):
+        n = int(rng.integers(1, 12))
+        adj = [float(np.float32(x)) for x in rng.random(n - 1)]
+        eps = float(np.float32(rng.uniform(0.05, 1.0)))
+        assert B.qc_lazy_mask_from_similarity(adj, eps) == selection.lazy_mask_from_similarity(adj, eps)
+    assert B.qc_lazy_mask_from_similarity([0.5], 0.5) == [0, 0]
+    for bad in (0.0, 1.5, float("nan")):
+        with pytest.raises(P.QcError) as e:
+            B.qc_lazy_mask_from_similarity([0.1, 0.2], bad)
+        assert e.value.status == B.QC_EINVAL
+
+
+def test_selection_calls_validate_before_launching():
+    cfg, kv, qc = make_handles(CONFIGS[1])     # mask [0,1,0]
+    ws = B.qc_select_workspace_bytes(cfg)
+    assert ws >= 5 * 2 * (77 + 2) * 4 and ws % 256 == 0
+    with pytest.raises(P.QcError) as e:         # no prefill pass yet
+        B.qc_last_row_attention(kv, 0, FAKE, FAKE, 80, 0.0, FAKE, ws)
+    assert e.value.status == B.QC_EORDER
+    with pytest.raises(P.QcError) as e:         # a lazy layer does not hold all of its keys
+        B.qc_last_row_attention(kv, 1, FAKE, FAKE, 80, 0.0, FAKE, ws)
+    assert e.value.status == B.QC_EINVAL
+    with pytest.raises(P.QcError) as e:
+        B.qc_attention_similarity(FAKE, FAKE, 16, 2, [4, 17], FAKE, FAKE)      # a row longer than the stride
+    assert e.value.status == B.QC_EINVAL
+    with pytest.raises(P.QcError) as e:
+        B.qc_attention_similarity(FAKE, None, 16, 1, [4], FAKE, FAKE)
+    assert e.value.status == B.QC_EINVAL
