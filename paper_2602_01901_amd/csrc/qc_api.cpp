@@ -3,6 +3,7 @@
 // kernels; this file only decides which rows live where (integers).
 #include "qcache.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -467,6 +468,72 @@ qc_status qc_stats(const qc_kvcache* kv, const qc_qcache* qc, qc_stats_t* out) {
   out->q_owner = qc ? qc->owner : -1;
   out->generated = kv->generated;
   out->next_layer = kv->next_layer;
+  return QC_OK;
+}
+
+// ---- query/key projection (Eq. 7: text rows only in a lazy layer) ----------------------------------
+qc_status qc_project_qk(const void* x, int64_t x_stride, const void* w_q, const void* w_k, void* q, void* k,
+                        int64_t token_stride, int64_t head_stride, int32_t d_model, int32_t n_heads,
+                        int32_t head_dim, int32_t batch, const int32_t* cu_seqlens, const int32_t* pos0,
+                        const int32_t* vis_start, const int32_t* vis_len, int32_t skip_span,
+                        float rope_theta, void* stream) {
+  if (!x || !w_q || !w_k || !q || !k || !cu_seqlens) return fail(QC_EINVAL, "qc_project_qk: null argument");
+  if (skip_span && (!vis_start || !vis_len)) return fail(QC_EINVAL, "qc_project_qk: skip_span needs the span arrays");
+  if (head_dim != 64 && head_dim != 128) return fail(QC_EINVAL, "qc_project_qk: head_dim must be 64 or 128");
+  if (batch < 1 || n_heads < 1 || d_model < 64 || d_model % 64) return fail(QC_EINVAL, "qc_project_qk: d_model must be a positive multiple of 64, batch and n_heads positive");
+  const int64_t n_out = (int64_t)n_heads * head_dim;
+  if (n_out % 256) return fail(QC_EINVAL, "qc_project_qk: n_heads*head_dim must be a multiple of 256");
+  if (x_stride < d_model || (x_stride * 2) % 16 || head_stride < head_dim || token_stride < head_dim)
+    return fail(QC_EINVAL, "qc_project_qk: bad strides");
+  if (((uintptr_t)x | (uintptr_t)w_q | (uintptr_t)w_k) & 15) return fail(QC_EINVAL, "qc_project_qk: x and the weights must be 16-byte aligned");
+  if (((uintptr_t)q | (uintptr_t)k) & 1) return fail(QC_EINVAL, "qc_project_qk: q and k must be 2-byte aligned");
+  if (!(rope_theta >= 0.0f) || !std::isfinite(rope_theta)) return fail(QC_EINVAL, "qc_project_qk: bad rope_theta");
+  if (cu_seqlens[0] != 0) return fail(QC_EINVAL, "qc_project_qk: cu_seqlens[0] must be 0");
+  for (int b = 0; b < batch; ++b) {
+    if (cu_seqlens[b + 1] < cu_seqlens[b]) return fail(QC_EINVAL, "qc_project_qk: cu_seqlens must not decrease");
+    if (pos0 && pos0[b] < 0) return fail(QC_EINVAL, "qc_project_qk: negative position");
+    if (skip_span && (vis_start[b] < 0 || vis_len[b] < 0)) return fail(QC_EINVAL, "qc_project_qk: negative span");
+  }
+  const int64_t tokens = cu_seqlens[batch];
+  if (tokens * x_stride * 2 >= ((int64_t)1 << 31) || n_out * d_model * 2 >= ((int64_t)1 << 31))
+    return fail(QC_EINVAL, "qc_project_qk: x or a weight matrix spans 2 GiB or more");
+
+  qc::ProjectArgs a;
+  a.x = x;
+  a.w[0] = w_q; a.w[1] = w_k;
+  a.out[0] = q; a.out[1] = k;
+  a.x_stride = x_stride; a.token_stride = token_stride; a.head_stride = head_stride;
+  a.d_model = d_model; a.n_heads = n_heads; a.head_dim = head_dim;
+  a.rope_theta = rope_theta;
+  a.log2_theta = rope_theta > 0.0f ? std::log2((double)rope_theta) : 0.0;
+  // Up to two token ranges per sequence; a launch takes as many sequences as fit its range list.
+  int b = 0;
+  while (b < batch) {
+    memset(&a.segs, 0, sizeof(a.segs));
+    int64_t rows = 0;
+    while (b < batch && a.segs.n + 2 <= qc::ProjectSegs::N) {
+      const int64_t t0 = cu_seqlens[b], len = cu_seqlens[b + 1] - t0, p0 = pos0 ? pos0[b] : 0;
+      int64_t cut_lo = p0 + len, cut_hi = p0 + len;   // positions [cut_lo, cut_hi) are skipped
+      if (skip_span && vis_len[b] > 0) {
+        cut_lo = std::min<int64_t>(std::max<int64_t>(vis_start[b], p0), p0 + len);
+        cut_hi = std::min<int64_t>(std::max<int64_t>((int64_t)vis_start[b] + vis_len[b], p0), p0 + len);
+      }
+      const int64_t ranges[2][2] = {{p0, cut_lo}, {cut_hi, p0 + len}};
+      for (auto& r : ranges)
+        if (r[1] > r[0]) {
+          const int i = a.segs.n++;
+          a.segs.tok_start[i] = (int32_t)(t0 + (r[0] - p0));
+          a.segs.count[i] = (int32_t)(r[1] - r[0]);
+          a.segs.pos_start[i] = (int32_t)r[0];
+          rows += r[1] - r[0];
+        }
+      ++b;
+    }
+    if (rows == 0) continue;
+    const int m_tiles = (int)((rows + 255) / 256);
+    hipError_t e = qc::launch_project_qk(a, m_tiles, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(QC_EDEVICE, "qc_project_qk: %s", hipGetErrorString(e));
+  }
   return QC_OK;
 }
 

@@ -89,6 +89,25 @@ struct JsChunk {          // by-value payload of the similarity kernel: row leng
   int32_t len[N];
 };
 
+struct ProjectSegs {      // rows to project: contiguous token ranges, in order (by value in the kernel arguments)
+  enum { N = 128 };
+  int32_t tok_start[N];   // first token index of the range in the packed tensors
+  int32_t count[N];
+  int32_t pos_start[N];   // position of that token inside its sequence
+  int32_t n;
+};
+
+struct ProjectArgs {
+  const void* x;          // [tokens][d_model] bf16, row stride x_stride elements
+  const void* w[2];       // W_Q, W_K: [H*D][d_model] bf16
+  void* out[2];           // q, k: element (t, h, d) at t*token_stride + h*head_stride + d
+  int64_t x_stride, token_stride, head_stride;
+  int32_t d_model, n_heads, head_dim;
+  float rope_theta;       // 0: no rotary embedding
+  double log2_theta;
+  ProjectSegs segs;
+};
+
 struct MetaChunk {        // by-value payload of the metadata upload kernel
   enum { N = 64 };
   int32_t v[META_ROWS][N];
@@ -147,5 +166,6 @@ hipError_t launch_last_row_attention(const SelectArgs& a, int dtype, int max_len
 hipError_t launch_js(const float* pm, const float* pn, int64_t stride, int first, int count, const JsChunk& c,
                      float* js_out, hipStream_t stream);
 hipError_t launch_mean(const float* x, int n, float* out, hipStream_t stream);
+hipError_t launch_project_qk(const ProjectArgs& a, int m_tiles, hipStream_t stream);
 
 }  // namespace qc

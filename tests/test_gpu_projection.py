@@ -1,0 +1,100 @@
+"""GPU parity for the text-rows-only Q/K projection with rotary embedding against the CPU oracle.
+
+Tolerance: the kernel accumulates bf16 products in fp32 (error ~1e-6 relative to the row's
+magnitude) and rounds the result to bf16 once, so |err| <= 2^-8 |y| + 2e-3 (a bf16 half-ulp is
+2^-9 |y|; the absolute term covers cancellation in the rotation for results near zero)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_01901_amd as P
+from paper_2602_01901_amd import binding as B
+import workloads
+from oracle import projection
+
+pytestmark = pytest.mark.gpu
+
+
+def make_inputs(tokens, d_model, n_out, seed):
+    g = torch.Generator().manual_seed(seed)
+    x = torch.randn(tokens, d_model, generator=g).to(torch.bfloat16)
+    wq = (torch.randn(n_out, d_model, generator=g) / d_model ** 0.5).to(torch.bfloat16)
+    wk = (torch.randn(n_out, d_model, generator=g) / d_model ** 0.5).to(torch.bfloat16)
+    return x, wq, wk
+
+
+def run_case(lens, spans, pos0, d_model, H, D, theta, skip_span, seed, sample_rows=None):
+    cu = [0]
+    for L in lens:
+        cu.append(cu[-1] + L)
+    tokens = cu[-1]
+    x, wq, wk = make_inputs(tokens, d_model, H * D, seed)
+    sentinel = 7.0
+    q = torch.full((tokens, H, D), sentinel, dtype=torch.bfloat16, device="cuda")
+    k = torch.full((tokens, H, D), sentinel, dtype=torch.bfloat16, device="cuda")
+    xd, wqd, wkd = x.cuda(), wq.cuda(), wk.cuda()
+    vs, vl = [s for s, _ in spans], [n for _, n in spans]
+    B.qc_project_qk(xd, d_model, wqd, wkd, q, k, H * D, D, d_model, H, D, len(lens), cu, pos0, vs, vl, skip_span, theta)
+    torch.cuda.synchronize()
+    rows, positions = [], []
+    for b, L in enumerate(lens):
+        p0 = pos0[b] if pos0 else 0
+        for i in range(L):
+            p = p0 + i
+            if skip_span and vs[b] <= p < vs[b] + vl[b]:
+                continue
+            rows.append(cu[b] + i)
+            positions.append(p)
+    skipped = sorted(set(range(tokens)) - set(rows))
+    if sample_rows is not None and len(rows) > sample_rows:
+        pick = np.random.default_rng(seed).choice(len(rows), sample_rows, replace=False)
+        pick = sorted(set(pick.tolist()) | {0, len(rows) - 1})
+        rows_c, pos_c = [rows[i] for i in pick], [positions[i] for i in pick]
+    else:
+        rows_c, pos_c = rows, positions
+    Qw, Kw = projection.project_qk(workloads.to_f64(x), workloads.to_f64(wq), workloads.to_f64(wk), H, D, rows_c, pos_c, theta)
+    worst = 0.0
+    for got_t, want in ((q, Qw), (k, Kw)):
+        if len(rows_c):
+            got = workloads.to_f64(got_t[rows_c])
+            err = np.abs(got - want)
+            assert np.all(err <= 2.0 ** -8 * np.abs(want) + 2e-3), float(err.max())
+            worst = max(worst, float(err.max()))
+        if skipped:   # rows inside the span are never written
+            assert torch.all(got_t[skipped] == sentinel)
+    return worst
+
+
+@pytest.mark.parametrize("D,H", [(128, 2), (64, 4)])
+@pytest.mark.parametrize("theta", [10000.0, 0.0])
+def test_projection_small_ragged_batch(D, H, theta):
+    lens, spans = [131, 64, 45, 300], [(5, 70), (0, 33), (17, 0), (40, 260)]
+    for skip in (0, 1):
+        w = run_case(lens, spans, None, 256, H, D, theta, skip, seed=D + skip)
+        print("projection D=%d theta=%g skip=%d: max abs err %.3g" % (D, theta, skip, w), flush=True)
+
+
+def test_projection_decode_shape_with_positions():
+    """One token per sequence at its current position (what a decode step projects)."""
+    lens = [1] * 9
+    pos0 = [640, 641, 12, 0, 4095, 77, 1000, 31999, 5]
+    run_case(lens, [(0, 0)] * 9, pos0, 512, 4, 128, 10000.0, 0, seed=3)
+    # a sequence whose only token lies inside its span projects nothing
+    run_case([1, 1], [(0, 10), (0, 0)], [5, 5], 256, 2, 128, 10000.0, 1, seed=4)
+
+
+def test_projection_everything_skipped_and_many_sequences():
+    run_case([20, 30], [(0, 20), (0, 30)], None, 256, 2, 128, 10000.0, 1, seed=5)     # nothing to do at all
+    n = 70                                                                          # more sequences than one launch takes
+    lens = [3 + (i % 5) for i in range(n)]
+    spans = [(1, 1 + (i % 2)) for i in range(n)]
+    run_case(lens, spans, None, 256, 2, 128, 10000.0, 1, seed=6)
+
+
+def test_projection_7b_shape_sampled():
+    """d_model 4096, 32 heads x 128: the lazy-layer case of the high-resolution prompt (8 x (32 + 96) text
+    rows out of 8 x 3008) and an ordinary layer over two full prompts; sampled rows against the oracle."""
+    lens, spans = [3008] * 8, [(32, 2880)] * 8
+    w1 = run_case(lens, spans, None, 4096, 32, 128, 10000.0, 1, seed=7, sample_rows=24)
+    w2 = run_case([3008, 640], [(32, 2880), (32, 576)], None, 4096, 32, 128, 10000.0, 0, seed=8, sample_rows=24)
+    print("projection 7B shape: max abs err lazy %.3g ordinary %.3g" % (w1, w2), flush=True)
