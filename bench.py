@@ -264,6 +264,63 @@ def bench_gla_decode_batched(args):
     return res
 
 
+def bench_projection(args):
+    """Q/K projection + rotary embedding at the high-resolution prompt shape (d_model 4096, 32 x 128): an
+    ordinary layer projects all 8 x 3008 tokens, a lazy layer only the 8 x 128 text tokens (Eq. 7)."""
+    import torch
+    import workloads
+    from paper_2602_01901_amd import binding as B
+    w = workloads.config(3)
+    d_model, H, D = 4096, w.n_heads, w.head_dim
+    tokens = sum(w.seq_len)
+    g = torch.Generator().manual_seed(0x51C0 + 77)
+    pad = int(os.environ.get("QC_BENCH_ROW_PAD", "0"))   # elements between rows of x and of the weights (no measurable effect)
+    ld = d_model + pad
+
+    def rows_of(t):
+        buf = torch.zeros(t.shape[0], ld, dtype=torch.bfloat16, device="cuda")
+        buf[:, :d_model] = t.cuda()
+        return buf
+    x = rows_of(torch.randn(tokens, d_model, generator=g).to(torch.bfloat16))
+    wq = rows_of((torch.randn(H * D, d_model, generator=g) / d_model ** 0.5).to(torch.bfloat16))
+    wk = rows_of((torch.randn(H * D, d_model, generator=g) / d_model ** 0.5).to(torch.bfloat16))
+    q = torch.empty(tokens, H, D, dtype=torch.bfloat16, device="cuda")
+    k = torch.empty_like(q)
+
+    def run(skip):
+        B.qc_project_qk(x, ld, wq, wk, ld, q, k, H * D, D, d_model, H, D, w.batch, w.cu_seqlens, None,
+                        w.vis_start, w.vis_len, skip, 10000.0)
+    out = {"workload": w.name, "d_model": d_model, "heads": H, "head_dim": D, "row_stride_elements": ld}
+    for name, skip, rows in (("ordinary_layer", 0, tokens), ("lazy_layer_text_rows", 1, tokens - sum(w.vis_len))):
+        run(skip)
+        _, ev_s = timed(torch, lambda: run(skip), 5)
+        flops = 2 * 2 * rows * d_model * H * D
+        out[name] = {"rows": rows, "us": ev_s * 1e6, "tflops": flops / ev_s / 1e12,
+                     "roofline": {"bound": "mfma", "kernel": "project_qk_kernel<128> (W_Q and W_K in one launch)",
+                                  "achieved": flops / ev_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                  "frac": flops / ev_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                                  "avg_launch_us": ev_s * 1e6, "algorithmic_flops_per_launch": flops}}
+    out["time_saved_per_lazy_layer_us"] = out["ordinary_layer"]["us"] - out["lazy_layer_text_rows"]["us"]
+    # decode: one token per sequence (batch 32): weight streaming, 2 x 33.5 MB per layer
+    wd = workloads.config(2)
+    cu = list(range(wd.batch + 1))
+    pos0 = list(wd.seq_len)
+
+    def run_dec():
+        B.qc_project_qk(x, ld, wq, wk, ld, q, k, H * D, D, d_model, H, D, wd.batch, cu, pos0, None, None, 0, 10000.0)
+    run_dec()
+    _, ev_s = timed(torch, run_dec, 10)
+    dec_bytes = 2 * H * D * d_model * 2 + wd.batch * d_model * 2 + 2 * wd.batch * H * D * 2   # weights, x rows, q and k rows
+    out["decode_batch32"] = {"us": ev_s * 1e6,
+                             "roofline": {"bound": "hbm", "kernel": "project_qk_skinny_kernel<128>",
+                                          "achieved": dec_bytes / ev_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                          "frac": dec_bytes / ev_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                                          "avg_launch_us": ev_s * 1e6, "algorithmic_bytes_per_launch": dec_bytes}}
+    del x, wq, wk, q, k
+    torch.cuda.empty_cache()
+    return out
+
+
 def bench_selection(args):
     """Lazy-block selection statistics (Eq. 3) at the batched 7B shape with every layer ordinary: the
     head-averaged last-row attention of all 32 layers, then the 31 adjacent-layer similarities."""
@@ -418,7 +475,7 @@ def main():
     ap.add_argument("--prefill-reps", type=int, default=3)
     ap.add_argument("--skip-extra", action="store_true", help="headline workload only")
     ap.add_argument("--skip-cpu", action="store_true")
-    ap.add_argument("--only", choices=["decode_batched", "prefill_highres", "gla_decode_batched", "selection"],
+    ap.add_argument("--only", choices=["decode_batched", "prefill_highres", "gla_decode_batched", "selection", "projection"],
                     help="profiling aid: run just this extra workload and print its object")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profiling aid: run plain 1 GiB device copies (known HBM traffic) and exit")
@@ -444,7 +501,8 @@ def main():
         return
     if args.only:
         fn = {"decode_batched": bench_decode_batched, "prefill_highres": bench_prefill_highres,
-              "gla_decode_batched": bench_gla_decode_batched, "selection": bench_selection}[args.only]
+              "gla_decode_batched": bench_gla_decode_batched, "selection": bench_selection,
+              "projection": bench_projection}[args.only]
         print(json.dumps({args.only: fn(args)}))
         return
 
@@ -467,6 +525,9 @@ def main():
                                                                  extra["gla_decode_batched"]["roofline"]["achieved"]))
         extra["gla_prefill_highres"] = bench_prefill_highres(args, traffic_key="gla_prefill_cfg4", mode="gla")
         log("GLA cfg4 done: %.1f TFLOP/s" % extra["gla_prefill_highres"]["prefill_tflops"])
+        extra["projection"] = bench_projection(args)
+        log("projection done: ordinary %.1f TFLOP/s, lazy layer %.1f us" % (extra["projection"]["ordinary_layer"]["tflops"],
+                                                                        extra["projection"]["lazy_layer_text_rows"]["us"]))
         extra["selection"] = bench_selection(args)
         log("selection done: %.1f us per layer" % extra["selection"]["last_row_attention_us_per_layer"])
     cpu = None if args.skip_cpu else cpu_baseline()

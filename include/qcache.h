@@ -201,8 +201,8 @@ qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t 
  * tokens inside each sequence's visual span are neither computed nor written: this is the projector
  * work the method omits ("Efficiency Analysis", FLOPs and Latency).  bf16 only.
  *   x: DEVICE, bf16, token t at x + t*x_stride (elements), d_model values; 16-byte aligned rows.
- *   w_q, w_k: DEVICE, bf16, [n_heads*head_dim][d_model] row-major (row = output feature), 16-byte
- *     aligned.  q, k: DEVICE, bf16, element (t, h, d) at t*token_stride + h*head_stride + d: the
+ *   w_q, w_k: DEVICE, bf16, [n_heads*head_dim] rows (row = output feature) of d_model values, row r at
+ *     w + r*w_stride (elements), 16-byte aligned rows.  q, k: DEVICE, bf16, element (t, h, d) at t*token_stride + h*head_stride + d: the
  *     tensors qc_prefill / qc_decode take.
  *   cu_seqlens: HOST, batch+1 entries: sequence b owns tokens cu_seqlens[b] .. cu_seqlens[b+1]-1.
  *   pos0: HOST, batch entries or NULL (= all 0): position of sequence b's first token (0 for a prompt,
@@ -212,9 +212,9 @@ qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t 
  *     convention: element d < D/2 of a head pairs with d + D/2, angle pos * theta^(-2d/D));
  *     0 = no rotation.
  * Limits (QC_EINVAL): head_dim 64 or 128; d_model a multiple of 64; n_heads*head_dim a multiple of
- * 256; tokens*x_stride*2 and n_heads*head_dim*d_model*2 below 2^31 bytes. */
-qc_status qc_project_qk(const void* x, int64_t x_stride, const void* w_q, const void* w_k, void* q, void* k,
-                        int64_t token_stride, int64_t head_stride, int32_t d_model, int32_t n_heads,
+ * 256; tokens*x_stride*2 and n_heads*head_dim*w_stride*2 below 2^31 bytes. */
+qc_status qc_project_qk(const void* x, int64_t x_stride, const void* w_q, const void* w_k, int64_t w_stride,
+                        void* q, void* k, int64_t token_stride, int64_t head_stride, int32_t d_model, int32_t n_heads,
                         int32_t head_dim, int32_t batch, const int32_t* cu_seqlens, const int32_t* pos0,
                         const int32_t* vis_start, const int32_t* vis_len, int32_t skip_span,
                         float rope_theta, void* stream);

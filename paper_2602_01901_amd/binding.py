@@ -55,7 +55,7 @@ _PROTOTYPES = {
     "qc_seq_len": (c_int32, [c_void_p, c_int32, POINTER(c_int32)]),
     "qc_locate": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, POINTER(c_int32),
                             POINTER(c_int64)]),
-    "qc_project_qk": (c_int32, [c_void_p, c_int64, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int32,
+    "qc_project_qk": (c_int32, [c_void_p, c_int64, c_void_p, c_void_p, c_int64, c_void_p, c_void_p, c_int64, c_int64, c_int32,
                                 c_int32, c_int32, c_int32, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32),
                                 POINTER(c_int32), c_int32, c_float, c_void_p]),
     "qc_select_workspace_bytes": (c_size_t, [POINTER(qc_config)]),
@@ -205,9 +205,9 @@ def qc_locate(kv, which, layer, b, h, pos):
     return src.value, off.value
 
 
-def qc_project_qk(x, x_stride, w_q, w_k, q, k, token_stride, head_stride, d_model, n_heads, head_dim, batch,
+def qc_project_qk(x, x_stride, w_q, w_k, w_stride, q, k, token_stride, head_stride, d_model, n_heads, head_dim, batch,
                   cu_seqlens, pos0, vis_start, vis_len, skip_span, rope_theta, stream=None):
-    return _check(load_library().qc_project_qk(_ptr(x), x_stride, _ptr(w_q), _ptr(w_k), _ptr(q), _ptr(k),
+    return _check(load_library().qc_project_qk(_ptr(x), x_stride, _ptr(w_q), _ptr(w_k), w_stride, _ptr(q), _ptr(k),
                                               token_stride, head_stride, d_model, n_heads, head_dim, batch,
                                               _i32(cu_seqlens), _i32(pos0), _i32(vis_start), _i32(vis_len),
                                               int(skip_span), rope_theta, stream))

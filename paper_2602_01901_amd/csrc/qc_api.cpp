@@ -472,8 +472,8 @@ qc_status qc_stats(const qc_kvcache* kv, const qc_qcache* qc, qc_stats_t* out) {
 }
 
 // ---- query/key projection (Eq. 7: text rows only in a lazy layer) ----------------------------------
-qc_status qc_project_qk(const void* x, int64_t x_stride, const void* w_q, const void* w_k, void* q, void* k,
-                        int64_t token_stride, int64_t head_stride, int32_t d_model, int32_t n_heads,
+qc_status qc_project_qk(const void* x, int64_t x_stride, const void* w_q, const void* w_k, int64_t w_stride,
+                        void* q, void* k, int64_t token_stride, int64_t head_stride, int32_t d_model, int32_t n_heads,
                         int32_t head_dim, int32_t batch, const int32_t* cu_seqlens, const int32_t* pos0,
                         const int32_t* vis_start, const int32_t* vis_len, int32_t skip_span,
                         float rope_theta, void* stream) {
@@ -483,10 +483,12 @@ qc_status qc_project_qk(const void* x, int64_t x_stride, const void* w_q, const 
   if (batch < 1 || n_heads < 1 || d_model < 64 || d_model % 64) return fail(QC_EINVAL, "qc_project_qk: d_model must be a positive multiple of 64, batch and n_heads positive");
   const int64_t n_out = (int64_t)n_heads * head_dim;
   if (n_out % 256) return fail(QC_EINVAL, "qc_project_qk: n_heads*head_dim must be a multiple of 256");
-  if (x_stride < d_model || (x_stride * 2) % 16 || head_stride < head_dim || token_stride < head_dim)
+  if (x_stride < d_model || (x_stride * 2) % 16 || w_stride < d_model || (w_stride * 2) % 16 ||
+      head_stride < head_dim || token_stride < head_dim)
     return fail(QC_EINVAL, "qc_project_qk: bad strides");
   if (((uintptr_t)x | (uintptr_t)w_q | (uintptr_t)w_k) & 15) return fail(QC_EINVAL, "qc_project_qk: x and the weights must be 16-byte aligned");
-  if (((uintptr_t)q | (uintptr_t)k) & 1) return fail(QC_EINVAL, "qc_project_qk: q and k must be 2-byte aligned");
+  if ((((uintptr_t)q | (uintptr_t)k) & 15) || (token_stride * 2) % 16 || (head_stride * 2) % 16)
+    return fail(QC_EINVAL, "qc_project_qk: q and k and their strides must keep rows 16-byte aligned");
   if (!(rope_theta >= 0.0f) || !std::isfinite(rope_theta)) return fail(QC_EINVAL, "qc_project_qk: bad rope_theta");
   if (cu_seqlens[0] != 0) return fail(QC_EINVAL, "qc_project_qk: cu_seqlens[0] must be 0");
   for (int b = 0; b < batch; ++b) {
@@ -495,14 +497,14 @@ qc_status qc_project_qk(const void* x, int64_t x_stride, const void* w_q, const 
     if (skip_span && (vis_start[b] < 0 || vis_len[b] < 0)) return fail(QC_EINVAL, "qc_project_qk: negative span");
   }
   const int64_t tokens = cu_seqlens[batch];
-  if (tokens * x_stride * 2 >= ((int64_t)1 << 31) || n_out * d_model * 2 >= ((int64_t)1 << 31))
+  if (tokens * x_stride * 2 >= ((int64_t)1 << 31) || n_out * w_stride * 2 >= ((int64_t)1 << 31))
     return fail(QC_EINVAL, "qc_project_qk: x or a weight matrix spans 2 GiB or more");
 
   qc::ProjectArgs a;
   a.x = x;
   a.w[0] = w_q; a.w[1] = w_k;
   a.out[0] = q; a.out[1] = k;
-  a.x_stride = x_stride; a.token_stride = token_stride; a.head_stride = head_stride;
+  a.x_stride = x_stride; a.w_stride = w_stride; a.token_stride = token_stride; a.head_stride = head_stride;
   a.d_model = d_model; a.n_heads = n_heads; a.head_dim = head_dim;
   a.rope_theta = rope_theta;
   a.log2_theta = rope_theta > 0.0f ? std::log2((double)rope_theta) : 0.0;
@@ -531,7 +533,9 @@ qc_status qc_project_qk(const void* x, int64_t x_stride, const void* w_q, const 
     }
     if (rows == 0) continue;
     const int m_tiles = (int)((rows + 255) / 256);
-    hipError_t e = qc::launch_project_qk(a, m_tiles, (hipStream_t)stream);
+    // A handful of rows (a decode step) is a matter of streaming the weights once: separate kernel.
+    hipError_t e = rows <= 32 ? qc::launch_project_qk_skinny(a, (int)rows, (hipStream_t)stream)
+                              : qc::launch_project_qk(a, m_tiles, (hipStream_t)stream);
     if (e != hipSuccess) return fail(QC_EDEVICE, "qc_project_qk: %s", hipGetErrorString(e));
   }
   return QC_OK;

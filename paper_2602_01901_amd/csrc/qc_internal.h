@@ -99,9 +99,9 @@ struct ProjectSegs {      // rows to project: contiguous token ranges, in order 
 
 struct ProjectArgs {
   const void* x;          // [tokens][d_model] bf16, row stride x_stride elements
-  const void* w[2];       // W_Q, W_K: [H*D][d_model] bf16
+  const void* w[2];       // W_Q, W_K: [H*D] rows of d_model bf16, row stride w_stride elements
   void* out[2];           // q, k: element (t, h, d) at t*token_stride + h*head_stride + d
-  int64_t x_stride, token_stride, head_stride;
+  int64_t x_stride, w_stride, token_stride, head_stride;
   int32_t d_model, n_heads, head_dim;
   float rope_theta;       // 0: no rotary embedding
   double log2_theta;
@@ -167,5 +167,6 @@ hipError_t launch_js(const float* pm, const float* pn, int64_t stride, int first
                      float* js_out, hipStream_t stream);
 hipError_t launch_mean(const float* x, int n, float* out, hipStream_t stream);
 hipError_t launch_project_qk(const ProjectArgs& a, int m_tiles, hipStream_t stream);
+hipError_t launch_project_qk_skinny(const ProjectArgs& a, int n_rows, hipStream_t stream);
 
 }  // namespace qc

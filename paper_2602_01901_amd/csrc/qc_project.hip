@@ -9,7 +9,8 @@
 // tensors the attention entry points take.  Rows inside the span are neither computed nor written.
 //
 // One workgroup = 8 waves = a 256 x 256 output tile of one matrix (W_Q or W_K); K is walked in
-// steps of 64 through a double-buffered LDS ring filled by global_load_lds_dwordx4.  Wave (wm, wn)
+// steps of 64 through a double-buffered LDS ring filled by global_load_lds_dwordx4 (steps of 32
+// with a four-stage ring, three tiles ahead, measured 8 % slower: twice as many half-line requests).  Wave (wm, wn)
 // owns 128 rows x 2 column blocks of 32 that form a rotary pair (d, d + D/2) of one head, so the
 // rotation needs no data exchange: both halves of a pair sit in the same lane and register index.
 // Per k-step of 16 a wave reads 4 row fragments and 2 column fragments for 8 MFMAs (0.75 KB of LDS
@@ -23,14 +24,25 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 namespace pj {
-constexpr int BM = 256, BN = 256, BK = 64;
+#ifndef PJ_BK
+#define PJ_BK 64
+#endif
+constexpr int BM = 256, BN = 256, BK = PJ_BK;
 constexpr int ROWB = BK * 2;            // bytes per tile row
-constexpr int TILE_A = BM * ROWB;       // 32 KB
-constexpr int TILE_B = BN * ROWB;       // 32 KB
-constexpr int STAGE = TILE_A + TILE_B;  // 64 KB
-constexpr int STAGES = 2;
+constexpr int CH = ROWB / 16;           // 16-byte chunks per row
+constexpr int RPI = 64 / CH;            // tile rows one wave-wide load instruction fills
+constexpr int LPT = 32 / RPI;           // load instructions per wave, tile and matrix (a wave fills 32 rows)
+constexpr int KSUB = BK / 16;           // MFMA k-steps per tile
+constexpr int TILE_A = BM * ROWB;       // 16 KB
+constexpr int TILE_B = BN * ROWB;       // 16 KB
+constexpr int STAGE = TILE_A + TILE_B;  // 32 KB
+constexpr int AHEAD = BK == 32 ? 3 : 1; // tiles in flight ahead of the one being multiplied
+constexpr int STAGES = AHEAD + 1;
+// chunk c of row r is stored at chunk c ^ swz(r): 16 consecutive rows then cover all 64 banks
+__device__ __forceinline__ int swz(int r) { return BK == 32 ? (r >> 2) & 3 : (r >> 1) & 7; }
 constexpr int TABLE = BM * 8;           // row table: (token, position) per tile row
-constexpr int LDS_BYTES = STAGES * STAGE + TABLE;
+constexpr int OUT_ROWB = BN * 2 + 16;   // output staging tile (bf16): padded rows, see the epilogue
+constexpr int LDS_BYTES = TABLE + (STAGES * STAGE > BM * OUT_ROWB ? STAGES * STAGE : BM * OUT_ROWB);
 }  // namespace pj
 
 __device__ __forceinline__ void pj_async_copy16(const char* sbase, uint32_t voff, uint32_t lds_off) {
@@ -52,8 +64,9 @@ template <int N> __device__ __forceinline__ void pj_wait_vmcnt() {
 template <int D>
 __global__ __launch_bounds__(512, 1) void project_qk_kernel(ProjectArgs a) {
   using namespace pj;
-  extern __shared__ __attribute__((aligned(16))) char lds[];
-  int2* table = (int2*)(lds + STAGES * STAGE);
+  extern __shared__ __attribute__((aligned(16))) char lds_all[];
+  int2* table = (int2*)lds_all;
+  char* lds = lds_all + TABLE;  // the tile ring; reused as the output staging tile at the end
 
   const int n0 = blockIdx.x * BN, m0 = blockIdx.y * BM, which = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -76,16 +89,16 @@ __global__ __launch_bounds__(512, 1) void project_qk_kernel(ProjectArgs a) {
   }
   __syncthreads();
 
-  // ---- tile loader: wave w fills rows w*32 + p*8 + lane/8 (p = 0..3) of the A and of the B tile
-  const int lrow = wave * 32 + (lane >> 3), lchunk = lane & 7;
-  uint32_t off_a[4], off_b[4];
+  // ---- tile loader: wave w fills rows w*32 + p*RPI + lane/CH (p < LPT) of the A and of the B tile
+  const int lrow = wave * 32 + lane / CH, lchunk = lane % CH;
+  uint32_t off_a[LPT], off_b[LPT];
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int r = lrow + p * 8;
+  for (int p = 0; p < LPT; ++p) {
+    const int r = lrow + p * RPI;
     const int tok = max(table[r].x, 0);  // rows past the end repeat token 0; their results are not stored
-    const int sw = (lchunk ^ ((r >> 1) & 7)) * 16;
+    const int sw = (lchunk ^ swz(r)) * 16;
     off_a[p] = (uint32_t)tok * (uint32_t)(a.x_stride * 2) + sw;
-    off_b[p] = (uint32_t)(n0 + r) * (uint32_t)(a.d_model * 2) + sw;
+    off_b[p] = (uint32_t)(n0 + r) * (uint32_t)(a.w_stride * 2) + sw;
   }
   const char* xbase = pj_uniform_ptr((const char*)a.x);
   const char* wbase = pj_uniform_ptr((const char*)a.w[which]);
@@ -96,28 +109,28 @@ __global__ __launch_bounds__(512, 1) void project_qk_kernel(ProjectArgs a) {
     const char* xs = xbase + (uint64_t)t * (BK * 2);
     const char* ws = wbase + (uint64_t)t * (BK * 2);
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      pj_async_copy16(xs, off_a[p], ab + p * 8 * ROWB);
-      pj_async_copy16(ws, off_b[p], bb + p * 8 * ROWB);
+    for (int p = 0; p < LPT; ++p) {
+      pj_async_copy16(xs, off_a[p], ab + p * RPI * ROWB);
+      pj_async_copy16(ws, off_b[p], bb + p * RPI * ROWB);
     }
   };
 
   // ---- fragment read offsets (tile-independent): k-substep ks uses logical chunk ks*2 + hf
-  int a_off[4][4], b_off[2][4];  // [block][ks]
+  int a_off[4][KSUB], b_off[2][KSUB];  // [block][ks]
   constexpr int PAIR = D / 2;    // distance of a rotary pair inside a head
   // column blocks of this wave inside the 256-column tile: a head's block j and j + PAIR/32
   const int col0 = (D == 128) ? (wn >> 1) * 128 + (wn & 1) * 32 : wn * 64;
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
+  for (int ks = 0; ks < KSUB; ++ks) {
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb) {
       const int r = wm * 128 + mb * 32 + l32;
-      a_off[mb][ks] = r * ROWB + (((ks * 2 + hf) ^ ((r >> 1) & 7)) * 16);
+      a_off[mb][ks] = r * ROWB + (((ks * 2 + hf) ^ swz(r)) * 16);
     }
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
       const int r = col0 + nb * PAIR + l32;
-      b_off[nb][ks] = TILE_A + r * ROWB + (((ks * 2 + hf) ^ ((r >> 1) & 7)) * 16);
+      b_off[nb][ks] = TILE_A + r * ROWB + (((ks * 2 + hf) ^ swz(r)) * 16);
     }
   }
 
@@ -130,64 +143,208 @@ __global__ __launch_bounds__(512, 1) void project_qk_kernel(ProjectArgs a) {
       for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
 
   const int n_steps = a.d_model / BK;
-  load_tile(0);
+#pragma unroll
+  for (int t = 0; t < AHEAD; ++t)
+    if (t < n_steps) load_tile(t);
+
+  // Operand fragments are double buffered in registers across the k-steps AND across the tile
+  // boundary: while the 8 MFMAs of one k-step run, the 6 fragment reads of the next one are in
+  // flight, so neither the LDS latency nor the barrier sits between two groups of MFMAs.
+  bf16x8 af[2][4], bf[2][2];
+  auto read_frags = [&](int buf, const char* sb, int ks) {
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) af[buf][mb] = *(const bf16x8*)(sb + a_off[mb][ks]);
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) bf[buf][nb] = *(const bf16x8*)(sb + b_off[nb][ks]);
+  };
+  auto multiply = [&](int buf) {
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][mb], bf[buf][nb], acc[mb][nb], 0, 0, 0);
+  };
+  static_assert(KSUB % 2 == 0, "the two register buffers alternate per k-step");
+  // Tile t has landed when at most the loads of the tiles behind it are outstanding (loads complete
+  // in order); near the end fewer tiles are in flight, so wait for everything.
+  if (AHEAD <= n_steps) pj_wait_vmcnt<(AHEAD - 1) * 2 * LPT>();
+  else pj_wait_vmcnt<0>();
+  __syncthreads();
+  if (AHEAD < n_steps) load_tile(AHEAD);
+  read_frags(0, lds, 0);
   for (int t = 0; t < n_steps; ++t) {
-    pj_wait_vmcnt<0>();
-    __syncthreads();  // tile t visible to every wave; every wave is done with tile t-1
-    if (t + 1 < n_steps) load_tile(t + 1);
     const char* sb = lds + (t % STAGES) * STAGE;
-    bf16x8 af[2][4], bf[2][2];
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb) af[0][mb] = *(const bf16x8*)(sb + a_off[mb][0]);
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) bf[0][nb] = *(const bf16x8*)(sb + b_off[nb][0]);
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const int cur = ks & 1, nxt = cur ^ 1;
-      if (ks + 1 < 4) {
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb) af[nxt][mb] = *(const bf16x8*)(sb + a_off[mb][ks + 1]);
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) bf[nxt][nb] = *(const bf16x8*)(sb + b_off[nb][ks + 1]);
+    for (int ks = 0; ks < KSUB; ++ks) {
+      const int cur = ks & 1;
+      if (ks + 1 < KSUB) {
+        read_frags(cur ^ 1, sb, ks + 1);
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+      } else if (t + 1 < n_steps) {
+        if (t + 1 + AHEAD <= n_steps) pj_wait_vmcnt<(AHEAD - 1) * 2 * LPT>();
+        else pj_wait_vmcnt<0>();
+        __syncthreads();  // tile t+1 visible to every wave; the stage refilled next was read a whole tile ago
+        if (t + 1 + AHEAD < n_steps) load_tile(t + 1 + AHEAD);
+        read_frags(cur ^ 1, lds + ((t + 1) % STAGES) * STAGE, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
       }
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-          acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][mb], bf[cur][nb], acc[mb][nb], 0, 0, 0);
+      multiply(cur);
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     }
   }
 
-  // ---- rotary embedding and store.  Accumulator register r of block (mb, nb) holds row
-  // wm*128 + mb*32 + (r/4)*8 + hf*4 + r%4 and column col0 + nb*PAIR + l32 of the tile.
-  const int col = n0 + col0 + l32;      // output feature of the lower half of the pair
-  const int head = col / D, d = col % D;  // d < PAIR
-  double inv_freq = 0.0;
-  if (a.rope_theta > 0.f) inv_freq = exp2(-2.0 * (double)d / (double)D * a.log2_theta);
-  char* obase = (char*)a.out[which] + ((int64_t)head * a.head_stride + d) * 2;
+  // ---- rotary embedding, then the tile goes through LDS so that it leaves in 16-byte pieces
+  // (two whole 512-byte output rows per wave instruction).  Accumulator register r of block
+  // (mb, nb) holds row wm*128 + mb*32 + (r/4)*8 + hf*4 + r%4 and column col0 + nb*PAIR + l32.
+  const int tcol = col0 + l32;            // tile column of the lower half of the pair
+  const int d = (n0 + tcol) % D;          // rotary index, < PAIR
+  // The hardware sine and cosine take their argument in revolutions: the angle pos * theta^(-2d/D)
+  // is formed and reduced to [-1/2, 1/2] revolutions in double precision, then evaluated in single.
+  double rev_per_pos = 0.0;
+  if (a.rope_theta > 0.f) rev_per_pos = exp2(-2.0 * (double)d / (double)D * a.log2_theta) * 0.15915494309189535;
+  __syncthreads();  // every wave is done with the ring
+  // Staging rows are 16 bytes longer than the tile row: the two lane halves of a wave write rows
+  // four apart, which then fall into different banks.
 #pragma unroll
   for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int row = wm * 128 + mb * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
-      const int2 tp = table[row];
-      if (tp.x < 0) continue;
       float lo = acc[mb][0][r], hi = acc[mb][1][r];
       if (a.rope_theta > 0.f) {
-        // angle reduced to [-pi, pi] in double, sine and cosine in single precision
-        const double ang = (double)tp.y * inv_freq;
-        const double turns = ang * 0.15915494309189535;  // 1 / (2 pi)
-        const float red = (float)((turns - rint(turns)) * 6.283185307179586);
-        float sn, cs;
-        __sincosf(red, &sn, &cs);
+        const double rev = (double)table[row].y * rev_per_pos;
+        const float frac = (float)(rev - rint(rev));
+        const float sn = __builtin_amdgcn_sinf(frac), cs = __builtin_amdgcn_cosf(frac);
         const float nlo = lo * cs - hi * sn, nhi = hi * cs + lo * sn;
         lo = nlo;
         hi = nhi;
       }
-      bf16_t* o = (bf16_t*)(obase + (int64_t)tp.x * a.token_stride * 2);
+      bf16_t* o = (bf16_t*)(lds + row * OUT_ROWB) + tcol;
       o[0] = (bf16_t)lo;
       o[PAIR] = (bf16_t)hi;
     }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < BM * (BN / 8) / 512; ++it) {
+    const int piece = it * 512 + tid;
+    const int row = piece / (BN / 8), ch = piece % (BN / 8);
+    const int tok = table[row].x;
+    if (tok < 0) continue;
+    const int col = n0 + ch * 8;
+    const uint4 v = *(const uint4*)(lds + row * OUT_ROWB + ch * 16);
+    *(uint4*)((char*)a.out[which] + ((int64_t)tok * a.token_stride + (int64_t)(col / D) * a.head_stride + col % D) * 2) = v;
+  }
+}
+
+// ---- at most 32 rows (a decode step): the work is reading both weight matrices once -------------
+// One workgroup = 4 waves = one rotary pair of 16-column groups (16 features d, 16 features d + D/2)
+// of one head of one matrix, all rows, all of K.  Wave w takes the k-steps of 32 congruent to w
+// mod 4, so that a round of the four waves reads 256 contiguous bytes of every weight row.
+// Operands go straight from global memory into v_mfma_f32_16x16x32_bf16 fragments (nothing is
+// reused inside a workgroup: the rows of x are few and stay in L2 for the other workgroups); the
+// four partial 32 x 32 results are added in a fixed order through LDS, rotated and stored.
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+template <int D>
+__global__ __launch_bounds__(256) void project_qk_skinny_kernel(ProjectArgs a, int n_rows) {
+  constexpr int PAIR = D / 2, GROUPS = PAIR / 16;
+  __shared__ float part[4][32][33];
+  __shared__ int2 table[32];
+  const int which = blockIdx.y;
+  const int head = blockIdx.x / GROUPS, grp = blockIdx.x % GROUPS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, kq = lane >> 4;  // fragment row / column, and which 8 of the 32 k values
+
+  if (tid < 32) {
+    int tok = -1, pos = 0, base = 0;
+    for (int s = 0; s < a.segs.n; ++s) {
+      const int c = a.segs.count[s];
+      if (tid >= base && tid < base + c) {
+        tok = a.segs.tok_start[s] + (tid - base);
+        pos = a.segs.pos_start[s] + (tid - base);
+      }
+      base += c;
+    }
+    table[tid] = make_int2(tok, pos);
+  }
+  __syncthreads();
+
+  const int col_lo = head * D + grp * 16 + l16;
+  const char* w_lo = (const char*)a.w[which] + ((int64_t)col_lo * a.w_stride + kq * 8) * 2;
+  const char* w_hi = w_lo + (int64_t)PAIR * a.w_stride * 2;
+  const char* x0 = (const char*)a.x + ((int64_t)max(table[l16].x, 0) * a.x_stride + kq * 8) * 2;
+  const char* x1 = (const char*)a.x + ((int64_t)max(table[16 + l16].x, 0) * a.x_stride + kq * 8) * 2;
+  const bool two = n_rows > 16;
+
+  f32x4 acc[2][2];  // [row block][lo, hi]
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int n_steps = a.d_model / 32;
+  constexpr int UN = 8;  // k-steps in flight per wave
+  for (int ks0 = wave; ks0 < n_steps; ks0 += 4 * UN) {
+    bf16x8 bl[UN], bh[UN], a0[UN], a1[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int ks = ks0 + 4 * u;
+      if (ks < n_steps) {
+        const int64_t off = (int64_t)ks * 64;
+        bl[u] = __builtin_bit_cast(bf16x8, *(const uint4*)(w_lo + off));
+        bh[u] = __builtin_bit_cast(bf16x8, *(const uint4*)(w_hi + off));
+        a0[u] = __builtin_bit_cast(bf16x8, *(const uint4*)(x0 + off));
+        if (two) a1[u] = __builtin_bit_cast(bf16x8, *(const uint4*)(x1 + off));
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      if (ks0 + 4 * u < n_steps) {
+        acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[u], bl[u], acc[0][0], 0, 0, 0);
+        acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[u], bh[u], acc[0][1], 0, 0, 0);
+        if (two) {
+          acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[u], bl[u], acc[1][0], 0, 0, 0);
+          acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[u], bh[u], acc[1][1], 0, 0, 0);
+        }
+      }
+    }
+  }
+  // accumulator register i of block (rb, c) holds row rb*16 + kq*4 + i, column c*16 + l16
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) part[wave][rb * 16 + kq * 4 + i][c * 16 + l16] = acc[rb][c][i];
+  __syncthreads();
+  // 32 rows x 16 pairs: two items per thread; the four partials are added in wave order
+  for (int item = tid; item < 32 * 16; item += 256) {
+    const int row = item >> 4, j = item & 15;
+    const int2 tp = table[row];
+    if (tp.x < 0) continue;
+    float lo = ((part[0][row][j] + part[1][row][j]) + part[2][row][j]) + part[3][row][j];
+    float hi = ((part[0][row][16 + j] + part[1][row][16 + j]) + part[2][row][16 + j]) + part[3][row][16 + j];
+    const int d = grp * 16 + j;
+    if (a.rope_theta > 0.f) {
+      const double rev = (double)tp.y * exp2(-2.0 * (double)d / (double)D * a.log2_theta) * 0.15915494309189535;
+      const float frac = (float)(rev - rint(rev));
+      const float sn = __builtin_amdgcn_sinf(frac), cs = __builtin_amdgcn_cosf(frac);
+      const float nlo = lo * cs - hi * sn, nhi = hi * cs + lo * sn;
+      lo = nlo;
+      hi = nhi;
+    }
+    bf16_t* o = (bf16_t*)a.out[which] + (int64_t)tp.x * a.token_stride + (int64_t)head * a.head_stride + d;
+    o[0] = (bf16_t)lo;
+    o[PAIR] = (bf16_t)hi;
+  }
+}
+
+hipError_t launch_project_qk_skinny(const ProjectArgs& a, int n_rows, hipStream_t stream) {
+  if (a.head_dim == 128) {
+    hipLaunchKernelGGL(project_qk_skinny_kernel<128>, dim3(a.n_heads * 4, 2), dim3(256), 0, stream, a, n_rows);
+  } else {
+    hipLaunchKernelGGL(project_qk_skinny_kernel<64>, dim3(a.n_heads * 2, 2), dim3(256), 0, stream, a, n_rows);
+  }
+  return hipGetLastError();
 }
 
 hipError_t launch_project_qk(const ProjectArgs& a, int m_tiles, hipStream_t stream) {

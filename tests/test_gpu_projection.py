@@ -23,7 +23,7 @@ def make_inputs(tokens, d_model, n_out, seed):
     return x, wq, wk
 
 
-def run_case(lens, spans, pos0, d_model, H, D, theta, skip_span, seed, sample_rows=None):
+def run_case(lens, spans, pos0, d_model, H, D, theta, skip_span, seed, sample_rows=None, pad=0):
     cu = [0]
     for L in lens:
         cu.append(cu[-1] + L)
@@ -32,9 +32,14 @@ def run_case(lens, spans, pos0, d_model, H, D, theta, skip_span, seed, sample_ro
     sentinel = 7.0
     q = torch.full((tokens, H, D), sentinel, dtype=torch.bfloat16, device="cuda")
     k = torch.full((tokens, H, D), sentinel, dtype=torch.bfloat16, device="cuda")
-    xd, wqd, wkd = x.cuda(), wq.cuda(), wk.cuda()
+    def padded(t):   # rows of d_model + pad elements; the padding holds NaN and must never be read
+        buf = torch.full((t.shape[0], d_model + pad), float("nan"), dtype=torch.bfloat16, device="cuda")
+        buf[:, :d_model] = t.cuda()
+        return buf
+    xd, wqd, wkd = padded(x), padded(wq), padded(wk)
     vs, vl = [s for s, _ in spans], [n for _, n in spans]
-    B.qc_project_qk(xd, d_model, wqd, wkd, q, k, H * D, D, d_model, H, D, len(lens), cu, pos0, vs, vl, skip_span, theta)
+    B.qc_project_qk(xd, d_model + pad, wqd, wkd, d_model + pad, q, k, H * D, D, d_model, H, D, len(lens), cu, pos0, vs,
+                    vl, skip_span, theta)
     torch.cuda.synchronize()
     rows, positions = [], []
     for b, L in enumerate(lens):
@@ -70,7 +75,7 @@ def run_case(lens, spans, pos0, d_model, H, D, theta, skip_span, seed, sample_ro
 def test_projection_small_ragged_batch(D, H, theta):
     lens, spans = [131, 64, 45, 300], [(5, 70), (0, 33), (17, 0), (40, 260)]
     for skip in (0, 1):
-        w = run_case(lens, spans, None, 256, H, D, theta, skip, seed=D + skip)
+        w = run_case(lens, spans, None, 256, H, D, theta, skip, seed=D + skip, pad=64 * skip)
         print("projection D=%d theta=%g skip=%d: max abs err %.3g" % (D, theta, skip, w), flush=True)
 
 
@@ -81,6 +86,10 @@ def test_projection_decode_shape_with_positions():
     run_case(lens, [(0, 0)] * 9, pos0, 512, 4, 128, 10000.0, 0, seed=3)
     # a sequence whose only token lies inside its span projects nothing
     run_case([1, 1], [(0, 10), (0, 0)], [5, 5], 256, 2, 128, 10000.0, 1, seed=4)
+    # 17..32 rows use the second row block of the few-rows kernel; head_dim 64; no rotation; short prompts
+    run_case([1] * 21, [(0, 0)] * 21, [100 + 37 * i for i in range(21)], 512, 4, 64, 10000.0, 0, seed=9)
+    run_case([1] * 32, [(0, 0)] * 32, [3 * i for i in range(32)], 4096, 32, 128, 10000.0, 0, seed=10)
+    run_case([5, 9, 14], [(1, 2), (0, 0), (4, 9)], None, 320, 2, 128, 0.0, 1, seed=11, pad=64)
 
 
 def test_projection_everything_skipped_and_many_sequences():

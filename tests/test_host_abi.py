@@ -274,7 +274,7 @@ def test_selection_calls_validate_before_launching():
 
 
 def test_project_qk_validation():
-    ok = dict(x=FAKE, x_stride=256, w_q=FAKE, w_k=FAKE, q=FAKE, k=FAKE, token_stride=256, head_stride=128,
+    ok = dict(x=FAKE, x_stride=256, w_q=FAKE, w_k=FAKE, w_stride=256, q=FAKE, k=FAKE, token_stride=256, head_stride=128,
               d_model=256, n_heads=2, head_dim=128, batch=1, cu_seqlens=[0, 10], pos0=None, vis_start=[2],
               vis_len=[3], skip_span=1, rope_theta=10000.0)
 
@@ -285,7 +285,7 @@ def test_project_qk_validation():
 
     for kw in (dict(head_dim=96), dict(d_model=200), dict(n_heads=1), dict(x=None), dict(x_stride=128),
                dict(x=FAKE + 2), dict(cu_seqlens=[1, 10]), dict(cu_seqlens=[0, -1]), dict(rope_theta=-1.0),
-               dict(vis_start=None), dict(pos0=[-1]), dict(x_stride=1 << 29)):
+               dict(vis_start=None), dict(pos0=[-1]), dict(x_stride=1 << 29), dict(w_stride=128), dict(w_stride=260)):
         with pytest.raises(P.QcError) as e:
             call(**kw)
         assert e.value.status == B.QC_EINVAL, kw
