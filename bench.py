@@ -298,7 +298,8 @@ def bench_projection(args):
         out[name] = {"rows": rows, "us": ev_s * 1e6, "tflops": flops / ev_s / 1e12,
                      "roofline": {"bound": "mfma", "kernel": "project_qk_kernel<128> (W_Q and W_K in one launch)",
                                   "achieved": flops / ev_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                  "frac": flops / ev_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                                  "frac": flops / ev_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                                  "traffic": measured_traffic("projection_ordinary" if not skip else "projection_lazy"),
                                   "avg_launch_us": ev_s * 1e6, "algorithmic_flops_per_launch": flops}}
     out["time_saved_per_lazy_layer_us"] = out["ordinary_layer"]["us"] - out["lazy_layer_text_rows"]["us"]
     # decode: one token per sequence (batch 32): weight streaming, 2 x 33.5 MB per layer
@@ -314,7 +315,8 @@ def bench_projection(args):
     out["decode_batch32"] = {"us": ev_s * 1e6,
                              "roofline": {"bound": "hbm", "kernel": "project_qk_skinny_kernel<128>",
                                           "achieved": dec_bytes / ev_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                          "frac": dec_bytes / ev_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                                          "frac": dec_bytes / ev_s / 1e9 / HBM_PEAK_GBS,
+                                          "traffic": measured_traffic("projection_decode"),
                                           "avg_launch_us": ev_s * 1e6, "algorithmic_bytes_per_launch": dec_bytes}}
     del x, wq, wk, q, k
     torch.cuda.empty_cache()
