@@ -532,10 +532,9 @@ qc_status qc_project_qk(const void* x, int64_t x_stride, const void* w_q, const 
       ++b;
     }
     if (rows == 0) continue;
-    const int m_tiles = (int)((rows + 255) / 256);
     // A handful of rows (a decode step) is a matter of streaming the weights once: separate kernel.
     hipError_t e = rows <= 32 ? qc::launch_project_qk_skinny(a, (int)rows, (hipStream_t)stream)
-                              : qc::launch_project_qk(a, m_tiles, (hipStream_t)stream);
+                              : qc::launch_project_qk(a, (int)rows, (hipStream_t)stream);
     if (e != hipSuccess) return fail(QC_EDEVICE, "qc_project_qk: %s", hipGetErrorString(e));
   }
   return QC_OK;

@@ -166,7 +166,7 @@ hipError_t launch_last_row_attention(const SelectArgs& a, int dtype, int max_len
 hipError_t launch_js(const float* pm, const float* pn, int64_t stride, int first, int count, const JsChunk& c,
                      float* js_out, hipStream_t stream);
 hipError_t launch_mean(const float* x, int n, float* out, hipStream_t stream);
-hipError_t launch_project_qk(const ProjectArgs& a, int m_tiles, hipStream_t stream);
+hipError_t launch_project_qk(const ProjectArgs& a, int rows, hipStream_t stream);
 hipError_t launch_project_qk_skinny(const ProjectArgs& a, int n_rows, hipStream_t stream);
 
 }  // namespace qc

@@ -27,22 +27,26 @@ namespace pj {
 #ifndef PJ_BK
 #define PJ_BK 64
 #endif
-constexpr int BM = 256, BN = 256, BK = PJ_BK;
+constexpr int BN = 256, BK = PJ_BK;      // BM = 64 * MB rows: MB row blocks of 32 per wave, two wave rows
 constexpr int ROWB = BK * 2;            // bytes per tile row
 constexpr int CH = ROWB / 16;           // 16-byte chunks per row
 constexpr int RPI = 64 / CH;            // tile rows one wave-wide load instruction fills
-constexpr int LPT = 32 / RPI;           // load instructions per wave, tile and matrix (a wave fills 32 rows)
+constexpr int LPT = 32 / RPI;           // load instructions per wave for the 256-row B tile (a wave fills 32 rows)
 constexpr int KSUB = BK / 16;           // MFMA k-steps per tile
-constexpr int TILE_A = BM * ROWB;       // 16 KB
-constexpr int TILE_B = BN * ROWB;       // 16 KB
-constexpr int STAGE = TILE_A + TILE_B;  // 32 KB
+constexpr int TILE_B = BN * ROWB;
 constexpr int AHEAD = BK == 32 ? 3 : 1; // tiles in flight ahead of the one being multiplied
 constexpr int STAGES = AHEAD + 1;
 // chunk c of row r is stored at chunk c ^ swz(r): 16 consecutive rows then cover all 64 banks
 __device__ __forceinline__ int swz(int r) { return BK == 32 ? (r >> 2) & 3 : (r >> 1) & 7; }
-constexpr int TABLE = BM * 8;           // row table: (token, position) per tile row
 constexpr int OUT_ROWB = BN * 2 + 16;   // output staging tile (bf16): padded rows, see the epilogue
-constexpr int LDS_BYTES = TABLE + (STAGES * STAGE > BM * OUT_ROWB ? STAGES * STAGE : BM * OUT_ROWB);
+template <int MB> struct Shape {
+  static constexpr int BM = 64 * MB;
+  static constexpr int TILE_A = BM * ROWB;
+  static constexpr int STAGE = TILE_A + TILE_B;
+  static constexpr int LPT_A = (BM / 8) / RPI;   // A-tile load instructions per wave (a wave fills BM/8 rows)
+  static constexpr int TABLE = BM * 8;           // row table: (token, position) per tile row
+  static constexpr int LDS_BYTES = TABLE + (STAGES * STAGE > BM * OUT_ROWB ? STAGES * STAGE : BM * OUT_ROWB);
+};
 }  // namespace pj
 
 __device__ __forceinline__ void pj_async_copy16(const char* sbase, uint32_t voff, uint32_t lds_off) {
@@ -61,14 +65,24 @@ template <int N> __device__ __forceinline__ void pj_wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <int D>
-__global__ __launch_bounds__(512, 1) void project_qk_kernel(ProjectArgs a) {
+template <int D, int MB>
+__global__ __launch_bounds__(512, 1) void project_qk_kernel(ProjectArgs a, int m_tiles) {
   using namespace pj;
+  using S = Shape<MB>;
+  constexpr int BM = S::BM, TILE_A = S::TILE_A, STAGE = S::STAGE, LPT_A = S::LPT_A, TABLE = S::TABLE;
+  static_assert(LPT_A >= 1, "a wave must fill at least one load instruction's worth of A rows");
   extern __shared__ __attribute__((aligned(16))) char lds_all[];
   int2* table = (int2*)lds_all;
   char* lds = lds_all + TABLE;  // the tile ring; reused as the output staging tile at the end
 
-  const int n0 = blockIdx.x * BN, m0 = blockIdx.y * BM, which = blockIdx.z;
+  // ---- which tile: column tiles (both matrices) fastest, so that the workgroups running together
+  // share a few row tiles of x.  (Dealing blocks of 4 x 8 tiles to each XCD was measured: +2 %, and
+  // it unbalances the XCDs when there are few row tiles.)
+  const int nt2 = 2 * (a.n_heads * a.head_dim / BN);
+  const int n_tile2 = blockIdx.x % nt2, m_tile = blockIdx.x / nt2;
+  if (m_tile >= m_tiles) return;
+  const int which = n_tile2 >= nt2 / 2;
+  const int n0 = (n_tile2 - which * (nt2 / 2)) * BN, m0 = m_tile * BM;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
   const int wm = wave >> 2, wn = wave & 3;
@@ -89,42 +103,47 @@ __global__ __launch_bounds__(512, 1) void project_qk_kernel(ProjectArgs a) {
   }
   __syncthreads();
 
-  // ---- tile loader: wave w fills rows w*32 + p*RPI + lane/CH (p < LPT) of the A and of the B tile
-  const int lrow = wave * 32 + lane / CH, lchunk = lane % CH;
-  uint32_t off_a[LPT], off_b[LPT];
+  // ---- tile loader: wave w fills rows w*(BM/8) + p*RPI + lane/CH (p < LPT_A) of the A tile and
+  // rows w*32 + p*RPI + lane/CH (p < LPT) of the B tile
+  const int lchunk = lane % CH;
+  uint32_t off_a[LPT_A], off_b[LPT];
+#pragma unroll
+  for (int p = 0; p < LPT_A; ++p) {
+    const int r = wave * (BM / 8) + lane / CH + p * RPI;
+    const int tok = max(table[r].x, 0);  // rows past the end repeat token 0; their results are not stored
+    off_a[p] = (uint32_t)tok * (uint32_t)(a.x_stride * 2) + (lchunk ^ swz(r)) * 16;
+  }
 #pragma unroll
   for (int p = 0; p < LPT; ++p) {
-    const int r = lrow + p * RPI;
-    const int tok = max(table[r].x, 0);  // rows past the end repeat token 0; their results are not stored
-    const int sw = (lchunk ^ swz(r)) * 16;
-    off_a[p] = (uint32_t)tok * (uint32_t)(a.x_stride * 2) + sw;
-    off_b[p] = (uint32_t)(n0 + r) * (uint32_t)(a.w_stride * 2) + sw;
+    const int r = wave * 32 + lane / CH + p * RPI;
+    off_b[p] = (uint32_t)(n0 + r) * (uint32_t)(a.w_stride * 2) + (lchunk ^ swz(r)) * 16;
   }
   const char* xbase = pj_uniform_ptr((const char*)a.x);
   const char* wbase = pj_uniform_ptr((const char*)a.w[which]);
   const uint32_t lds_base = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)lds;
   auto load_tile = [&](int t) {
-    const uint32_t ab = __builtin_amdgcn_readfirstlane(lds_base + (t % STAGES) * STAGE + wave * 32 * ROWB);
-    const uint32_t bb = ab + TILE_A;
+    const uint32_t st = lds_base + (t % STAGES) * STAGE;
+    const uint32_t ab = __builtin_amdgcn_readfirstlane(st + wave * (BM / 8) * ROWB);
+    const uint32_t bb = __builtin_amdgcn_readfirstlane(st + TILE_A + wave * 32 * ROWB);
     const char* xs = xbase + (uint64_t)t * (BK * 2);
     const char* ws = wbase + (uint64_t)t * (BK * 2);
 #pragma unroll
-    for (int p = 0; p < LPT; ++p) {
-      pj_async_copy16(xs, off_a[p], ab + p * RPI * ROWB);
-      pj_async_copy16(ws, off_b[p], bb + p * RPI * ROWB);
-    }
+    for (int p = 0; p < LPT_A; ++p) pj_async_copy16(xs, off_a[p], ab + p * RPI * ROWB);
+#pragma unroll
+    for (int p = 0; p < LPT; ++p) pj_async_copy16(ws, off_b[p], bb + p * RPI * ROWB);
   };
+  constexpr int LOADS = LPT_A + LPT;  // load instructions per wave and tile
 
   // ---- fragment read offsets (tile-independent): k-substep ks uses logical chunk ks*2 + hf
-  int a_off[4][KSUB], b_off[2][KSUB];  // [block][ks]
+  int a_off[MB][KSUB], b_off[2][KSUB];  // [block][ks]
   constexpr int PAIR = D / 2;    // distance of a rotary pair inside a head
   // column blocks of this wave inside the 256-column tile: a head's block j and j + PAIR/32
   const int col0 = (D == 128) ? (wn >> 1) * 128 + (wn & 1) * 32 : wn * 64;
 #pragma unroll
   for (int ks = 0; ks < KSUB; ++ks) {
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb) {
-      const int r = wm * 128 + mb * 32 + l32;
+    for (int mb = 0; mb < MB; ++mb) {
+      const int r = wm * (32 * MB) + mb * 32 + l32;
       a_off[mb][ks] = r * ROWB + (((ks * 2 + hf) ^ swz(r)) * 16);
     }
 #pragma unroll
@@ -134,9 +153,9 @@ __global__ __launch_bounds__(512, 1) void project_qk_kernel(ProjectArgs a) {
     }
   }
 
-  f32x16 acc[4][2];
+  f32x16 acc[MB][2];
 #pragma unroll
-  for (int mb = 0; mb < 4; ++mb)
+  for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
@@ -148,18 +167,18 @@ __global__ __launch_bounds__(512, 1) void project_qk_kernel(ProjectArgs a) {
     if (t < n_steps) load_tile(t);
 
   // Operand fragments are double buffered in registers across the k-steps AND across the tile
-  // boundary: while the 8 MFMAs of one k-step run, the 6 fragment reads of the next one are in
+  // boundary: while the 2*MB MFMAs of one k-step run, the MB+2 fragment reads of the next one are in
   // flight, so neither the LDS latency nor the barrier sits between two groups of MFMAs.
-  bf16x8 af[2][4], bf[2][2];
+  bf16x8 af[2][MB], bf[2][2];
   auto read_frags = [&](int buf, const char* sb, int ks) {
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb) af[buf][mb] = *(const bf16x8*)(sb + a_off[mb][ks]);
+    for (int mb = 0; mb < MB; ++mb) af[buf][mb] = *(const bf16x8*)(sb + a_off[mb][ks]);
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) bf[buf][nb] = *(const bf16x8*)(sb + b_off[nb][ks]);
   };
   auto multiply = [&](int buf) {
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb)
         acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][mb], bf[buf][nb], acc[mb][nb], 0, 0, 0);
@@ -167,7 +186,7 @@ __global__ __launch_bounds__(512, 1) void project_qk_kernel(ProjectArgs a) {
   static_assert(KSUB % 2 == 0, "the two register buffers alternate per k-step");
   // Tile t has landed when at most the loads of the tiles behind it are outstanding (loads complete
   // in order); near the end fewer tiles are in flight, so wait for everything.
-  if (AHEAD <= n_steps) pj_wait_vmcnt<(AHEAD - 1) * 2 * LPT>();
+  if (AHEAD <= n_steps) pj_wait_vmcnt<(AHEAD - 1) * LOADS>();
   else pj_wait_vmcnt<0>();
   __syncthreads();
   if (AHEAD < n_steps) load_tile(AHEAD);
@@ -179,23 +198,23 @@ __global__ __launch_bounds__(512, 1) void project_qk_kernel(ProjectArgs a) {
       const int cur = ks & 1;
       if (ks + 1 < KSUB) {
         read_frags(cur ^ 1, sb, ks + 1);
-        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, MB + 2, 0);
       } else if (t + 1 < n_steps) {
-        if (t + 1 + AHEAD <= n_steps) pj_wait_vmcnt<(AHEAD - 1) * 2 * LPT>();
+        if (t + 1 + AHEAD <= n_steps) pj_wait_vmcnt<(AHEAD - 1) * LOADS>();
         else pj_wait_vmcnt<0>();
         __syncthreads();  // tile t+1 visible to every wave; the stage refilled next was read a whole tile ago
         if (t + 1 + AHEAD < n_steps) load_tile(t + 1 + AHEAD);
         read_frags(cur ^ 1, lds + ((t + 1) % STAGES) * STAGE, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, MB + 2, 0);
       }
       multiply(cur);
-      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * MB, 0);
     }
   }
 
   // ---- rotary embedding, then the tile goes through LDS so that it leaves in 16-byte pieces
   // (two whole 512-byte output rows per wave instruction).  Accumulator register r of block
-  // (mb, nb) holds row wm*128 + mb*32 + (r/4)*8 + hf*4 + r%4 and column col0 + nb*PAIR + l32.
+  // (mb, nb) holds row wm*32*MB + mb*32 + (r/4)*8 + hf*4 + r%4 and column col0 + nb*PAIR + l32.
   const int tcol = col0 + l32;            // tile column of the lower half of the pair
   const int d = (n0 + tcol) % D;          // rotary index, < PAIR
   // The hardware sine and cosine take their argument in revolutions: the angle pos * theta^(-2d/D)
@@ -206,10 +225,10 @@ __global__ __launch_bounds__(512, 1) void project_qk_kernel(ProjectArgs a) {
   // Staging rows are 16 bytes longer than the tile row: the two lane halves of a wave write rows
   // four apart, which then fall into different banks.
 #pragma unroll
-  for (int mb = 0; mb < 4; ++mb)
+  for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int row = wm * 128 + mb * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
+      const int row = wm * (32 * MB) + mb * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
       float lo = acc[mb][0][r], hi = acc[mb][1][r];
       if (a.rope_theta > 0.f) {
         const double rev = (double)table[row].y * rev_per_pos;
@@ -347,19 +366,28 @@ hipError_t launch_project_qk_skinny(const ProjectArgs& a, int n_rows, hipStream_
   return hipGetLastError();
 }
 
-hipError_t launch_project_qk(const ProjectArgs& a, int m_tiles, hipStream_t stream) {
-  static bool attr_set[2] = {false, false};
-  const int which = a.head_dim == 128 ? 1 : 0;
-  const void* fn = which ? (const void*)project_qk_kernel<128> : (const void*)project_qk_kernel<64>;
-  if (!attr_set[which]) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, pj::LDS_BYTES);
+template <int D, int MB>
+static hipError_t launch_project_qk_t(const ProjectArgs& a, int rows, hipStream_t stream) {
+  static bool attr_set = false;
+  constexpr int lds_bytes = pj::Shape<MB>::LDS_BYTES;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)project_qk_kernel<D, MB>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
-    attr_set[which] = true;
+    attr_set = true;
   }
-  dim3 grid(a.n_heads * a.head_dim / pj::BN, m_tiles, 2);
-  if (which) hipLaunchKernelGGL(project_qk_kernel<128>, grid, dim3(512), pj::LDS_BYTES, stream, a);
-  else hipLaunchKernelGGL(project_qk_kernel<64>, grid, dim3(512), pj::LDS_BYTES, stream, a);
+  const int m_tiles = (rows + pj::Shape<MB>::BM - 1) / pj::Shape<MB>::BM;
+  const int nt2 = 2 * (a.n_heads * a.head_dim / pj::BN);
+  hipLaunchKernelGGL((project_qk_kernel<D, MB>), dim3(m_tiles * nt2), dim3(512), lds_bytes, stream, a, m_tiles);
   return hipGetLastError();
+}
+
+// 256-row tiles when they fill the chip at least twice over, 128-row tiles for fewer rows (the text
+// rows of a lazy layer): twice as many workgroups, each half as long.
+hipError_t launch_project_qk(const ProjectArgs& a, int rows, hipStream_t stream) {
+  const int nt2 = 2 * (a.n_heads * a.head_dim / pj::BN);
+  const bool big = (int64_t)((rows + 255) / 256) * nt2 >= 512;
+  if (a.head_dim == 128) return big ? launch_project_qk_t<128, 4>(a, rows, stream) : launch_project_qk_t<128, 2>(a, rows, stream);
+  return big ? launch_project_qk_t<64, 4>(a, rows, stream) : launch_project_qk_t<64, 2>(a, rows, stream);
 }
 
 }  // namespace qc
