@@ -24,17 +24,14 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 namespace pj {
-#ifndef PJ_BK
-#define PJ_BK 64
-#endif
-constexpr int BN = 256, BK = PJ_BK;      // BM = 64 * MB rows: MB row blocks of 32 per wave, two wave rows
+constexpr int BN = 256, BK = 64;      // BM = 64 * MB rows: MB row blocks of 32 per wave, two wave rows
 constexpr int ROWB = BK * 2;            // bytes per tile row
 constexpr int CH = ROWB / 16;           // 16-byte chunks per row
 constexpr int RPI = 64 / CH;            // tile rows one wave-wide load instruction fills
 constexpr int LPT = 32 / RPI;           // load instructions per wave for the 256-row B tile (a wave fills 32 rows)
 constexpr int KSUB = BK / 16;           // MFMA k-steps per tile
 constexpr int TILE_B = BN * ROWB;
-constexpr int AHEAD = BK == 32 ? 3 : 1; // tiles in flight ahead of the one being multiplied
+constexpr int AHEAD = 1;                // tiles in flight ahead of the one being multiplied
 constexpr int STAGES = AHEAD + 1;
 // chunk c of row r is stored at chunk c ^ swz(r): 16 consecutive rows then cover all 64 banks
 __device__ __forceinline__ int swz(int r) { return BK == 32 ? (r >> 2) & 3 : (r >> 1) & 7; }
