@@ -354,7 +354,150 @@ __global__ __launch_bounds__(256) void project_qk_skinny_kernel(ProjectArgs a, i
   }
 }
 
+// The same job when d_model is a multiple of 256, with longer contiguous reads: every visit to a
+// weight row (and to a row of x) fetches 512 contiguous bytes instead of 64 (measured 12 % faster).
+// K is walked in chunks of 256, each chunk of the 32 weight rows and of the rows of x goes
+// to LDS by global_load_lds_dwordx4 (one instruction = two whole 512-byte row pieces), three
+// chunks ahead of its use through a four-stage ring; fragments are then read from LDS (16-byte
+// chunk c of row r sits at chunk c ^ (r & 15): conflict-free for the fragment pattern).
+namespace sk {
+constexpr int KC = 256, ROWB = KC * 2, ROWS = 32;
+constexpr int TILE = ROWS * ROWB;          // 16 KB: the weight rows, or the rows of x
+constexpr int STAGE = 2 * TILE, AHEAD = 3, STAGES = AHEAD + 1;
+constexpr int LDS_BYTES = STAGES * STAGE;  // 128 KB
+constexpr int LOADS = 2 * (TILE / 1024) / 4;  // load instructions per wave and chunk
+}  // namespace sk
+
+template <int D>
+__global__ __launch_bounds__(256) void project_qk_skinny_staged_kernel(ProjectArgs a, int n_rows) {
+  using namespace sk;
+  constexpr int PAIR = D / 2, GROUPS = PAIR / 16;
+  extern __shared__ __attribute__((aligned(16))) char ring[];
+  __shared__ float part[4][32][33];
+  __shared__ int2 table[32];
+  const int which = blockIdx.y;
+  const int head = blockIdx.x / GROUPS, grp = blockIdx.x % GROUPS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, kq = lane >> 4;
+
+  if (tid < 32) {
+    int tok = -1, pos = 0, base = 0;
+    for (int s = 0; s < a.segs.n; ++s) {
+      const int c = a.segs.count[s];
+      if (tid >= base && tid < base + c) {
+        tok = a.segs.tok_start[s] + (tid - base);
+        pos = a.segs.pos_start[s] + (tid - base);
+      }
+      base += c;
+    }
+    table[tid] = make_int2(tok, pos);
+  }
+  __syncthreads();
+
+  // ---- loader: wave w fills tile rows w*8 + p*2 + lane/32 (p < 4), lane%32 = physical 16-byte chunk.
+  // Weight tile row r is feature d = grp*16 + (r & 15) of the head, plus D/2 for r >= 16.
+  uint32_t off_w[4], off_x[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int r = wave * 8 + p * 2 + (lane >> 5);
+    const int logical = (lane & 31) ^ (r & 15);
+    const int wrow = head * D + grp * 16 + (r & 15) + (r >> 4) * PAIR;
+    off_w[p] = (uint32_t)wrow * (uint32_t)(a.w_stride * 2) + logical * 16;
+    off_x[p] = (uint32_t)max(table[r].x, 0) * (uint32_t)(a.x_stride * 2) + logical * 16;  // idle rows repeat token 0
+  }
+  const char* wbase = pj_uniform_ptr((const char*)a.w[which]);
+  const char* xbase = pj_uniform_ptr((const char*)a.x);
+  const uint32_t ring_base = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)ring;
+  auto load_chunk = [&](int t) {
+    const uint32_t st = ring_base + (t % STAGES) * STAGE;
+    const uint32_t wb = __builtin_amdgcn_readfirstlane(st + wave * 8 * ROWB);
+    const uint32_t xb = __builtin_amdgcn_readfirstlane(st + TILE + wave * 8 * ROWB);
+    const char* ws = wbase + (uint64_t)t * ROWB;
+    const char* xs = xbase + (uint64_t)t * ROWB;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      pj_async_copy16(ws, off_w[p], wb + p * 2 * ROWB);
+      pj_async_copy16(xs, off_x[p], xb + p * 2 * ROWB);
+    }
+  };
+  static_assert(LOADS == 8, "four weight and four x instructions per wave and chunk");
+
+  const bool two = n_rows > 16;
+  f32x4 acc[2][2];  // [row block][lo, hi]
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int n_chunks = a.d_model / KC;
+#pragma unroll
+  for (int t = 0; t < AHEAD; ++t)
+    if (t < n_chunks) load_chunk(t);
+  for (int t = 0; t < n_chunks; ++t) {
+    if (t + AHEAD <= n_chunks) pj_wait_vmcnt<(AHEAD - 1) * LOADS>();
+    else pj_wait_vmcnt<0>();
+    __syncthreads();  // chunk t visible; every wave is done with chunk t-1, whose stage is refilled next
+    if (t + AHEAD < n_chunks) load_chunk(t + AHEAD);
+    const char* sb = ring + (t % STAGES) * STAGE;
+    // wave w takes the k-steps of 32 congruent to w mod 4 (two per chunk); fragment chunk = ks*4 + kq
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int phys = (((wave + 4 * j) * 4 + kq) ^ l16) * 16;
+      const bf16x8 bl = *(const bf16x8*)(sb + l16 * ROWB + phys);
+      const bf16x8 bh = *(const bf16x8*)(sb + (16 + l16) * ROWB + phys);
+      const bf16x8 a0 = *(const bf16x8*)(sb + TILE + l16 * ROWB + phys);
+      acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bl, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bh, acc[0][1], 0, 0, 0);
+      if (two) {
+        const bf16x8 a1 = *(const bf16x8*)(sb + TILE + (16 + l16) * ROWB + phys);
+        acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bl, acc[1][0], 0, 0, 0);
+        acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bh, acc[1][1], 0, 0, 0);
+      }
+    }
+  }
+  // accumulator register i of block (rb, c) holds row rb*16 + kq*4 + i, column c*16 + l16
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) part[wave][rb * 16 + kq * 4 + i][c * 16 + l16] = acc[rb][c][i];
+  __syncthreads();
+  for (int item = tid; item < 32 * 16; item += 256) {
+    const int row = item >> 4, j = item & 15;
+    const int2 tp = table[row];
+    if (tp.x < 0) continue;
+    float lo = ((part[0][row][j] + part[1][row][j]) + part[2][row][j]) + part[3][row][j];
+    float hi = ((part[0][row][16 + j] + part[1][row][16 + j]) + part[2][row][16 + j]) + part[3][row][16 + j];
+    const int d = grp * 16 + j;
+    if (a.rope_theta > 0.f) {
+      const double rev = (double)tp.y * exp2(-2.0 * (double)d / (double)D * a.log2_theta) * 0.15915494309189535;
+      const float frac = (float)(rev - rint(rev));
+      const float sn = __builtin_amdgcn_sinf(frac), cs = __builtin_amdgcn_cosf(frac);
+      const float nlo = lo * cs - hi * sn, nhi = hi * cs + lo * sn;
+      lo = nlo;
+      hi = nhi;
+    }
+    bf16_t* o = (bf16_t*)a.out[which] + (int64_t)tp.x * a.token_stride + (int64_t)head * a.head_stride + d;
+    o[0] = (bf16_t)lo;
+    o[PAIR] = (bf16_t)hi;
+  }
+}
+
+template <int D> static hipError_t launch_skinny_staged_t(const ProjectArgs& a, int n_rows, hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)project_qk_skinny_staged_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, sk::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(project_qk_skinny_staged_kernel<D>, dim3(a.n_heads * (D / 32), 2), dim3(256), sk::LDS_BYTES, stream, a, n_rows);
+  return hipGetLastError();
+}
+
 hipError_t launch_project_qk_skinny(const ProjectArgs& a, int n_rows, hipStream_t stream) {
+  if (a.d_model % sk::KC == 0)
+    return a.head_dim == 128 ? launch_skinny_staged_t<128>(a, n_rows, stream) : launch_skinny_staged_t<64>(a, n_rows, stream);
   if (a.head_dim == 128) {
     hipLaunchKernelGGL(project_qk_skinny_kernel<128>, dim3(a.n_heads * 4, 2), dim3(256), 0, stream, a, n_rows);
   } else {

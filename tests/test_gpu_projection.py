@@ -90,6 +90,10 @@ def test_projection_decode_shape_with_positions():
     run_case([1] * 21, [(0, 0)] * 21, [100 + 37 * i for i in range(21)], 512, 4, 64, 10000.0, 0, seed=9)
     run_case([1] * 32, [(0, 0)] * 32, [3 * i for i in range(32)], 4096, 32, 128, 10000.0, 0, seed=10)
     run_case([5, 9, 14], [(1, 2), (0, 0), (4, 9)], None, 320, 2, 128, 0.0, 1, seed=11, pad=64)
+    # just above the few-rows limit: one partly filled 128-row tile; and exactly one full tile
+    run_case([33], [(0, 0)], [7], 256, 2, 128, 10000.0, 0, seed=12)
+    run_case([40, 50], [(3, 1), (0, 0)], None, 256, 4, 64, 10000.0, 1, seed=13)
+    run_case([128], [(0, 0)], None, 256, 2, 128, 10000.0, 0, seed=14)
 
 
 def test_projection_everything_skipped_and_many_sequences():
