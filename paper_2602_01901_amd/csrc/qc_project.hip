@@ -163,49 +163,28 @@ __global__ __launch_bounds__(512, 1) void project_qk_kernel(ProjectArgs a, int m
   for (int t = 0; t < AHEAD; ++t)
     if (t < n_steps) load_tile(t);
 
-  // Operand fragments are double buffered in registers across the k-steps AND across the tile
-  // boundary: while the 2*MB MFMAs of one k-step run, the MB+2 fragment reads of the next one are in
-  // flight, so neither the LDS latency nor the barrier sits between two groups of MFMAs.
-  bf16x8 af[2][MB], bf[2][2];
-  auto read_frags = [&](int buf, const char* sb, int ks) {
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) af[buf][mb] = *(const bf16x8*)(sb + a_off[mb][ks]);
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) bf[buf][nb] = *(const bf16x8*)(sb + b_off[nb][ks]);
-  };
-  auto multiply = [&](int buf) {
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][mb], bf[buf][nb], acc[mb][nb], 0, 0, 0);
-  };
-  static_assert(KSUB % 2 == 0, "the two register buffers alternate per k-step");
-  // Tile t has landed when at most the loads of the tiles behind it are outstanding (loads complete
-  // in order); near the end fewer tiles are in flight, so wait for everything.
-  if (AHEAD <= n_steps) pj_wait_vmcnt<(AHEAD - 1) * LOADS>();
-  else pj_wait_vmcnt<0>();
-  __syncthreads();
-  if (AHEAD < n_steps) load_tile(AHEAD);
-  read_frags(0, lds, 0);
   for (int t = 0; t < n_steps; ++t) {
+    // Tile t has landed when at most the loads of the tiles behind it are outstanding (loads complete
+    // in order); near the end fewer tiles are in flight, so wait for everything.
+    if (t + AHEAD <= n_steps) pj_wait_vmcnt<(AHEAD - 1) * LOADS>();
+    else pj_wait_vmcnt<0>();
+    __syncthreads();  // tile t visible to every wave; every wave is done with tile t-1, whose stage is refilled next
+    if (t + AHEAD < n_steps) load_tile(t + AHEAD);
     const char* sb = lds + (t % STAGES) * STAGE;
+    // Fragment reads and MFMAs of the four k-steps are left to the compiler's scheduler (hand-placed
+    // double buffering across the barrier with scheduling fences measured 30 % slower).
 #pragma unroll
     for (int ks = 0; ks < KSUB; ++ks) {
-      const int cur = ks & 1;
-      if (ks + 1 < KSUB) {
-        read_frags(cur ^ 1, sb, ks + 1);
-        __builtin_amdgcn_sched_group_barrier(0x100, MB + 2, 0);
-      } else if (t + 1 < n_steps) {
-        if (t + 1 + AHEAD <= n_steps) pj_wait_vmcnt<(AHEAD - 1) * LOADS>();
-        else pj_wait_vmcnt<0>();
-        __syncthreads();  // tile t+1 visible to every wave; the stage refilled next was read a whole tile ago
-        if (t + 1 + AHEAD < n_steps) load_tile(t + 1 + AHEAD);
-        read_frags(cur ^ 1, lds + ((t + 1) % STAGES) * STAGE, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, MB + 2, 0);
-      }
-      multiply(cur);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2 * MB, 0);
+      bf16x8 af[MB], bf[2];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) af[mb] = *(const bf16x8*)(sb + a_off[mb][ks]);
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) bf[nb] = *(const bf16x8*)(sb + b_off[nb][ks]);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+          acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mb], bf[nb], acc[mb][nb], 0, 0, 0);
     }
   }
 
