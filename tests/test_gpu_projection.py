@@ -111,3 +111,42 @@ def test_projection_7b_shape_sampled():
     w1 = run_case(lens, spans, None, 4096, 32, 128, 10000.0, 1, seed=7, sample_rows=24)
     w2 = run_case([3008, 640], [(32, 2880), (32, 576)], None, 4096, 32, 128, 10000.0, 0, seed=8, sample_rows=24)
     print("projection 7B shape: max abs err lazy %.3g ordinary %.3g" % (w1, w2), flush=True)
+
+
+def test_projection_feeds_prefill_end_to_end():
+    """Three layers (ordinary, lazy, lazy): Q and K of every layer come from qc_project_qk (text rows only in
+    the lazy layers, whose q/k tensors are NaN elsewhere), then qc_prefill; the oracle chain is projection
+    oracle -> rounding to bf16 -> Visual Lazy Attention oracle."""
+    from stack_runner import TOL, new_oracles
+    d_model, H, D, theta = 256, 2, 128, 10000.0
+    w = workloads.custom("proj_e2e", 3, H, D, "bf16", [7, 0], [90, 40], [150, 77], 0, [0, 1, 1])
+    sess = P.Session.for_workload(w)
+    sess.reset(w.vis_start, w.vis_len)
+    stacks = new_oracles(w)
+    cu = w.cu_seqlens
+    tokens = cu[-1]
+    worst = 0.0
+    for l in range(w.n_layers):
+        x, wq, wk = make_inputs(tokens, d_model, H * D, seed=100 + l)
+        v = workloads.prefill_qkv(w, l)[2]
+        q = torch.full((tokens, H, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        k = torch.full((tokens, H, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        lazy = w.lazy_mask[l]
+        B.qc_project_qk(x.cuda(), d_model, wq.cuda(), wk.cuda(), d_model, q, k, H * D, D, d_model, H, D, w.batch, cu, None,
+                        w.vis_start, w.vis_len, lazy, theta)
+        out = sess.prefill(l, q, k, v.cuda(), cu)
+        for b in range(w.batch):
+            L = w.seq_len[b]
+            rows = projection.text_rows(L, w.vis_start[b], w.vis_len[b]) if lazy else list(range(L))
+            Qr, Kr = projection.project_qk(workloads.to_f64(x[cu[b]:cu[b + 1]]), workloads.to_f64(wq), workloads.to_f64(wk),
+                                           H, D, rows, rows, theta)
+            Q = np.full((L, H, D), np.nan)
+            K = np.full((L, H, D), np.nan)
+            Q[rows] = workloads.to_f64(torch.from_numpy(Qr).to(torch.bfloat16))     # the tensors hold bf16
+            K[rows] = workloads.to_f64(torch.from_numpy(Kr).to(torch.bfloat16))
+            ref = stacks[b].prefill(l, Q, K, workloads.to_f64(v[cu[b]:cu[b + 1]]))
+            err = float(np.max(np.abs(workloads.to_f64(out[cu[b]:cu[b + 1]]) - ref)))
+            assert np.isfinite(err)
+            worst = max(worst, err)
+    print("projection -> prefill max abs err %.3g" % worst, flush=True)
+    assert worst <= TOL["bf16"]
