@@ -54,24 +54,29 @@ def test_last_row_attention_and_similarity_match_oracle(dtype, D):
             rows.append(selection.last_row_attention(workloads.to_f64(qs[l][cu[b + 1] - 1]), K, scale))
         want_rows.append(rows)
     torch.cuda.synchronize()
+    worst_p = 0.0
     for l in range(w.n_layers):
         got = probs[l].cpu().numpy().astype(np.float64)
         for b in range(w.batch):
             err = np.abs(got[b, :lens[b]] - want_rows[l][b])
             assert np.all(err <= 1e-5 + 1e-4 * want_rows[l][b]), (l, b, err.max())
+            worst_p = max(worst_p, float(err.max()))
             assert np.all(got[b, lens[b]:] == -1.0)            # nothing written past the row
             assert abs(got[b, :lens[b]].sum() - 1.0) < 1e-4
     js = torch.empty(w.batch, dtype=torch.float32, device="cuda")
     sim = torch.empty(1, dtype=torch.float32, device="cuda")
     adjacent = []
+    worst_js = 0.0
     for l in range(w.n_layers - 1):
         B.qc_attention_similarity(probs[l], probs[l + 1], stride, w.batch, lens, js, sim)
         torch.cuda.synchronize()
         want_js = [selection.js_divergence(p, q) for p, q in zip(want_rows[l], want_rows[l + 1])]
         np.testing.assert_allclose(js.cpu().numpy(), want_js, rtol=0, atol=1e-4)
+        worst_js = max(worst_js, float(np.max(np.abs(js.cpu().numpy() - np.array(want_js)))))
         want_s = selection.similarity(want_rows[l], want_rows[l + 1])
         assert abs(float(sim.item()) - want_s) <= 1e-4
         adjacent.append(float(sim.item()))
+    print("selection %s D=%d: max |dp| %.3g, max |dJS| %.3g" % (dtype, D, worst_p, worst_js), flush=True)
     eps = float(np.float32(np.median(adjacent)))
     eps = min(max(eps, 1e-3), 1.0)
     assert B.qc_lazy_mask_from_similarity(adjacent, eps) == selection.lazy_mask_from_similarity(adjacent, eps)
