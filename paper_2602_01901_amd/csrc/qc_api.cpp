@@ -387,12 +387,10 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   a.workspace = (float*)workspace;
   a.batch = kv->batch; a.n_heads = c.H; a.head_dim = c.D;
   a.is_lazy = c.lazy[layer];
-  a.inherit_all = c.gla() ? 1 : 0;
-  a.write_q = (c.gla() && c.writes_q(layer)) ? 1 : 0;
-  a.scores = c.gla() ? (float*)((char*)workspace + partial_bytes(c)) : nullptr;
-  a.score_stride = (int32_t)score_stride(c);
-  a.store_scores = a.write_q;
-  a.use_scores = qk_unused ? 1 : 0;
+  qc::DecodeGlaArgs g;
+  g.scores = c.gla() ? (float*)((char*)workspace + partial_bytes(c)) : nullptr;
+  g.score_stride = (int32_t)score_stride(c);
+  g.mode = qk_unused ? 2 : ((c.gla() && c.writes_q(layer)) ? 1 : 0);
   a.generated = kv->generated;
   a.max_len = max_len;
   a.chunk_keys = chunk;
@@ -405,11 +403,11 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
     a.vis_start_inline[b] = ok ? kv->vis_start[b] : 0;
     a.vis_len_inline[b] = ok ? kv->vis_len[b] : 0;
   }
-  qc::KernelTimer* timer = !kv->timing ? nullptr : (a.use_scores ? &kv->decode_shared_timer : &kv->decode_timer);
-  hipError_t err = qc::launch_decode(a, c.dtype, (hipStream_t)stream, timer);
+  qc::KernelTimer* timer = !kv->timing ? nullptr : (g.mode == 2 ? &kv->decode_shared_timer : &kv->decode_timer);
+  hipError_t err = qc::launch_decode(a, g, c.dtype, (hipStream_t)stream, timer);
   if (err != hipSuccess) return fail(QC_EDEVICE, "qc_decode: %s", hipGetErrorString(err));
 
-  if (a.write_q) {
+  if (g.mode == 1) {
     qc->owner = layer;
     kv->score_workspace = workspace;
   }

@@ -43,8 +43,12 @@ __device__ __forceinline__ SeqMeta decode_meta(const DecodeArgs& a, int b) {
   return load_meta(a.lv, b);
 }
 
-template <typename T, int D, bool SHARED>
-__global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
+// MODE 0: ordinary and Visual Lazy Attention layers.  MODE 1: first layer of a Global Lazy Attention
+// block (also stores its scores and its query).  MODE 2: lazy layer under Global Lazy Attention
+// (reuses the stored scores, streams V only).
+template <typename T, int D, int MODE>
+__device__ __forceinline__ void decode_split_body(const DecodeArgs& a, const DecodeGlaArgs& g) {
+  constexpr bool SHARED = MODE == 2, STORE = MODE == 1;
   constexpr int EPL = ElemTraits<T>::kPer16;  // elements per lane (16 bytes)
   constexpr int LPR = D / EPL;                // lanes per row
   constexpr int GPW = 64 / LPR;               // row groups per wave
@@ -71,7 +75,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
   const char* knew = (const char*)a.k + bh * ROWB + li * 16;
   const char* vnew = (const char*)a.v + bh * ROWB + li * 16;
 
-  float* score_row = (SHARED || a.store_scores) ? a.scores + bh * a.score_stride : nullptr;
+  float* score_row = (SHARED || STORE) ? g.scores + bh * g.score_stride : nullptr;
 
   float qf[EPL];
   uint4 qraw = make_uint4(0, 0, 0, 0);
@@ -110,7 +114,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
             kr[u] = *(const uint4*)knew;
             const int krow = lazy ? len - sm.vis_len : len;
             *(uint4*)(kown + (int64_t)krow * ROWB) = kr[u];
-            if (a.write_q) *(uint4*)(a.lv.q_cache + (bh * a.lv.cap_q + len) * ROWB + li * 16) = qraw;
+            if (STORE) *(uint4*)(a.lv.q_cache + (bh * a.lv.cap_q + len) * ROWB + li * 16) = qraw;
           }
         } else {
           if (!SHARED) {
@@ -138,7 +142,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
         const int pos = r0 + u * GROUPS;
         if (pos < kend) {
           sc[u] = d;
-          if (a.store_scores && li == 0) score_row[pos] = d;
+          if (STORE && li == 0) score_row[pos] = d;
         }
       }
       mt = fmaxf(mt, sc[u]);
@@ -194,6 +198,15 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
   }
 }
 
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
+  decode_split_body<T, D, 0>(a, DecodeGlaArgs{nullptr, 0, 0});
+}
+template <typename T, int D, int MODE>
+__global__ __launch_bounds__(256) void decode_split_gla_kernel(DecodeArgs a, DecodeGlaArgs g) {
+  decode_split_body<T, D, MODE>(a, g);
+}
+
 // Merge the chunk partials of one (sequence, head) in chunk order.  Partials are loaded in batches
 // of 16 chunks (all loads of a batch are independent, so their latencies overlap); within a batch
 // the usual running (max, sum) update is applied chunk by chunk in a fixed order, so results are
@@ -234,11 +247,12 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
   store_elem((T*)a.out + bh * D + d, o / l);
 }
 
-template <typename T, int D> static hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t stream, KernelTimer* timer) {
+template <typename T, int D> static hipError_t launch_decode_t(const DecodeArgs& a, const DecodeGlaArgs& g, hipStream_t stream, KernelTimer* timer) {
   dim3 grid(a.max_chunks, a.n_heads, a.batch);
   if (timer) timer->begin(stream);
-  if (a.use_scores) hipLaunchKernelGGL((decode_split_kernel<T, D, true>), grid, dim3(256), 0, stream, a);
-  else hipLaunchKernelGGL((decode_split_kernel<T, D, false>), grid, dim3(256), 0, stream, a);
+  if (g.mode == 2) hipLaunchKernelGGL((decode_split_gla_kernel<T, D, 2>), grid, dim3(256), 0, stream, a, g);
+  else if (g.mode == 1) hipLaunchKernelGGL((decode_split_gla_kernel<T, D, 1>), grid, dim3(256), 0, stream, a, g);
+  else hipLaunchKernelGGL((decode_split_kernel<T, D>), grid, dim3(256), 0, stream, a);
   if (timer) timer->end(stream);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.max_chunks == 1) return e;
@@ -246,13 +260,13 @@ template <typename T, int D> static hipError_t launch_decode_t(const DecodeArgs&
   return hipGetLastError();
 }
 
-hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t stream, KernelTimer* timer) {
+hipError_t launch_decode(const DecodeArgs& a, const DecodeGlaArgs& g, int dtype, hipStream_t stream, KernelTimer* timer) {
   if (dtype == 0) {
-    if (a.head_dim == 64) return launch_decode_t<float, 64>(a, stream, timer);
-    if (a.head_dim == 128) return launch_decode_t<float, 128>(a, stream, timer);
+    if (a.head_dim == 64) return launch_decode_t<float, 64>(a, g, stream, timer);
+    if (a.head_dim == 128) return launch_decode_t<float, 128>(a, g, stream, timer);
   } else {
-    if (a.head_dim == 64) return launch_decode_t<bf16_t, 64>(a, stream, timer);
-    if (a.head_dim == 128) return launch_decode_t<bf16_t, 128>(a, stream, timer);
+    if (a.head_dim == 64) return launch_decode_t<bf16_t, 64>(a, g, stream, timer);
+    if (a.head_dim == 128) return launch_decode_t<bf16_t, 128>(a, g, stream, timer);
   }
   return hipErrorInvalidValue;
 }

@@ -49,14 +49,8 @@ struct DecodeArgs {
   const void* v;
   void* out;
   float* workspace;       // [batch][H][max_chunks][D + 2] partial (o, m, l)
-  float* scores;          // [batch][H][score_stride] scaled scores of the current step (GLA), else nullptr
-  int32_t score_stride;   // floats per (sequence, head) in `scores`
-  int32_t store_scores;   // first layer of a GLA block: write the score of every position
-  int32_t use_scores;     // lazy GLA layer: take the scores from `scores` instead of reading keys
   int32_t batch, n_heads, head_dim;
   int32_t is_lazy;
-  int32_t inherit_all;    // Global Lazy Attention: a lazy layer shares query and keys of the block's first layer
-  int32_t write_q;        // store the query at row len of the Q Cache (first layer of a GLA block)
   int32_t generated;      // decode steps completed before this one: len_b = len0_b + generated
   int32_t max_len;        // longest len_b in the batch (before this step)
   int32_t chunk_keys;     // key positions per workgroup
@@ -106,6 +100,17 @@ struct ProjectArgs {
   float rope_theta;       // 0: no rotary embedding
   double log2_theta;
   ProjectSegs segs;
+};
+
+// What a decode call needs in addition under Global Lazy Attention.  Kept out of DecodeArgs so that
+// the kernel arguments of the ordinary path stay as small as they were (a few-microsecond launch
+// notices an extra argument load).
+struct DecodeGlaArgs {
+  float* scores;          // [batch][H][score_stride] scaled scores of the current step
+  int32_t score_stride;   // floats per (sequence, head) in `scores`
+  int32_t mode;           // 0: no Global Lazy Attention work in this call; 1: first layer of a block:
+                          // store the score of every position and the query at row len of the Q Cache;
+                          // 2: lazy layer: take the scores from `scores` instead of reading keys
 };
 
 struct MetaChunk {        // by-value payload of the metadata upload kernel
@@ -161,7 +166,7 @@ hipError_t launch_fill_zero(void* dev, size_t bytes, hipStream_t stream);
 hipError_t launch_meta_upload(int32_t* meta_dev, int32_t max_batch, int32_t first, int32_t count,
                               const MetaChunk& chunk, hipStream_t stream);
 hipError_t launch_prefill(const PrefillArgs& a, int dtype, hipStream_t stream, KernelTimer* timer);
-hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t stream, KernelTimer* timer);
+hipError_t launch_decode(const DecodeArgs& a, const DecodeGlaArgs& g, int dtype, hipStream_t stream, KernelTimer* timer);
 hipError_t launch_last_row_attention(const SelectArgs& a, int dtype, int max_len, hipStream_t stream);
 hipError_t launch_js(const float* pm, const float* pn, int64_t stride, int first, int count, const JsChunk& c,
                      float* js_out, hipStream_t stream);
