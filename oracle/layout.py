@@ -10,9 +10,11 @@ can be compared byte for byte:
   K region   layers in order; layer l holds [max_batch][H][capK(l)][D] elements,
              capK(l) = max_text for a lazy layer, max_seq otherwise.
   V region   follows the K region; layer l holds [max_batch][H][max_seq][D].
-  meta       follows the V region (256-byte aligned): int32 [4][max_batch] =
-             first token index in the packed prompt, prompt length, vis_start,
-             vis_len of every sequence; total rounded up to 256 bytes.
+  meta       follows the V region (256-byte aligned): int32 [2][4][max_batch].
+             Block 0: first token index in the packed prompt, prompt length,
+             vis_start, vis_len of every sequence.  Block 1: the same four rows
+             as the layers after a token-pruning boundary see them (all zero
+             when no pruning took place).  Total rounded up to 256 bytes.
   Q arena    [max_batch][H][max_vis][D].
 
 Row maps: V row = position.  K row = position in a normal layer.  In a lazy
@@ -72,7 +74,7 @@ class ArenaLayout:
         return _round_up(self.off_v(self.N), 256)
 
     def meta_bytes(self):
-        return _round_up(4 * 4 * self.max_batch, 256)
+        return _round_up(2 * 4 * 4 * self.max_batch, 256)
 
     def kv_arena_bytes(self):
         return self.off_meta() + self.meta_bytes()
@@ -142,14 +144,21 @@ def kv_arena_image(layout, stacks, tok0=None):
                 vr = st.Vc[l][h]
                 o = layout.v_offset(l, b, h, 0)
                 img[o:o + vr.shape[0] * rowb] = encode_rows(vr, layout.dtype).reshape(-1)
-    meta = np.zeros((4, layout.max_batch), dtype=np.int32)
-    start = 0
+    meta = np.zeros((2, 4, layout.max_batch), dtype=np.int32)
+    start = start_late = 0
     for b, st in enumerate(stacks):
-        meta[0, b] = start if tok0 is None else tok0[b]
-        meta[1, b] = st.prefill_len
-        meta[2, b] = st.s
-        meta[3, b] = st.Vn
+        meta[0, 0, b] = start if tok0 is None else tok0[b]
+        meta[0, 1, b] = st.prefill_len
+        meta[0, 2, b] = st.s
+        meta[0, 3, b] = st.Vn
         start += st.prefill_len
+        late = getattr(st, "late", None)          # a stack pruned between two layers (oracle.pruning)
+        if late is not None and late.prefill_len:
+            meta[1, 0, b] = start_late
+            meta[1, 1, b] = late.prefill_len
+            meta[1, 2, b] = late.s
+            meta[1, 3, b] = late.Vn
+            start_late += late.prefill_len
     o = layout.off_meta()
     img[o:o + meta.nbytes] = meta.view(np.uint8).reshape(-1)
     return img
