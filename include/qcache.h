@@ -111,8 +111,10 @@ typedef struct qc_stats_t {
  *   K region: layers in order, layer l is [max_batch][n_heads][capK(l)][head_dim],
  *             capK(l) = max_text if lazy else max_seq;
  *   V region: layers in order, each [max_batch][n_heads][max_seq][head_dim];
- *   meta    : at the next multiple of 256: int32 [4][max_batch] = {first packed token index,
- *             prompt length, vis_start, vis_len} per sequence, padded to a multiple of 256 bytes.
+ *   meta    : at the next multiple of 256: int32 [2][4][max_batch]; block 0 = {first packed token
+ *             index, prompt length, vis_start, vis_len} per sequence; block 1 = the same rows as the
+ *             layers after a qc_prune boundary see them (zero without one); padded to a multiple of
+ *             256 bytes.
  * Q arena: [max_batch][n_heads][max_vis][head_dim] (one layer's worth, visual rows only).
  * Under QC_GLA: capK(l) = 0 for a lazy layer, and the Q arena is
  *   [max_batch][n_heads][max_seq][head_dim] with row = token position.
@@ -228,8 +230,9 @@ qc_status qc_project_qk(const void* x, int64_t x_stride, const void* w_q, const 
  *   q_last: DEVICE, [batch][n_heads][head_dim], element type of the configuration: the query of each
  *   sequence's last token at `layer`.  probs: DEVICE, fp32, row b starts at b*probs_stride
  *   (probs_stride >= longest sequence); entries at and beyond len_b are not written.
- *   workspace: DEVICE, at least qc_select_workspace_bytes(cfg).  Requires a finished prefill pass
- *   (QC_EORDER otherwise) and an ordinary `layer` (QC_EINVAL: a lazy layer does not hold all its keys).
+ *   workspace: DEVICE, at least qc_select_workspace_bytes(cfg).  Requires a finished prefill pass, or
+ *   an open one in which `layer` has already run (QC_EORDER otherwise; not between the layers of a
+ *   decode step), and an ordinary `layer` (QC_EINVAL: a lazy layer does not hold all its keys).
  * qc_attention_similarity: js_out[i] = JS(probs_m row i, probs_n row i) over lens[i] entries, in bits
  *   (JS = (KL(p||m) + KL(q||m))/2, m = (p+q)/2, terms with zero probability contribute zero), and
  *   *s_out = their mean over the n_samples rows = S(l_m, l_n) of Eq. 3.  probs_m, probs_n, js_out,
@@ -246,6 +249,48 @@ qc_status qc_attention_similarity(const float* probs_m, const float* probs_n, in
                                   int32_t n_samples, const int32_t* lens, float* js_out, float* s_out,
                                   void* stream);
 qc_status qc_lazy_mask_from_similarity(const float* adjacent, int32_t n_layers, float eps, uint8_t* mask_out);
+
+/* ---- token-wise pruning on top of Lazy Attention ("Compatibility" paragraph and its table) ---------
+ * The paper states that a token pruning method (it names FastV) can run on a model that already uses
+ * Lazy Attention and says no more.  Here pruning is one boundary inside a prefill pass: the layers
+ * before it see the whole prompt, the layers after it, in this pass and in every later decode step,
+ * see each sequence without the visual tokens that were dropped.  For those later layers the
+ * sequence simply is shorter: their cache rows, their span [vis_start, vis_start + keep) and their
+ * lazy blocks are those of the shortened sequence, so a boundary may not fall inside a lazy block.
+ *
+ * qc_prune_select: which tokens survive.  scores: DEVICE fp32, row b at b*stride, entry p ranks
+ *   position p of sequence b (the rows qc_last_row_attention writes serve as they are: the attention
+ *   the last prompt token pays to every position, which is the ranking FastV-style methods use).  Of
+ *   each sequence's span the keep[b] positions of highest score survive, a tie going to the lower
+ *   position (NaN scores: unspecified choice); text tokens always survive.  row_map: DEVICE int32,
+ *   sum over b of (len_b - vis_len[b] + keep[b]) entries: the packed-prompt index
+ *   (cu_seqlens[b] + position) of every surviving token, sequence after sequence in position order.
+ *   cu_seqlens, vis_start, vis_len, keep: HOST.  QC_EINVAL unless 0 <= keep[b] <= vis_len[b] and the
+ *   span lies inside the sequence and stride >= every length.
+ * qc_gather_rows: dst row i = src row row_map[i], i = 0..n_rows-1: drops the pruned rows of any packed
+ *   per-token tensor (hidden states, or q/k/v).  src, dst: DEVICE, rows of row_bytes bytes (a multiple
+ *   of 16) at multiples of src_stride / dst_stride bytes (multiples of 16, >= row_bytes), 16-byte
+ *   aligned, not overlapping.  row_map: DEVICE int32, entries must index rows of src (not checked).
+ * qc_prune: moves the boundary into the cache state.  Allowed once per prefill pass, after at least
+ *   one layer has run and before the last (QC_EORDER otherwise), and only if the next layer is an
+ *   ordinary one (QC_EINVAL).  keep: HOST, batch entries, 0 <= keep[b] <= vis_len[b].  Host only.
+ *   From then on every call that names a layer at or after the boundary takes vis_len = keep in its
+ *   span arrays and, in qc_prefill, cu_seqlens of the shortened prompts (len_b - vis_len[b] + keep[b]
+ *   tokens each); calls naming earlier layers keep the original values.  qc_seq_len keeps reporting
+ *   the unpruned length; qc_stats, qc_layer_rows and qc_locate answer per layer.  qc_reset ends it. */
+qc_status qc_prune_select(const float* scores, int64_t stride, int32_t batch, const int32_t* cu_seqlens,
+                          const int32_t* vis_start, const int32_t* vis_len, const int32_t* keep,
+                          int32_t* row_map, void* stream);
+qc_status qc_gather_rows(const void* src, int64_t src_stride, const int32_t* row_map, int64_t n_rows,
+                         int64_t row_bytes, void* dst, int64_t dst_stride, void* stream);
+qc_status qc_prune(qc_kvcache* kv, qc_qcache* qc, const int32_t* keep);
+
+/* ---- capacity planning (the maximum-batch comparison of the "Efficiency Evaluation" paragraph) ----
+ * Largest max_batch for which the buffers named by `what` (a sum of the QC_PLAN_ values), sized for
+ * cfg with that max_batch, fit together into budget_bytes; cfg->max_batch itself is ignored.  0 if
+ * not even one sequence fits.  Host only.  QC_EINVAL for an invalid configuration or what == 0. */
+enum { QC_PLAN_KV = 1, QC_PLAN_Q = 2, QC_PLAN_WORKSPACE = 4 };
+qc_status qc_plan_max_batch(const qc_config* cfg, size_t budget_bytes, int32_t what, int32_t* max_batch);
 
 /* ---- optional instrumentation ------------------------------------------------------------------
  * While enabled, qc_prefill and qc_decode record a pair of HIP events on the call's stream around

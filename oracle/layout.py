@@ -210,3 +210,17 @@ def q_cache_share_closed_form(n_layers):
     """Same paragraph: a Q Cache that holds every token is 1/(2N) of a standard KV cache."""
     from fractions import Fraction
     return Fraction(1, 2 * n_layers)
+
+
+def max_batch_within(budget_bytes, n_layers, n_heads, head_dim, dtype, max_seq, max_vis, max_text, lazy_mask,
+                     mode="vla", count_q=False):
+    """Largest batch whose K/V arena (plus the Q arena with count_q) fits the budget: the comparison
+    behind the maximum-batch figures of the "Efficiency Evaluation" paragraph.  Plain search upward."""
+    batch = 0
+    while True:
+        lay = ArenaLayout(n_layers, n_heads, head_dim, dtype, batch + 1, max_seq, max_vis, max_text, lazy_mask,
+                          mode=mode)
+        need = lay.kv_arena_bytes() + (lay.q_arena_bytes() if count_q else 0)
+        if need > budget_bytes:
+            return batch
+        batch += 1

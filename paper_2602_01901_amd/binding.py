@@ -15,6 +15,7 @@ QC_OK, QC_EINVAL, QC_EORDER, QC_ECAPACITY, QC_EDEVICE = range(5)
 QC_F32, QC_BF16 = 0, 1
 QC_K, QC_V = 0, 1
 QC_VLA, QC_GLA = 0, 1
+QC_PLAN_KV, QC_PLAN_Q, QC_PLAN_WORKSPACE = 1, 2, 4
 DTYPE_CODE = {"f32": QC_F32, "bf16": QC_BF16}
 MODE_CODE = {"vla": QC_VLA, "gla": QC_GLA}
 
@@ -64,6 +65,11 @@ _PROTOTYPES = {
     "qc_attention_similarity": (c_int32, [c_void_p, c_void_p, c_int64, c_int32, POINTER(c_int32), c_void_p, c_void_p,
                                           c_void_p]),
     "qc_lazy_mask_from_similarity": (c_int32, [POINTER(c_float), c_int32, c_float, POINTER(c_uint8)]),
+    "qc_prune_select": (c_int32, [c_void_p, c_int64, c_int32, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32),
+                                  POINTER(c_int32), c_void_p, c_void_p]),
+    "qc_gather_rows": (c_int32, [c_void_p, c_int64, c_void_p, c_int64, c_int64, c_void_p, c_int64, c_void_p]),
+    "qc_prune": (c_int32, [c_void_p, c_void_p, POINTER(c_int32)]),
+    "qc_plan_max_batch": (c_int32, [POINTER(qc_config), c_size_t, c_int32, POINTER(c_int32)]),
     "qc_timing_enable": (c_int32, [c_void_p, c_int32]),
     "qc_timing_read": (c_int32, [c_void_p, c_int32, POINTER(ctypes.c_double), POINTER(c_int64)]),
     "qc_status_str": (c_char_p, [c_int32]),
@@ -235,6 +241,26 @@ def qc_lazy_mask_from_similarity(adjacent, eps):
     out = (c_uint8 * n)()
     _check(load_library().qc_lazy_mask_from_similarity(adj, n, eps, out))
     return [int(x) for x in out]
+
+
+def qc_prune_select(scores, stride, batch, cu_seqlens, vis_start, vis_len, keep, row_map, stream=None):
+    return _check(load_library().qc_prune_select(_ptr(scores), stride, batch, _i32(cu_seqlens), _i32(vis_start),
+                                                _i32(vis_len), _i32(keep), _ptr(row_map), stream))
+
+
+def qc_gather_rows(src, src_stride, row_map, n_rows, row_bytes, dst, dst_stride, stream=None):
+    return _check(load_library().qc_gather_rows(_ptr(src), src_stride, _ptr(row_map), n_rows, row_bytes, _ptr(dst),
+                                               dst_stride, stream))
+
+
+def qc_prune(kv, qc, keep):
+    return _check(load_library().qc_prune(kv, qc, _i32(keep)))
+
+
+def qc_plan_max_batch(cfg, budget_bytes, what):
+    out = c_int32()
+    _check(load_library().qc_plan_max_batch(byref(cfg), int(budget_bytes), int(what), byref(out)))
+    return out.value
 
 
 def qc_timing_enable(kv, enable):

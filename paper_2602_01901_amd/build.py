@@ -9,7 +9,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libqcache.so")
 
 SOURCES = ["qc_api.cpp", "qc_util.hip", "qc_decode.hip", "qc_prefill_simple.hip", "qc_prefill_mfma.hip",
-           "qc_select.hip", "qc_project.hip"]
+           "qc_select.hip", "qc_project.hip", "qc_prune.hip"]
 
 # Packed fp32 instructions are kept out of the generated code on purpose.
 HIPCC_FLAGS = [

@@ -49,7 +49,7 @@ struct Config {
   }
   int64_t off_v(int l) const { return off_k(N) + (int64_t)l * v_layer_bytes(); }
   int64_t off_meta() const { return round_up(off_v(N), 256); }
-  int64_t meta_bytes() const { return round_up((int64_t)qc::META_ROWS * 4 * max_batch, 256); }
+  int64_t meta_bytes() const { return round_up((int64_t)qc::META_BLOCKS * qc::META_ROWS * 4 * max_batch, 256); }
   int64_t kv_bytes() const { return off_meta() + meta_bytes(); }
   int64_t q_bytes() const { return (int64_t)max_batch * H * cap_q() * D * e(); }
   int64_t row_bytes() const { return (int64_t)D * e(); }
@@ -101,6 +101,14 @@ struct qc_kvcache {
   int32_t next_layer = 0;
   int32_t generated = 0;
   std::vector<int32_t> vis_start, vis_len, len0, tok0;
+  // Token pruning: layers >= first_late see sequence b with vis_len1[b] visual tokens and len1[b]
+  // prompt tokens, packed from tok1[b] (the last two known once the first such layer has run).
+  int32_t first_late = -1;
+  bool late_known = false;
+  std::vector<int32_t> vis_len1, len1, tok1;
+  bool late(int layer) const { return first_late >= 0 && layer >= first_late; }
+  int32_t vis_len_of(int layer, int b) const { return late(layer) ? vis_len1[b] : vis_len[b]; }
+  int32_t len_of(int layer, int b) const { return late(layer) ? len0[b] - vis_len[b] + vis_len1[b] : len0[b]; }
   bool timing = false;
   qc::KernelTimer prefill_timer, decode_timer, decode_shared_timer;
   const void* score_workspace = nullptr;  // workspace the current block's scores were written to (GLA)
@@ -218,6 +226,8 @@ qc_status qc_reset(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* 
   kv->next_layer = 0;
   kv->generated = 0;
   kv->score_workspace = nullptr;
+  kv->first_late = -1;
+  kv->late_known = false;
   qc->owner = -1;
   return QC_OK;
 }
@@ -234,16 +244,17 @@ static qc::LayerView make_view(const qc_kvcache* kv, const qc_qcache* qc, int la
   lv.cap_k_anchor = (int32_t)c.cap_k(a);
   lv.q_cache = qc ? qc->arena : nullptr;
   lv.cap_q = (int32_t)c.cap_q();
-  lv.meta = (const int32_t*)(kv->arena + c.off_meta());
+  lv.meta = (const int32_t*)(kv->arena + c.off_meta()) + (kv->late(layer) ? qc::META_ROWS * c.max_batch : 0);
   lv.max_batch = c.max_batch;
   return lv;
 }
 
-static qc_status check_spans(const char* who, const qc_kvcache* kv, const int32_t* vis_start, const int32_t* vis_len) {
+static qc_status check_spans(const char* who, const qc_kvcache* kv, int layer, const int32_t* vis_start, const int32_t* vis_len) {
   if (!vis_start || !vis_len) return fail(QC_EINVAL, "%s: null span arrays", who);
   for (int b = 0; b < kv->batch; ++b)
-    if (vis_start[b] != kv->vis_start[b] || vis_len[b] != kv->vis_len[b])
-      return fail(QC_EINVAL, "%s: span of sequence %d differs from the one given to qc_reset", who, b);
+    if (vis_start[b] != kv->vis_start[b] || vis_len[b] != kv->vis_len_of(layer, b))
+      return fail(QC_EINVAL, "%s: span of sequence %d differs from the one given to %s", who, b,
+                  kv->late(layer) ? "qc_reset and qc_prune" : "qc_reset");
   return QC_OK;
 }
 
@@ -269,16 +280,21 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
   if (kv->phase != PH_RESET && kv->phase != PH_PREFILL)
     return fail(QC_EORDER, "qc_prefill: no prefill pass is open (call qc_reset first)");
   if (layer != kv->next_layer) return fail(QC_EORDER, "qc_prefill: expected layer %d, got %d", kv->next_layer, layer);
-  if (qc_status s = check_spans("qc_prefill", kv, vis_start, vis_len)) return s;
+  if (qc_status s = check_spans("qc_prefill", kv, layer, vis_start, vis_len)) return s;
+  // The first layer of the pass, and the first layer after a pruning boundary, fix the packing.
+  const bool opens = layer == 0 || layer == kv->first_late;
   if (cu_seqlens[0] != 0) return fail(QC_EINVAL, "qc_prefill: cu_seqlens[0] must be 0");
   int32_t max_len = 0;
   for (int b = 0; b < kv->batch; ++b) {
     int64_t len = (int64_t)cu_seqlens[b + 1] - cu_seqlens[b];
     if (len < 1) return fail(QC_EINVAL, "qc_prefill: sequence %d is empty", b);
-    if (kv->vis_start[b] + kv->vis_len[b] > len) return fail(QC_EINVAL, "qc_prefill: span of sequence %d exceeds its %lld tokens", b, (long long)len);
+    const int32_t vn = kv->vis_len_of(layer, b);
+    if (layer > 0 && len != kv->len_of(layer, b))
+      return fail(QC_EINVAL, "qc_prefill: sequence %d has %lld tokens, layer %d expects %d", b, (long long)len, layer, kv->len_of(layer, b));
+    if (kv->vis_start[b] + vn > len) return fail(QC_EINVAL, "qc_prefill: span of sequence %d exceeds its %lld tokens", b, (long long)len);
     if (len > c.max_seq) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld tokens, max_seq %d", b, (long long)len, c.max_seq);
-    if (!c.gla() && len - kv->vis_len[b] > c.max_text) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld text tokens, max_text %d", b, (long long)(len - kv->vis_len[b]), c.max_text);
-    if (layer > 0 && (len != kv->len0[b] || cu_seqlens[b] != kv->tok0[b]))
+    if (!c.gla() && len - vn > c.max_text) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld text tokens, max_text %d", b, (long long)(len - vn), c.max_text);
+    if (!opens && cu_seqlens[b] != (kv->late(layer) ? kv->tok1[b] : kv->tok0[b]))
       return fail(QC_EINVAL, "qc_prefill: cu_seqlens changed between layers");
     if (len > max_len) max_len = (int32_t)len;
   }
@@ -289,7 +305,7 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
 
   hipStream_t st = (hipStream_t)stream;
   qc::LayerView lv = make_view(kv, qc, layer);
-  if (layer == 0) {
+  if (opens) {
     for (int first = 0; first < kv->batch; first += qc::MetaChunk::N) {
       qc::MetaChunk mc;
       memset(&mc, 0, sizeof(mc));
@@ -299,9 +315,9 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
         mc.v[qc::META_TOK0][i] = cu_seqlens[b];
         mc.v[qc::META_LEN0][i] = cu_seqlens[b + 1] - cu_seqlens[b];
         mc.v[qc::META_VIS_START][i] = kv->vis_start[b];
-        mc.v[qc::META_VIS_LEN][i] = kv->vis_len[b];
+        mc.v[qc::META_VIS_LEN][i] = kv->vis_len_of(layer, b);
       }
-      hipError_t e2 = qc::launch_meta_upload((int32_t*)(kv->arena + c.off_meta()), c.max_batch, first, count, mc, st);
+      hipError_t e2 = qc::launch_meta_upload(const_cast<int32_t*>(lv.meta), c.max_batch, first, count, mc, st);
       if (e2 != hipSuccess) return fail(QC_EDEVICE, "qc_prefill: metadata upload: %s", hipGetErrorString(e2));
     }
   }
@@ -324,6 +340,10 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
       kv->tok0[b] = cu_seqlens[b];
       kv->len0[b] = cu_seqlens[b + 1] - cu_seqlens[b];
     }
+  else if (opens) {
+    for (int b = 0; b < kv->batch; ++b) kv->tok1[b] = cu_seqlens[b];
+    kv->late_known = true;
+  }
   if (a.write_q) qc->owner = layer;
   kv->next_layer = layer + 1;
   kv->phase = PH_PREFILL;
@@ -355,12 +375,13 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return fail(QC_EINVAL, "qc_decode: bad softmax_scale");
   if (kv->phase != PH_READY && kv->phase != PH_DECODE) return fail(QC_EORDER, "qc_decode: prefill has not finished");
   if (layer != kv->next_layer) return fail(QC_EORDER, "qc_decode: expected layer %d, got %d", kv->next_layer, layer);
-  if (qc_status s = check_spans("qc_decode", kv, vis_start, vis_len)) return s;
+  if (qc_status s = check_spans("qc_decode", kv, layer, vis_start, vis_len)) return s;
   int32_t max_len = 0;
   for (int b = 0; b < kv->batch; ++b) {
-    int64_t len = (int64_t)kv->len0[b] + kv->generated;
+    int64_t len = (int64_t)kv->len_of(layer, b) + kv->generated;
+    const int32_t vn = kv->vis_len_of(layer, b);
     if (len + 1 > c.max_seq) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld positions, max_seq %d", b, (long long)(len + 1), c.max_seq);
-    if (!c.gla() && len + 1 - kv->vis_len[b] > c.max_text) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld text rows, max_text %d", b, (long long)(len + 1 - kv->vis_len[b]), c.max_text);
+    if (!c.gla() && len + 1 - vn > c.max_text) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld text rows, max_text %d", b, (long long)(len + 1 - vn), c.max_text);
     if (len > max_len) max_len = (int32_t)len;
   }
   if (qk_unused && qc->owner != c.anchor[layer])
@@ -399,9 +420,9 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   a.inline_meta = kv->batch <= qc::DecodeArgs::kInlineSeqs ? 1 : 0;
   for (int b = 0; b < qc::DecodeArgs::kInlineSeqs; ++b) {
     const bool ok = a.inline_meta && b < kv->batch;
-    a.len0_inline[b] = ok ? kv->len0[b] : 0;
+    a.len0_inline[b] = ok ? kv->len_of(layer, b) : 0;
     a.vis_start_inline[b] = ok ? kv->vis_start[b] : 0;
-    a.vis_len_inline[b] = ok ? kv->vis_len[b] : 0;
+    a.vis_len_inline[b] = ok ? kv->vis_len_of(layer, b) : 0;
   }
   qc::KernelTimer* timer = !kv->timing ? nullptr : (g.mode == 2 ? &kv->decode_shared_timer : &kv->decode_timer);
   hipError_t err = qc::launch_decode(a, g, c.dtype, (hipStream_t)stream, timer);
@@ -428,13 +449,13 @@ static void rows_of(const qc_kvcache* kv, int layer, int b, int64_t* rk, int64_t
   switch (kv->phase) {
     case PH_EMPTY:
     case PH_RESET: len = 0; break;
-    case PH_PREFILL: len = layer < kv->next_layer ? kv->len0[b] : 0; break;
-    case PH_READY: len = (int64_t)kv->len0[b] + kv->generated; break;
-    case PH_DECODE: len = (int64_t)kv->len0[b] + kv->generated + (layer < kv->next_layer ? 1 : 0); break;
+    case PH_PREFILL: len = layer < kv->next_layer ? kv->len_of(layer, b) : 0; break;
+    case PH_READY: len = (int64_t)kv->len_of(layer, b) + kv->generated; break;
+    case PH_DECODE: len = (int64_t)kv->len_of(layer, b) + kv->generated + (layer < kv->next_layer ? 1 : 0); break;
   }
   *rv = len;
   if (c.gla()) *rk = c.lazy[layer] ? 0 : len;
-  else *rk = len ? len - (c.lazy[layer] ? kv->vis_len[b] : 0) : 0;
+  else *rk = len ? len - (c.lazy[layer] ? kv->vis_len_of(layer, b) : 0) : 0;
 }
 
 qc_status qc_stats(const qc_kvcache* kv, const qc_qcache* qc, qc_stats_t* out) {
@@ -450,12 +471,11 @@ qc_status qc_stats(const qc_kvcache* kv, const qc_qcache* qc, qc_stats_t* out) {
       out->v_bytes += rv * per_row;
     }
     if (qc && qc->owner >= 0) {
-      int64_t q_rows = kv->vis_len[b];
+      // rows of the layer that wrote the Q Cache last (after a pruning boundary: of the shortened sequence)
+      int64_t q_rows = kv->vis_len_of(qc->owner, b);
       if (c.gla()) {  // one row per position; the row of the token in flight once a block's first layer has run
-        q_rows = (int64_t)kv->len0[b] + kv->generated;
-        if (kv->phase == PH_DECODE)
-          for (int l = 0; l < kv->next_layer; ++l)
-            if (c.writes_q(l)) { q_rows += 1; break; }
+        q_rows = (int64_t)kv->len_of(qc->owner, b) + kv->generated;
+        if (kv->phase == PH_DECODE && qc->owner < kv->next_layer) q_rows += 1;
       }
       out->q_bytes += q_rows * per_row;
     }
@@ -558,10 +578,11 @@ qc_status qc_last_row_attention(qc_kvcache* kv, int32_t layer, const void* q_las
   if (((uintptr_t)q_last | (uintptr_t)workspace) & 15) return fail(QC_EINVAL, "qc_last_row_attention: q_last and workspace must be 16-byte aligned");
   if ((uintptr_t)probs & 3) return fail(QC_EINVAL, "qc_last_row_attention: probs must be 4-byte aligned");
   if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return fail(QC_EINVAL, "qc_last_row_attention: bad softmax_scale");
-  if (kv->phase != PH_READY) return fail(QC_EORDER, "qc_last_row_attention: needs a finished prefill pass and no decode step in flight");
+  if (kv->phase != PH_READY && !(kv->phase == PH_PREFILL && layer < kv->next_layer))
+    return fail(QC_EORDER, "qc_last_row_attention: needs a prefill pass in which layer %d has run and no decode step in flight", layer);
   int32_t max_len = 0;
   for (int b = 0; b < kv->batch; ++b) {
-    int32_t len = kv->len0[b] + kv->generated;
+    int32_t len = kv->len_of(layer, b) + kv->generated;
     if (len > max_len) max_len = len;
   }
   if (probs_stride < max_len) return fail(QC_EINVAL, "qc_last_row_attention: probs_stride %lld is shorter than the longest sequence (%d)", (long long)probs_stride, max_len);
@@ -609,6 +630,103 @@ qc_status qc_lazy_mask_from_similarity(const float* adjacent, int32_t n_layers, 
   if (!(eps > 0.0f) || !(eps <= 1.0f)) return fail(QC_EINVAL, "qc_lazy_mask_from_similarity: eps must lie in (0, 1]");
   mask_out[0] = 0;
   for (int i = 1; i < n_layers; ++i) mask_out[i] = adjacent[i - 1] < eps ? 1 : 0;
+  return QC_OK;
+}
+
+// ---- token-wise pruning between two layers ("Compatibility" paragraph) ---------------------------
+qc_status qc_prune_select(const float* scores, int64_t stride, int32_t batch, const int32_t* cu_seqlens,
+                          const int32_t* vis_start, const int32_t* vis_len, const int32_t* keep,
+                          int32_t* row_map, void* stream) {
+  if (!scores || !cu_seqlens || !vis_start || !vis_len || !keep || !row_map) return fail(QC_EINVAL, "qc_prune_select: null argument");
+  if (((uintptr_t)scores | (uintptr_t)row_map) & 3) return fail(QC_EINVAL, "qc_prune_select: scores and row_map must be 4-byte aligned");
+  if (batch < 1 || stride < 1) return fail(QC_EINVAL, "qc_prune_select: batch and stride must be positive");
+  if (cu_seqlens[0] != 0) return fail(QC_EINVAL, "qc_prune_select: cu_seqlens[0] must be 0");
+  int64_t survivors = 0;
+  for (int b = 0; b < batch; ++b) {
+    const int64_t len = (int64_t)cu_seqlens[b + 1] - cu_seqlens[b];
+    if (len < 1 || len > stride) return fail(QC_EINVAL, "qc_prune_select: sequence %d has %lld tokens, stride %lld", b, (long long)len, (long long)stride);
+    if (vis_start[b] < 0 || vis_len[b] < 0 || (int64_t)vis_start[b] + vis_len[b] > len)
+      return fail(QC_EINVAL, "qc_prune_select: span of sequence %d lies outside its %lld tokens", b, (long long)len);
+    if (keep[b] < 0 || keep[b] > vis_len[b]) return fail(QC_EINVAL, "qc_prune_select: keep[%d] = %d outside 0..%d", b, keep[b], vis_len[b]);
+    survivors += len - vis_len[b] + keep[b];
+  }
+  if (survivors >= ((int64_t)1 << 31)) return fail(QC_EINVAL, "qc_prune_select: too many tokens");
+  int64_t out0 = 0;
+  for (int first = 0; first < batch; first += qc::PruneChunk::N) {
+    qc::PruneChunk ch;
+    memset(&ch, 0, sizeof(ch));
+    const int count = batch - first < qc::PruneChunk::N ? batch - first : qc::PruneChunk::N;
+    for (int i = 0; i < count; ++i) {
+      const int b = first + i;
+      ch.tok0[i] = cu_seqlens[b];
+      ch.len[i] = cu_seqlens[b + 1] - cu_seqlens[b];
+      ch.vis_start[i] = vis_start[b];
+      ch.vis_len[i] = vis_len[b];
+      ch.keep[i] = keep[b];
+      ch.out0[i] = (int32_t)out0;
+      out0 += ch.len[i] - vis_len[b] + keep[b];
+    }
+    hipError_t e = qc::launch_prune_select(scores, stride, first, count, ch, row_map, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(QC_EDEVICE, "qc_prune_select: %s", hipGetErrorString(e));
+  }
+  return QC_OK;
+}
+
+qc_status qc_gather_rows(const void* src, int64_t src_stride, const int32_t* row_map, int64_t n_rows,
+                         int64_t row_bytes, void* dst, int64_t dst_stride, void* stream) {
+  if (n_rows < 0) return fail(QC_EINVAL, "qc_gather_rows: negative row count");
+  if (n_rows == 0) return QC_OK;
+  if (!src || !row_map || !dst) return fail(QC_EINVAL, "qc_gather_rows: null argument");
+  if (row_bytes < 16 || row_bytes % 16 || src_stride < row_bytes || dst_stride < row_bytes || src_stride % 16 || dst_stride % 16)
+    return fail(QC_EINVAL, "qc_gather_rows: rows and strides must be multiples of 16 bytes, strides >= row_bytes");
+  if ((((uintptr_t)src | (uintptr_t)dst) & 15) || ((uintptr_t)row_map & 3)) return fail(QC_EINVAL, "qc_gather_rows: misaligned pointer");
+  if (row_bytes / 16 >= ((int64_t)1 << 31) || n_rows >= ((int64_t)1 << 31)) return fail(QC_EINVAL, "qc_gather_rows: too large");
+  hipError_t e = qc::launch_gather_rows(src, src_stride, row_map, n_rows, row_bytes, dst, dst_stride, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(QC_EDEVICE, "qc_gather_rows: %s", hipGetErrorString(e));
+  return QC_OK;
+}
+
+qc_status qc_prune(qc_kvcache* kv, qc_qcache* qc, const int32_t* keep) {
+  if (!kv || !qc || !keep) return fail(QC_EINVAL, "qc_prune: null argument");
+  const Config& c = kv->cfg;
+  if (!c.same(qc->cfg)) return fail(QC_EINVAL, "qc_prune: handles were created with different configurations");
+  if (kv->phase != PH_PREFILL) return fail(QC_EORDER, "qc_prune: allowed only inside a prefill pass, between two layers");
+  if (kv->first_late >= 0) return fail(QC_EORDER, "qc_prune: this pass already has a pruning boundary (before layer %d)", kv->first_late);
+  if (c.lazy[kv->next_layer]) return fail(QC_EINVAL, "qc_prune: layer %d is lazy: a boundary cannot fall inside a lazy block", kv->next_layer);
+  for (int b = 0; b < kv->batch; ++b)
+    if (keep[b] < 0 || keep[b] > kv->vis_len[b]) return fail(QC_EINVAL, "qc_prune: keep[%d] = %d outside 0..%d", b, keep[b], kv->vis_len[b]);
+  kv->vis_len1.assign(keep, keep + kv->batch);
+  kv->tok1.assign(kv->batch, 0);
+  kv->late_known = false;
+  kv->first_late = kv->next_layer;
+  return QC_OK;
+}
+
+// ---- capacity planning ---------------------------------------------------------------------------
+qc_status qc_plan_max_batch(const qc_config* cfg, size_t budget_bytes, int32_t what, int32_t* max_batch) {
+  if (!cfg || !max_batch) return fail(QC_EINVAL, "qc_plan_max_batch: null argument");
+  if (what <= 0 || (what & ~(QC_PLAN_KV | QC_PLAN_Q | QC_PLAN_WORKSPACE))) return fail(QC_EINVAL, "qc_plan_max_batch: what must be a sum of QC_PLAN_ values");
+  qc_config probe = *cfg;
+  probe.max_batch = 1;
+  Config c;
+  if (!parse_config(&probe, &c)) return fail(QC_EINVAL, "qc_plan_max_batch: invalid configuration");
+  auto need = [&](int64_t batch) {
+    c.max_batch = (int32_t)batch;
+    int64_t n = 0;
+    if (what & QC_PLAN_KV) n += c.kv_bytes();
+    if (what & QC_PLAN_Q) n += c.q_bytes();
+    if (what & QC_PLAN_WORKSPACE) n += partial_bytes(c) + score_bytes(c);
+    return n;
+  };
+  // Every size grows with the batch: bisect on the largest batch that fits.
+  const int64_t budget = budget_bytes > (size_t)INT64_MAX ? INT64_MAX : (int64_t)budget_bytes;
+  int64_t lo = 0, hi = 1;
+  while (hi < ((int64_t)1 << 24) && need(hi) <= budget) { lo = hi; hi *= 2; }
+  while (hi - lo > 1) {
+    const int64_t mid = lo + (hi - lo) / 2;
+    if (need(mid) <= budget) lo = mid; else hi = mid;
+  }
+  *max_batch = (int32_t)lo;
   return QC_OK;
 }
 
@@ -660,7 +778,7 @@ qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t 
     *byte_offset = c.off_v(layer) + (((int64_t)b * c.H + h) * c.max_seq + pos) * rb;
     return QC_OK;
   }
-  const int32_t s = kv->vis_start[b], vn = kv->vis_len[b];
+  const int32_t s = kv->vis_start[b], vn = kv->vis_len_of(layer, b);
   int src = layer;
   int64_t row = pos;
   if (c.lazy[layer]) {

@@ -8,8 +8,10 @@
 
 namespace qc {
 
-// Per-sequence metadata rows in the arena's meta region: meta[row * max_batch + b].
-enum { META_TOK0 = 0, META_LEN0 = 1, META_VIS_START = 2, META_VIS_LEN = 3, META_ROWS = 4 };
+// Per-sequence metadata rows in the arena's meta region: meta[row * max_batch + b].  The region holds
+// META_BLOCKS such blocks of META_ROWS rows: block 0 describes the prompts as given, block 1 the
+// prompts as the layers after a token-pruning boundary see them.
+enum { META_TOK0 = 0, META_LEN0 = 1, META_VIS_START = 2, META_VIS_LEN = 3, META_ROWS = 4, META_BLOCKS = 2 };
 
 // Device addresses of everything one layer call touches.  Cache regions are
 // [batch][head][cap][D] with the element type of the configuration.
@@ -113,6 +115,16 @@ struct DecodeGlaArgs {
                           // 2: lazy layer: take the scores from `scores` instead of reading keys
 };
 
+struct PruneChunk {       // by-value payload of the survivor selection kernel: up to N sequences
+  enum { N = 64 };
+  int32_t tok0[N];        // first packed token index of the sequence
+  int32_t len[N];
+  int32_t vis_start[N];
+  int32_t vis_len[N];
+  int32_t keep[N];
+  int32_t out0[N];        // first entry of the sequence in the row map
+};
+
 struct MetaChunk {        // by-value payload of the metadata upload kernel
   enum { N = 64 };
   int32_t v[META_ROWS][N];
@@ -171,6 +183,10 @@ hipError_t launch_last_row_attention(const SelectArgs& a, int dtype, int max_len
 hipError_t launch_js(const float* pm, const float* pn, int64_t stride, int first, int count, const JsChunk& c,
                      float* js_out, hipStream_t stream);
 hipError_t launch_mean(const float* x, int n, float* out, hipStream_t stream);
+hipError_t launch_prune_select(const float* scores, int64_t stride, int first, int count, const PruneChunk& c,
+                               int32_t* row_map, hipStream_t stream);
+hipError_t launch_gather_rows(const void* src, int64_t src_stride, const int32_t* row_map, int64_t n_rows,
+                              int64_t row_bytes, void* dst, int64_t dst_stride, hipStream_t stream);
 hipError_t launch_project_qk(const ProjectArgs& a, int rows, hipStream_t stream);
 hipError_t launch_project_qk_skinny(const ProjectArgs& a, int n_rows, hipStream_t stream);
 

@@ -52,7 +52,17 @@ class Session:
         self.batch = len(self.vis_start)
         # marshalled once per batch: the span arrays every later call repeats
         self._vs_c, self._vl_c = B._i32(self.vis_start), B._i32(self.vis_len)
+        self.first_late, self.keep = None, None
+        self._vl_by_layer = [(self.vis_len, self._vl_c)] * self.n_layers   # span lengths each layer's calls repeat
         B.qc_reset(self.kv, self.qc, self.batch, self.vis_start, self.vis_len, int(zero_fill), self._stream())
+
+    def prune(self, next_layer, keep):
+        """Token pruning boundary before `next_layer` (the layer the prefill pass runs next): from there on
+        sequence b keeps keep[b] of its visual tokens.  Later prefill calls take the shortened prompts."""
+        B.qc_prune(self.kv, self.qc, keep)
+        self.first_late, self.keep = next_layer, list(keep)
+        late = (self.keep, B._i32(self.keep))
+        self._vl_by_layer = [late if l >= next_layer else (self.vis_len, self._vl_c) for l in range(self.n_layers)]
 
     def prefill(self, layer, q, k, v, cu_seqlens, out=None, softmax_scale=0.0):
         """q, k, v: [tokens, H, D] tensors sharing strides.  Returns out.  In "gla" mode a lazy
@@ -63,7 +73,7 @@ class Session:
             assert t is None or t.stride() == v.stride()
         assert v.stride(2) == 1
         B.qc_prefill(self.kv, self.qc, layer, self.lazy_mask[layer], q, k, v, out, cu_seqlens, v.stride(0),
-                     v.stride(1), self.vis_start, self.vis_len, softmax_scale, self._stream())
+                     v.stride(1), self.vis_start, self._vl_by_layer[layer][0], softmax_scale, self._stream())
         return out
 
     def decode(self, layer, q, k, v, out=None, softmax_scale=0.0, stream=None):
@@ -76,7 +86,7 @@ class Session:
         assert (q is None or q.is_contiguous()) and (k is None or k.is_contiguous())
         status = self._lib.qc_decode(self.kv, self.qc, layer, self.lazy_mask[layer],
                                      None if q is None else q.data_ptr(), None if k is None else k.data_ptr(),
-                                     v.data_ptr(), out.data_ptr(), self._vs_c, self._vl_c, softmax_scale,
+                                     v.data_ptr(), out.data_ptr(), self._vs_c, self._vl_by_layer[layer][1], softmax_scale,
                                      self._ws_ptr, self.ws_bytes, self._stream() if stream is None else stream)
         if status != B.QC_OK:
             raise B.QcError(status, B.qc_last_error())

@@ -289,3 +289,70 @@ def test_project_qk_validation():
         with pytest.raises(P.QcError) as e:
             call(**kw)
         assert e.value.status == B.QC_EINVAL, kw
+
+
+PLAN_CASES = [(4, 8, 64, "f32", 1, 192, 144, 48, [0, 0, 1, 1], "vla"),
+              (6, 3, 128, "bf16", 1, 300, 200, 120, [0, 1, 1, 1, 0, 1], "vla"),
+              (6, 3, 128, "bf16", 1, 300, 200, 120, [0, 1, 1, 1, 0, 1], "gla"),
+              (3, 2, 64, "bf16", 1, 77, 0, 77, [0, 0, 0], "vla")]
+
+
+@pytest.mark.parametrize("c", PLAN_CASES)
+def test_plan_max_batch_matches_oracle_search(c):
+    from oracle.layout import max_batch_within
+    cfg = P.make_config(*c[:9], mode=c[9])
+    per_seq = ArenaLayout(*c[:9], mode=c[9]).off_meta()
+    for budget in (0, per_seq - 1, per_seq + 4096, 7 * per_seq + 12345, 40 * per_seq, 41 * per_seq + 3000):
+        for what, count_q in ((B.QC_PLAN_KV, False), (B.QC_PLAN_KV | B.QC_PLAN_Q, True)):
+            want = max_batch_within(budget, *c[:4], *c[5:9], mode=c[9], count_q=count_q)
+            assert B.qc_plan_max_batch(cfg, budget, what) == want, (budget, what)
+    # with the workspace counted the answer is the largest batch whose three buffers fit
+    budget = 23 * per_seq
+    got = B.qc_plan_max_batch(cfg, budget, B.QC_PLAN_KV | B.QC_PLAN_Q | B.QC_PLAN_WORKSPACE)
+    def total(batch):
+        cc = P.make_config(*c[:4], batch, *c[5:9], mode=c[9])
+        return B.qc_kv_arena_bytes(cc) + B.qc_q_arena_bytes(cc) + B.qc_decode_workspace_bytes(cc)
+    assert got >= 1 and total(got) <= budget < total(got + 1)
+
+
+def test_plan_max_batch_reproduces_the_papers_pair():
+    """"Efficiency Evaluation" paragraph: 21 -> 32 sequences of 2048 positions on the same memory at a 35 % KV
+    saving (N = 32, hence n = 22 lazy layers under Global Lazy Attention; the Q Cache not counted)."""
+    N_, pct, b0, b1 = [int(x) for x in open(os.path.join(ROOT, "tests", "golden", "max_batch_fig5.txt")).read().split("\n")[-2].split()]
+    plain = P.make_config(N_, 32, 128, "bf16", 1, 2048, 2048, 2048, [0] * N_)
+    lazy = P.make_config(N_, 32, 128, "bf16", 1, 2048, 2048, 2048, [0] * (N_ - 22) + [1] * 22, mode="gla")
+    # memory that holds exactly b0 plain sequences, plus 4 KiB for the per-sequence integers of a larger batch
+    budget = B.qc_kv_arena_bytes(P.make_config(N_, 32, 128, "bf16", b0, 2048, 2048, 2048, [0] * N_)) + 4096
+    assert B.qc_plan_max_batch(plain, budget, B.QC_PLAN_KV) == b0
+    assert B.qc_plan_max_batch(lazy, budget, B.QC_PLAN_KV) == b1
+
+
+def test_plan_and_prune_calls_validate_before_launching():
+    cfg = P.make_config(4, 8, 64, "f32", 1, 192, 144, 48, [0, 0, 1, 1])
+    for what in (0, 8, -1):
+        with pytest.raises(B.QcError) as e:
+            B.qc_plan_max_batch(cfg, 1 << 30, what)
+        assert e.value.status == B.QC_EINVAL
+    bad_cfg = P.make_config(4, 8, 96, "f32", 1, 192, 144, 48, [0, 0, 1, 1])
+    with pytest.raises(B.QcError):
+        B.qc_plan_max_batch(bad_cfg, 1 << 30, B.QC_PLAN_KV)
+    ok = dict(scores=FAKE, stride=64, batch=2, cu_seqlens=[0, 40, 100], vis_start=[2, 0], vis_len=[30, 60],
+              keep=[10, 0], row_map=FAKE)
+    for change in (dict(scores=None), dict(row_map=None), dict(stride=59), dict(cu_seqlens=[1, 40, 100]),
+                   dict(keep=[31, 0]), dict(keep=[-1, 0]), dict(vis_len=[39, 60]), dict(vis_start=[-1, 0]),
+                   dict(batch=0), dict(scores=FAKE + 2)):
+        args = dict(ok, **change)
+        with pytest.raises(B.QcError) as e:
+            B.qc_prune_select(**args)
+        assert e.value.status == B.QC_EINVAL, change
+    okg = dict(src=FAKE, src_stride=256, row_map=FAKE, n_rows=5, row_bytes=256, dst=FAKE * 2, dst_stride=256)
+    for change in (dict(src=None), dict(dst=None), dict(row_map=None), dict(row_bytes=24), dict(src_stride=128),
+                   dict(dst_stride=264), dict(n_rows=-1), dict(src=FAKE + 8), dict(row_bytes=0)):
+        args = dict(okg, **change)
+        with pytest.raises(B.QcError) as e:
+            B.qc_gather_rows(**args)
+        assert e.value.status == B.QC_EINVAL, change
+    assert B.qc_gather_rows(**dict(okg, n_rows=0)) == B.QC_OK          # nothing to do, nothing launched
+    with pytest.raises(B.QcError) as e:
+        B.qc_prune(None, None, [1])
+    assert e.value.status == B.QC_EINVAL
