@@ -400,6 +400,193 @@ def bench_prefill_highres(args, w=None, traffic_key="prefill_cfg4", layers=None,
     return res
 
 
+class PrunedRunner(Runner):
+    """Runner with a token-pruning boundary: layers >= first_late see `keep_frac` of each span.
+
+    The prefill pass ranks the visual tokens by the last prompt token's attention in the last ordinary
+    early layer, selects the survivors, drops the pruned rows of one hidden-state-sized tensor
+    ([tokens][d_model] bf16, what a model would carry across the boundary) and moves the boundary into
+    the cache state; all of that is inside the timed pass.  The late layers' q/k/v inputs are gathered
+    once at construction with the same row map (the ranking is deterministic)."""
+
+    def __init__(self, w, decode_steps, first_late, keep_frac, d_model=4096, **kw):
+        super().__init__(w, decode_steps, **kw)
+        from paper_2602_01901_amd import binding as B
+        torch = self.torch
+        self.B, self.first_late = B, first_late
+        self.keep = [int(v * keep_frac) for v in w.vis_len]
+        self.rank_layer = max(l for l in range(first_late) if not w.lazy_mask[l])
+        self.late_len = [L - v + k for L, v, k in zip(w.seq_len, w.vis_len, self.keep)]
+        self.cu_late = [0]
+        for n in self.late_len:
+            self.cu_late.append(self.cu_late[-1] + n)
+        dev = self.sess.device
+        cu = w.cu_seqlens
+        self.q_last = torch.stack([self.pre[self.rank_layer][0][cu[b + 1] - 1] for b in range(w.batch)]).contiguous()
+        self.sel_ws = torch.empty(B.qc_select_workspace_bytes(self.sess.cfg), dtype=torch.uint8, device=dev)
+        self.stride = w.max_seq
+        self.probs = torch.zeros((w.batch, self.stride), dtype=torch.float32, device=dev)
+        self.row_map = torch.zeros(self.cu_late[-1], dtype=torch.int32, device=dev)
+        self.hidden = torch.randn(w.total_tokens, d_model, device=dev).to(torch.bfloat16)
+        self.hidden_late = torch.empty(self.cu_late[-1], d_model, dtype=torch.bfloat16, device=dev)
+        self.row_bytes = d_model * 2
+        self.out_late = None
+        self.prefill_stack()                 # first pass: fixes the row map; late layers still read full-length inputs' heads
+        torch.cuda.synchronize()
+        rows = self.row_map.long()
+        for l in range(first_late, w.n_layers):
+            self.pre[l] = tuple(t.index_select(0, rows).contiguous() for t in self.pre[l])
+        self.out_late = torch.empty_like(self.pre[first_late][2])
+
+    def prefill_stack(self):
+        w, s, B = self.w, self.sess, self.B
+        s.reset(w.vis_start, w.vis_len, zero_fill=False)
+        for l in range(w.n_layers):
+            q, k, v = self.pre[l]
+            late = l >= self.first_late
+            if late and self.out_late is None:          # construction pass: any rows of the right count will do
+                q, k, v = (t[: self.cu_late[-1]] for t in (q, k, v))
+            if self.no_qk[l]:
+                q = k = None
+            out = self.out_pre[: v.shape[0]] if (not late or self.out_late is None) else self.out_late
+            s.prefill(l, q, k, v, self.cu_late if late else w.cu_seqlens, out=out)
+            if l == self.rank_layer:
+                B.qc_last_row_attention(s.kv, l, self.q_last, self.probs, self.stride, 0.0, self.sel_ws,
+                                        self.sel_ws.numel())
+                B.qc_prune_select(self.probs, self.stride, w.batch, w.cu_seqlens, w.vis_start, w.vis_len, self.keep,
+                                  self.row_map)
+                B.qc_gather_rows(self.hidden, self.row_bytes, self.row_map, self.cu_late[-1], self.row_bytes,
+                                 self.hidden_late, self.row_bytes)
+            if l == self.first_late - 1:
+                s.prune(self.first_late, self.keep)
+
+    def decode_bytes_per_step(self, generated):
+        """Algorithmic decode bytes of one step over all layers (late layers stream the shortened sequences)."""
+        w = self.w
+        e = w.n_heads * w.head_dim * w.elem_bytes
+        early = sum((2 * (L + generated + 1) + 6) * e for L in w.seq_len)
+        late = sum((2 * (L + generated + 1) + 6) * e for L in self.late_len)
+        return self.first_late * early + (w.n_layers - self.first_late) * late
+
+
+def bench_pruning(args):
+    """Token pruning on top of Visual Lazy Attention ("Compatibility" paragraph): the batched-decode
+    configuration with a boundary after layer 1 that keeps half of every image's tokens, beside the same
+    configuration without pruning, timed in the same run; then the cost of the boundary itself."""
+    import torch
+    import workloads
+    from paper_2602_01901_amd import binding as B
+    w = workloads.config(2)
+    steps = args.decode_batched_steps
+    first_late, keep_frac = 2, 0.5
+    out = {"workload": w.name + " + pruning", "boundary_before_layer": first_late, "kept_fraction_of_visual_tokens": keep_frac}
+    for name in ("unpruned", "pruned"):
+        r = (PrunedRunner(w, steps, first_late, keep_frac, distinct_decode_inputs=4) if name == "pruned"
+             else Runner(w, steps, distinct_decode_inputs=4))
+        r.prefill_stack()
+        _, pre_s = timed(torch, r.prefill_stack, 3)
+        r.decode_steps_run(2)
+        torch.cuda.synchronize()
+        g0 = r.sess.stats()["generated"]
+        _, ev_s = timed(torch, lambda: r.decode_steps_run(steps), 1)
+        g1 = r.sess.stats()["generated"]
+        kt = r.kernel_times(lambda: r.decode_steps_run(4))
+        call_us, call_n = kt["decode"]
+        if name == "pruned":
+            bytes_call = sum(r.decode_bytes_per_step(g1 + t) for t in range(4)) / 4 / w.n_layers
+        else:
+            bytes_call = sum(decode_bytes_per_layer(w, g1 + t) for t in range(4)) / 4
+        stats = r.sess.stats()
+        achieved = bytes_call / (call_us * 1e-6) / 1e9
+        out[name] = {
+            "prefill_ms": pre_s * 1e3,
+            "decode_tokens_per_s": w.batch * steps / ev_s, "decode_ms_per_step": ev_s / steps * 1e3,
+            "kv_cache_bytes_per_token": (stats["k_bytes"] + stats["v_bytes"]) / stats["tokens"],
+            "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<bf16,128> (mean over the layers of a step)",
+                         "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                         "traffic": None, "avg_launch_us": call_us, "launches_timed": call_n,
+                         "algorithmic_bytes_per_launch": bytes_call},
+        }
+        if name == "pruned":
+            def boundary_select():
+                B.qc_prune_select(r.probs, r.stride, w.batch, w.cu_seqlens, w.vis_start, w.vis_len, r.keep, r.row_map)
+
+            def boundary_gather():
+                B.qc_gather_rows(r.hidden, r.row_bytes, r.row_map, r.cu_late[-1], r.row_bytes, r.hidden_late, r.row_bytes)
+            _, sel_s = timed(torch, boundary_select, 20)
+            _, gat_s = timed(torch, boundary_gather, 20)
+            moved = 2 * r.cu_late[-1] * r.row_bytes + 4 * r.cu_late[-1]
+            out["boundary"] = {"select_us": sel_s * 1e6, "gather_us": gat_s * 1e6,
+                               "gather_rows": r.cu_late[-1], "gather_row_bytes": r.row_bytes,
+                               "gather_roofline": {"bound": "hbm", "kernel": "gather_rows_kernel", "achieved": moved / gat_s / 1e9,
+                                                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": moved / gat_s / 1e9 / HBM_PEAK_GBS,
+                                                   "traffic": None, "avg_launch_us": gat_s * 1e6,
+                                                   "algorithmic_bytes_per_launch": moved}}
+        del r
+        torch.cuda.empty_cache()
+    out["decode_speedup"] = out["pruned"]["decode_tokens_per_s"] / out["unpruned"]["decode_tokens_per_s"]
+    return out
+
+
+def bench_capacity(args):
+    """The maximum-batch comparison of the "Efficiency Evaluation" paragraph, re-run here: 7B shape, 2048
+    positions per sequence, and the memory that holds exactly 21 such sequences without lazy layers.
+    qc_plan_max_batch gives the batch each variant fits into that memory (22 lazy layers: the count
+    whose Global-Lazy-Attention saving n/2N is closest to the 35 % the paper reports); each variant then
+    decodes at its own maximum batch."""
+    import torch
+    import workloads
+    import paper_2602_01901_amd as P
+    from paper_2602_01901_amd import binding as B
+    N, H, D, steps = 32, 32, 128, args.decode_batched_steps
+    L0, vis, vs = 2048 - steps - 2, 1728, 32
+    lazy22 = [int(2 <= l <= 30 and ((l - 2) % 4 != 0 or l == 30)) for l in range(N)]
+    assert sum(lazy22) == 22 and not lazy22[0]
+    plain_cfg = lambda b: P.make_config(N, H, D, "bf16", b, 2048, vis, 2048 - vis, [0] * N)
+    budget = B.qc_kv_arena_bytes(plain_cfg(21)) + 4096
+    out = {"positions_per_sequence": 2048, "visual_tokens": vis, "lazy_layers": 22, "budget_bytes": budget, "variants": {}}
+    for name, mask, mode in (("plain", [0] * N, "vla"), ("vla", lazy22, "vla"), ("gla", lazy22, "gla")):
+        cfg1 = P.make_config(N, H, D, "bf16", 1, 2048, vis, 2048 - vis, mask, mode=mode)
+        batch = B.qc_plan_max_batch(cfg1, budget, B.QC_PLAN_KV)
+        batch_all = B.qc_plan_max_batch(cfg1, budget, B.QC_PLAN_KV | B.QC_PLAN_Q | B.QC_PLAN_WORKSPACE)
+        w = workloads.custom("capacity_" + name, N, H, D, "bf16", [vs] * batch, [vis] * batch, [L0] * batch, steps + 2,
+                             mask, max_seq=2048, max_vis=vis, max_text=2048 - vis)
+        s = P.Session.for_workload(w, mode=mode)
+        q, k, v = workloads.prefill_qkv(w, 0, device=s.device)      # one set of inputs serves every layer
+        o = torch.empty_like(v)
+        s.reset(w.vis_start, w.vis_len, zero_fill=False)
+        for l in range(N):
+            no_qk = mode == "gla" and mask[l]
+            s.prefill(l, None if no_qk else q, None if no_qk else k, v, w.cu_seqlens, out=o)
+        dq, dk, dv = workloads.decode_qkv(w, 0, 0, device=s.device)
+        do = torch.empty_like(dv)
+
+        def run(n):
+            for _ in range(n):
+                for l in range(N):
+                    no_qk = mode == "gla" and mask[l]
+                    s.decode(l, None if no_qk else dq, None if no_qk else dk, dv, out=do)
+        run(2)
+        _, ev_s = timed(torch, lambda: run(steps), 1)
+        st = s.stats()
+        out["variants"][name] = {"max_batch": batch, "max_batch_counting_q_cache_and_workspace": batch_all,
+                                 "kv_arena_bytes": s.kv_bytes, "q_arena_bytes": s.q_bytes,
+                                 "decode_tokens_per_s": batch * steps / ev_s, "decode_ms_per_step": ev_s / steps * 1e3,
+                                 "kv_cache_bytes_per_token": (st["k_bytes"] + st["v_bytes"]) / st["tokens"]}
+        log("capacity %s: batch %d, %.0f tok/s" % (name, batch, batch * steps / ev_s))
+        s.close()
+        del s, q, k, v, o
+        torch.cuda.empty_cache()
+    p = out["variants"]["plain"]
+    for name in ("vla", "gla"):
+        out["variants"][name]["batch_vs_plain"] = out["variants"][name]["max_batch"] / p["max_batch"]
+        out["variants"][name]["attention_throughput_vs_plain"] = out["variants"][name]["decode_tokens_per_s"] / p["decode_tokens_per_s"]
+    out["note"] = ("attention only: streaming a sequence's caches costs the same at any batch, so the larger batch "
+                   "raises throughput here only where the bytes per token drop (score sharing under GLA); the "
+                   "weight-streaming part of a decode step, which a larger batch amortises, lies outside this path")
+    return out
+
+
 def bench_video(args):
     """13B-shaped video workload (batch 4, 4864-token prompts, 40 heads): prefill, then decode steps."""
     import torch
@@ -477,7 +664,8 @@ def main():
     ap.add_argument("--prefill-reps", type=int, default=3)
     ap.add_argument("--skip-extra", action="store_true", help="headline workload only")
     ap.add_argument("--skip-cpu", action="store_true")
-    ap.add_argument("--only", choices=["decode_batched", "prefill_highres", "gla_decode_batched", "selection", "projection"],
+    ap.add_argument("--only", choices=["decode_batched", "prefill_highres", "gla_decode_batched", "selection", "projection", "pruning",
+                                      "capacity"],
                     help="profiling aid: run just this extra workload and print its object")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profiling aid: run plain 1 GiB device copies (known HBM traffic) and exit")
@@ -504,7 +692,7 @@ def main():
     if args.only:
         fn = {"decode_batched": bench_decode_batched, "prefill_highres": bench_prefill_highres,
               "gla_decode_batched": bench_gla_decode_batched, "selection": bench_selection,
-              "projection": bench_projection}[args.only]
+              "projection": bench_projection, "pruning": bench_pruning, "capacity": bench_capacity}[args.only]
         print(json.dumps({args.only: fn(args)}))
         return
 
@@ -532,6 +720,10 @@ def main():
                                                                         extra["projection"]["lazy_layer_text_rows"]["us"]))
         extra["selection"] = bench_selection(args)
         log("selection done: %.1f us per layer" % extra["selection"]["last_row_attention_us_per_layer"])
+        extra["pruning"] = bench_pruning(args)
+        log("pruning done: %.1f -> %.1f tok/s" % (extra["pruning"]["unpruned"]["decode_tokens_per_s"],
+                                                extra["pruning"]["pruned"]["decode_tokens_per_s"]))
+        extra["capacity"] = bench_capacity(args)
     cpu = None if args.skip_cpu else cpu_baseline()
     line = {
         "metric": "decode_tokens_per_s", "value": r["decode_tokens_per_s"], "unit": "tokens/s",
