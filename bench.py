@@ -55,7 +55,7 @@ def decode_bytes_per_layer(w, generated):
 class Runner:
     """Holds resident inputs for one workload and drives the library."""
 
-    def __init__(self, w, decode_steps, distinct_decode_inputs=8, mode="vla"):
+    def __init__(self, w, decode_steps, distinct_decode_inputs=8, mode="vla", graph=False):
         import torch
         import paper_2602_01901_amd as P
         import workloads
@@ -70,6 +70,10 @@ class Runner:
         nd = max(1, min(distinct_decode_inputs, decode_steps))
         self.dec = [[workloads.decode_qkv(w, l, t, device=dev) for l in range(w.n_layers)] for t in range(nd)]
         self.out_dec = torch.empty_like(self.dec[0][0][0])
+        # graph=True: a decode step is one replay of a HIP graph recorded once (after the first prefill)
+        # over the first set of decode inputs, which then stand for the buffers a model's projections
+        # would refill in place before every step
+        self.use_graph, self.graph = graph, None
         torch.cuda.synchronize()
 
     def prefill_stack(self):
@@ -84,6 +88,15 @@ class Runner:
     def decode_steps_run(self, steps):
         w, s = self.w, self.sess
         stream = self.torch.cuda.current_stream(s.device).cuda_stream
+        if self.use_graph:
+            if self.graph is None:
+                row = self.dec[0]
+                self.graph = s.decode_graph([None if self.no_qk[l] else row[l][0] for l in range(w.n_layers)],
+                                            [None if self.no_qk[l] else row[l][1] for l in range(w.n_layers)],
+                                            [row[l][2] for l in range(w.n_layers)], [self.out_dec] * w.n_layers)
+            for t in range(steps):
+                s.graph_launch(self.graph, stream)
+            return
         for t in range(steps):
             row = self.dec[t % len(self.dec)]
             for l in range(w.n_layers):
@@ -104,7 +117,9 @@ class Runner:
         B.qc_timing_read(self.sess.kv, 0)
         B.qc_timing_read(self.sess.kv, 1)
         B.qc_timing_read(self.sess.kv, 2)
+        graph, self.use_graph = self.use_graph, False      # events sit between individual launches: ordinary calls
         fn()
+        self.use_graph = graph
         self.torch.cuda.synchronize()
         out = {}
         for name, which in (("prefill", 0), ("decode", 1), ("decode_shared", 2)):
@@ -132,7 +147,7 @@ def bench_cfg2(args):
     import torch
     import workloads
     w = workloads.config(1)
-    r = Runner(w, w.decode_steps)
+    r = Runner(w, w.decode_steps, graph=not args.no_graph)
     log("cfg2: warmup %d" % args.warmup)
     for _ in range(args.warmup):
         r.step()
@@ -664,6 +679,8 @@ def main():
     ap.add_argument("--prefill-reps", type=int, default=3)
     ap.add_argument("--skip-extra", action="store_true", help="headline workload only")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="headline workload: ordinary qc_decode calls instead of one HIP-graph replay per decode step")
     ap.add_argument("--only", choices=["decode_batched", "prefill_highres", "gla_decode_batched", "selection", "projection", "pruning",
                                       "capacity"],
                     help="profiling aid: run just this extra workload and print its object")
@@ -732,7 +749,9 @@ def main():
         "config": {"workload": w.name, "layers": w.n_layers, "heads": w.n_heads, "head_dim": w.head_dim,
                    "batch": w.batch, "visual_tokens": w.vis_len[0], "text_tokens": w.seq_len[0] - w.vis_len[0],
                    "decode_steps": w.decode_steps, "lazy_layers": w.n_lazy,
-                   "step": "reset + 32-layer prefill + 256 decode steps x 32 layers"},
+                   "step": "reset + 32-layer prefill + 256 decode steps x 32 layers",
+                   "decode_launch": "ordinary qc_decode calls" if args.no_graph else
+                                    "one replay of a HIP graph of the 32 layer calls per decode step"},
         "prefill_tflops": r["prefill_tflops"], "prefill_ms": r["prefill_ms"],
         "decode_ms_per_token_step": r["decode_ms_per_token_step"],
         "k_cache_bytes_per_token": r["k_cache_bytes_per_token"],

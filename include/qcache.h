@@ -113,8 +113,8 @@ typedef struct qc_stats_t {
  *   V region: layers in order, each [max_batch][n_heads][max_seq][head_dim];
  *   meta    : at the next multiple of 256: int32 [2][4][max_batch]; block 0 = {first packed token
  *             index, prompt length, vis_start, vis_len} per sequence; block 1 = the same rows as the
- *             layers after a qc_prune boundary see them (zero without one); padded to a multiple of
- *             256 bytes.
+ *             layers after a qc_prune boundary see them (zero without one); then 256 bytes of
+ *             counters (int32 [0]: decode steps completed, kept for replayed decode graphs).
  * Q arena: [max_batch][n_heads][max_vis][head_dim] (one layer's worth, visual rows only).
  * Under QC_GLA: capK(l) = 0 for a lazy layer, and the Q arena is
  *   [max_batch][n_heads][max_seq][head_dim] with row = token position.
@@ -184,6 +184,33 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
                     const void* k, const void* v, void* out, const int32_t* vis_start,
                     const int32_t* vis_len, float softmax_scale, void* workspace,
                     size_t workspace_bytes, void* stream);
+
+/* ---- a whole decode step as one replayable HIP graph --------------------------------------------
+ * At batch sizes where a layer call lasts a few microseconds, a decode step is bound by the gaps
+ * between dependent launches on a stream (about 4 us each here); replayed from a graph the same
+ * launches follow each other in under 2 us.  qc_decode_graph_create records the n_layers calls
+ * qc_decode would make for one step, in layer order, into a HIP graph: same kernels, same
+ * arithmetic, but they take the number of completed steps from a counter in the arena's meta
+ * region (which the graph itself advances) and every per-sequence integer from device memory, so
+ * one graph serves step after step, and any later batch of the same size on these handles.
+ *   q, k, v, out: HOST arrays of n_layers DEVICE pointers, [batch][n_heads][head_dim] each: the
+ *     buffers layer l reads and writes at EVERY replay (the caller refills q/k/v between replays; under
+ *     QC_GLA the q and k entries of lazy layers are ignored and may be NULL).
+ *   workspace: as for qc_decode, sized by qc_decode_workspace_bytes; used by every replay.
+ * Requires a finished prefill pass with no decode step in flight (QC_EORDER otherwise).  Creation
+ * records on a stream of its own and instantiates the graph: it allocates (host and runtime memory)
+ * and must not itself be called under stream capture.
+ * qc_decode_graph_launch replays the step on `stream` and moves the bookkeeping forward exactly as
+ * n_layers qc_decode calls would; steps made with qc_decode and replays may alternate.  QC_EORDER if
+ * no step may start now, or if the cache holds another number of sequences or another pruning
+ * boundary than at creation; QC_ECAPACITY as qc_decode.  The graph holds the device pointers given
+ * at creation; it must be destroyed before the handles it was made from. */
+typedef struct qc_decode_graph qc_decode_graph;
+qc_status qc_decode_graph_create(qc_kvcache* kv, qc_qcache* qc, const void* const* q, const void* const* k,
+                                 const void* const* v, void* const* out, float softmax_scale, void* workspace,
+                                 size_t workspace_bytes, qc_decode_graph** out_graph);
+qc_status qc_decode_graph_launch(qc_decode_graph* graph, void* stream);
+void qc_decode_graph_destroy(qc_decode_graph* graph);
 
 /* ---- bookkeeping queries (host only, no HIP call) ---------------------------------------------- */
 qc_status qc_stats(const qc_kvcache* kv, const qc_qcache* qc, qc_stats_t* out);

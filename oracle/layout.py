@@ -14,7 +14,9 @@ can be compared byte for byte:
              Block 0: first token index in the packed prompt, prompt length,
              vis_start, vis_len of every sequence.  Block 1: the same four rows
              as the layers after a token-pruning boundary see them (all zero
-             when no pruning took place).  Total rounded up to 256 bytes.
+             when no pruning took place).  Then 256 bytes of counters: int32 [0]
+             is the number of decode steps a replayed decode graph has counted
+             (zero if none was used).  Total rounded up to 256 bytes.
   Q arena    [max_batch][H][max_vis][D].
 
 Row maps: V row = position.  K row = position in a normal layer.  In a lazy
@@ -74,7 +76,7 @@ class ArenaLayout:
         return _round_up(self.off_v(self.N), 256)
 
     def meta_bytes(self):
-        return _round_up(2 * 4 * 4 * self.max_batch, 256)
+        return _round_up(2 * 4 * 4 * self.max_batch + 256, 256)
 
     def kv_arena_bytes(self):
         return self.off_meta() + self.meta_bytes()
@@ -127,7 +129,7 @@ def encode_rows(x, dtype):
     return (bits >> 16).astype(np.uint16).view(np.uint8)
 
 
-def kv_arena_image(layout, stacks, tok0=None):
+def kv_arena_image(layout, stacks, tok0=None, graph_steps=0):
     """Expected bytes of the whole K/V arena given one stack oracle (of the layout's mode) per sequence.
 
     Unwritten bytes are zero.  `tok0[b]` is the first packed-prompt token index
@@ -161,6 +163,8 @@ def kv_arena_image(layout, stacks, tok0=None):
             start_late += late.prefill_len
     o = layout.off_meta()
     img[o:o + meta.nbytes] = meta.view(np.uint8).reshape(-1)
+    # the device-side step counter (graph_steps: its value if a decode graph has been replayed)
+    img[o + meta.nbytes:o + meta.nbytes + 4] = np.array([graph_steps], dtype=np.int32).view(np.uint8)
     return img
 
 

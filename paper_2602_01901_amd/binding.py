@@ -51,6 +51,10 @@ _PROTOTYPES = {
                              c_void_p]),
     "qc_decode": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                             POINTER(c_int32), POINTER(c_int32), c_float, c_void_p, c_size_t, c_void_p]),
+    "qc_decode_graph_create": (c_int32, [c_void_p, c_void_p, POINTER(c_void_p), POINTER(c_void_p), POINTER(c_void_p),
+                                         POINTER(c_void_p), c_float, c_void_p, c_size_t, POINTER(c_void_p)]),
+    "qc_decode_graph_launch": (c_int32, [c_void_p, c_void_p]),
+    "qc_decode_graph_destroy": (None, [c_void_p]),
     "qc_stats": (c_int32, [c_void_p, c_void_p, POINTER(qc_stats_t)]),
     "qc_layer_rows": (c_int32, [c_void_p, c_int32, POINTER(c_int64), POINTER(c_int64)]),
     "qc_seq_len": (c_int32, [c_void_p, c_int32, POINTER(c_int32)]),
@@ -185,6 +189,26 @@ def qc_decode(kv, qc, layer, is_lazy, q, k, v, out, vis_start, vis_len, softmax_
     return _check(load_library().qc_decode(kv, qc, layer, int(is_lazy), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
                                           _i32(vis_start), _i32(vis_len), softmax_scale, _ptr(workspace),
                                           workspace_bytes, stream))
+
+
+def _ptr_array(xs):
+    return (c_void_p * max(len(xs), 1))(*[_ptr(x) for x in xs])
+
+
+def qc_decode_graph_create(kv, qc, q, k, v, out, softmax_scale, workspace, workspace_bytes):
+    """q, k, v, out: per-layer lists of tensors (or device addresses; None where a layer has none)."""
+    g = c_void_p()
+    _check(load_library().qc_decode_graph_create(kv, qc, _ptr_array(q), _ptr_array(k), _ptr_array(v), _ptr_array(out),
+                                                softmax_scale, _ptr(workspace), workspace_bytes, byref(g)))
+    return g
+
+
+def qc_decode_graph_launch(graph, stream=None):
+    return _check(load_library().qc_decode_graph_launch(graph, stream))
+
+
+def qc_decode_graph_destroy(graph):
+    load_library().qc_decode_graph_destroy(graph)
 
 
 def qc_stats(kv, qc):

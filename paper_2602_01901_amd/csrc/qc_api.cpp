@@ -49,7 +49,10 @@ struct Config {
   }
   int64_t off_v(int l) const { return off_k(N) + (int64_t)l * v_layer_bytes(); }
   int64_t off_meta() const { return round_up(off_v(N), 256); }
-  int64_t meta_bytes() const { return round_up((int64_t)qc::META_BLOCKS * qc::META_ROWS * 4 * max_batch, 256); }
+  // after the per-sequence integers: 256 bytes of device-side counters (int32 [0] = decode steps
+  // completed, as maintained for replayed decode graphs)
+  int64_t off_counters() const { return off_meta() + (int64_t)qc::META_BLOCKS * qc::META_ROWS * 4 * max_batch; }
+  int64_t meta_bytes() const { return round_up((int64_t)qc::META_BLOCKS * qc::META_ROWS * 4 * max_batch + 256, 256); }
   int64_t kv_bytes() const { return off_meta() + meta_bytes(); }
   int64_t q_bytes() const { return (int64_t)max_batch * H * cap_q() * D * e(); }
   int64_t row_bytes() const { return (int64_t)D * e(); }
@@ -109,6 +112,8 @@ struct qc_kvcache {
   bool late(int layer) const { return first_late >= 0 && layer >= first_late; }
   int32_t vis_len_of(int layer, int b) const { return late(layer) ? vis_len1[b] : vis_len[b]; }
   int32_t len_of(int layer, int b) const { return late(layer) ? len0[b] - vis_len[b] + vis_len1[b] : len0[b]; }
+  // Value the device-side step counter holds once everything enqueued so far has run (-1: not set).
+  int64_t dev_generated = -1;
   bool timing = false;
   qc::KernelTimer prefill_timer, decode_timer, decode_shared_timer;
   const void* score_workspace = nullptr;  // workspace the current block's scores were written to (GLA)
@@ -118,6 +123,15 @@ struct qc_qcache {
   Config cfg;
   char* arena = nullptr;
   int32_t owner = -1;
+};
+
+struct qc_decode_graph {
+  qc_kvcache* kv = nullptr;
+  qc_qcache* qc = nullptr;
+  hipGraphExec_t exec = nullptr;
+  int32_t batch = 0, first_late = -1;
+  int32_t final_owner = -1;              // Q Cache owner after a step (Global Lazy Attention)
+  const void* score_workspace = nullptr;
 };
 
 extern "C" {
@@ -228,6 +242,7 @@ qc_status qc_reset(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* 
   kv->score_workspace = nullptr;
   kv->first_late = -1;
   kv->late_known = false;
+  kv->dev_generated = -1;
   qc->owner = -1;
   return QC_OK;
 }
@@ -354,10 +369,16 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
   return QC_OK;
 }
 
-qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_lazy, const void* q,
-                    const void* k, const void* v, void* out, const int32_t* vis_start,
-                    const int32_t* vis_len, float softmax_scale, void* workspace,
-                    size_t workspace_bytes, void* stream) {
+// Launch geometry of a decode call that is being recorded into a graph: fixed for every later replay.
+struct GraphGeom {
+  int32_t chunk, max_chunks;
+  const int32_t* generated_dev;
+};
+
+static qc_status decode_impl(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_lazy, const void* q,
+                             const void* k, const void* v, void* out, const int32_t* vis_start,
+                             const int32_t* vis_len, float softmax_scale, void* workspace,
+                             size_t workspace_bytes, void* stream, const GraphGeom* geom) {
   if (!kv) return fail(QC_EINVAL, "qc_decode: null handle");
   const Config& c = kv->cfg;
   // Visual Lazy Attention never touches the Q Cache while decoding; Global Lazy Attention does.
@@ -375,7 +396,8 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return fail(QC_EINVAL, "qc_decode: bad softmax_scale");
   if (kv->phase != PH_READY && kv->phase != PH_DECODE) return fail(QC_EORDER, "qc_decode: prefill has not finished");
   if (layer != kv->next_layer) return fail(QC_EORDER, "qc_decode: expected layer %d, got %d", kv->next_layer, layer);
-  if (qc_status s = check_spans("qc_decode", kv, layer, vis_start, vis_len)) return s;
+  if (!geom)
+    if (qc_status s = check_spans("qc_decode", kv, layer, vis_start, vis_len)) return s;
   int32_t max_len = 0;
   for (int b = 0; b < kv->batch; ++b) {
     int64_t len = (int64_t)kv->len_of(layer, b) + kv->generated;
@@ -396,6 +418,10 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   int64_t per = (max_len + 1 + want - 1) / want;
   int32_t chunk = (int32_t)round_up(per < kMinChunkKeys ? kMinChunkKeys : per, kMinChunkKeys);
   int32_t max_chunks = (max_len + 1 + chunk - 1) / chunk;
+  if (geom) {
+    chunk = geom->chunk;
+    max_chunks = geom->max_chunks;
+  }
   size_t need = (size_t)kv->batch * c.H * max_chunks * (c.D + 2) * 4;
   if (c.gla()) need = (size_t)(partial_bytes(c) + score_bytes(c));
   if (workspace_bytes < need) return fail(QC_ECAPACITY, "qc_decode: workspace holds %zu bytes, %zu needed", workspace_bytes, need);
@@ -406,6 +432,7 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   a.lv = make_view(kv, c.gla() ? qc : nullptr, layer);
   a.q = q; a.k = k; a.v = v; a.out = out;
   a.workspace = (float*)workspace;
+  a.generated_dev = geom ? geom->generated_dev : nullptr;
   a.batch = kv->batch; a.n_heads = c.H; a.head_dim = c.D;
   a.is_lazy = c.lazy[layer];
   qc::DecodeGlaArgs g;
@@ -417,14 +444,15 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
   a.chunk_keys = chunk;
   a.max_chunks = max_chunks;
   a.scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)c.D);
-  a.inline_meta = kv->batch <= qc::DecodeArgs::kInlineSeqs ? 1 : 0;
+  // a recorded launch reads everything per-sequence from device memory: it then serves any batch of this size
+  a.inline_meta = (!geom && kv->batch <= qc::DecodeArgs::kInlineSeqs) ? 1 : 0;
   for (int b = 0; b < qc::DecodeArgs::kInlineSeqs; ++b) {
     const bool ok = a.inline_meta && b < kv->batch;
     a.len0_inline[b] = ok ? kv->len_of(layer, b) : 0;
     a.vis_start_inline[b] = ok ? kv->vis_start[b] : 0;
     a.vis_len_inline[b] = ok ? kv->vis_len_of(layer, b) : 0;
   }
-  qc::KernelTimer* timer = !kv->timing ? nullptr : (g.mode == 2 ? &kv->decode_shared_timer : &kv->decode_timer);
+  qc::KernelTimer* timer = (!kv->timing || geom) ? nullptr : (g.mode == 2 ? &kv->decode_shared_timer : &kv->decode_timer);
   hipError_t err = qc::launch_decode(a, g, c.dtype, (hipStream_t)stream, timer);
   if (err != hipSuccess) return fail(QC_EDEVICE, "qc_decode: %s", hipGetErrorString(err));
 
@@ -440,6 +468,127 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
     kv->phase = PH_READY;
   }
   return QC_OK;
+}
+
+qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_lazy, const void* q,
+                    const void* k, const void* v, void* out, const int32_t* vis_start,
+                    const int32_t* vis_len, float softmax_scale, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+  return decode_impl(kv, qc, layer, is_lazy, q, k, v, out, vis_start, vis_len, softmax_scale, workspace,
+                     workspace_bytes, stream, nullptr);
+}
+
+// ---- one whole decode step as a replayable graph -------------------------------------------------
+// Capacity checks of a step about to be replayed: every layer's appended row must fit.
+static qc_status step_fits(const char* who, const qc_kvcache* kv) {
+  const Config& c = kv->cfg;
+  for (int stage = 0; stage < 2; ++stage) {
+    const int layer = stage ? kv->first_late : 0;
+    if (layer < 0) break;
+    for (int b = 0; b < kv->batch; ++b) {
+      const int64_t len = (int64_t)kv->len_of(layer, b) + kv->generated;
+      if (len + 1 > c.max_seq) return fail(QC_ECAPACITY, "%s: sequence %d would reach %lld positions, max_seq %d", who, b, (long long)(len + 1), c.max_seq);
+      if (!c.gla() && len + 1 - kv->vis_len_of(layer, b) > c.max_text)
+        return fail(QC_ECAPACITY, "%s: sequence %d would reach %lld text rows, max_text %d", who, b, (long long)(len + 1 - kv->vis_len_of(layer, b)), c.max_text);
+    }
+  }
+  return QC_OK;
+}
+
+qc_status qc_decode_graph_create(qc_kvcache* kv, qc_qcache* qc, const void* const* q, const void* const* k,
+                                 const void* const* v, void* const* out, float softmax_scale, void* workspace,
+                                 size_t workspace_bytes, qc_decode_graph** out_graph) {
+  if (!out_graph) return fail(QC_EINVAL, "qc_decode_graph_create: out_graph is null");
+  *out_graph = nullptr;
+  if (!kv || !qc || !q || !k || !v || !out) return fail(QC_EINVAL, "qc_decode_graph_create: null argument");
+  const Config& c = kv->cfg;
+  if (!c.same(qc->cfg)) return fail(QC_EINVAL, "qc_decode_graph_create: handles were created with different configurations");
+  if (kv->phase != PH_READY) return fail(QC_EORDER, "qc_decode_graph_create: needs a finished prefill pass and no decode step in flight");
+  if (qc_status s = step_fits("qc_decode_graph_create", kv)) return s;
+  // Launch geometry for any length up to the capacity (workgroups past a sequence's end leave at once).
+  constexpr int64_t kTargetGroups = 1024;
+  const int64_t pairs = (int64_t)kv->batch * c.H;
+  const int64_t want = std::max<int64_t>(1, (kTargetGroups + pairs - 1) / pairs);
+  const int64_t per = (c.max_seq + want - 1) / want;
+  GraphGeom geom;
+  geom.chunk = (int32_t)round_up(per < kMinChunkKeys ? kMinChunkKeys : per, kMinChunkKeys);
+  geom.max_chunks = (c.max_seq + geom.chunk - 1) / geom.chunk;
+  geom.generated_dev = (const int32_t*)(kv->arena + c.off_counters());
+
+  hipStream_t cap = nullptr;
+  hipError_t e = hipStreamCreateWithFlags(&cap, hipStreamNonBlocking);
+  if (e != hipSuccess) return fail(QC_EDEVICE, "qc_decode_graph_create: %s", hipGetErrorString(e));
+  // Recording runs the ordinary call sequence of a step, which moves the bookkeeping forward as if
+  // the step had happened; it is put back afterwards (nothing executes while recording).
+  const int saved_phase = kv->phase, saved_next = kv->next_layer, saved_gen = kv->generated, saved_owner = qc->owner;
+  const void* saved_score_ws = kv->score_workspace;
+  qc_status st = QC_OK;
+  hipGraph_t graph = nullptr;
+  e = hipStreamBeginCapture(cap, hipStreamCaptureModeThreadLocal);
+  if (e == hipSuccess) {
+    for (int l = 0; l < c.N && st == QC_OK; ++l)
+      st = decode_impl(kv, qc, l, c.lazy[l], q[l], k[l], v[l], out[l], nullptr, nullptr, softmax_scale, workspace,
+                       workspace_bytes, cap, &geom);
+    if (st == QC_OK) {
+      hipError_t e2 = qc::launch_counter_update((int32_t*)(kv->arena + c.off_counters()), 1, 1, cap);
+      if (e2 != hipSuccess) st = fail(QC_EDEVICE, "qc_decode_graph_create: %s", hipGetErrorString(e2));
+    }
+    hipError_t e3 = hipStreamEndCapture(cap, &graph);
+    if (st == QC_OK && e3 != hipSuccess) st = fail(QC_EDEVICE, "qc_decode_graph_create: %s", hipGetErrorString(e3));
+  } else {
+    st = fail(QC_EDEVICE, "qc_decode_graph_create: %s", hipGetErrorString(e));
+  }
+  const int final_owner = qc->owner;
+  const void* final_score_ws = kv->score_workspace;
+  kv->phase = saved_phase; kv->next_layer = saved_next; kv->generated = saved_gen; qc->owner = saved_owner;
+  kv->score_workspace = saved_score_ws;
+  (void)hipStreamDestroy(cap);
+  if (st != QC_OK) {
+    if (graph) (void)hipGraphDestroy(graph);
+    return st;
+  }
+  hipGraphExec_t exec = nullptr;
+  e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (e != hipSuccess) return fail(QC_EDEVICE, "qc_decode_graph_create: %s", hipGetErrorString(e));
+  qc_decode_graph* g = new (std::nothrow) qc_decode_graph;
+  if (!g) {
+    (void)hipGraphExecDestroy(exec);
+    return fail(QC_ECAPACITY, "qc_decode_graph_create: out of host memory");
+  }
+  g->kv = kv; g->qc = qc; g->exec = exec;
+  g->batch = kv->batch; g->first_late = kv->first_late;
+  g->final_owner = final_owner; g->score_workspace = final_score_ws;
+  *out_graph = g;
+  return QC_OK;
+}
+
+qc_status qc_decode_graph_launch(qc_decode_graph* g, void* stream) {
+  if (!g) return fail(QC_EINVAL, "qc_decode_graph_launch: null handle");
+  qc_kvcache* kv = g->kv;
+  const Config& c = kv->cfg;
+  if (kv->phase != PH_READY) return fail(QC_EORDER, "qc_decode_graph_launch: needs a finished prefill pass and no decode step in flight");
+  if (kv->batch != g->batch || kv->first_late != g->first_late)
+    return fail(QC_EORDER, "qc_decode_graph_launch: the graph was recorded for %d sequences (pruning boundary %d), the cache now holds %d (%d)", g->batch, g->first_late, kv->batch, kv->first_late);
+  if (qc_status s = step_fits("qc_decode_graph_launch", kv)) return s;
+  if (kv->dev_generated != kv->generated) {  // first replay, or ordinary qc_decode steps ran in between
+    hipError_t e = qc::launch_counter_update((int32_t*)(kv->arena + c.off_counters()), kv->generated, 0, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(QC_EDEVICE, "qc_decode_graph_launch: %s", hipGetErrorString(e));
+    kv->dev_generated = kv->generated;
+  }
+  hipError_t e = hipGraphLaunch(g->exec, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(QC_EDEVICE, "qc_decode_graph_launch: %s", hipGetErrorString(e));
+  kv->generated += 1;
+  kv->dev_generated += 1;
+  if (g->final_owner >= 0) g->qc->owner = g->final_owner;
+  kv->score_workspace = g->score_workspace;
+  return QC_OK;
+}
+
+void qc_decode_graph_destroy(qc_decode_graph* g) {
+  if (!g) return;
+  (void)hipGraphExecDestroy(g->exec);
+  delete g;
 }
 
 // Rows resident in `layer` for sequence b, given how far the current pass has come.

@@ -30,23 +30,33 @@ __device__ __forceinline__ uint4 stream_load16(const char* p) {
   return make_uint4(t.x, t.y, t.z, t.w);
 }
 
-// Per-sequence integers: from the kernel arguments for small batches, else from the arena's meta region.
-__device__ __forceinline__ SeqMeta decode_meta(const DecodeArgs& a, int b) {
-  if (a.inline_meta) {
+// Per-sequence integers: from the kernel arguments for small batches (INLINE), else from the arena's
+// meta region.  Two instantiations rather than a run-time choice: with a choice the compiler selects
+// between the two addresses and issues one per-lane load, a full memory round trip ahead of
+// everything else; kept apart, both become scalar loads.
+template <bool INLINE> __device__ __forceinline__ SeqMeta decode_meta(const DecodeArgs& a, int b) {
+  if constexpr (INLINE) {
     SeqMeta m;
     m.tok0 = 0;
     m.len0 = a.len0_inline[b];
     m.vis_start = a.vis_start_inline[b];
     m.vis_len = a.vis_len_inline[b];
     return m;
+  } else {
+    return load_meta(a.lv, b);
   }
-  return load_meta(a.lv, b);
+}
+// Decode steps completed before this one: by value, or (launches recorded in a graph that is replayed
+// step after step) from the counter in device memory that the replayed graph itself advances.
+__device__ __forceinline__ int decode_generated(const DecodeArgs& a) {
+  if (a.generated_dev) return uniform_load(a.generated_dev);
+  return a.generated;
 }
 
 // MODE 0: ordinary and Visual Lazy Attention layers.  MODE 1: first layer of a Global Lazy Attention
 // block (also stores its scores and its query).  MODE 2: lazy layer under Global Lazy Attention
 // (reuses the stored scores, streams V only).
-template <typename T, int D, int MODE>
+template <typename T, int D, int MODE, bool INLINE>
 __device__ __forceinline__ void decode_split_body(const DecodeArgs& a, const DecodeGlaArgs& g) {
   constexpr bool SHARED = MODE == 2, STORE = MODE == 1;
   constexpr int EPL = ElemTraits<T>::kPer16;  // elements per lane (16 bytes)
@@ -57,8 +67,8 @@ __device__ __forceinline__ void decode_split_body(const DecodeArgs& a, const Dec
   constexpr int ROWB = D * (int)sizeof(T);
 
   const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  const SeqMeta sm = decode_meta(a, b);
-  const int len = sm.len0 + a.generated;  // position of the new token
+  const SeqMeta sm = decode_meta<INLINE>(a, b);
+  const int len = sm.len0 + decode_generated(a);  // position of the new token
   const int kbeg = chunk * a.chunk_keys;
   if (kbeg > len) return;
   const int kend = min(kbeg + a.chunk_keys, len + 1);
@@ -198,23 +208,23 @@ __device__ __forceinline__ void decode_split_body(const DecodeArgs& a, const Dec
   }
 }
 
-template <typename T, int D>
+template <typename T, int D, bool INLINE>
 __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
-  decode_split_body<T, D, 0>(a, DecodeGlaArgs{nullptr, 0, 0});
+  decode_split_body<T, D, 0, INLINE>(a, DecodeGlaArgs{nullptr, 0, 0});
 }
-template <typename T, int D, int MODE>
+template <typename T, int D, int MODE, bool INLINE>
 __global__ __launch_bounds__(256) void decode_split_gla_kernel(DecodeArgs a, DecodeGlaArgs g) {
-  decode_split_body<T, D, MODE>(a, g);
+  decode_split_body<T, D, MODE, INLINE>(a, g);
 }
 
 // Merge the chunk partials of one (sequence, head) in chunk order.  Partials are loaded in batches
 // of 16 chunks (all loads of a batch are independent, so their latencies overlap); within a batch
 // the usual running (max, sum) update is applied chunk by chunk in a fixed order, so results are
 // bitwise reproducible.
-template <typename T, int D>
+template <typename T, int D, bool INLINE>
 __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
   const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
-  const int len = decode_meta(a, b).len0 + a.generated;
+  const int len = decode_meta<INLINE>(a, b).len0 + decode_generated(a);
   const int n = (len + a.chunk_keys) / a.chunk_keys;  // ceil((len + 1) / chunk_keys)
   const int64_t bh = (int64_t)b * a.n_heads + h;
   const float* w = a.workspace + bh * a.max_chunks * (D + 2);
@@ -247,26 +257,32 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
   store_elem((T*)a.out + bh * D + d, o / l);
 }
 
-template <typename T, int D> static hipError_t launch_decode_t(const DecodeArgs& a, const DecodeGlaArgs& g, hipStream_t stream, KernelTimer* timer) {
+template <typename T, int D, bool INLINE>
+static hipError_t launch_decode_t(const DecodeArgs& a, const DecodeGlaArgs& g, hipStream_t stream, KernelTimer* timer) {
   dim3 grid(a.max_chunks, a.n_heads, a.batch);
   if (timer) timer->begin(stream);
-  if (g.mode == 2) hipLaunchKernelGGL((decode_split_gla_kernel<T, D, 2>), grid, dim3(256), 0, stream, a, g);
-  else if (g.mode == 1) hipLaunchKernelGGL((decode_split_gla_kernel<T, D, 1>), grid, dim3(256), 0, stream, a, g);
-  else hipLaunchKernelGGL((decode_split_kernel<T, D>), grid, dim3(256), 0, stream, a);
+  if (g.mode == 2) hipLaunchKernelGGL((decode_split_gla_kernel<T, D, 2, INLINE>), grid, dim3(256), 0, stream, a, g);
+  else if (g.mode == 1) hipLaunchKernelGGL((decode_split_gla_kernel<T, D, 1, INLINE>), grid, dim3(256), 0, stream, a, g);
+  else hipLaunchKernelGGL((decode_split_kernel<T, D, INLINE>), grid, dim3(256), 0, stream, a);
   if (timer) timer->end(stream);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.max_chunks == 1) return e;
-  hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(a.n_heads, a.batch), dim3(D), 0, stream, a);
+  hipLaunchKernelGGL((decode_merge_kernel<T, D, INLINE>), dim3(a.n_heads, a.batch), dim3(D), 0, stream, a);
   return hipGetLastError();
+}
+
+template <typename T, int D>
+static hipError_t launch_decode_m(const DecodeArgs& a, const DecodeGlaArgs& g, hipStream_t stream, KernelTimer* timer) {
+  return a.inline_meta ? launch_decode_t<T, D, true>(a, g, stream, timer) : launch_decode_t<T, D, false>(a, g, stream, timer);
 }
 
 hipError_t launch_decode(const DecodeArgs& a, const DecodeGlaArgs& g, int dtype, hipStream_t stream, KernelTimer* timer) {
   if (dtype == 0) {
-    if (a.head_dim == 64) return launch_decode_t<float, 64>(a, g, stream, timer);
-    if (a.head_dim == 128) return launch_decode_t<float, 128>(a, g, stream, timer);
+    if (a.head_dim == 64) return launch_decode_m<float, 64>(a, g, stream, timer);
+    if (a.head_dim == 128) return launch_decode_m<float, 128>(a, g, stream, timer);
   } else {
-    if (a.head_dim == 64) return launch_decode_t<bf16_t, 64>(a, g, stream, timer);
-    if (a.head_dim == 128) return launch_decode_t<bf16_t, 128>(a, g, stream, timer);
+    if (a.head_dim == 64) return launch_decode_m<bf16_t, 64>(a, g, stream, timer);
+    if (a.head_dim == 128) return launch_decode_m<bf16_t, 128>(a, g, stream, timer);
   }
   return hipErrorInvalidValue;
 }

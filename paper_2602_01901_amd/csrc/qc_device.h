@@ -84,16 +84,22 @@ template <int kLanes> __device__ __forceinline__ float group_max(float x) {
   return x;
 }
 
+// Wave-uniform integer that an earlier launch wrote and no lane of this launch writes: fetched through
+// the constant address space, so that it arrives by a scalar load instead of a per-lane one.
+__device__ __forceinline__ int32_t uniform_load(const int32_t* p) {
+  return *(const __attribute__((address_space(4))) int32_t*)(uintptr_t)p;
+}
+
 struct SeqMeta {
   int32_t tok0, len0, vis_start, vis_len;
 };
 // With inherit_all (Global Lazy Attention) the span a lazy layer inherits is the whole prompt.
 __device__ __forceinline__ SeqMeta load_meta(const LayerView& lv, int b, int inherit_all = 0) {
   SeqMeta m;
-  m.tok0 = lv.meta[META_TOK0 * lv.max_batch + b];
-  m.len0 = lv.meta[META_LEN0 * lv.max_batch + b];
-  m.vis_start = inherit_all ? 0 : lv.meta[META_VIS_START * lv.max_batch + b];
-  m.vis_len = inherit_all ? m.len0 : lv.meta[META_VIS_LEN * lv.max_batch + b];
+  m.tok0 = uniform_load(lv.meta + META_TOK0 * lv.max_batch + b);
+  m.len0 = uniform_load(lv.meta + META_LEN0 * lv.max_batch + b);
+  m.vis_start = inherit_all ? 0 : uniform_load(lv.meta + META_VIS_START * lv.max_batch + b);
+  m.vis_len = inherit_all ? m.len0 : uniform_load(lv.meta + META_VIS_LEN * lv.max_batch + b);
   return m;
 }
 

@@ -51,6 +51,7 @@ struct DecodeArgs {
   const void* v;
   void* out;
   float* workspace;       // [batch][H][max_chunks][D + 2] partial (o, m, l)
+  const int32_t* generated_dev;  // nullptr, or where the number of completed decode steps lives in device memory
   int32_t batch, n_heads, head_dim;
   int32_t is_lazy;
   int32_t generated;      // decode steps completed before this one: len_b = len0_b + generated
@@ -175,6 +176,7 @@ struct KernelTimer {
 };
 
 hipError_t launch_fill_zero(void* dev, size_t bytes, hipStream_t stream);
+hipError_t launch_counter_update(int32_t* counter, int32_t value, int32_t add, hipStream_t stream);
 hipError_t launch_meta_upload(int32_t* meta_dev, int32_t max_batch, int32_t first, int32_t count,
                               const MetaChunk& chunk, hipStream_t stream);
 hipError_t launch_prefill(const PrefillArgs& a, int dtype, hipStream_t stream, KernelTimer* timer);

@@ -24,6 +24,16 @@ hipError_t launch_fill_zero(void* dev, size_t bytes, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// *counter = add ? *counter + value : value (one lane): the decode-step counter a replayed graph reads.
+__global__ void counter_update_kernel(int32_t* counter, int32_t value, int32_t add) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *counter = add ? *counter + value : value;
+}
+
+hipError_t launch_counter_update(int32_t* counter, int32_t value, int32_t add, hipStream_t stream) {
+  hipLaunchKernelGGL(counter_update_kernel, dim3(1), dim3(64), 0, stream, counter, value, add);
+  return hipGetLastError();
+}
+
 __global__ void meta_upload_kernel(int32_t* meta, int32_t max_batch, int32_t first, int32_t count, MetaChunk c) {
   int i = threadIdx.x;
   if (i < count)

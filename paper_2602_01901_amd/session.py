@@ -38,6 +38,7 @@ class Session:
         self.batch = 0
         self._lib = B.load_library()
         self._ws_ptr = self.workspace.data_ptr()
+        self._graphs = []
 
     @classmethod
     def for_workload(cls, w, device="cuda:0", mode="vla"):
@@ -92,11 +93,26 @@ class Session:
             raise B.QcError(status, B.qc_last_error())
         return out
 
+    def decode_graph(self, q, k, v, out, softmax_scale=0.0):
+        """One decode step recorded as a HIP graph over per-layer lists of contiguous [B, H, D] buffers
+        (None for q and k of lazy layers in "gla" mode).  Returns a handle for graph_launch."""
+        g = B.qc_decode_graph_create(self.kv, self.qc, q, k, v, out, softmax_scale, self._ws_ptr, self.ws_bytes)
+        self._graphs.append(g)
+        return g
+
+    def graph_launch(self, graph, stream=None):
+        status = self._lib.qc_decode_graph_launch(graph, self._stream() if stream is None else stream)
+        if status != B.QC_OK:
+            raise B.QcError(status, B.qc_last_error())
+
     def stats(self):
         return B.qc_stats(self.kv, self.qc)
 
     def close(self):
         if self.kv is not None:
+            for g in self._graphs:
+                B.qc_decode_graph_destroy(g)
+            self._graphs = []
             B.qc_kvcache_destroy(self.kv)
             B.qc_qcache_destroy(self.qc)
             self.kv = self.qc = None

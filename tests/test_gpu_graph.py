@@ -1,0 +1,153 @@
+"""GPU parity for decode steps replayed from a HIP graph (qc_decode_graph_*) against the CPU oracle.
+
+Every replay is checked, with eager work (input copies, ordinary qc_decode steps) and
+synchronisations between replays; the caches must end up byte for byte as the oracle's image."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_01901_amd as P
+from paper_2602_01901_amd import binding as B
+import workloads
+from oracle import layout as olayout
+from stack_runner import TOL, max_abs_err, new_oracles, oracle_decode_layer, oracle_layout, oracle_prefill_layer
+
+pytestmark = pytest.mark.gpu
+
+
+def prefill_both(w, s, stacks, mode):
+    s.reset(w.vis_start, w.vis_len, zero_fill=True)
+    for l in range(w.n_layers):
+        q, k, v = workloads.prefill_qkv(w, l)
+        oracle_prefill_layer(w, stacks, l, q, k, v)
+        qg, kg = q.cuda(), k.cuda()
+        if mode == "gla" and w.lazy_mask[l]:
+            qg = kg = None
+        s.prefill(l, qg, kg, v.cuda(), w.cu_seqlens)
+
+
+def step_buffers(w, mode):
+    shape = (w.batch, w.n_heads, w.head_dim)
+    dt = workloads.TORCH_DTYPE[w.dtype]
+    mk = lambda: [torch.zeros(shape, dtype=dt, device="cuda") for _ in range(w.n_layers)]
+    q, k, v, out = mk(), mk(), mk(), mk()
+    if mode == "gla":
+        q = [None if w.lazy_mask[l] else q[l] for l in range(w.n_layers)]
+        k = [None if w.lazy_mask[l] else k[l] for l in range(w.n_layers)]
+    return q, k, v, out
+
+
+def run_steps(w, s, stacks, mode, graph, bufs, schedule, t0=0):
+    """schedule: one letter per step, 'g' = graph replay, 'e' = ordinary qc_decode calls.  Returns the worst error."""
+    q, k, v, out = bufs
+    worst = 0.0
+    for i, kind in enumerate(schedule):
+        t = t0 + i
+        ins = [workloads.decode_qkv(w, l, t) for l in range(w.n_layers)]
+        refs = [oracle_decode_layer(w, stacks, l, *ins[l]) for l in range(w.n_layers)]
+        if kind == "g":
+            for l in range(w.n_layers):
+                if q[l] is not None:
+                    q[l].copy_(ins[l][0])
+                    k[l].copy_(ins[l][1])
+                v[l].copy_(ins[l][2])
+                out[l].zero_()
+            s.graph_launch(graph)
+            torch.cuda.synchronize()
+            got = out
+        else:
+            got = []
+            for l in range(w.n_layers):
+                skip = mode == "gla" and w.lazy_mask[l]
+                got.append(s.decode(l, None if skip else ins[l][0].cuda(), None if skip else ins[l][1].cuda(), ins[l][2].cuda()))
+            torch.cuda.synchronize()
+        for l in range(w.n_layers):
+            err = max_abs_err(got[l], refs[l])
+            assert np.isfinite(err) and err <= TOL[w.dtype], (t, kind, l, err)
+            worst = max(worst, err)
+    return worst
+
+
+def check_caches(w, s, stacks, mode, graph_steps):
+    lay = oracle_layout(w, mode)
+    assert np.array_equal(s.kv_arena.cpu().numpy(), olayout.kv_arena_image(lay, stacks, graph_steps=graph_steps)), "K/V arena differs"
+    assert np.array_equal(s.q_arena.cpu().numpy()[: lay.q_arena_bytes()], olayout.q_arena_image(lay, stacks)), "Q arena differs"
+    res = olayout.resident_bytes(lay, stacks)
+    st = s.stats()
+    for key in ("k_bytes", "v_bytes", "q_bytes", "tokens"):
+        assert st[key] == res[key], key
+    assert st["q_owner"] == stacks[0].q_owner
+
+
+CASES = [
+    # name, layers, heads, D, dtype, vis_start, vis_len, seq_len, mask
+    ("split_f32", 4, 8, 64, "f32", [8], [144], [176], [0, 0, 1, 1]),                       # 3 key chunks per head, merged
+    ("ragged_bf16", 5, 4, 128, "bf16", [3, 0, 10], [60, 0, 33], [130, 70, 65], [0, 1, 0, 1, 1]),
+    ("batch11_bf16", 3, 2, 64, "bf16", [i % 3 for i in range(11)], [20 + i for i in range(11)], [40 + 5 * i for i in range(11)], [0, 1, 1]),
+]
+
+
+@pytest.mark.parametrize("mode", ["vla", "gla"])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_graph_replays_match_oracle(case, mode):
+    name, N, H, D, dtype, vs, vl, lens, mask = case
+    w = workloads.custom(name, N, H, D, dtype, vs, vl, lens, 7, mask, seed_tag=31)
+    s = P.Session.for_workload(w, mode=mode)
+    stacks = new_oracles(w, mode=mode)
+    prefill_both(w, s, stacks, mode)
+    bufs = step_buffers(w, mode)
+    g = s.decode_graph(*bufs)
+    schedule = "ggeggeg"
+    worst = run_steps(w, s, stacks, mode, g, bufs, schedule)
+    check_caches(w, s, stacks, mode, graph_steps=len(schedule))       # the last step was a replay
+    print("graph %s %s: worst |err| %.3g" % (name, mode, worst), flush=True)
+    # the sequences are full now: neither path may start another step
+    with pytest.raises(B.QcError) as e:
+        s.graph_launch(g)
+    assert e.value.status == B.QC_ECAPACITY
+    s.close()
+
+
+def test_graph_serves_a_new_batch_of_the_same_size_and_refuses_another():
+    w1 = workloads.custom("g1", 3, 2, 64, "bf16", [2, 0], [30, 10], [50, 90], 4, [0, 1, 0], seed_tag=32,
+                          max_seq=128, max_vis=40, max_text=100)
+    s = P.Session.for_workload(w1)
+    stacks = new_oracles(w1)
+    prefill_both(w1, s, stacks, "vla")
+    bufs = step_buffers(w1, "vla")
+    g = s.decode_graph(*bufs)
+    run_steps(w1, s, stacks, "vla", g, bufs, "gg")
+    # another batch of two sequences with other lengths and spans: same graph
+    w2 = workloads.custom("g2", 3, 2, 64, "bf16", [0, 5], [25, 40], [100, 61], 4, [0, 1, 0], seed_tag=33,
+                          max_seq=128, max_vis=40, max_text=100)
+    stacks2 = new_oracles(w2)
+    prefill_both(w2, s, stacks2, "vla")
+    run_steps(w2, s, stacks2, "vla", g, bufs, "geg")
+    check_caches(w2, s, stacks2, "vla", graph_steps=3)
+    # one sequence only: the graph does not fit
+    w3 = workloads.custom("g3", 3, 2, 64, "bf16", [0], [25], [100], 4, [0, 1, 0], seed_tag=34,
+                          max_seq=128, max_vis=40, max_text=100)
+    s.reset(w3.vis_start, w3.vis_len)
+    for l in range(3):
+        q, k, v = (t.cuda() for t in workloads.prefill_qkv(w3, l))
+        s.prefill(l, q, k, v, w3.cu_seqlens)
+    with pytest.raises(B.QcError) as e:
+        s.graph_launch(g)
+    assert e.value.status == B.QC_EORDER
+    s.close()
+
+
+def test_graph_create_needs_a_finished_prefill():
+    w = workloads.custom("g4", 2, 2, 64, "f32", [0], [8], [16], 2, [0, 1], seed_tag=35)
+    s = P.Session.for_workload(w)
+    bufs = step_buffers(w, "vla")
+    s.reset(w.vis_start, w.vis_len)
+    with pytest.raises(B.QcError) as e:
+        s.decode_graph(*bufs)
+    assert e.value.status == B.QC_EORDER
+    q, k, v = (t.cuda() for t in workloads.prefill_qkv(w, 0))
+    s.prefill(0, q, k, v, w.cu_seqlens)
+    with pytest.raises(B.QcError) as e:
+        s.decode_graph(*bufs)
+    assert e.value.status == B.QC_EORDER
+    s.close()

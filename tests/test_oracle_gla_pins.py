@@ -251,7 +251,7 @@ def test_gla_layout_sizes_and_row_map():
     assert lay.off_k(4) == 2 * 3 * 2 * 20 * row                  # two ordinary layers only
     assert lay.off_v(1) - lay.off_v(0) == 3 * 2 * 20 * row
     assert lay.q_arena_bytes() == 3 * 2 * 20 * row               # every position, not only the span
-    assert lay.kv_arena_bytes() == lay.off_meta() + 256
+    assert lay.kv_arena_bytes() == lay.off_meta() + 512           # 2 x 48 bytes of per-sequence integers + 256 of counters, rounded up
     for pos in (0, 7, 19):
         assert lay.locate_k(2, 1, 1, pos, 3, 5) == (0, lay.k_offset(0, 1, 1, pos))
         assert lay.locate_k(3, 1, 1, pos, 3, 5) == (3, lay.k_offset(3, 1, 1, pos))
