@@ -535,7 +535,7 @@ def bench_pruning(args):
                                "gather_rows": r.cu_late[-1], "gather_row_bytes": r.row_bytes,
                                "gather_roofline": {"bound": "hbm", "kernel": "gather_rows_kernel", "achieved": moved / gat_s / 1e9,
                                                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": moved / gat_s / 1e9 / HBM_PEAK_GBS,
-                                                   "traffic": None, "avg_launch_us": gat_s * 1e6,
+                                                   "traffic": measured_traffic("pruning_gather"), "avg_launch_us": gat_s * 1e6,
                                                    "algorithmic_bytes_per_launch": moved}}
         del r
         torch.cuda.empty_cache()
