@@ -157,3 +157,118 @@ def test_gla_cfg3_batched_decode_sampled():
     tokens = sum(w.seq_len) + 3 * 32
     assert st["tokens"] == tokens
     assert st["k_bytes"] == (w.n_layers - w.n_lazy) * tokens * per_row and st["q_bytes"] == tokens * per_row
+
+
+def test_cfg2_headline_decode_graph_sampled():
+    """The headline configuration as bench.py times it: 32 layers, batch 1, 640-token prompt, decode steps
+    replayed from the HIP graph (one replay per step), sampled heads against the oracle at every step."""
+    w = workloads.config(1)
+    pairs = [(0, 0), (0, 13), (0, 31)]
+    sess = P.Session.for_workload(w)
+    sess.reset(w.vis_start, w.vis_len, zero_fill=False)
+    oracles = {p: LazyStackOracle(w.n_layers, 1, w.head_dim, w.lazy_mask, w.vis_start[0], w.vis_len[0]) for p in pairs}
+    for l in range(w.n_layers):
+        q, k, v = workloads.prefill_qkv(w, l, device="cuda")
+        sess.prefill(l, q, k, v, w.cu_seqlens)
+        for p in pairs:
+            oracles[p].prefill(l, head_slice(q, w, 0, p[1]), head_slice(k, w, 0, p[1]), head_slice(v, w, 0, p[1]), rows=[0])
+    shape = (1, w.n_heads, w.head_dim)
+    mk = lambda: [torch.zeros(shape, dtype=torch.bfloat16, device="cuda") for _ in range(w.n_layers)]
+    qb, kb, vb, ob = mk(), mk(), mk(), mk()
+    g = sess.decode_graph(qb, kb, vb, ob)
+    worst = 0.0
+    steps = 24
+    for t in range(steps):
+        ins = [workloads.decode_qkv(w, l, t, device="cuda") for l in range(w.n_layers)]
+        for l in range(w.n_layers):
+            qb[l].copy_(ins[l][0]); kb[l].copy_(ins[l][1]); vb[l].copy_(ins[l][2])
+        sess.graph_launch(g)
+        torch.cuda.synchronize()
+        for l in range(w.n_layers):
+            q, k, v = ins[l]
+            for (b, h) in pairs:
+                ref = oracles[(b, h)].decode(l, workloads.to_f64(q[b, h:h + 1]), workloads.to_f64(k[b, h:h + 1]),
+                                             workloads.to_f64(v[b, h:h + 1]))
+                err = float(np.max(np.abs(workloads.to_f64(ob[l][b, h]) - ref[0])))
+                assert np.isfinite(err) and err <= TOL["bf16"], (t, l, h, err)
+                worst = max(worst, err)
+    print("cfg2 graph replays sampled max abs err %.3g" % worst, flush=True)
+    st = sess.stats()
+    assert st["generated"] == steps and st["tokens"] == 640 + steps
+    sess.close()
+
+
+def test_cfg3_pruned_decode_sampled():
+    """The pruning configuration bench.py times: cfg3 (batch 32), boundary before layer 2, half of every
+    image kept by the last prompt token's attention in layer 1; 32-layer prefill and 2 decode steps."""
+    from oracle.pruning import PrunedStackOracle, kept_visual_positions, packed_row_map
+    w = workloads.config(2)
+    first_late, rank_layer = 2, 1
+    keep = [v // 2 for v in w.vis_len]
+    pairs = [(0, 5), (13, 0), (31, 31)]
+    rng = np.random.default_rng(4)
+    sess = P.Session.for_workload(w)
+    sess.reset(w.vis_start, w.vis_len, zero_fill=False)
+    oracles = {p: PrunedStackOracle(w.n_layers, 1, w.head_dim, w.lazy_mask, w.vis_start[p[0]], w.vis_len[p[0]],
+                                    first_late, keep[p[0]]) for p in pairs}
+    cu = w.cu_seqlens
+    late_len = [L - v + k for L, v, k in zip(w.seq_len, w.vis_len, keep)]
+    cu_late = [0]
+    for n in late_len:
+        cu_late.append(cu_late[-1] + n)
+    worst = 0.0
+    row_map = row_map_host = None
+    for l in range(w.n_layers):
+        q, k, v = workloads.prefill_qkv(w, l, device="cuda")
+        late = l >= first_late
+        if late:
+            eb = w.n_heads * w.head_dim * 2
+            parts = []
+            for t in (q, k, v):
+                d = torch.empty((cu_late[-1],) + tuple(t.shape[1:]), dtype=t.dtype, device="cuda")
+                B.qc_gather_rows(t, eb, row_map, cu_late[-1], eb, d, eb)
+                parts.append(d)
+            q, k, v = parts
+        cu_l = cu_late if late else cu
+        out = sess.prefill(l, q, k, v, cu_l)
+        for (b, h) in pairs:
+            Lb = cu_l[b + 1] - cu_l[b]
+            rows = sorted(set([0, Lb - 1, Lb // 2] + [int(x) for x in rng.integers(0, Lb, size=4)]))
+            sl = lambda t: workloads.to_f64(t[cu_l[b]:cu_l[b + 1], h:h + 1, :])
+            ref = oracles[(b, h)].prefill(l, sl(q), sl(k), sl(v), rows=rows)
+            got = workloads.to_f64(out[cu_l[b]:cu_l[b + 1], h, :][rows])
+            err = float(np.max(np.abs(got - ref[:, 0, :])))
+            assert np.isfinite(err)
+            worst = max(worst, err)
+        if l == rank_layer:
+            q_last = torch.stack([q[cu[b + 1] - 1] for b in range(w.batch)]).contiguous()
+            ws = torch.empty(B.qc_select_workspace_bytes(sess.cfg), dtype=torch.uint8, device="cuda")
+            stride = w.max_seq
+            probs = torch.zeros((w.batch, stride), dtype=torch.float32, device="cuda")
+            B.qc_last_row_attention(sess.kv, l, q_last, probs, stride, 0.0, ws, ws.numel())
+            row_map = torch.empty(cu_late[-1], dtype=torch.int32, device="cuda")
+            B.qc_prune_select(probs, stride, w.batch, cu, w.vis_start, w.vis_len, keep, row_map)
+            torch.cuda.synchronize()
+            p_host = probs.cpu().numpy()
+            kept = [kept_visual_positions(p_host[b], w.vis_start[b], w.vis_len[b], keep[b]) for b in range(w.batch)]
+            row_map_host = packed_row_map(w.seq_len, w.vis_start, w.vis_len, kept)
+            assert np.array_equal(row_map.cpu().numpy(), row_map_host)
+        if l == first_late - 1:
+            sess.prune(first_late, keep)
+        del q, k, v, out
+    for t in range(2):
+        for l in range(w.n_layers):
+            q, k, v = workloads.decode_qkv(w, l, t, device="cuda")
+            out = sess.decode(l, q, k, v)
+            for (b, h) in pairs:
+                ref = oracles[(b, h)].decode(l, workloads.to_f64(q[b, h:h + 1]), workloads.to_f64(k[b, h:h + 1]),
+                                             workloads.to_f64(v[b, h:h + 1]))
+                err = float(np.max(np.abs(workloads.to_f64(out[b, h]) - ref[0])))
+                assert np.isfinite(err)
+                worst = max(worst, err)
+    print("cfg3 pruned sampled max abs err %.3g" % worst, flush=True)
+    assert worst <= TOL["bf16"]
+    per_row = 32 * 128 * 2
+    st = sess.stats()
+    want_v = sum((2 * (L + 2) + 30 * (Ll + 2)) for L, Ll in zip(w.seq_len, late_len)) * per_row
+    assert st["v_bytes"] == want_v
