@@ -592,6 +592,7 @@ def bench_capacity(args):
         s.close()
         del s, q, k, v, o
         torch.cuda.empty_cache()
+    out["ragged_batch"] = bench_ragged_arena(args)
     p = out["variants"]["plain"]
     for name in ("vla", "gla"):
         out["variants"][name]["batch_vs_plain"] = out["variants"][name]["max_batch"] / p["max_batch"]
@@ -600,6 +601,51 @@ def bench_capacity(args):
                    "raises throughput here only where the bytes per token drop (score sharing under GLA); the "
                    "weight-streaming part of a decode step, which a larger batch amortises, lies outside this path")
     return out
+
+
+def bench_ragged_arena(args):
+    """The batched-decode configuration (32 prompts of 704..1088 tokens, 512 generated) in an arena with one
+    capacity for all (sized by the longest sequence) and in one with per-sequence capacities (sized by the
+    sum): bytes allocated and decode throughput of the same batch."""
+    import torch
+    import workloads
+    import paper_2602_01901_amd as P
+    base = workloads.config(2)
+    steps = args.decode_batched_steps
+    cap_seq = [(L + base.decode_steps + 7) // 8 * 8 for L in base.seq_len]
+    cap_text = [L - v + base.decode_steps for L, v in zip(base.seq_len, base.vis_len)]
+    n = base.batch
+    per = lambda total: -(-total // n)
+    ragged = workloads.custom("cfg3_ragged_arena", base.n_layers, base.n_heads, base.head_dim, "bf16", base.vis_start,
+                              base.vis_len, base.seq_len, base.decode_steps, base.lazy_mask, seed_tag=0,
+                              max_seq=per(sum(cap_seq)), max_vis=base.max_vis, max_text=per(sum(cap_text)))
+    res = {}
+    for name, w, caps in (("one_capacity_for_all", base, None), ("per_sequence_capacities", ragged, (cap_seq, cap_text))):
+        s = P.Session.for_workload(w)
+        q, k, v = workloads.prefill_qkv(w, 0, device=s.device)
+        o = torch.empty_like(v)
+        if caps:
+            s.reset(w.vis_start, w.vis_len, zero_fill=False, cap_seq=caps[0], cap_text=caps[1])
+        else:
+            s.reset(w.vis_start, w.vis_len, zero_fill=False)
+        for l in range(w.n_layers):
+            s.prefill(l, q, k, v, w.cu_seqlens, out=o)
+        dq, dk, dv = workloads.decode_qkv(w, 0, 0, device=s.device)
+        do = torch.empty_like(dv)
+
+        def run(nsteps):
+            for _ in range(nsteps):
+                for l in range(w.n_layers):
+                    s.decode(l, dq, dk, dv, out=do)
+        run(2)
+        _, ev_s = timed(torch, lambda: run(steps), 1)
+        res[name] = {"kv_arena_bytes": s.kv_bytes, "q_arena_bytes": s.q_bytes, "max_seq": w.max_seq, "max_text": w.max_text,
+                     "decode_tokens_per_s": w.batch * steps / ev_s}
+        s.close()
+        del s, q, k, v, o
+        torch.cuda.empty_cache()
+    res["arena_bytes_ratio"] = res["per_sequence_capacities"]["kv_arena_bytes"] / res["one_capacity_for_all"]["kv_arena_bytes"]
+    return res
 
 
 def bench_video(args):

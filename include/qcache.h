@@ -114,7 +114,9 @@ typedef struct qc_stats_t {
  *   meta    : at the next multiple of 256: int32 [2][4][max_batch]; block 0 = {first packed token
  *             index, prompt length, vis_start, vis_len} per sequence; block 1 = the same rows as the
  *             layers after a qc_prune boundary see them (zero without one); then 256 bytes of
- *             counters (int32 [0]: decode steps completed, kept for replayed decode graphs).
+ *             counters (int32 [0]: decode steps completed, kept for replayed decode graphs); then
+ *             int32 [6][max_batch] = {cap_seq, first row, cap_text, first row, vis_len, first row}
+ *             per sequence after qc_reset_ragged (zero otherwise); padded to a multiple of 256.
  * Q arena: [max_batch][n_heads][max_vis][head_dim] (one layer's worth, visual rows only).
  * Under QC_GLA: capK(l) = 0 for a lazy layer, and the Q arena is
  *   [max_batch][n_heads][max_seq][head_dim] with row = token position.
@@ -139,6 +141,22 @@ void qc_qcache_destroy(qc_qcache* qc);
  * written stay zero and whole-arena comparisons are meaningful; with 0 the call is host-only. */
 qc_status qc_reset(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* vis_start,
                    const int32_t* vis_len, int32_t zero_fill, void* stream);
+
+/* The same with capacities per sequence, for batches of unequal lengths: sequence b may reach
+ * cap_seq[b] positions and cap_text[b] text rows, instead of max_seq and max_text for everyone.  The
+ * regions keep their sizes; inside each, the sequences' rows follow one another (sequence b's rows of
+ * head h start at row (sum of the capacities before b)*n_heads + h*cap[b]; the Q arena is split by
+ * vis_len[b] in the same way), so nothing is reserved for lengths a sequence cannot reach.
+ * Equal capacities reproduce the layout described under "sizes".
+ *   cap_seq, cap_text: HOST, `batch` entries; cap_seq[b] a positive multiple of 8, cap_text[b] >= 0
+ *   (QC_EINVAL otherwise).  QC_ECAPACITY unless sum cap_seq <= max_batch*max_seq and, under QC_VLA,
+ *   sum cap_text <= max_batch*max_text and sum vis_len <= max_batch*max_vis; batch <= max_batch.
+ * The capacities are written to the arena's meta region on `stream` (the call is never host-only).
+ * A workspace from qc_decode_workspace_bytes / qc_select_workspace_bytes is large enough for any
+ * split of the pools.  qc_reset returns to equal capacities. */
+qc_status qc_reset_ragged(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* vis_start,
+                          const int32_t* vis_len, const int32_t* cap_seq, const int32_t* cap_text,
+                          int32_t zero_fill, void* stream);
 
 /* ---- prefill: one layer over the packed prompts (paper Eq. 1; Eq. 7 in a lazy layer) -----------
  * q, k, v, out: DEVICE, element (token t, head h, dim d) at t*token_stride + h*head_stride + d
@@ -300,7 +318,8 @@ qc_status qc_lazy_mask_from_similarity(const float* adjacent, int32_t n_layers, 
  *   aligned, not overlapping.  row_map: DEVICE int32, entries must index rows of src (not checked).
  * qc_prune: moves the boundary into the cache state.  Allowed once per prefill pass, after at least
  *   one layer has run and before the last (QC_EORDER otherwise), and only if the next layer is an
- *   ordinary one (QC_EINVAL).  keep: HOST, batch entries, 0 <= keep[b] <= vis_len[b].  Host only.
+ *   ordinary one (QC_EINVAL).  keep: HOST, batch entries, 0 <= keep[b] <= vis_len[b], and every
+ *   sequence must keep at least one token (QC_EINVAL).  Host only.
  *   From then on every call that names a layer at or after the boundary takes vis_len = keep in its
  *   span arrays and, in qc_prefill, cu_seqlens of the shortened prompts (len_b - vis_len[b] + keep[b]
  *   tokens each); calls naming earlier layers keep the original values.  qc_seq_len keeps reporting

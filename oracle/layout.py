@@ -16,13 +16,26 @@ can be compared byte for byte:
              as the layers after a token-pruning boundary see them (all zero
              when no pruning took place).  Then 256 bytes of counters: int32 [0]
              is the number of decode steps a replayed decode graph has counted
-             (zero if none was used).  Total rounded up to 256 bytes.
+             (zero if none was used).  Then int32 [6][max_batch]: cap_seq,
+             base_seq, cap_text, base_text, cap_vis, base_vis of every sequence
+             when capacities are per sequence (all zero otherwise).  Total
+             rounded up to 256 bytes.
   Q arena    [max_batch][H][max_vis][D].
 
 Row maps: V row = position.  K row = position in a normal layer.  In a lazy
 layer positions before the span keep their index, positions after it move
 down by vis_len, and positions inside the span have no row in that layer:
 they resolve to the same position in the block's first layer.
+
+Per-sequence capacities (`ragged`): the regions keep their sizes, but sequence b
+owns cap_seq[b] rows per head in every [.., max_seq, ..] block, cap_text[b] in a
+lazy layer's K block and vis_len[b] in the Q arena, and its rows start where the
+rows of the sequences before it end: with base[b] = sum of the capacities of the
+sequences before b, row r of head h sits at row index base[b]*H + h*cap[b] + r
+of the region.  Equal capacities (cap_seq = max_seq, ...) give back the layout
+above; the sums must fit the pools max_batch*max_seq, max_batch*max_text and
+max_batch*max_vis.  The arena then wastes nothing on a batch of unequal lengths.
+The capacities live in a third block of the meta region (below).
 
 Global Lazy Attention (mode "gla"; Eq. 5/6 and the sentence after Eq. 6: a lazy
 layer stores no K rows, the Q Cache holds the queries of every token): capK(l) = 0
@@ -41,8 +54,19 @@ def _round_up(x, m):
 
 class ArenaLayout:
     def __init__(self, n_layers, n_heads, head_dim, dtype, max_batch, max_seq, max_vis, max_text,
-                 lazy_mask, mode="vla"):
+                 lazy_mask, mode="vla", ragged=None):
+        """ragged: None, or (cap_seq, cap_text, cap_vis) lists with one entry per sequence of the batch."""
         assert mode in ("vla", "gla")
+        self.ragged = None
+        if ragged is not None:
+            cap_seq, cap_text, cap_vis = ([int(x) for x in r] for r in ragged)
+            assert len(cap_seq) == len(cap_text) == len(cap_vis) <= max_batch
+            assert sum(cap_seq) <= max_batch * max_seq
+            if mode == "vla":
+                assert sum(cap_text) <= max_batch * max_text and sum(cap_vis) <= max_batch * max_vis
+            base = lambda caps: [sum(caps[:b]) for b in range(len(caps))]
+            self.ragged = {"seq": (cap_seq, base(cap_seq)), "text": (cap_text, base(cap_text)),
+                           "vis": (cap_vis, base(cap_vis))}
         self.mode = mode
         self.N, self.H, self.D = n_layers, n_heads, head_dim
         self.dtype = dtype
@@ -76,7 +100,18 @@ class ArenaLayout:
         return _round_up(self.off_v(self.N), 256)
 
     def meta_bytes(self):
-        return _round_up(2 * 4 * 4 * self.max_batch + 256, 256)
+        return _round_up(2 * 4 * 4 * self.max_batch + 256 + 6 * 4 * self.max_batch, 256)
+
+    def _row_index(self, kind, uniform_cap, b, h, row):
+        """Row index inside a region of `kind` rows ("seq", "text" or "vis")."""
+        if self.ragged is None:
+            return (b * self.H + h) * uniform_cap + row
+        cap, base = self.ragged[kind]
+        assert 0 <= row < max(cap[b], 1)
+        return base[b] * self.H + h * cap[b] + row
+
+    def _k_kind(self, l):
+        return "text" if (self.lazy[l] and self.mode == "vla") else "seq"
 
     def kv_arena_bytes(self):
         return self.off_meta() + self.meta_bytes()
@@ -85,13 +120,14 @@ class ArenaLayout:
         return self.max_batch * self.H * self.cap_q() * self.D * self.e
 
     def k_offset(self, l, b, h, row):
-        return self.off_k(l) + ((b * self.H + h) * self.cap_k(l) + row) * self.D * self.e
+        return self.off_k(l) + self._row_index(self._k_kind(l), self.cap_k(l), b, h, row) * self.D * self.e
 
     def v_offset(self, l, b, h, row):
-        return self.off_v(l) + ((b * self.H + h) * self.max_seq + row) * self.D * self.e
+        return self.off_v(l) + self._row_index("seq", self.max_seq, b, h, row) * self.D * self.e
 
     def q_offset(self, b, h, row):
-        return ((b * self.H + h) * self.cap_q() + row) * self.D * self.e
+        kind = "vis" if self.mode == "vla" else "seq"
+        return self._row_index(kind, self.cap_q(), b, h, row) * self.D * self.e
 
     def anchor(self, l):
         a = l - 1
@@ -165,6 +201,14 @@ def kv_arena_image(layout, stacks, tok0=None, graph_steps=0):
     img[o:o + meta.nbytes] = meta.view(np.uint8).reshape(-1)
     # the device-side step counter (graph_steps: its value if a decode graph has been replayed)
     img[o + meta.nbytes:o + meta.nbytes + 4] = np.array([graph_steps], dtype=np.int32).view(np.uint8)
+    if layout.ragged is not None:
+        caps = np.zeros((6, layout.max_batch), dtype=np.int32)
+        for i, kind in enumerate(("seq", "text", "vis")):
+            cap, base = layout.ragged[kind]
+            caps[2 * i, :len(cap)] = cap
+            caps[2 * i + 1, :len(base)] = base
+        o2 = o + meta.nbytes + 256
+        img[o2:o2 + caps.nbytes] = caps.view(np.uint8).reshape(-1)
     return img
 
 

@@ -46,6 +46,8 @@ _PROTOTYPES = {
     "qc_kvcache_destroy": (None, [c_void_p]),
     "qc_qcache_destroy": (None, [c_void_p]),
     "qc_reset": (c_int32, [c_void_p, c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32), c_int32, c_void_p]),
+    "qc_reset_ragged": (c_int32, [c_void_p, c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32),
+                                  POINTER(c_int32), c_int32, c_void_p]),
     "qc_prefill": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                              POINTER(c_int32), c_int64, c_int64, POINTER(c_int32), POINTER(c_int32), c_float,
                              c_void_p]),
@@ -175,6 +177,11 @@ def qc_qcache_destroy(qc):
 
 def qc_reset(kv, qc, batch, vis_start, vis_len, zero_fill=1, stream=None):
     return _check(load_library().qc_reset(kv, qc, batch, _i32(vis_start), _i32(vis_len), int(zero_fill), stream))
+
+
+def qc_reset_ragged(kv, qc, batch, vis_start, vis_len, cap_seq, cap_text, zero_fill=1, stream=None):
+    return _check(load_library().qc_reset_ragged(kv, qc, batch, _i32(vis_start), _i32(vis_len), _i32(cap_seq),
+                                                _i32(cap_text), int(zero_fill), stream))
 
 
 def qc_prefill(kv, qc, layer, is_lazy, q, k, v, out, cu_seqlens, token_stride, head_stride, vis_start, vis_len,

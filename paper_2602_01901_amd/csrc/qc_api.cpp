@@ -52,7 +52,12 @@ struct Config {
   // after the per-sequence integers: 256 bytes of device-side counters (int32 [0] = decode steps
   // completed, as maintained for replayed decode graphs)
   int64_t off_counters() const { return off_meta() + (int64_t)qc::META_BLOCKS * qc::META_ROWS * 4 * max_batch; }
-  int64_t meta_bytes() const { return round_up((int64_t)qc::META_BLOCKS * qc::META_ROWS * 4 * max_batch + 256, 256); }
+  // then the capacity rows (per-sequence capacities; zero otherwise)
+  int64_t off_caps() const { return off_counters() + 4 * qc::META_COUNTER_WORDS; }
+  int64_t meta_bytes() const {
+    return round_up((int64_t)qc::META_BLOCKS * qc::META_ROWS * 4 * max_batch + 4 * qc::META_COUNTER_WORDS +
+                        (int64_t)qc::CAPS_ROWS * 4 * max_batch, 256);
+  }
   int64_t kv_bytes() const { return off_meta() + meta_bytes(); }
   int64_t q_bytes() const { return (int64_t)max_batch * H * cap_q() * D * e(); }
   int64_t row_bytes() const { return (int64_t)D * e(); }
@@ -112,6 +117,16 @@ struct qc_kvcache {
   bool late(int layer) const { return first_late >= 0 && layer >= first_late; }
   int32_t vis_len_of(int layer, int b) const { return late(layer) ? vis_len1[b] : vis_len[b]; }
   int32_t len_of(int layer, int b) const { return late(layer) ? len0[b] - vis_len[b] + vis_len1[b] : len0[b]; }
+  // Per-sequence capacities (qc_reset_ragged): rows sequence b may use, and where they start.
+  bool ragged = false;
+  std::vector<int32_t> cap_seq, cap_text, base_seq, base_text, base_vis;
+  int64_t cap_seq_of(int b) const { return ragged ? cap_seq[b] : cfg.max_seq; }
+  int64_t cap_text_of(int b) const { return ragged ? cap_text[b] : cfg.max_text; }
+  int64_t longest_cap() const {
+    int64_t m = ragged ? 0 : cfg.max_seq;
+    if (ragged) for (int b = 0; b < batch; ++b) m = std::max<int64_t>(m, cap_seq[b]);
+    return m;
+  }
   // Value the device-side step counter holds once everything enqueued so far has run (-1: not set).
   int64_t dev_generated = -1;
   bool timing = false;
@@ -130,6 +145,8 @@ struct qc_decode_graph {
   qc_qcache* qc = nullptr;
   hipGraphExec_t exec = nullptr;
   int32_t batch = 0, first_late = -1;
+  bool ragged = false;                   // recorded with per-sequence capacities
+  int64_t covered = 0;                   // positions the recorded launch grids cover
   int32_t final_owner = -1;              // Q Cache owner after a step (Global Lazy Attention)
   const void* score_workspace = nullptr;
 };
@@ -165,7 +182,11 @@ size_t qc_q_arena_bytes(const qc_config* cfg) {
 // max_seq rounded up to 8 floats and the region starts 256-byte aligned.
 static int64_t partial_bytes(const Config& c) {
   int64_t chunks = (c.max_seq + kMinChunkKeys - 1) / kMinChunkKeys;
-  int64_t b = (int64_t)c.max_batch * c.H * chunks * (c.D + 2) * 4;
+  // a call never uses more than 1024 + batch*H partial slots, whatever the lengths (the key axis is
+  // split only until about 1024 workgroups exist): that bound also covers per-sequence capacities
+  // beyond max_seq
+  int64_t slots = std::max<int64_t>((int64_t)c.max_batch * c.H * chunks, 1024 + (int64_t)c.max_batch * c.H);
+  int64_t b = slots * (c.D + 2) * 4;
   return c.gla() ? round_up(b, 256) : b;
 }
 static int64_t score_stride(const Config& c) { return round_up(c.max_seq, 8); }
@@ -213,18 +234,36 @@ qc_status qc_qcache_create(const qc_config* cfg, void* dev_arena, size_t arena_b
 void qc_kvcache_destroy(qc_kvcache* kv) { delete kv; }
 void qc_qcache_destroy(qc_qcache* qc) { delete qc; }
 
-qc_status qc_reset(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* vis_start,
-                   const int32_t* vis_len, int32_t zero_fill, void* stream) {
+static qc_status reset_impl(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* vis_start,
+                            const int32_t* vis_len, const int32_t* cap_seq, const int32_t* cap_text,
+                            int32_t zero_fill, void* stream) {
   if (!kv || !qc) return fail(QC_EINVAL, "qc_reset: null handle");
   if (!kv->cfg.same(qc->cfg)) return fail(QC_EINVAL, "qc_reset: K/V cache and Q Cache were created with different configurations");
   if (!vis_start || !vis_len) return fail(QC_EINVAL, "qc_reset: null span arrays");
   const Config& c = kv->cfg;
   if (batch < 1) return fail(QC_EINVAL, "qc_reset: batch %d", batch);
   if (batch > c.max_batch) return fail(QC_ECAPACITY, "qc_reset: batch %d exceeds max_batch %d", batch, c.max_batch);
+  const bool ragged = cap_seq != nullptr;
+  if (ragged && !cap_text) return fail(QC_EINVAL, "qc_reset_ragged: null capacity array");
+  int64_t sum_seq = 0, sum_text = 0, sum_vis = 0;
   for (int b = 0; b < batch; ++b) {
     if (vis_start[b] < 0 || vis_len[b] < 0) return fail(QC_EINVAL, "qc_reset: negative span for sequence %d", b);
-    if (!c.gla() && vis_len[b] > c.max_vis) return fail(QC_ECAPACITY, "qc_reset: sequence %d has %d visual tokens, max_vis %d", b, vis_len[b], c.max_vis);
-    if ((int64_t)vis_start[b] + vis_len[b] > c.max_seq) return fail(QC_ECAPACITY, "qc_reset: span of sequence %d exceeds max_seq", b);
+    if (!ragged) {
+      if (!c.gla() && vis_len[b] > c.max_vis) return fail(QC_ECAPACITY, "qc_reset: sequence %d has %d visual tokens, max_vis %d", b, vis_len[b], c.max_vis);
+      if ((int64_t)vis_start[b] + vis_len[b] > c.max_seq) return fail(QC_ECAPACITY, "qc_reset: span of sequence %d exceeds max_seq", b);
+      continue;
+    }
+    if (cap_seq[b] < 8 || cap_seq[b] % 8 || cap_text[b] < 0)
+      return fail(QC_EINVAL, "qc_reset_ragged: cap_seq[%d] must be a positive multiple of 8, cap_text[%d] not negative", b, b);
+    if ((int64_t)vis_start[b] + vis_len[b] > cap_seq[b]) return fail(QC_ECAPACITY, "qc_reset_ragged: span of sequence %d exceeds its %d positions", b, cap_seq[b]);
+    sum_seq += cap_seq[b];
+    sum_text += cap_text[b];
+    sum_vis += vis_len[b];
+  }
+  if (ragged) {
+    if (sum_seq > (int64_t)c.max_batch * c.max_seq) return fail(QC_ECAPACITY, "qc_reset_ragged: %lld positions asked for, the arena holds max_batch*max_seq = %lld", (long long)sum_seq, (long long)c.max_batch * c.max_seq);
+    if (!c.gla() && sum_text > (int64_t)c.max_batch * c.max_text) return fail(QC_ECAPACITY, "qc_reset_ragged: %lld text rows asked for, the arena holds max_batch*max_text = %lld", (long long)sum_text, (long long)c.max_batch * c.max_text);
+    if (!c.gla() && sum_vis > (int64_t)c.max_batch * c.max_vis) return fail(QC_ECAPACITY, "qc_reset_ragged: %lld visual tokens, the Q arena holds max_batch*max_vis = %lld", (long long)sum_vis, (long long)c.max_batch * c.max_vis);
   }
   if (zero_fill) {
     hipError_t e = qc::launch_fill_zero(kv->arena, (size_t)c.kv_bytes(), (hipStream_t)stream);
@@ -244,7 +283,49 @@ qc_status qc_reset(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* 
   kv->late_known = false;
   kv->dev_generated = -1;
   qc->owner = -1;
+  kv->ragged = ragged;
+  if (ragged) {
+    kv->cap_seq.assign(cap_seq, cap_seq + batch);
+    kv->cap_text.assign(cap_text, cap_text + batch);
+    kv->base_seq.assign(batch, 0);
+    kv->base_text.assign(batch, 0);
+    kv->base_vis.assign(batch, 0);
+    for (int b = 1; b < batch; ++b) {
+      kv->base_seq[b] = kv->base_seq[b - 1] + cap_seq[b - 1];
+      kv->base_text[b] = kv->base_text[b - 1] + cap_text[b - 1];
+      kv->base_vis[b] = kv->base_vis[b - 1] + vis_len[b - 1];
+    }
+    // the capacity rows the kernels read (after the optional clear above, on the same stream)
+    for (int first = 0; first < batch; first += qc::MetaChunk::N) {
+      qc::MetaChunk mc;
+      memset(&mc, 0, sizeof(mc));
+      const int count = batch - first < qc::MetaChunk::N ? batch - first : qc::MetaChunk::N;
+      for (int i = 0; i < count; ++i) {
+        const int b = first + i;
+        mc.v[qc::CAP_SEQ][i] = cap_seq[b];
+        mc.v[qc::BASE_SEQ][i] = kv->base_seq[b];
+        mc.v[qc::CAP_TEXT][i] = cap_text[b];
+        mc.v[qc::BASE_TEXT][i] = kv->base_text[b];
+        mc.v[qc::CAP_VIS][i] = vis_len[b];
+        mc.v[qc::BASE_VIS][i] = kv->base_vis[b];
+      }
+      hipError_t e = qc::launch_meta_upload((int32_t*)(kv->arena + c.off_caps()), c.max_batch, first, count, qc::CAPS_ROWS, mc, (hipStream_t)stream);
+      if (e != hipSuccess) return fail(QC_EDEVICE, "qc_reset_ragged: %s", hipGetErrorString(e));
+    }
+  }
   return QC_OK;
+}
+
+qc_status qc_reset(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* vis_start,
+                   const int32_t* vis_len, int32_t zero_fill, void* stream) {
+  return reset_impl(kv, qc, batch, vis_start, vis_len, nullptr, nullptr, zero_fill, stream);
+}
+
+qc_status qc_reset_ragged(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* vis_start,
+                          const int32_t* vis_len, const int32_t* cap_seq, const int32_t* cap_text,
+                          int32_t zero_fill, void* stream) {
+  if (!cap_seq || !cap_text) return fail(QC_EINVAL, "qc_reset_ragged: null capacity array");
+  return reset_impl(kv, qc, batch, vis_start, vis_len, cap_seq, cap_text, zero_fill, stream);
 }
 
 static qc::LayerView make_view(const qc_kvcache* kv, const qc_qcache* qc, int layer) {
@@ -261,6 +342,8 @@ static qc::LayerView make_view(const qc_kvcache* kv, const qc_qcache* qc, int la
   lv.cap_q = (int32_t)c.cap_q();
   lv.meta = (const int32_t*)(kv->arena + c.off_meta()) + (kv->late(layer) ? qc::META_ROWS * c.max_batch : 0);
   lv.max_batch = c.max_batch;
+  lv.flags = (kv->ragged ? qc::LV_RAGGED : 0) | ((c.lazy[layer] && !c.gla()) ? qc::LV_K_TEXT : 0) |
+             (c.gla() ? 0 : qc::LV_Q_VIS) | (kv->late(layer) ? qc::LV_LATE : 0);
   return lv;
 }
 
@@ -307,8 +390,8 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
     if (layer > 0 && len != kv->len_of(layer, b))
       return fail(QC_EINVAL, "qc_prefill: sequence %d has %lld tokens, layer %d expects %d", b, (long long)len, layer, kv->len_of(layer, b));
     if (kv->vis_start[b] + vn > len) return fail(QC_EINVAL, "qc_prefill: span of sequence %d exceeds its %lld tokens", b, (long long)len);
-    if (len > c.max_seq) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld tokens, max_seq %d", b, (long long)len, c.max_seq);
-    if (!c.gla() && len - vn > c.max_text) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld text tokens, max_text %d", b, (long long)(len - vn), c.max_text);
+    if (len > kv->cap_seq_of(b)) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld tokens, its capacity is %lld", b, (long long)len, (long long)kv->cap_seq_of(b));
+    if (!c.gla() && len - vn > kv->cap_text_of(b)) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld text tokens, its capacity is %lld", b, (long long)(len - vn), (long long)kv->cap_text_of(b));
     if (!opens && cu_seqlens[b] != (kv->late(layer) ? kv->tok1[b] : kv->tok0[b]))
       return fail(QC_EINVAL, "qc_prefill: cu_seqlens changed between layers");
     if (len > max_len) max_len = (int32_t)len;
@@ -332,7 +415,7 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
         mc.v[qc::META_VIS_START][i] = kv->vis_start[b];
         mc.v[qc::META_VIS_LEN][i] = kv->vis_len_of(layer, b);
       }
-      hipError_t e2 = qc::launch_meta_upload(const_cast<int32_t*>(lv.meta), c.max_batch, first, count, mc, st);
+      hipError_t e2 = qc::launch_meta_upload(const_cast<int32_t*>(lv.meta), c.max_batch, first, count, qc::META_ROWS, mc, st);
       if (e2 != hipSuccess) return fail(QC_EDEVICE, "qc_prefill: metadata upload: %s", hipGetErrorString(e2));
     }
   }
@@ -402,8 +485,8 @@ static qc_status decode_impl(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32
   for (int b = 0; b < kv->batch; ++b) {
     int64_t len = (int64_t)kv->len_of(layer, b) + kv->generated;
     const int32_t vn = kv->vis_len_of(layer, b);
-    if (len + 1 > c.max_seq) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld positions, max_seq %d", b, (long long)(len + 1), c.max_seq);
-    if (!c.gla() && len + 1 - vn > c.max_text) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld text rows, max_text %d", b, (long long)(len + 1 - vn), c.max_text);
+    if (len + 1 > kv->cap_seq_of(b)) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld positions, its capacity is %lld", b, (long long)(len + 1), (long long)kv->cap_seq_of(b));
+    if (!c.gla() && len + 1 - vn > kv->cap_text_of(b)) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld text rows, its capacity is %lld", b, (long long)(len + 1 - vn), (long long)kv->cap_text_of(b));
     if (len > max_len) max_len = (int32_t)len;
   }
   if (qk_unused && qc->owner != c.anchor[layer])
@@ -487,9 +570,9 @@ static qc_status step_fits(const char* who, const qc_kvcache* kv) {
     if (layer < 0) break;
     for (int b = 0; b < kv->batch; ++b) {
       const int64_t len = (int64_t)kv->len_of(layer, b) + kv->generated;
-      if (len + 1 > c.max_seq) return fail(QC_ECAPACITY, "%s: sequence %d would reach %lld positions, max_seq %d", who, b, (long long)(len + 1), c.max_seq);
-      if (!c.gla() && len + 1 - kv->vis_len_of(layer, b) > c.max_text)
-        return fail(QC_ECAPACITY, "%s: sequence %d would reach %lld text rows, max_text %d", who, b, (long long)(len + 1 - kv->vis_len_of(layer, b)), c.max_text);
+      if (len + 1 > kv->cap_seq_of(b)) return fail(QC_ECAPACITY, "%s: sequence %d would reach %lld positions, its capacity is %lld", who, b, (long long)(len + 1), (long long)kv->cap_seq_of(b));
+      if (!c.gla() && len + 1 - kv->vis_len_of(layer, b) > kv->cap_text_of(b))
+        return fail(QC_ECAPACITY, "%s: sequence %d would reach %lld text rows, its capacity is %lld", who, b, (long long)(len + 1 - kv->vis_len_of(layer, b)), (long long)kv->cap_text_of(b));
     }
   }
   return QC_OK;
@@ -509,10 +592,11 @@ qc_status qc_decode_graph_create(qc_kvcache* kv, qc_qcache* qc, const void* cons
   constexpr int64_t kTargetGroups = 1024;
   const int64_t pairs = (int64_t)kv->batch * c.H;
   const int64_t want = std::max<int64_t>(1, (kTargetGroups + pairs - 1) / pairs);
-  const int64_t per = (c.max_seq + want - 1) / want;
+  const int64_t longest = kv->longest_cap();
+  const int64_t per = (longest + want - 1) / want;
   GraphGeom geom;
   geom.chunk = (int32_t)round_up(per < kMinChunkKeys ? kMinChunkKeys : per, kMinChunkKeys);
-  geom.max_chunks = (c.max_seq + geom.chunk - 1) / geom.chunk;
+  geom.max_chunks = (int32_t)((longest + geom.chunk - 1) / geom.chunk);
   geom.generated_dev = (const int32_t*)(kv->arena + c.off_counters());
 
   hipStream_t cap = nullptr;
@@ -558,6 +642,7 @@ qc_status qc_decode_graph_create(qc_kvcache* kv, qc_qcache* qc, const void* cons
   }
   g->kv = kv; g->qc = qc; g->exec = exec;
   g->batch = kv->batch; g->first_late = kv->first_late;
+  g->ragged = kv->ragged; g->covered = (int64_t)geom.chunk * geom.max_chunks;
   g->final_owner = final_owner; g->score_workspace = final_score_ws;
   *out_graph = g;
   return QC_OK;
@@ -570,6 +655,8 @@ qc_status qc_decode_graph_launch(qc_decode_graph* g, void* stream) {
   if (kv->phase != PH_READY) return fail(QC_EORDER, "qc_decode_graph_launch: needs a finished prefill pass and no decode step in flight");
   if (kv->batch != g->batch || kv->first_late != g->first_late)
     return fail(QC_EORDER, "qc_decode_graph_launch: the graph was recorded for %d sequences (pruning boundary %d), the cache now holds %d (%d)", g->batch, g->first_late, kv->batch, kv->first_late);
+  if (kv->ragged != g->ragged || kv->longest_cap() > g->covered)
+    return fail(QC_EORDER, "qc_decode_graph_launch: the graph was recorded for another kind of capacities, or for at most %lld positions", (long long)g->covered);
   if (qc_status s = step_fits("qc_decode_graph_launch", kv)) return s;
   if (kv->dev_generated != kv->generated) {  // first replay, or ordinary qc_decode steps ran in between
     hipError_t e = qc::launch_counter_update((int32_t*)(kv->arena + c.off_counters()), kv->generated, 0, (hipStream_t)stream);
@@ -842,8 +929,10 @@ qc_status qc_prune(qc_kvcache* kv, qc_qcache* qc, const int32_t* keep) {
   if (kv->phase != PH_PREFILL) return fail(QC_EORDER, "qc_prune: allowed only inside a prefill pass, between two layers");
   if (kv->first_late >= 0) return fail(QC_EORDER, "qc_prune: this pass already has a pruning boundary (before layer %d)", kv->first_late);
   if (c.lazy[kv->next_layer]) return fail(QC_EINVAL, "qc_prune: layer %d is lazy: a boundary cannot fall inside a lazy block", kv->next_layer);
-  for (int b = 0; b < kv->batch; ++b)
+  for (int b = 0; b < kv->batch; ++b) {
     if (keep[b] < 0 || keep[b] > kv->vis_len[b]) return fail(QC_EINVAL, "qc_prune: keep[%d] = %d outside 0..%d", b, keep[b], kv->vis_len[b]);
+    if (kv->len0[b] - kv->vis_len[b] + keep[b] < 1) return fail(QC_EINVAL, "qc_prune: sequence %d would be left without a token", b);
+  }
   kv->vis_len1.assign(keep, keep + kv->batch);
   kv->tok1.assign(kv->batch, 0);
   kv->late_known = false;
@@ -919,12 +1008,16 @@ qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t 
   if (!kv || !src_layer || !byte_offset) return fail(QC_EINVAL, "qc_locate: null argument");
   const Config& c = kv->cfg;
   if (which != QC_K && which != QC_V) return fail(QC_EINVAL, "qc_locate: which must be QC_K or QC_V");
-  if (layer < 0 || layer >= c.N || b < 0 || b >= kv->batch || h < 0 || h >= c.H || pos < 0 || pos >= c.max_seq)
+  if (layer < 0 || layer >= c.N || b < 0 || b >= kv->batch || h < 0 || h >= c.H || pos < 0)
     return fail(QC_EINVAL, "qc_locate: index out of range");
+  if (!kv->ragged && pos >= c.max_seq) return fail(QC_EINVAL, "qc_locate: index out of range");
   const int64_t rb = c.row_bytes();
+  // row index of (b, h, row 0) in a region of full-length rows / of a lazy layer's text rows
+  const int64_t seq0 = kv->ragged ? (int64_t)kv->base_seq[b] * c.H + (int64_t)h * kv->cap_seq[b] : ((int64_t)b * c.H + h) * c.max_seq;
+  if (pos >= kv->cap_seq_of(b)) return fail(QC_ECAPACITY, "qc_locate: position %d is beyond the sequence's capacity", pos);
   if (which == QC_V) {
     *src_layer = layer;
-    *byte_offset = c.off_v(layer) + (((int64_t)b * c.H + h) * c.max_seq + pos) * rb;
+    *byte_offset = c.off_v(layer) + (seq0 + pos) * rb;
     return QC_OK;
   }
   const int32_t s = kv->vis_start[b], vn = kv->vis_len_of(layer, b);
@@ -934,9 +1027,12 @@ qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t 
     if (c.gla() || (pos >= s && pos < s + vn)) src = c.anchor[layer];
     else if (pos >= s + vn) row = pos - vn;
   }
-  if (row >= c.cap_k(src)) return fail(QC_ECAPACITY, "qc_locate: position %d has no row within the layer's capacity", pos);
+  const bool text_rows = c.lazy[src] && !c.gla();
+  const int64_t cap = text_rows ? kv->cap_text_of(b) : (c.cap_k(src) ? kv->cap_seq_of(b) : 0);
+  if (row >= cap) return fail(QC_ECAPACITY, "qc_locate: position %d has no row within the layer's capacity", pos);
+  const int64_t row0 = !text_rows ? seq0 : (kv->ragged ? (int64_t)kv->base_text[b] * c.H + (int64_t)h * kv->cap_text[b] : ((int64_t)b * c.H + h) * c.max_text);
   *src_layer = src;
-  *byte_offset = c.off_k(src) + (((int64_t)b * c.H + h) * c.cap_k(src) + row) * rb;
+  *byte_offset = c.off_k(src) + (row0 + row) * rb;
   return QC_OK;
 }
 

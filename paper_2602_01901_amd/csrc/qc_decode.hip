@@ -79,13 +79,15 @@ __device__ __forceinline__ void decode_split_body(const DecodeArgs& a, const Dec
   const int li = lane % LPR, gid = wave * GPW + lane / LPR;
   const int64_t bh = (int64_t)b * a.n_heads + h;
 
-  char* kown = a.lv.k_own + bh * a.lv.cap_k * ROWB + li * 16;
-  const char* kanc = lazy ? a.lv.k_anchor + bh * a.lv.cap_k_anchor * ROWB + li * 16 : nullptr;
-  char* vown = a.lv.v_own + bh * a.lv.cap_v * ROWB + li * 16;
+  const RowBase rb = row_bases(a.lv, b, h, a.n_heads);
+  char* kown = a.lv.k_own + rb.k * ROWB + li * 16;
+  const char* kanc = lazy ? a.lv.k_anchor + rb.anchor * ROWB + li * 16 : nullptr;
+  char* vown = a.lv.v_own + rb.v * ROWB + li * 16;
   const char* knew = (const char*)a.k + bh * ROWB + li * 16;
   const char* vnew = (const char*)a.v + bh * ROWB + li * 16;
 
-  float* score_row = (SHARED || STORE) ? g.scores + bh * g.score_stride : nullptr;
+  // one score per position: rows of score_stride floats, or (per-sequence capacities) laid out like the V rows
+  float* score_row = (SHARED || STORE) ? g.scores + ((a.lv.flags & LV_RAGGED) ? rb.v : bh * g.score_stride) : nullptr;
 
   float qf[EPL];
   uint4 qraw = make_uint4(0, 0, 0, 0);
@@ -124,7 +126,7 @@ __device__ __forceinline__ void decode_split_body(const DecodeArgs& a, const Dec
             kr[u] = *(const uint4*)knew;
             const int krow = lazy ? len - sm.vis_len : len;
             *(uint4*)(kown + (int64_t)krow * ROWB) = kr[u];
-            if (STORE) *(uint4*)(a.lv.q_cache + (bh * a.lv.cap_q + len) * ROWB + li * 16) = qraw;
+            if (STORE) *(uint4*)(a.lv.q_cache + (rb.q + len) * ROWB + li * 16) = qraw;
           }
         } else {
           if (!SHARED) {

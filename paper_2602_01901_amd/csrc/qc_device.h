@@ -103,4 +103,33 @@ __device__ __forceinline__ SeqMeta load_meta(const LayerView& lv, int b, int inh
   return m;
 }
 
+// Index of row 0 of (sequence b, head h) in each cache region a layer call touches, in rows.
+struct RowBase {
+  int64_t k, v, anchor, q;   // k_own, v_own, k_anchor, q_cache
+};
+__device__ __forceinline__ RowBase row_bases(const LayerView& lv, int b, int h, int n_heads) {
+  RowBase r;
+  if (!(lv.flags & LV_RAGGED)) {
+    const int64_t bh = (int64_t)b * n_heads + h;
+    r.k = bh * lv.cap_k;
+    r.v = bh * lv.cap_v;
+    r.anchor = bh * lv.cap_k_anchor;
+    r.q = bh * lv.cap_q;
+    return r;
+  }
+  // per-sequence capacities: sequence b's rows start where those of the sequences before it end
+  const int32_t* caps = lv.meta + (META_BLOCKS - ((lv.flags & LV_LATE) ? 1 : 0)) * META_ROWS * lv.max_batch + META_COUNTER_WORDS;
+  const int64_t seq = (int64_t)uniform_load(caps + BASE_SEQ * lv.max_batch + b) * n_heads +
+                      (int64_t)h * uniform_load(caps + CAP_SEQ * lv.max_batch + b);
+  r.v = seq;
+  r.anchor = seq;
+  r.k = (lv.flags & LV_K_TEXT) ? (int64_t)uniform_load(caps + BASE_TEXT * lv.max_batch + b) * n_heads +
+                                     (int64_t)h * uniform_load(caps + CAP_TEXT * lv.max_batch + b)
+                               : seq;
+  r.q = (lv.flags & LV_Q_VIS) ? (int64_t)uniform_load(caps + BASE_VIS * lv.max_batch + b) * n_heads +
+                                    (int64_t)h * uniform_load(caps + CAP_VIS * lv.max_batch + b)
+                              : seq;
+  return r;
+}
+
 }  // namespace qc

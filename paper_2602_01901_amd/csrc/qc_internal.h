@@ -13,8 +13,19 @@ namespace qc {
 // prompts as the layers after a token-pruning boundary see them.
 enum { META_TOK0 = 0, META_LEN0 = 1, META_VIS_START = 2, META_VIS_LEN = 3, META_ROWS = 4, META_BLOCKS = 2 };
 
+// Capacity rows of the meta region (per-sequence capacities): meta layout is META_BLOCKS blocks of
+// META_ROWS rows, META_COUNTER_WORDS counter words, then CAPS_ROWS rows of max_batch integers.
+enum { CAP_SEQ = 0, BASE_SEQ = 1, CAP_TEXT = 2, BASE_TEXT = 3, CAP_VIS = 4, BASE_VIS = 5, CAPS_ROWS = 6 };
+enum { META_COUNTER_WORDS = 64 };
+// LayerView::flags
+enum { LV_RAGGED = 1,    // capacities are per sequence: row bases come from the capacity rows
+       LV_K_TEXT = 2,    // k_own holds text rows only (lazy layer, Visual Lazy Attention)
+       LV_Q_VIS = 4,     // q_cache holds visual rows only (Visual Lazy Attention)
+       LV_LATE = 8 };    // meta points at block 1 (layer behind a pruning boundary)
+
 // Device addresses of everything one layer call touches.  Cache regions are
-// [batch][head][cap][D] with the element type of the configuration.
+// [batch][head][cap][D] with the element type of the configuration (with per-sequence capacities:
+// sequence after sequence, each [head][cap_b][D]).
 struct LayerView {
   char* k_own;            // this layer's K rows
   char* v_own;            // this layer's V rows
@@ -26,6 +37,7 @@ struct LayerView {
   int32_t cap_k_anchor;
   int32_t cap_q;
   int32_t max_batch;
+  int32_t flags;
 };
 
 struct PrefillArgs {
@@ -126,9 +138,9 @@ struct PruneChunk {       // by-value payload of the survivor selection kernel: 
   int32_t out0[N];        // first entry of the sequence in the row map
 };
 
-struct MetaChunk {        // by-value payload of the metadata upload kernel
-  enum { N = 64 };
-  int32_t v[META_ROWS][N];
+struct MetaChunk {        // by-value payload of the metadata upload kernel: up to ROWS rows of N sequences
+  enum { N = 64, ROWS = 6 };
+  int32_t v[ROWS][N];
 };
 
 // Optional instrumentation: HIP events recorded on the call's stream around the dominant kernel
@@ -177,7 +189,7 @@ struct KernelTimer {
 
 hipError_t launch_fill_zero(void* dev, size_t bytes, hipStream_t stream);
 hipError_t launch_counter_update(int32_t* counter, int32_t value, int32_t add, hipStream_t stream);
-hipError_t launch_meta_upload(int32_t* meta_dev, int32_t max_batch, int32_t first, int32_t count,
+hipError_t launch_meta_upload(int32_t* meta_dev, int32_t max_batch, int32_t first, int32_t count, int32_t rows,
                               const MetaChunk& chunk, hipStream_t stream);
 hipError_t launch_prefill(const PrefillArgs& a, int dtype, hipStream_t stream, KernelTimer* timer);
 hipError_t launch_decode(const DecodeArgs& a, const DecodeGlaArgs& g, int dtype, hipStream_t stream, KernelTimer* timer);

@@ -55,14 +55,14 @@ constexpr float kRescaleThreshold = 8.0f;  // log2 units
 // consecutive LDS addresses), so the swizzle is applied on the global side: lane i of an
 // instruction that fills rows r0..r0+3 fetches logical chunk (i % 16) ^ swz(row).
 
-__device__ __forceinline__ const char* pf_q_row(const PrefillArgs& a, const SeqMeta& sm, int64_t bh, int h, int pos) {
+__device__ __forceinline__ const char* pf_q_row(const PrefillArgs& a, const SeqMeta& sm, const RowBase& rb, int h, int pos) {
   if (a.is_lazy && pos >= sm.vis_start && pos < sm.vis_start + sm.vis_len)
-    return a.lv.q_cache + (bh * a.lv.cap_q + (pos - sm.vis_start)) * pf::ROWB;
+    return a.lv.q_cache + (rb.q + (pos - sm.vis_start)) * pf::ROWB;
   return (const char*)a.q + ((int64_t)(sm.tok0 + pos) * a.token_stride + (int64_t)h * a.head_stride) * 2;
 }
-__device__ __forceinline__ const char* pf_k_row(const PrefillArgs& a, const SeqMeta& sm, int64_t bh, int h, int pos) {
+__device__ __forceinline__ const char* pf_k_row(const PrefillArgs& a, const SeqMeta& sm, const RowBase& rb, int h, int pos) {
   if (a.is_lazy && pos >= sm.vis_start && pos < sm.vis_start + sm.vis_len)
-    return a.lv.k_anchor + (bh * a.lv.cap_k_anchor + pos) * pf::ROWB;
+    return a.lv.k_anchor + (rb.anchor + pos) * pf::ROWB;
   return (const char*)a.k + ((int64_t)(sm.tok0 + pos) * a.token_stride + (int64_t)h * a.head_stride) * 2;
 }
 
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
   const int len = sm.len0;
   const int q0 = qt * BM;
   if (q0 >= len) return;
-  const int64_t bh = bhi;
+  const RowBase rb = row_bases(a.lv, b, h, a.n_heads);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
   const uint32_t ts2 = (uint32_t)(a.token_stride * 2);
   const char* kin_base = uniform_ptr((const char*)a.k + ((int64_t)sm.tok0 * a.token_stride + (int64_t)h * a.head_stride) * 2);
   const char* vin_base = uniform_ptr((const char*)a.v + ((int64_t)sm.tok0 * a.token_stride + (int64_t)h * a.head_stride) * 2);
-  const char* kanc_base = uniform_ptr(a.is_lazy ? a.lv.k_anchor + bh * a.lv.cap_k_anchor * ROWB : nullptr);
+  const char* kanc_base = uniform_ptr(a.is_lazy ? a.lv.k_anchor + rb.anchor * ROWB : nullptr);
   uint32_t off_kin[LPT], off_kanc[LPT], off_v[LPT];
 #pragma unroll
   for (int p = 0; p < LPT; ++p) {
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
       for (int p = 0; p < LPT; ++p) {
         const int r = lrow + 4 * p;
         const int pos = min(k0 + r, len - 1);  // rows past the end repeat the last row; their scores are masked
-        async_copy16(pf_k_row(a, sm, bh, h, pos) + ((lchunk ^ (r & 15)) * 16), kb + p * 4 * ROWB);
+        async_copy16(pf_k_row(a, sm, rb, h, pos) + ((lchunk ^ (r & 15)) * 16), kb + p * 4 * ROWB);
         async_copy16(vin_base + (int64_t)pos * ts2 + ((lchunk ^ ((r & 3) << 2)) * 16), vb + p * 4 * ROWB);
       }
     }
@@ -204,13 +204,13 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
   // ---- Q fragments (B operand of S^T = K Q^T): query qi, dims ks*16 + hf*8 .. +8
   bf16x8 qf[8];
   {
-    const char* qp = pf_q_row(a, sm, bh, h, min(qi, len - 1));
+    const char* qp = pf_q_row(a, sm, rb, h, min(qi, len - 1));
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + (ks * 16 + hf * 8) * 2));
     // Q Cache write (ordinary layer followed by a lazy one): the span rows of Q, straight from the
     // fragments this lane holds (the two lane halves of a row write alternate 16-byte pieces).
     if (a.write_q && qi < len && qi >= sm.vis_start && qi < sm.vis_start + sm.vis_len) {
-      char* qc = a.lv.q_cache + (bh * a.lv.cap_q + (qi - sm.vis_start)) * ROWB;
+      char* qc = a.lv.q_cache + (rb.q + (qi - sm.vis_start)) * ROWB;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) *(uint4*)(qc + (ks * 16 + hf * 8) * 2) = __builtin_bit_cast(uint4, qf[ks]);
     }
@@ -235,8 +235,8 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
     const char* kb = lds + (t % STAGES) * STAGE;
     const char* vb = kb + TILE;
     const int k0 = t * BN;
-    char* kdst = a.lv.k_own + bh * a.lv.cap_k * ROWB;
-    char* vdst = a.lv.v_own + bh * a.lv.cap_v * ROWB;
+    char* kdst = a.lv.k_own + rb.k * ROWB;
+    char* vdst = a.lv.v_own + rb.v * ROWB;
     const int s0 = sm.vis_start, s1 = sm.vis_start + sm.vis_len;
 #pragma unroll
     for (int p = 0; p < BN * 16 / (NW * 64); ++p) {

@@ -23,8 +23,10 @@ __global__ __launch_bounds__(256) void last_row_scores_kernel(SelectArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int li = lane % LPR, gid = wave * GPW + lane / LPR;
   const int64_t bh = (int64_t)b * a.n_heads + h;
-  const char* krows = a.lv.k_own + bh * a.lv.cap_k * ROWB + li * 16;
-  float* srow = a.scores + bh * a.score_stride;
+  const RowBase rb = row_bases(a.lv, b, h, a.n_heads);
+  const char* krows = a.lv.k_own + rb.k * ROWB + li * 16;
+  // score rows: score_stride floats each, or (per-sequence capacities) laid out like the layer's rows
+  float* srow = a.scores + ((a.lv.flags & LV_RAGGED) ? rb.k : bh * a.score_stride);
 
   float qf[EPL];
   {
@@ -72,7 +74,7 @@ __global__ __launch_bounds__(256) void last_row_probs_kernel(SelectArgs a) {
   float acc = 0.f;
   for (int h = 0; h < a.n_heads; ++h) {
     const int64_t bh = (int64_t)b * a.n_heads + h;
-    const float s = a.scores[bh * a.score_stride + pos];
+    const float s = a.scores[((a.lv.flags & LV_RAGGED) ? row_bases(a.lv, b, h, a.n_heads).k : bh * a.score_stride) + pos];
     acc += __builtin_amdgcn_exp2f(s - a.row_stats[bh * 2]) / a.row_stats[bh * 2 + 1];
   }
   a.probs[(int64_t)b * a.probs_stride + pos] = acc / (float)a.n_heads;

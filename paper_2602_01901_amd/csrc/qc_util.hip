@@ -34,16 +34,16 @@ hipError_t launch_counter_update(int32_t* counter, int32_t value, int32_t add, h
   return hipGetLastError();
 }
 
-__global__ void meta_upload_kernel(int32_t* meta, int32_t max_batch, int32_t first, int32_t count, MetaChunk c) {
+__global__ void meta_upload_kernel(int32_t* meta, int32_t max_batch, int32_t first, int32_t count, int32_t rows, MetaChunk c) {
   int i = threadIdx.x;
   if (i < count)
-    for (int r = 0; r < META_ROWS; ++r) meta[r * max_batch + first + i] = c.v[r][i];
+    for (int r = 0; r < rows; ++r) meta[r * max_batch + first + i] = c.v[r][i];
 }
 
-hipError_t launch_meta_upload(int32_t* meta_dev, int32_t max_batch, int32_t first, int32_t count,
+hipError_t launch_meta_upload(int32_t* meta_dev, int32_t max_batch, int32_t first, int32_t count, int32_t rows,
                               const MetaChunk& chunk, hipStream_t stream) {
   hipLaunchKernelGGL(meta_upload_kernel, dim3(1), dim3(MetaChunk::N), 0, stream, meta_dev, max_batch, first,
-                     count, chunk);
+                     count, rows, chunk);
   return hipGetLastError();
 }
 

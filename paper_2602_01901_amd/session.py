@@ -48,14 +48,19 @@ class Session:
     def _stream(self):
         return torch.cuda.current_stream(self.device).cuda_stream
 
-    def reset(self, vis_start, vis_len, zero_fill=True):
+    def reset(self, vis_start, vis_len, zero_fill=True, cap_seq=None, cap_text=None):
+        """cap_seq / cap_text: optional per-sequence capacities (qc_reset_ragged)."""
         self.vis_start, self.vis_len = list(vis_start), list(vis_len)
         self.batch = len(self.vis_start)
         # marshalled once per batch: the span arrays every later call repeats
         self._vs_c, self._vl_c = B._i32(self.vis_start), B._i32(self.vis_len)
         self.first_late, self.keep = None, None
         self._vl_by_layer = [(self.vis_len, self._vl_c)] * self.n_layers   # span lengths each layer's calls repeat
-        B.qc_reset(self.kv, self.qc, self.batch, self.vis_start, self.vis_len, int(zero_fill), self._stream())
+        if cap_seq is not None:
+            B.qc_reset_ragged(self.kv, self.qc, self.batch, self.vis_start, self.vis_len, cap_seq, cap_text,
+                              int(zero_fill), self._stream())
+        else:
+            B.qc_reset(self.kv, self.qc, self.batch, self.vis_start, self.vis_len, int(zero_fill), self._stream())
 
     def prune(self, next_layer, keep):
         """Token pruning boundary before `next_layer` (the layer the prefill pass runs next): from there on

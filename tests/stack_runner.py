@@ -10,9 +10,18 @@ from oracle.lazy_stack import LazyStackOracle
 TOL = {"f32": 1e-4, "bf16": 3e-2}   # max-abs-error bars for outputs (fp32 / bf16 storage)
 
 
-def oracle_layout(w, mode="vla"):
+def oracle_layout(w, mode="vla", caps=None):
+    """caps: None, or (cap_seq, cap_text) per sequence (the Q arena is then split by vis_len)."""
+    ragged = None if caps is None else (caps[0], caps[1], w.vis_len)
     return olayout.ArenaLayout(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.batch, w.max_seq, w.max_vis,
-                               w.max_text, w.lazy_mask, mode=mode)
+                               w.max_text, w.lazy_mask, mode=mode, ragged=ragged)
+
+
+def reset_session(session, w, caps=None, zero_fill=True):
+    if caps is None:
+        session.reset(w.vis_start, w.vis_len, zero_fill=zero_fill)
+    else:
+        session.reset(w.vis_start, w.vis_len, zero_fill=zero_fill, cap_seq=caps[0], cap_text=caps[1])
 
 
 def new_oracles(w, heads=None, mode="vla"):
@@ -42,7 +51,7 @@ def max_abs_err(gpu_tensor, ref64):
     return float(np.max(np.abs(workloads.to_f64(gpu_tensor) - ref64)))
 
 
-def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=True):
+def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=True, caps=None):
     """Prefill every layer then `decode_steps` decode steps on both sides; returns worst errors.
 
     With poison_span the span rows of q and k handed to lazy layers hold NaN on the GPU side
@@ -54,7 +63,7 @@ def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=Tru
     mode = session.mode
     gla = mode == "gla"
     stacks = new_oracles(w, mode=mode)
-    session.reset(w.vis_start, w.vis_len, zero_fill=True)
+    reset_session(session, w, caps)
     worst_p = worst_d = 0.0
     for l in range(w.n_layers):
         q, k, v = workloads.prefill_qkv(w, l)
@@ -85,7 +94,7 @@ def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=Tru
             worst_d = max(worst_d, err)
     torch.cuda.synchronize()
     if check_arena:
-        lay = oracle_layout(w, mode)
+        lay = oracle_layout(w, mode, caps)
         want_kv = olayout.kv_arena_image(lay, stacks)
         got_kv = session.kv_arena.cpu().numpy()
         assert got_kv.shape == want_kv.shape

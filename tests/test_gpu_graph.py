@@ -10,13 +10,14 @@ import paper_2602_01901_amd as P
 from paper_2602_01901_amd import binding as B
 import workloads
 from oracle import layout as olayout
-from stack_runner import TOL, max_abs_err, new_oracles, oracle_decode_layer, oracle_layout, oracle_prefill_layer
+from stack_runner import (TOL, max_abs_err, new_oracles, oracle_decode_layer, oracle_layout, oracle_prefill_layer,
+                          reset_session)
 
 pytestmark = pytest.mark.gpu
 
 
-def prefill_both(w, s, stacks, mode):
-    s.reset(w.vis_start, w.vis_len, zero_fill=True)
+def prefill_both(w, s, stacks, mode, caps=None):
+    reset_session(s, w, caps)
     for l in range(w.n_layers):
         q, k, v = workloads.prefill_qkv(w, l)
         oracle_prefill_layer(w, stacks, l, q, k, v)
@@ -68,8 +69,8 @@ def run_steps(w, s, stacks, mode, graph, bufs, schedule, t0=0):
     return worst
 
 
-def check_caches(w, s, stacks, mode, graph_steps):
-    lay = oracle_layout(w, mode)
+def check_caches(w, s, stacks, mode, graph_steps, caps=None):
+    lay = oracle_layout(w, mode, caps)
     assert np.array_equal(s.kv_arena.cpu().numpy(), olayout.kv_arena_image(lay, stacks, graph_steps=graph_steps)), "K/V arena differs"
     assert np.array_equal(s.q_arena.cpu().numpy()[: lay.q_arena_bytes()], olayout.q_arena_image(lay, stacks)), "Q arena differs"
     res = olayout.resident_bytes(lay, stacks)

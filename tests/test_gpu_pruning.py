@@ -14,7 +14,7 @@ import workloads
 from oracle import layout as olayout
 from oracle import selection
 from oracle.pruning import PrunedStackOracle, kept_visual_positions, packed_row_map
-from stack_runner import TOL, max_abs_err, oracle_layout
+from stack_runner import TOL, max_abs_err, oracle_layout, reset_session
 
 pytestmark = pytest.mark.gpu
 
@@ -91,10 +91,10 @@ def test_gather_rows_is_bit_exact(row_elems, dtype, pad):
     assert np.all(got[:, row_elems:] == 0)              # padding of the destination rows untouched
 
 
-def run_pruned_parity(w, first_late, keep, mode, decode_steps):
+def run_pruned_parity(w, first_late, keep, mode, decode_steps, caps=None):
     """Early layers, ranking from the last early layer's last-row attention, pruning, late layers, decode."""
     s = P.Session.for_workload(w, mode=mode)
-    s.reset(w.vis_start, w.vis_len, zero_fill=True)
+    reset_session(s, w, caps)
     stacks = [PrunedStackOracle(w.n_layers, w.n_heads, w.head_dim, w.lazy_mask, w.vis_start[b], w.vis_len[b],
                                 first_late, keep[b], mode=mode) for b in range(w.batch)]
     cu = w.cu_seqlens
@@ -134,7 +134,7 @@ def run_pruned_parity(w, first_late, keep, mode, decode_steps):
             # ranking: the last prompt token's attention in that layer, read in the middle of the pass
             q_last = torch.stack([q[cu[b + 1] - 1] for b in range(w.batch)]).contiguous().cuda()
             ws = torch.empty(B.qc_select_workspace_bytes(s.cfg), dtype=torch.uint8, device="cuda")
-            stride = w.max_seq + 5
+            stride = max(w.max_seq, max(w.seq_len)) + 5
             probs = torch.zeros((w.batch, stride), dtype=torch.float32, device="cuda")
             B.qc_last_row_attention(s.kv, l, q_last, probs, stride, 0.0, ws, ws.numel())
             torch.cuda.synchronize()
@@ -164,7 +164,7 @@ def run_pruned_parity(w, first_late, keep, mode, decode_steps):
             assert np.isfinite(err)
             worst = max(worst, err)
     torch.cuda.synchronize()
-    lay = oracle_layout(w, mode)
+    lay = oracle_layout(w, mode, caps)
     assert np.array_equal(s.kv_arena.cpu().numpy(), olayout.kv_arena_image(lay, stacks)), "K/V arena differs"
     assert np.array_equal(s.q_arena.cpu().numpy()[: lay.q_arena_bytes()], olayout.q_arena_image(lay, stacks)), "Q arena differs"
     res = olayout.resident_bytes(lay, stacks)

@@ -1,0 +1,103 @@
+"""GPU parity with per-sequence capacities (qc_reset_ragged): a batch of very unequal lengths in an arena
+whose pools would not hold it at one capacity for all; outputs within the usual bars, arenas byte for
+byte as the oracle's layout places the rows."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_01901_amd as P
+from paper_2602_01901_amd import binding as B
+import workloads
+from oracle.layout import ArenaLayout
+from stack_runner import TOL, new_oracles, run_full_parity
+from test_gpu_graph import check_caches, prefill_both, run_steps, step_buffers
+from test_gpu_pruning import run_pruned_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def up8(x):
+    return (x + 7) // 8 * 8
+
+
+def ragged_workload(name, N, H, D, dtype, vs, vl, lens, steps, mask, seed_tag):
+    """Pools sized for the sum of the capacities, not for batch x longest."""
+    cap_seq = [up8(L + steps) for L in lens]
+    cap_text = [L - v + steps for L, v in zip(lens, vl)]
+    n = len(lens)
+    per = lambda total: max(1, -(-total // n))
+    w = workloads.custom(name, N, H, D, dtype, vs, vl, lens, steps, mask, seed_tag=seed_tag,
+                         max_seq=per(sum(cap_seq)), max_vis=max(per(sum(vl)), 1), max_text=per(sum(cap_text)))
+    return w, (cap_seq, cap_text)
+
+
+CASES = [
+    ("r_f32", 4, 3, 64, "f32", [5, 0, 2, 0], [150, 10, 0, 8], [200, 24, 40, 16], [0, 1, 0, 1]),
+    ("r_bf16", 5, 2, 128, "bf16", [3, 1, 0], [100, 20, 30], [260, 33, 30], [0, 1, 1, 0, 1]),
+    ("r_b10", 3, 2, 64, "bf16", [i % 3 for i in range(10)], [5 + 9 * (i % 4) for i in range(10)],
+     [20 + 37 * (i % 5) for i in range(10)], [0, 0, 1]),
+]
+
+
+@pytest.mark.parametrize("mode", ["vla", "gla"])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_ragged_capacities_match_oracle(case, mode):
+    name, N, H, D, dtype, vs, vl, lens, mask = case
+    w, caps = ragged_workload(name, N, H, D, dtype, vs, vl, lens, 3, mask, 41)
+    assert max(caps[0]) > w.max_seq          # the longest sequence would not fit a uniform slot
+    s = P.Session.for_workload(w, mode=mode)
+    wp, wd = run_full_parity(w, 3, s, caps=caps)
+    assert max(wp, wd) <= TOL[dtype]
+    # key locations as the oracle's layout places them
+    lay = ArenaLayout(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.batch, w.max_seq, w.max_vis, w.max_text, w.lazy_mask,
+                      mode=mode, ragged=(caps[0], caps[1], w.vis_len))
+    for l in range(N):
+        for b in range(w.batch):
+            for pos in (0, lens[b] - 1, lens[b] + 2):
+                assert B.qc_locate(s.kv, B.QC_K, l, b, H - 1, pos) == lay.locate_k(l, b, H - 1, pos, vs[b], vl[b])
+                assert B.qc_locate(s.kv, B.QC_V, l, b, H - 1, pos) == lay.locate_v(l, b, H - 1, pos)
+    # the text rows are used up (Visual Lazy Attention sizes them exactly): one more step must be refused
+    if mode == "vla":
+        ins = [t.cuda() for t in workloads.decode_qkv(w, 0, 3)]
+        with pytest.raises(B.QcError) as e:
+            s.decode(0, *ins)
+        assert e.value.status == B.QC_ECAPACITY
+    s.close()
+
+
+@pytest.mark.parametrize("mode", ["vla", "gla"])
+def test_ragged_capacities_with_graph_replays_and_pruning(mode):
+    name, N, H, D, dtype, vs, vl, lens, mask = CASES[1]
+    w, caps = ragged_workload("rg", N, H, D, dtype, vs, vl, lens, 4, mask, 42)
+    s = P.Session.for_workload(w, mode=mode)
+    stacks = new_oracles(w, mode=mode)
+    prefill_both(w, s, stacks, mode, caps=caps)
+    bufs = step_buffers(w, mode)
+    g = s.decode_graph(*bufs)
+    run_steps(w, s, stacks, mode, g, bufs, "gegg")
+    check_caches(w, s, stacks, mode, graph_steps=4, caps=caps)
+    s.close()
+    assert run_pruned_parity(w, 3, [40, 20, 5], mode, 3, caps=caps) <= TOL[dtype]
+
+
+def test_reset_ragged_validation():
+    w, caps = ragged_workload("rv", 2, 2, 64, "f32", [0, 0], [8, 8], [40, 16], 2, [0, 1], 43)
+    s = P.Session.for_workload(w)
+    st = torch.cuda.current_stream().cuda_stream
+    ok = dict(kv=s.kv, qc=s.qc, batch=2, vis_start=[0, 0], vis_len=[8, 8], cap_seq=list(caps[0]), cap_text=list(caps[1]),
+              zero_fill=0, stream=st)
+    cases = [(dict(cap_seq=[41, 16]), B.QC_EINVAL), (dict(cap_seq=[0, 16]), B.QC_EINVAL), (dict(cap_text=[-1, 10]), B.QC_EINVAL),
+             (dict(cap_seq=[4096, 16]), B.QC_ECAPACITY), (dict(cap_text=[4096, 10]), B.QC_ECAPACITY),
+             (dict(vis_len=[48, 8]), B.QC_ECAPACITY), (dict(batch=3, vis_start=[0] * 3, vis_len=[0] * 3, cap_seq=[8] * 3, cap_text=[8] * 3), B.QC_ECAPACITY),
+             (dict(cap_seq=None), B.QC_EINVAL)]
+    for change, status in cases:
+        with pytest.raises(B.QcError) as e:
+            B.qc_reset_ragged(**dict(ok, **change))
+        assert e.value.status == status, change
+    B.qc_reset_ragged(**ok)
+    q, k, v = (t.cuda() for t in workloads.prefill_qkv(w, 0))
+    s.vis_start, s.vis_len, s.batch = [0, 0], [8, 8], 2
+    with pytest.raises(B.QcError) as e:                     # sequence 1 has 16 tokens; give it 40 and it overflows its 24 rows
+        B.qc_prefill(s.kv, s.qc, 0, 0, q, k, v, torch.empty_like(v), [0, 16, 56], v.stride(0), v.stride(1), [0, 0], [8, 8])
+    assert e.value.status == B.QC_ECAPACITY
+    s.close()

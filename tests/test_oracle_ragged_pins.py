@@ -1,0 +1,79 @@
+"""Pins for the per-sequence-capacity arena layout (oracle.layout, `ragged`): worked by hand, against the
+equal-capacity layout, and by brute force over every row."""
+import numpy as np
+import pytest
+
+from oracle.layout import ArenaLayout
+
+
+def test_offsets_worked_by_hand():
+    # 2 heads of 64 bf16 elements: a row is 128 bytes.  Two sequences with 8 and 16 positions.
+    lay = ArenaLayout(2, 2, 64, "bf16", 2, 12, 6, 6, [0, 1], ragged=([8, 16], [4, 8], [3, 5]))
+    row = 128
+    # V region of layer 1: sequence 1 starts after sequence 0's 8 rows x 2 heads; head 1 after head 0's 16 rows
+    assert lay.v_offset(1, 1, 1, 3) - lay.off_v(1) == (8 * 2 + 1 * 16 + 3) * row
+    assert lay.v_offset(0, 0, 1, 0) - lay.off_v(0) == (0 + 1 * 8 + 0) * row
+    # layer 1 is lazy: its K block holds text rows only, 4 and 8 per head
+    assert lay.k_offset(1, 1, 0, 7) - lay.off_k(1) == (4 * 2 + 0 * 8 + 7) * row
+    assert lay.k_offset(0, 1, 0, 7) - lay.off_k(0) == (8 * 2 + 0 * 16 + 7) * row
+    # Q arena: 3 and 5 visual rows per head
+    assert lay.q_offset(1, 1, 4) == (3 * 2 + 1 * 5 + 4) * row
+    # region sizes are those of the pools, whatever the split
+    assert lay.off_k(1) == 2 * 2 * 12 * row and lay.off_k(2) - lay.off_k(1) == 2 * 2 * 6 * row
+
+
+@pytest.mark.parametrize("mode", ["vla", "gla"])
+def test_equal_capacities_give_back_the_uniform_layout(mode):
+    args = (4, 3, 64, "f32", 3, 20, 12, 9, [0, 1, 1, 0])
+    a = ArenaLayout(*args, mode=mode)
+    b = ArenaLayout(*args, mode=mode, ragged=([20] * 3, [9] * 3, [12] * 3))
+    assert a.kv_arena_bytes() == b.kv_arena_bytes() and a.q_arena_bytes() == b.q_arena_bytes()
+    for l in range(4):
+        for s in range(3):
+            for h in range(3):
+                for r in range(a.cap_k(l)):
+                    assert a.k_offset(l, s, h, r) == b.k_offset(l, s, h, r)
+                for r in range(20):
+                    assert a.v_offset(l, s, h, r) == b.v_offset(l, s, h, r)
+    for s in range(3):
+        for h in range(3):
+            for r in range(a.cap_q()):
+                assert a.q_offset(s, h, r) == b.q_offset(s, h, r)
+
+
+@pytest.mark.parametrize("mode", ["vla", "gla"])
+def test_rows_are_disjoint_and_inside_their_regions(mode):
+    caps = ([24, 8, 40, 8], [16, 0, 8, 8], [10, 8, 30, 0])
+    lay = ArenaLayout(3, 2, 64, "bf16", 4, 20, 12, 8, [0, 1, 0], mode=mode, ragged=caps)
+    rowb = 128
+    owner = np.full(lay.off_meta() // rowb, -1, dtype=np.int64)
+    tag = 0
+    for l in range(3):
+        k_caps = caps[0] if lay._k_kind(l) == "seq" else caps[1]
+        for b in range(4):
+            for h in range(2):
+                rows = k_caps[b] if lay.cap_k(l) else 0
+                for which, n in (("k", rows), ("v", caps[0][b])):
+                    for r in range(n):
+                        off = lay.k_offset(l, b, h, r) if which == "k" else lay.v_offset(l, b, h, r)
+                        lo, hi = (lay.off_k(l), lay.off_k(l + 1)) if which == "k" else (lay.off_v(l), lay.off_v(l) + lay.v_layer_bytes())
+                        assert lo <= off and off + rowb <= hi and off % rowb == 0
+                        assert owner[off // rowb] == -1, "two rows share bytes"
+                        owner[off // rowb] = tag
+                        tag += 1
+    q_caps = caps[2] if mode == "vla" else caps[0]
+    seen = set()
+    for b in range(4):
+        for h in range(2):
+            for r in range(q_caps[b]):
+                off = lay.q_offset(b, h, r)
+                assert 0 <= off and off + rowb <= lay.q_arena_bytes() and off not in seen
+                seen.add(off)
+
+
+def test_pools_bound_the_capacities():
+    with pytest.raises(AssertionError):
+        ArenaLayout(2, 1, 64, "bf16", 2, 10, 5, 5, [0, 1], ragged=([16, 8], [4, 4], [2, 2]))     # 24 > 2 x 10 positions
+    with pytest.raises(AssertionError):
+        ArenaLayout(2, 1, 64, "bf16", 2, 10, 5, 5, [0, 1], ragged=([8, 8], [8, 4], [2, 2]))      # 12 > 2 x 5 text rows
+    ArenaLayout(2, 1, 64, "bf16", 2, 10, 5, 5, [0, 1], mode="gla", ragged=([8, 8], [8, 4], [2, 2]))  # text rows size nothing under GLA
