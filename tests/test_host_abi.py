@@ -356,3 +356,23 @@ def test_plan_and_prune_calls_validate_before_launching():
     with pytest.raises(B.QcError) as e:
         B.qc_prune(None, None, [1])
     assert e.value.status == B.QC_EINVAL
+
+
+def test_reset_ragged_validation_happens_before_any_launch():
+    c = CONFIGS[1]                      # max_batch 5, max_seq 77, max_vis 30, max_text 50: pools of 385 / 150 / 250 rows
+    cfg, kv, qc = make_handles(c)
+    ok = dict(kv=kv, qc=qc, batch=2, vis_start=[0, 4], vis_len=[20, 8], cap_seq=[200, 40], cap_text=[180, 32], zero_fill=0)
+    cases = [(dict(cap_seq=[201, 40]), B.QC_EINVAL),          # not a multiple of 8
+             (dict(cap_seq=[0, 40]), B.QC_EINVAL),
+             (dict(cap_text=[-1, 32]), B.QC_EINVAL),
+             (dict(cap_seq=None), B.QC_EINVAL),
+             (dict(cap_text=None), B.QC_EINVAL),
+             (dict(cap_seq=[352, 40]), B.QC_ECAPACITY),       # 392 > 385 positions
+             (dict(cap_text=[230, 32]), B.QC_ECAPACITY),      # 262 > 250 text rows
+             (dict(vis_len=[140, 12], vis_start=[0, 0]), B.QC_ECAPACITY),   # 152 > 150 visual tokens
+             (dict(vis_start=[190, 4]), B.QC_ECAPACITY),      # span beyond the sequence's own capacity
+             (dict(batch=6, vis_start=[0] * 6, vis_len=[0] * 6, cap_seq=[8] * 6, cap_text=[8] * 6), B.QC_ECAPACITY)]
+    for change, status in cases:
+        with pytest.raises(P.QcError) as e:
+            B.qc_reset_ragged(**dict(ok, **change))
+        assert e.value.status == status, change
