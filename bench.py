@@ -654,7 +654,7 @@ def bench_video(args):
     import workloads
     w = workloads.config(4)
     steps = 8
-    r = Runner(w, steps, distinct_decode_inputs=2)
+    r = Runner(w, steps, distinct_decode_inputs=2)     # 68 us kernels: graph replay gains nothing here (measured)
     r.prefill_stack()
     torch.cuda.synchronize()
     _, pre_s = timed(torch, r.prefill_stack, 1)
@@ -728,7 +728,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true",
                     help="headline workload: ordinary qc_decode calls instead of one HIP-graph replay per decode step")
     ap.add_argument("--only", choices=["decode_batched", "prefill_highres", "gla_decode_batched", "selection", "projection", "pruning",
-                                      "capacity"],
+                                      "capacity", "video"],
                     help="profiling aid: run just this extra workload and print its object")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profiling aid: run plain 1 GiB device copies (known HBM traffic) and exit")
@@ -755,7 +755,7 @@ def main():
     if args.only:
         fn = {"decode_batched": bench_decode_batched, "prefill_highres": bench_prefill_highres,
               "gla_decode_batched": bench_gla_decode_batched, "selection": bench_selection,
-              "projection": bench_projection, "pruning": bench_pruning, "capacity": bench_capacity}[args.only]
+              "projection": bench_projection, "pruning": bench_pruning, "capacity": bench_capacity, "video": bench_video}[args.only]
         print(json.dumps({args.only: fn(args)}))
         return
 
