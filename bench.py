@@ -559,20 +559,35 @@ def bench_capacity(args):
     assert sum(lazy22) == 22 and not lazy22[0]
     plain_cfg = lambda b: P.make_config(N, H, D, "bf16", b, 2048, vis, 2048 - vis, [0] * N)
     budget = B.qc_kv_arena_bytes(plain_cfg(21)) + 4096
-    out = {"positions_per_sequence": 2048, "visual_tokens": vis, "lazy_layers": 22, "budget_bytes": budget, "variants": {}}
-    for name, mask, mode in (("plain", [0] * N, "vla"), ("vla", lazy22, "vla"), ("gla", lazy22, "gla")):
-        cfg1 = P.make_config(N, H, D, "bf16", 1, 2048, vis, 2048 - vis, mask, mode=mode)
+    out = {"positions_per_sequence": 2048, "visual_tokens": vis, "lazy_layers": 22, "budget_bytes": budget,
+           "pruned_variants": "boundary before layer 2, half of the visual tokens kept, later layers sized for the shortened sequences",
+           "variants": {}}
+    keep = vis // 2                       # token pruning: half of the visual tokens survive a boundary before layer 2
+    late = dict(prune_before_layer=2, max_seq_late=2048 - (vis - keep))
+    for name, mask, mode, prune in (("plain", [0] * N, "vla", False), ("vla", lazy22, "vla", False),
+                                    ("gla", lazy22, "gla", False), ("vla_pruned", lazy22, "vla", True),
+                                    ("gla_pruned", lazy22, "gla", True)):
+        extra = late if prune else {}
+        cfg1 = P.make_config(N, H, D, "bf16", 1, 2048, vis, 2048 - vis, mask, mode=mode, **extra)
         batch = B.qc_plan_max_batch(cfg1, budget, B.QC_PLAN_KV)
         batch_all = B.qc_plan_max_batch(cfg1, budget, B.QC_PLAN_KV | B.QC_PLAN_Q | B.QC_PLAN_WORKSPACE)
         w = workloads.custom("capacity_" + name, N, H, D, "bf16", [vs] * batch, [vis] * batch, [L0] * batch, steps + 2,
                              mask, max_seq=2048, max_vis=vis, max_text=2048 - vis)
-        s = P.Session.for_workload(w, mode=mode)
+        s = P.Session.for_workload(w, mode=mode, **extra)
         q, k, v = workloads.prefill_qkv(w, 0, device=s.device)      # one set of inputs serves every layer
         o = torch.empty_like(v)
         s.reset(w.vis_start, w.vis_len, zero_fill=False)
+        L1 = L0 - (vis - keep)
+        cu_late = [b * L1 for b in range(batch + 1)]
         for l in range(N):
             no_qk = mode == "gla" and mask[l]
-            s.prefill(l, None if no_qk else q, None if no_qk else k, v, w.cu_seqlens, out=o)
+            if prune and l == 2:
+                s.prune(2, [keep] * batch)
+            if prune and l >= 2:                # the shortened prompts: any rows of the right count will do here
+                n = cu_late[-1]
+                s.prefill(l, None if no_qk else q[:n], None if no_qk else k[:n], v[:n], cu_late, out=o[:n])
+            else:
+                s.prefill(l, None if no_qk else q, None if no_qk else k, v, w.cu_seqlens, out=o)
         dq, dk, dv = workloads.decode_qkv(w, 0, 0, device=s.device)
         do = torch.empty_like(dv)
 
@@ -594,7 +609,7 @@ def bench_capacity(args):
         torch.cuda.empty_cache()
     out["ragged_batch"] = bench_ragged_arena(args)
     p = out["variants"]["plain"]
-    for name in ("vla", "gla"):
+    for name in ("vla", "gla", "vla_pruned", "gla_pruned"):
         out["variants"][name]["batch_vs_plain"] = out["variants"][name]["max_batch"] / p["max_batch"]
         out["variants"][name]["attention_throughput_vs_plain"] = out["variants"][name]["decode_tokens_per_s"] / p["decode_tokens_per_s"]
     out["note"] = ("attention only: streaming a sequence's caches costs the same at any batch, so the larger batch "

@@ -68,6 +68,12 @@ enum { QC_K = 0, QC_V = 1 };
  * max_text : most text rows (prompt text + generated) any sequence may reach; this is the row
  *            capacity of a lazy layer's K cache, which is what makes its allocation smaller.
  * head_dim : 64 or 128.  dtype: element type of Q/K/V/O and of all caches.
+ * prune_before_layer, max_seq_late: both 0, or a token-pruning boundary known when the caches are
+ *            created: the layers from prune_before_layer on (an ordinary layer, 1..n_layers-1) then get
+ *            regions of max_seq_late instead of max_seq rows per head, so that dropping tokens also
+ *            shrinks the allocation, not only the rows in use.  qc_prune must then be called at exactly
+ *            that boundary (QC_EINVAL elsewhere); without it the later layers still run, within their
+ *            smaller capacity.  Not combinable with qc_reset_ragged.
  * mode     : QC_VLA or QC_GLA.  Under QC_GLA max_vis and max_text size nothing (a lazy layer has
  *            no K rows, the Q Cache has max_seq rows) but must still be valid (0..max_seq). */
 typedef struct qc_config {
@@ -81,6 +87,9 @@ typedef struct qc_config {
   int32_t max_text;
   int32_t mode;     /* qc_mode */
   int32_t reserved; /* must be 0 */
+  int32_t prune_before_layer; /* 0, or the layer a qc_prune boundary will precede (see max_seq_late) */
+  int32_t max_seq_late;       /* 0, or the most positions a sequence may reach in the layers from
+                                 prune_before_layer on (1..max_seq) */
   const uint8_t* lazy_mask;
 } qc_config;
 
@@ -110,7 +119,8 @@ typedef struct qc_stats_t {
  * K/V arena layout (all offsets in bytes, e = element size):
  *   K region: layers in order, layer l is [max_batch][n_heads][capK(l)][head_dim],
  *             capK(l) = max_text if lazy else max_seq;
- *   V region: layers in order, each [max_batch][n_heads][max_seq][head_dim];
+ *   V region: layers in order, each [max_batch][n_heads][max_seq][head_dim] (max_seq_late in place of
+ *             max_seq, here and in capK, for the layers from prune_before_layer on, if configured);
  *   meta    : at the next multiple of 256: int32 [2][4][max_batch]; block 0 = {first packed token
  *             index, prompt length, vis_start, vis_len} per sequence; block 1 = the same rows as the
  *             layers after a qc_prune boundary see them (zero without one); then 256 bytes of

@@ -37,6 +37,11 @@ above; the sums must fit the pools max_batch*max_seq, max_batch*max_text and
 max_batch*max_vis.  The arena then wastes nothing on a batch of unequal lengths.
 The capacities live in a third block of the meta region (below).
 
+Separately sized late layers (`late`): when a token-pruning boundary is known
+as the arena is sized, the layers from the boundary on hold max_seq_late
+positions per sequence instead of max_seq; their K blocks (ordinary layers) and V
+blocks shrink accordingly and the regions behind them move up.
+
 Global Lazy Attention (mode "gla"; Eq. 5/6 and the sentence after Eq. 6: a lazy
 layer stores no K rows, the Q Cache holds the queries of every token): capK(l) = 0
 for a lazy layer, every key position of a lazy layer resolves to the same
@@ -54,8 +59,12 @@ def _round_up(x, m):
 
 class ArenaLayout:
     def __init__(self, n_layers, n_heads, head_dim, dtype, max_batch, max_seq, max_vis, max_text,
-                 lazy_mask, mode="vla", ragged=None):
-        """ragged: None, or (cap_seq, cap_text, cap_vis) lists with one entry per sequence of the batch."""
+                 lazy_mask, mode="vla", ragged=None, late=None):
+        """ragged: None, or (cap_seq, cap_text, cap_vis) lists with one entry per sequence of the batch.
+        late: None, or (first late layer, max_seq_late): the layers from there on hold max_seq_late
+        positions per sequence instead of max_seq (a pruning boundary known when the arena is sized)."""
+        self.late = late
+        assert late is None or (ragged is None and 1 <= late[0] < n_layers and 1 <= late[1] <= max_seq)
         assert mode in ("vla", "gla")
         self.ragged = None
         if ragged is not None:
@@ -76,9 +85,12 @@ class ArenaLayout:
         self.lazy = [int(bool(x)) for x in lazy_mask]
         assert len(self.lazy) == n_layers and not (n_layers and self.lazy[0])
 
+    def cap_v(self, l):
+        return self.late[1] if (self.late is not None and l >= self.late[0]) else self.max_seq
+
     def cap_k(self, l):
         if not self.lazy[l]:
-            return self.max_seq
+            return self.cap_v(l)
         return self.max_text if self.mode == "vla" else 0
 
     def cap_q(self):
@@ -87,14 +99,14 @@ class ArenaLayout:
     def k_layer_bytes(self, l):
         return self.max_batch * self.H * self.cap_k(l) * self.D * self.e
 
-    def v_layer_bytes(self):
-        return self.max_batch * self.H * self.max_seq * self.D * self.e
+    def v_layer_bytes(self, l=0):
+        return self.max_batch * self.H * self.cap_v(l) * self.D * self.e
 
     def off_k(self, l):
         return sum(self.k_layer_bytes(i) for i in range(l))
 
     def off_v(self, l):
-        return self.off_k(self.N) + l * self.v_layer_bytes()
+        return self.off_k(self.N) + sum(self.v_layer_bytes(i) for i in range(l))
 
     def off_meta(self):
         return _round_up(self.off_v(self.N), 256)
@@ -123,7 +135,7 @@ class ArenaLayout:
         return self.off_k(l) + self._row_index(self._k_kind(l), self.cap_k(l), b, h, row) * self.D * self.e
 
     def v_offset(self, l, b, h, row):
-        return self.off_v(l) + self._row_index("seq", self.max_seq, b, h, row) * self.D * self.e
+        return self.off_v(l) + self._row_index("seq", self.cap_v(l), b, h, row) * self.D * self.e
 
     def q_offset(self, b, h, row):
         kind = "vis" if self.mode == "vla" else "seq"

@@ -23,7 +23,8 @@ MODE_CODE = {"vla": QC_VLA, "gla": QC_GLA}
 class qc_config(ctypes.Structure):
     _fields_ = [("n_layers", c_int32), ("n_heads", c_int32), ("head_dim", c_int32), ("dtype", c_int32),
                 ("max_batch", c_int32), ("max_seq", c_int32), ("max_vis", c_int32), ("max_text", c_int32),
-                ("mode", c_int32), ("reserved", c_int32), ("lazy_mask", POINTER(c_uint8))]
+                ("mode", c_int32), ("reserved", c_int32), ("prune_before_layer", c_int32), ("max_seq_late", c_int32),
+                ("lazy_mask", POINTER(c_uint8))]
 
 
 class qc_stats_t(ctypes.Structure):
@@ -134,11 +135,12 @@ def qc_last_error():
 
 
 def make_config(n_layers, n_heads, head_dim, dtype, max_batch, max_seq, max_vis, max_text, lazy_mask,
-                mode="vla"):
+                mode="vla", prune_before_layer=0, max_seq_late=0):
     """Returns a qc_config; the mask buffer is kept alive by the returned object."""
     mask = (c_uint8 * max(len(lazy_mask), 1))(*[int(bool(x)) for x in lazy_mask])
     cfg = qc_config(n_layers, n_heads, head_dim, DTYPE_CODE.get(dtype, dtype), max_batch, max_seq, max_vis,
-                    max_text, MODE_CODE.get(mode, mode), 0, ctypes.cast(mask, POINTER(c_uint8)))
+                    max_text, MODE_CODE.get(mode, mode), 0, prune_before_layer, max_seq_late,
+                    ctypes.cast(mask, POINTER(c_uint8)))
     cfg._mask_keepalive = mask
     return cfg
 

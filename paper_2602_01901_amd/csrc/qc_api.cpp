@@ -31,23 +31,31 @@ struct Config {
   int32_t N = 0, H = 0, D = 0, dtype = 0;
   int32_t max_batch = 0, max_seq = 0, max_vis = 0, max_text = 0;
   int32_t mode = QC_VLA;
+  // Smaller regions for the layers behind a pruning boundary fixed at creation: layers >= late_from
+  // hold at most max_seq_late positions per sequence (late_from = 0: no such boundary).
+  int32_t late_from = 0, max_seq_late = 0;
   std::vector<uint8_t> lazy;
   std::vector<int32_t> anchor;  // anchor[l] = first layer of l's block (l itself if not lazy)
 
   int e() const { return dtype == QC_BF16 ? 2 : 4; }
   bool gla() const { return mode == QC_GLA; }
-  int64_t cap_k(int l) const { return lazy[l] ? (gla() ? 0 : max_text) : max_seq; }
+  int64_t cap_v(int l) const { return (late_from > 0 && l >= late_from) ? max_seq_late : max_seq; }
+  int64_t cap_k(int l) const { return lazy[l] ? (gla() ? 0 : max_text) : cap_v(l); }
   int64_t cap_q() const { return gla() ? max_seq : max_vis; }
   // An ordinary layer stores queries in the Q Cache exactly when the next layer is lazy.
   bool writes_q(int l) const { return !lazy[l] && l + 1 < N && lazy[l + 1]; }
   int64_t k_layer_bytes(int l) const { return (int64_t)max_batch * H * cap_k(l) * D * e(); }
-  int64_t v_layer_bytes() const { return (int64_t)max_batch * H * max_seq * D * e(); }
+  int64_t v_layer_bytes(int l) const { return (int64_t)max_batch * H * cap_v(l) * D * e(); }
   int64_t off_k(int l) const {
     int64_t o = 0;
     for (int i = 0; i < l; ++i) o += k_layer_bytes(i);
     return o;
   }
-  int64_t off_v(int l) const { return off_k(N) + (int64_t)l * v_layer_bytes(); }
+  int64_t off_v(int l) const {
+    int64_t o = off_k(N);
+    for (int i = 0; i < l; ++i) o += v_layer_bytes(i);
+    return o;
+  }
   int64_t off_meta() const { return round_up(off_v(N), 256); }
   // after the per-sequence integers: 256 bytes of device-side counters (int32 [0] = decode steps
   // completed, as maintained for replayed decode graphs)
@@ -64,6 +72,7 @@ struct Config {
   bool same(const Config& o) const {
     return N == o.N && H == o.H && D == o.D && dtype == o.dtype && max_batch == o.max_batch &&
            max_seq == o.max_seq && max_vis == o.max_vis && max_text == o.max_text && mode == o.mode &&
+           late_from == o.late_from && max_seq_late == o.max_seq_late &&
            lazy == o.lazy;
   }
 };
@@ -79,6 +88,11 @@ bool parse_config(const qc_config* c, Config* out) {
   if (c->head_dim != 64 && c->head_dim != 128) return false;
   if (c->dtype != QC_F32 && c->dtype != QC_BF16) return false;
   if ((c->mode != QC_VLA && c->mode != QC_GLA) || c->reserved != 0) return false;
+  if (c->prune_before_layer != 0 &&
+      (c->prune_before_layer < 1 || c->prune_before_layer >= c->n_layers || c->lazy_mask[c->prune_before_layer] ||
+       c->max_seq_late < 1 || c->max_seq_late > c->max_seq))
+    return false;
+  if (c->prune_before_layer == 0 && c->max_seq_late != 0) return false;
   if (c->max_vis > c->max_seq || c->max_text > c->max_seq) return false;
   if (c->lazy_mask[0]) return false;
   out->N = c->n_layers;
@@ -90,6 +104,8 @@ bool parse_config(const qc_config* c, Config* out) {
   out->max_vis = c->max_vis;
   out->max_text = c->max_text;
   out->mode = c->mode;
+  out->late_from = c->prune_before_layer;
+  out->max_seq_late = c->max_seq_late;
   out->lazy.assign(c->lazy_mask, c->lazy_mask + c->n_layers);
   for (auto& f : out->lazy) f = f ? 1 : 0;
   out->anchor.resize(out->N);
@@ -121,6 +137,8 @@ struct qc_kvcache {
   bool ragged = false;
   std::vector<int32_t> cap_seq, cap_text, base_seq, base_text, base_vis;
   int64_t cap_seq_of(int b) const { return ragged ? cap_seq[b] : cfg.max_seq; }
+  // positions sequence b may reach in `layer` (smaller behind a configured pruning boundary)
+  int64_t cap_of(int layer, int b) const { return ragged ? cap_seq[b] : cfg.cap_v(layer); }
   int64_t cap_text_of(int b) const { return ragged ? cap_text[b] : cfg.max_text; }
   int64_t longest_cap() const {
     int64_t m = ragged ? 0 : cfg.max_seq;
@@ -245,6 +263,7 @@ static qc_status reset_impl(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const 
   if (batch > c.max_batch) return fail(QC_ECAPACITY, "qc_reset: batch %d exceeds max_batch %d", batch, c.max_batch);
   const bool ragged = cap_seq != nullptr;
   if (ragged && !cap_text) return fail(QC_EINVAL, "qc_reset_ragged: null capacity array");
+  if (ragged && c.late_from > 0) return fail(QC_EINVAL, "qc_reset_ragged: per-sequence capacities cannot be combined with a configuration that sizes the layers behind a pruning boundary separately");
   int64_t sum_seq = 0, sum_text = 0, sum_vis = 0;
   for (int b = 0; b < batch; ++b) {
     if (vis_start[b] < 0 || vis_len[b] < 0) return fail(QC_EINVAL, "qc_reset: negative span for sequence %d", b);
@@ -334,7 +353,7 @@ static qc::LayerView make_view(const qc_kvcache* kv, const qc_qcache* qc, int la
   lv.k_own = kv->arena + c.off_k(layer);
   lv.v_own = kv->arena + c.off_v(layer);
   lv.cap_k = (int32_t)c.cap_k(layer);
-  lv.cap_v = c.max_seq;
+  lv.cap_v = (int32_t)c.cap_v(layer);
   int a = c.anchor[layer];
   lv.k_anchor = c.lazy[layer] ? kv->arena + c.off_k(a) : nullptr;
   lv.cap_k_anchor = (int32_t)c.cap_k(a);
@@ -390,7 +409,7 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
     if (layer > 0 && len != kv->len_of(layer, b))
       return fail(QC_EINVAL, "qc_prefill: sequence %d has %lld tokens, layer %d expects %d", b, (long long)len, layer, kv->len_of(layer, b));
     if (kv->vis_start[b] + vn > len) return fail(QC_EINVAL, "qc_prefill: span of sequence %d exceeds its %lld tokens", b, (long long)len);
-    if (len > kv->cap_seq_of(b)) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld tokens, its capacity is %lld", b, (long long)len, (long long)kv->cap_seq_of(b));
+    if (len > kv->cap_of(layer, b)) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld tokens, its capacity in layer %d is %lld", b, (long long)len, layer, (long long)kv->cap_of(layer, b));
     if (!c.gla() && len - vn > kv->cap_text_of(b)) return fail(QC_ECAPACITY, "qc_prefill: sequence %d has %lld text tokens, its capacity is %lld", b, (long long)(len - vn), (long long)kv->cap_text_of(b));
     if (!opens && cu_seqlens[b] != (kv->late(layer) ? kv->tok1[b] : kv->tok0[b]))
       return fail(QC_EINVAL, "qc_prefill: cu_seqlens changed between layers");
@@ -485,7 +504,7 @@ static qc_status decode_impl(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32
   for (int b = 0; b < kv->batch; ++b) {
     int64_t len = (int64_t)kv->len_of(layer, b) + kv->generated;
     const int32_t vn = kv->vis_len_of(layer, b);
-    if (len + 1 > kv->cap_seq_of(b)) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld positions, its capacity is %lld", b, (long long)(len + 1), (long long)kv->cap_seq_of(b));
+    if (len + 1 > kv->cap_of(layer, b)) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld positions, its capacity in layer %d is %lld", b, (long long)(len + 1), layer, (long long)kv->cap_of(layer, b));
     if (!c.gla() && len + 1 - vn > kv->cap_text_of(b)) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld text rows, its capacity is %lld", b, (long long)(len + 1 - vn), (long long)kv->cap_text_of(b));
     if (len > max_len) max_len = (int32_t)len;
   }
@@ -566,11 +585,11 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
 static qc_status step_fits(const char* who, const qc_kvcache* kv) {
   const Config& c = kv->cfg;
   for (int stage = 0; stage < 2; ++stage) {
-    const int layer = stage ? kv->first_late : 0;
+    const int layer = stage ? (kv->first_late >= 0 ? kv->first_late : (c.late_from > 0 ? c.late_from : -1)) : 0;
     if (layer < 0) break;
     for (int b = 0; b < kv->batch; ++b) {
       const int64_t len = (int64_t)kv->len_of(layer, b) + kv->generated;
-      if (len + 1 > kv->cap_seq_of(b)) return fail(QC_ECAPACITY, "%s: sequence %d would reach %lld positions, its capacity is %lld", who, b, (long long)(len + 1), (long long)kv->cap_seq_of(b));
+      if (len + 1 > kv->cap_of(layer, b)) return fail(QC_ECAPACITY, "%s: sequence %d would reach %lld positions, its capacity in layer %d is %lld", who, b, (long long)(len + 1), layer, (long long)kv->cap_of(layer, b));
       if (!c.gla() && len + 1 - kv->vis_len_of(layer, b) > kv->cap_text_of(b))
         return fail(QC_ECAPACITY, "%s: sequence %d would reach %lld text rows, its capacity is %lld", who, b, (long long)(len + 1 - kv->vis_len_of(layer, b)), (long long)kv->cap_text_of(b));
     }
@@ -929,6 +948,7 @@ qc_status qc_prune(qc_kvcache* kv, qc_qcache* qc, const int32_t* keep) {
   if (kv->phase != PH_PREFILL) return fail(QC_EORDER, "qc_prune: allowed only inside a prefill pass, between two layers");
   if (kv->first_late >= 0) return fail(QC_EORDER, "qc_prune: this pass already has a pruning boundary (before layer %d)", kv->first_late);
   if (c.lazy[kv->next_layer]) return fail(QC_EINVAL, "qc_prune: layer %d is lazy: a boundary cannot fall inside a lazy block", kv->next_layer);
+  if (c.late_from > 0 && kv->next_layer != c.late_from) return fail(QC_EINVAL, "qc_prune: the configuration sizes the layers from %d on for a boundary there, not before layer %d", c.late_from, kv->next_layer);
   for (int b = 0; b < kv->batch; ++b) {
     if (keep[b] < 0 || keep[b] > kv->vis_len[b]) return fail(QC_EINVAL, "qc_prune: keep[%d] = %d outside 0..%d", b, keep[b], kv->vis_len[b]);
     if (kv->len0[b] - kv->vis_len[b] + keep[b] < 1) return fail(QC_EINVAL, "qc_prune: sequence %d would be left without a token", b);
@@ -1013,8 +1033,11 @@ qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t 
   if (!kv->ragged && pos >= c.max_seq) return fail(QC_EINVAL, "qc_locate: index out of range");
   const int64_t rb = c.row_bytes();
   // row index of (b, h, row 0) in a region of full-length rows / of a lazy layer's text rows
-  const int64_t seq0 = kv->ragged ? (int64_t)kv->base_seq[b] * c.H + (int64_t)h * kv->cap_seq[b] : ((int64_t)b * c.H + h) * c.max_seq;
-  if (pos >= kv->cap_seq_of(b)) return fail(QC_ECAPACITY, "qc_locate: position %d is beyond the sequence's capacity", pos);
+  auto seq0_of = [&](int l) {
+    return kv->ragged ? (int64_t)kv->base_seq[b] * c.H + (int64_t)h * kv->cap_seq[b] : ((int64_t)b * c.H + h) * c.cap_v(l);
+  };
+  const int64_t seq0 = seq0_of(layer);
+  if (pos >= kv->cap_of(layer, b)) return fail(QC_ECAPACITY, "qc_locate: position %d is beyond the sequence's capacity", pos);
   if (which == QC_V) {
     *src_layer = layer;
     *byte_offset = c.off_v(layer) + (seq0 + pos) * rb;
@@ -1028,9 +1051,9 @@ qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t 
     else if (pos >= s + vn) row = pos - vn;
   }
   const bool text_rows = c.lazy[src] && !c.gla();
-  const int64_t cap = text_rows ? kv->cap_text_of(b) : (c.cap_k(src) ? kv->cap_seq_of(b) : 0);
+  const int64_t cap = text_rows ? kv->cap_text_of(b) : (c.cap_k(src) ? kv->cap_of(src, b) : 0);
   if (row >= cap) return fail(QC_ECAPACITY, "qc_locate: position %d has no row within the layer's capacity", pos);
-  const int64_t row0 = !text_rows ? seq0 : (kv->ragged ? (int64_t)kv->base_text[b] * c.H + (int64_t)h * kv->cap_text[b] : ((int64_t)b * c.H + h) * c.max_text);
+  const int64_t row0 = !text_rows ? seq0_of(src) : (kv->ragged ? (int64_t)kv->base_text[b] * c.H + (int64_t)h * kv->cap_text[b] : ((int64_t)b * c.H + h) * c.max_text);
   *src_layer = src;
   *byte_offset = c.off_k(src) + (row0 + row) * rb;
   return QC_OK;

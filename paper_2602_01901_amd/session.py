@@ -12,7 +12,7 @@ _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 class Session:
     def __init__(self, n_layers, n_heads, head_dim, dtype, lazy_mask, max_batch, max_seq, max_vis, max_text,
-                 device="cuda:0", mode="vla"):
+                 device="cuda:0", mode="vla", prune_before_layer=0, max_seq_late=0):
         if not torch.cuda.is_available():
             raise RuntimeError("the Lazy Attention library needs a GPU; there is no CPU path")
         B.load_library()
@@ -23,7 +23,8 @@ class Session:
         self.lazy_mask = [int(bool(x)) for x in lazy_mask]
         self.mode = mode
         self.cfg = B.make_config(n_layers, n_heads, head_dim, dtype, max_batch, max_seq, max_vis, max_text,
-                                 self.lazy_mask, mode=mode)
+                                 self.lazy_mask, mode=mode, prune_before_layer=prune_before_layer,
+                                 max_seq_late=max_seq_late)
         self.kv_bytes = B.qc_kv_arena_bytes(self.cfg)
         self.q_bytes = B.qc_q_arena_bytes(self.cfg)
         self.ws_bytes = B.qc_decode_workspace_bytes(self.cfg)
@@ -41,9 +42,10 @@ class Session:
         self._graphs = []
 
     @classmethod
-    def for_workload(cls, w, device="cuda:0", mode="vla"):
+    def for_workload(cls, w, device="cuda:0", mode="vla", prune_before_layer=0, max_seq_late=0):
         return cls(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.lazy_mask, w.batch, w.max_seq, w.max_vis,
-                   w.max_text, device=device, mode=mode)
+                   w.max_text, device=device, mode=mode, prune_before_layer=prune_before_layer,
+                   max_seq_late=max_seq_late)
 
     def _stream(self):
         return torch.cuda.current_stream(self.device).cuda_stream

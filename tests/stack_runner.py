@@ -10,11 +10,12 @@ from oracle.lazy_stack import LazyStackOracle
 TOL = {"f32": 1e-4, "bf16": 3e-2}   # max-abs-error bars for outputs (fp32 / bf16 storage)
 
 
-def oracle_layout(w, mode="vla", caps=None):
-    """caps: None, or (cap_seq, cap_text) per sequence (the Q arena is then split by vis_len)."""
+def oracle_layout(w, mode="vla", caps=None, late=None):
+    """caps: None, or (cap_seq, cap_text) per sequence (the Q arena is then split by vis_len).
+    late: None, or (first late layer, max_seq_late) of a configuration with smaller late layers."""
     ragged = None if caps is None else (caps[0], caps[1], w.vis_len)
     return olayout.ArenaLayout(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.batch, w.max_seq, w.max_vis,
-                               w.max_text, w.lazy_mask, mode=mode, ragged=ragged)
+                               w.max_text, w.lazy_mask, mode=mode, ragged=ragged, late=late)
 
 
 def reset_session(session, w, caps=None, zero_fill=True):

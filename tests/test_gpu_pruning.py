@@ -91,9 +91,10 @@ def test_gather_rows_is_bit_exact(row_elems, dtype, pad):
     assert np.all(got[:, row_elems:] == 0)              # padding of the destination rows untouched
 
 
-def run_pruned_parity(w, first_late, keep, mode, decode_steps, caps=None):
+def run_pruned_parity(w, first_late, keep, mode, decode_steps, caps=None, max_seq_late=0):
     """Early layers, ranking from the last early layer's last-row attention, pruning, late layers, decode."""
-    s = P.Session.for_workload(w, mode=mode)
+    s = (P.Session.for_workload(w, mode=mode, prune_before_layer=first_late, max_seq_late=max_seq_late) if max_seq_late
+         else P.Session.for_workload(w, mode=mode))
     reset_session(s, w, caps)
     stacks = [PrunedStackOracle(w.n_layers, w.n_heads, w.head_dim, w.lazy_mask, w.vis_start[b], w.vis_len[b],
                                 first_late, keep[b], mode=mode) for b in range(w.batch)]
@@ -164,7 +165,7 @@ def run_pruned_parity(w, first_late, keep, mode, decode_steps, caps=None):
             assert np.isfinite(err)
             worst = max(worst, err)
     torch.cuda.synchronize()
-    lay = oracle_layout(w, mode, caps)
+    lay = oracle_layout(w, mode, caps, late=(first_late, max_seq_late) if max_seq_late else None)
     assert np.array_equal(s.kv_arena.cpu().numpy(), olayout.kv_arena_image(lay, stacks)), "K/V arena differs"
     assert np.array_equal(s.q_arena.cpu().numpy()[: lay.q_arena_bytes()], olayout.q_arena_image(lay, stacks)), "Q arena differs"
     res = olayout.resident_bytes(lay, stacks)
@@ -245,3 +246,56 @@ def test_prune_validation():
     s.prefill(2, *qkv[2], w.cu_seqlens)
     s.prefill(3, *qkv[3], w.cu_seqlens)
     assert B.qc_layer_rows(s.kv, 3) == (20, 20)
+
+
+@pytest.mark.parametrize("mode", ["vla", "gla"])
+def test_pruned_stack_with_smaller_late_layers(mode):
+    """The boundary is known when the caches are sized: the layers behind it get regions for the
+    shortened sequences only, and the whole arena still matches the oracle's image byte for byte."""
+    lens, vs, vl, keep = [150, 97, 64], [5, 0, 20], [100, 80, 0], [37, 20, 0]
+    steps = 3
+    w = workloads.custom("pruned_late", 6, 3, 128, "bf16", vs, vl, lens, steps, MASK6, seed_tag=24)
+    late_cap = max(L - v + k for L, v, k in zip(lens, vl, keep)) + steps
+    assert late_cap < w.max_seq
+    plain = P.make_config(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.batch, w.max_seq, w.max_vis, w.max_text, w.lazy_mask,
+                          mode=mode)
+    small = P.make_config(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.batch, w.max_seq, w.max_vis, w.max_text, w.lazy_mask,
+                          mode=mode, prune_before_layer=3, max_seq_late=late_cap)
+    assert B.qc_kv_arena_bytes(small) < B.qc_kv_arena_bytes(plain)
+    assert run_pruned_parity(w, 3, keep, mode, steps, max_seq_late=late_cap) <= TOL["bf16"]
+
+
+def test_smaller_late_layers_validation():
+    w = workloads.custom("late_val", 4, 2, 64, "f32", [2], [10], [20], 2, [0, 0, 1, 0], seed_tag=25)
+    mk = lambda **kw: P.make_config(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.batch, w.max_seq, w.max_vis, w.max_text,
+                                    w.lazy_mask, **kw)
+    assert B.qc_kv_arena_bytes(mk(prune_before_layer=2, max_seq_late=12)) == 0       # layer 2 is lazy
+    assert B.qc_kv_arena_bytes(mk(prune_before_layer=0, max_seq_late=12)) == 0       # capacity without a boundary
+    assert B.qc_kv_arena_bytes(mk(prune_before_layer=3, max_seq_late=0)) == 0
+    assert B.qc_kv_arena_bytes(mk(prune_before_layer=3, max_seq_late=w.max_seq + 1)) == 0
+    s = P.Session.for_workload(w, prune_before_layer=3, max_seq_late=17)
+    s.reset(w.vis_start, w.vis_len)
+    qkv = [tuple(t.cuda() for t in workloads.prefill_qkv(w, l)) for l in range(4)]
+    s.prefill(0, *qkv[0], w.cu_seqlens)
+    with pytest.raises(B.QcError) as e:
+        B.qc_prune(s.kv, s.qc, [5])                       # the configuration expects the boundary before layer 3
+    assert e.value.status == B.QC_EINVAL
+    s.prefill(1, *qkv[1], w.cu_seqlens)
+    s.prefill(2, *qkv[2], w.cu_seqlens)
+    with pytest.raises(B.QcError) as e:
+        s.prefill(3, *qkv[3], w.cu_seqlens)               # unpruned: 20 tokens do not fit the late layers' 17 rows
+    assert e.value.status == B.QC_ECAPACITY
+    s.prune(3, [5])
+    short = tuple(t[:15].contiguous() for t in qkv[3])
+    s.prefill(3, *short, [0, 15])
+    ins = [t.cuda() for t in workloads.decode_qkv(w, 0, 0)]
+    for t in range(2):
+        for l in range(4):
+            s.decode(l, *ins)
+    with pytest.raises(B.QcError) as e:                   # 17 rows in the late layers: a third step does not fit
+        s.decode(0, *ins)
+    assert e.value.status == B.QC_ECAPACITY
+    with pytest.raises(B.QcError) as e:
+        B.qc_reset_ragged(s.kv, s.qc, 1, [2], [10], [24], [12], 0, torch.cuda.current_stream().cuda_stream)
+    assert e.value.status == B.QC_EINVAL
+    s.close()

@@ -376,3 +376,16 @@ def test_reset_ragged_validation_happens_before_any_launch():
         with pytest.raises(P.QcError) as e:
             B.qc_reset_ragged(**dict(ok, **change))
         assert e.value.status == status, change
+
+
+def test_smaller_late_layers_sizes_match_oracle_layout():
+    for mode in ("vla", "gla"):
+        c = (6, 3, 128, "bf16", 4, 300, 200, 120, [0, 1, 1, 0, 1, 0])
+        cfg = P.make_config(*c, mode=mode, prune_before_layer=3, max_seq_late=160)
+        lay = ArenaLayout(*c, mode=mode, late=(3, 160))
+        assert B.qc_kv_arena_bytes(cfg) == lay.kv_arena_bytes()
+        assert B.qc_q_arena_bytes(cfg) == lay.q_arena_bytes()
+        assert B.qc_kv_arena_bytes(cfg) < B.qc_kv_arena_bytes(P.make_config(*c, mode=mode))
+        # the planner sees the smaller arena
+        budget = 10 * lay.off_meta()
+        assert B.qc_plan_max_batch(cfg, budget, B.QC_PLAN_KV) > B.qc_plan_max_batch(P.make_config(*c, mode=mode), budget, B.QC_PLAN_KV)

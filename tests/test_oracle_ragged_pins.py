@@ -56,7 +56,7 @@ def test_rows_are_disjoint_and_inside_their_regions(mode):
                 for which, n in (("k", rows), ("v", caps[0][b])):
                     for r in range(n):
                         off = lay.k_offset(l, b, h, r) if which == "k" else lay.v_offset(l, b, h, r)
-                        lo, hi = (lay.off_k(l), lay.off_k(l + 1)) if which == "k" else (lay.off_v(l), lay.off_v(l) + lay.v_layer_bytes())
+                        lo, hi = (lay.off_k(l), lay.off_k(l + 1)) if which == "k" else (lay.off_v(l), lay.off_v(l) + lay.v_layer_bytes(l))
                         assert lo <= off and off + rowb <= hi and off % rowb == 0
                         assert owner[off // rowb] == -1, "two rows share bytes"
                         owner[off // rowb] = tag
@@ -77,3 +77,21 @@ def test_pools_bound_the_capacities():
     with pytest.raises(AssertionError):
         ArenaLayout(2, 1, 64, "bf16", 2, 10, 5, 5, [0, 1], ragged=([8, 8], [8, 4], [2, 2]))      # 12 > 2 x 5 text rows
     ArenaLayout(2, 1, 64, "bf16", 2, 10, 5, 5, [0, 1], mode="gla", ragged=([8, 8], [8, 4], [2, 2]))  # text rows size nothing under GLA
+
+
+def test_smaller_late_layers_worked_by_hand_and_against_the_uniform_layout():
+    row = 128
+    # 4 layers (layer 2 lazy), boundary before layer 1: layers 1..3 hold 8 positions instead of 20
+    lay = ArenaLayout(4, 2, 64, "bf16", 3, 20, 12, 9, [0, 0, 1, 0], late=(1, 8))
+    assert [lay.cap_k(l) for l in range(4)] == [20, 8, 9, 8]
+    assert [lay.cap_v(l) for l in range(4)] == [20, 8, 8, 8]
+    assert lay.off_k(1) == 3 * 2 * 20 * row and lay.off_k(2) - lay.off_k(1) == 3 * 2 * 8 * row
+    assert lay.off_v(0) == lay.off_k(4) == 3 * 2 * (20 + 8 + 9 + 8) * row
+    assert lay.off_v(2) - lay.off_v(0) == 3 * 2 * (20 + 8) * row
+    assert lay.v_offset(3, 2, 1, 5) - lay.off_v(3) == ((2 * 2 + 1) * 8 + 5) * row
+    assert lay.k_offset(1, 1, 0, 7) - lay.off_k(1) == ((1 * 2 + 0) * 8 + 7) * row
+    # a late capacity equal to max_seq changes nothing
+    a = ArenaLayout(4, 2, 64, "bf16", 3, 20, 12, 9, [0, 0, 1, 0])
+    b = ArenaLayout(4, 2, 64, "bf16", 3, 20, 12, 9, [0, 0, 1, 0], late=(1, 20))
+    assert a.kv_arena_bytes() == b.kv_arena_bytes()
+    assert all(a.v_offset(l, 2, 1, 19) == b.v_offset(l, 2, 1, 19) and a.off_k(l) == b.off_k(l) for l in range(4))
