@@ -91,7 +91,7 @@ def test_gather_rows_is_bit_exact(row_elems, dtype, pad):
     assert np.all(got[:, row_elems:] == 0)              # padding of the destination rows untouched
 
 
-def run_pruned_parity(w, first_late, keep, mode, decode_steps, caps=None, max_seq_late=0):
+def run_pruned_parity(w, first_late, keep, mode, decode_steps, caps=None, max_seq_late=0, use_graph=False):
     """Early layers, ranking from the last early layer's last-row attention, pruning, late layers, decode."""
     s = (P.Session.for_workload(w, mode=mode, prune_before_layer=first_late, max_seq_late=max_seq_late) if max_seq_late
          else P.Session.for_workload(w, mode=mode))
@@ -152,21 +152,41 @@ def run_pruned_parity(w, first_late, keep, mode, decode_steps, caps=None, max_se
             assert np.array_equal(row_map.cpu().numpy(), row_map_host)
         if l == first_late - 1:
             s.prune(first_late, keep)
+    graph = bufs = None
+    if use_graph:                              # decode steps as replays of one graph recorded behind the boundary
+        shape = (w.batch, w.n_heads, w.head_dim)
+        mk = lambda: [torch.zeros(shape, dtype=workloads.TORCH_DTYPE[w.dtype], device="cuda") for _ in range(w.n_layers)]
+        bufs = [mk(), mk(), mk(), mk()]
+        if gla:
+            for i in (0, 1):
+                bufs[i] = [None if w.lazy_mask[l] else bufs[i][l] for l in range(w.n_layers)]
+        graph = s.decode_graph(*bufs)
     for t in range(decode_steps):
+        ins = [workloads.decode_qkv(w, l, t) for l in range(w.n_layers)]
+        if use_graph:
+            for l in range(w.n_layers):
+                if bufs[0][l] is not None:
+                    bufs[0][l].copy_(ins[l][0]); bufs[1][l].copy_(ins[l][1])
+                bufs[2][l].copy_(ins[l][2])
+            s.graph_launch(graph)
+            torch.cuda.synchronize()
         for l in range(w.n_layers):
-            q, k, v = workloads.decode_qkv(w, l, t)
+            q, k, v = ins[l]
             q64, k64, v64 = (workloads.to_f64(x) for x in (q, k, v))
             ref = np.stack([stacks[b].decode(l, q64[b], k64[b], v64[b]) for b in range(w.batch)], axis=0)
-            qg, kg = q.cuda(), k.cuda()
-            if gla and w.lazy_mask[l]:
-                qg = kg = None
-            out = s.decode(l, qg, kg, v.cuda())
+            if use_graph:
+                out = bufs[3][l]
+            else:
+                qg, kg = q.cuda(), k.cuda()
+                if gla and w.lazy_mask[l]:
+                    qg = kg = None
+                out = s.decode(l, qg, kg, v.cuda())
             err = max_abs_err(out, ref)
             assert np.isfinite(err)
             worst = max(worst, err)
     torch.cuda.synchronize()
     lay = oracle_layout(w, mode, caps, late=(first_late, max_seq_late) if max_seq_late else None)
-    assert np.array_equal(s.kv_arena.cpu().numpy(), olayout.kv_arena_image(lay, stacks)), "K/V arena differs"
+    assert np.array_equal(s.kv_arena.cpu().numpy(), olayout.kv_arena_image(lay, stacks, graph_steps=decode_steps if use_graph else 0)), "K/V arena differs"
     assert np.array_equal(s.q_arena.cpu().numpy()[: lay.q_arena_bytes()], olayout.q_arena_image(lay, stacks)), "Q arena differs"
     res = olayout.resident_bytes(lay, stacks)
     st = s.stats()
