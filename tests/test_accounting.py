@@ -72,3 +72,14 @@ def test_max_batch_figures_of_the_paper_follow_from_the_cache_layout():
     assert budget // per_seq(mask, "gla") == b1
     assert (b0 + 1) * per_seq([0] * N_, "vla") > budget   # 22 plain sequences do not fit
     assert layout.gla_kv_saving_closed_form(N_, n) == pytest.approx(pct / 100, abs=0.01)
+
+
+def test_bench_refuses_more_than_one_gpu_and_needs_no_gpu_to_say_so():
+    """bench.py --gpus N with N > 1 exits with a message: nothing in this path uses a second GPU."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "one GPU" in res.stderr
+    assert res.stdout.strip() == ""
