@@ -821,6 +821,10 @@ def main():
         "roofline": r["roofline"],
         "prefill_kernel": r["prefill_kernel"],
         "cpu_baseline": cpu,
+        # the workloads that can approach a roofline on a 256-CU part, each timed in this run (details under "workloads")
+        "roofline_summary": {k: {"bound": v["roofline"]["bound"], "frac": v["roofline"]["frac"],
+                                 "achieved": v["roofline"]["achieved"], "unit": v["roofline"]["unit"]}
+                             for k, v in extra.items() if isinstance(v, dict) and "roofline" in v},
         "workloads": extra,
     }
     print(json.dumps(line))
