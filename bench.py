@@ -821,6 +821,11 @@ def main():
         "roofline": r["roofline"],
         "prefill_kernel": r["prefill_kernel"],
         "cpu_baseline": cpu,
+        # what the paper itself reports, as context (another machine, whole model): not a target of this run
+        "paper_context": {"hardware": "one 80 GB A100, LLaVA-NeXT-7B, input length 2048",
+                          "kv_cache_saving": "35 % (GLA and VLA)", "max_batch": "21 -> 32",
+                          "decode_throughput": "1.6x (GLA), 1.5x (VLA) over the unmodified model",
+                          "efficiency_table_with_FastV": "prefill 30.88 -> 18.49 TFLOPs, 142.60 -> 67.21 ms, KV cache 1.01 -> 0.36 GB (VLA)"},
         # the workloads that can approach a roofline on a 256-CU part, each timed in this run (details under "workloads")
         "roofline_summary": {k: {"bound": v["roofline"]["bound"], "frac": v["roofline"]["frac"],
                                  "achieved": v["roofline"]["achieved"], "unit": v["roofline"]["unit"]}
