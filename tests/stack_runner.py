@@ -52,7 +52,7 @@ def max_abs_err(gpu_tensor, ref64):
     return float(np.max(np.abs(workloads.to_f64(gpu_tensor) - ref64)))
 
 
-def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=True, caps=None):
+def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=True, caps=None, zero_fill=True):
     """Prefill every layer then `decode_steps` decode steps on both sides; returns worst errors.
 
     With poison_span the span rows of q and k handed to lazy layers hold NaN on the GPU side
@@ -64,7 +64,7 @@ def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=Tru
     mode = session.mode
     gla = mode == "gla"
     stacks = new_oracles(w, mode=mode)
-    reset_session(session, w, caps)
+    reset_session(session, w, caps, zero_fill=zero_fill)
     worst_p = worst_d = 0.0
     for l in range(w.n_layers):
         q, k, v = workloads.prefill_qkv(w, l)

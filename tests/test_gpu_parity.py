@@ -180,3 +180,35 @@ def test_kernel_timing_counts_launches():
     assert (n_p, n_d) == (2, 4) and ms_p > 0 and ms_d > 0
     assert B.qc_timing_read(s.kv, 1) == (0.0, 0)
     B.qc_timing_enable(s.kv, 0)
+
+
+@pytest.mark.parametrize("mode", ["vla", "gla"])
+@pytest.mark.parametrize("dtype,D", [("f32", 64), ("bf16", 128)])
+def test_nothing_reads_memory_it_has_not_written(mode, dtype, D):
+    """Arenas and workspace start as all-ones bytes (NaN in either element type) and are not cleared:
+    every output must still be finite and within the bar, for ordinary calls and for graph replays."""
+    import paper_2602_01901_amd as P2
+    from test_gpu_graph import prefill_both, run_steps, step_buffers
+    from stack_runner import new_oracles
+    w = workloads.custom("poison", 5, 3, D, dtype, [4, 0, 9], [70, 0, 33], [150, 40, 65], 3, [0, 1, 0, 1, 1], seed_tag=51)
+    s = P2.Session.for_workload(w, mode=mode)
+    for t in (s.kv_arena, s.q_arena, s.workspace):
+        t.fill_(0xFF)
+    wp, wd = run_full_parity(w, 3, s, check_arena=False, zero_fill=False)
+    assert max(wp, wd) <= TOL[dtype]
+    s.close()
+    s = P2.Session.for_workload(w, mode=mode)
+    for t in (s.kv_arena, s.q_arena, s.workspace):
+        t.fill_(0xFF)
+    stacks = new_oracles(w, mode=mode)
+    s.reset(w.vis_start, w.vis_len, zero_fill=False)
+    for l in range(w.n_layers):
+        q, k, v = workloads.prefill_qkv(w, l)
+        from stack_runner import oracle_prefill_layer
+        oracle_prefill_layer(w, stacks, l, q, k, v)
+        no_qk = mode == "gla" and w.lazy_mask[l]
+        s.prefill(l, None if no_qk else q.cuda(), None if no_qk else k.cuda(), v.cuda(), w.cu_seqlens)
+    bufs = step_buffers(w, mode)
+    g = s.decode_graph(*bufs)
+    run_steps(w, s, stacks, mode, g, bufs, "ggg")
+    s.close()
