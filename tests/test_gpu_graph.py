@@ -189,3 +189,40 @@ def test_graph_replays_are_bitwise_equal_to_ordinary_calls_and_repeatable(mode):
         for a, b in zip(results[0][0], outs):
             assert np.array_equal(a, b)
         assert np.array_equal(results[0][1], kv)
+
+
+def test_everything_runs_on_the_callers_stream():
+    """Prefill, ordinary decode calls and graph replays enqueued on a side stream only, with a long-running
+    kernel ahead of them on that stream: results are right once that stream has drained, which they
+    would not be if any launch had gone to another stream."""
+    w = workloads.custom("side", 4, 2, 64, "bf16", [2, 0], [30, 12], [80, 50], 4, [0, 1, 0, 1], seed_tag=37)
+    s = P.Session.for_workload(w)
+    stacks = new_oracles(w)
+    side = torch.cuda.Stream()
+    big = torch.randn(4096, 4096, device="cuda")
+    with torch.cuda.stream(side):
+        for _ in range(20):
+            big = big @ big * 1e-4                       # keeps the side stream busy for a while
+        prefill_both(w, s, stacks, "vla")
+        bufs = step_buffers(w, "vla")
+        g = s.decode_graph(*bufs)
+        q, k, v, out = bufs
+        refs, gots = [], []
+        for t, kind in enumerate("egge"):
+            ins = [workloads.decode_qkv(w, l, t) for l in range(w.n_layers)]
+            refs.append([oracle_decode_layer(w, stacks, l, *ins[l]) for l in range(w.n_layers)])
+            for l in range(w.n_layers):
+                q[l].copy_(ins[l][0].cuda(), non_blocking=True)
+                k[l].copy_(ins[l][1].cuda(), non_blocking=True)
+                v[l].copy_(ins[l][2].cuda(), non_blocking=True)
+            if kind == "g":
+                s.graph_launch(g)
+            else:
+                for l in range(w.n_layers):
+                    s.decode(l, q[l], k[l], v[l], out=out[l])
+            gots.append([o.clone() for o in out])
+    side.synchronize()
+    for t in range(4):
+        for l in range(w.n_layers):
+            assert max_abs_err(gots[t][l], refs[t][l]) <= TOL["bf16"], (t, l)
+    s.close()
