@@ -814,6 +814,9 @@ def main():
                    "decode_launch": "ordinary qc_decode calls" if args.no_graph else
                                     "one replay of a HIP graph of the 32 layer calls per decode step"},
         "prefill_tflops": r["prefill_tflops"], "prefill_ms": r["prefill_ms"],
+        # the headline shape's prompt (one sequence of 640 tokens) is latency-bound; the prefill-dominated
+        # configuration (batch 8 x 3008 tokens) timed in this run:
+        "prefill_tflops_highres": extra.get("prefill_highres", {}).get("prefill_tflops"),
         "decode_ms_per_token_step": r["decode_ms_per_token_step"],
         "k_cache_bytes_per_token": r["k_cache_bytes_per_token"],
         "k_cache_bytes_per_token_after_prefill": r["k_cache_bytes_per_token_after_prefill"],
