@@ -213,6 +213,26 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
                     const int32_t* vis_len, float softmax_scale, void* workspace,
                     size_t workspace_bytes, void* stream);
 
+/* ---- decode for callers that cannot allocate ------------------------------------------------------
+ * For callers that must not call hipMalloc (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation) and therefore cannot bring a workspace: qc_decode with the
+ * workspace replaced by an array of QC_STATIC_SCRATCH_BYTES bytes that the library itself holds in
+ * device memory, one copy per GPU, from load until the process ends.  Same kernels, same results,
+ * same arguments and errors as qc_decode otherwise.  The call allocates nothing, on the host or on
+ * the device (leave qc_timing_enable off: event creation allocates).
+ *   QC_ECAPACITY if the call needs more scratch than the array holds.  Under QC_VLA a call needs at
+ *   most 2047 partial results of head_dim + 2 floats (about 1 MiB), so it always fits; under QC_GLA
+ *   it needs qc_decode_workspace_bytes(cfg), which fits only small configurations.
+ *   The device that is current at the call must be the one `stream` and the arenas belong to.
+ *   All calls on one GPU share that GPU's array, from every handle and every thread: calls that
+ *   overlap on one GPU (two streams, two threads) race.  Nothing in it has to start at zero: each
+ *   call writes every partial result it later reads.  Under QC_GLA the layers of a block must all use
+ *   this entry point (or all qc_decode with one workspace). */
+enum { QC_STATIC_SCRATCH_BYTES = 4194304 };
+qc_status qc_decode_static(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_lazy, const void* q,
+                           const void* k, const void* v, void* out, const int32_t* vis_start,
+                           const int32_t* vis_len, float softmax_scale, void* stream);
+
 /* ---- a whole decode step as one replayable HIP graph --------------------------------------------
  * At batch sizes where a layer call lasts a few microseconds, a decode step is bound by the gaps
  * between dependent launches on a stream (about 4 us each here); replayed from a graph the same

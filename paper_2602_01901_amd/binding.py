@@ -16,6 +16,7 @@ QC_F32, QC_BF16 = 0, 1
 QC_K, QC_V = 0, 1
 QC_VLA, QC_GLA = 0, 1
 QC_PLAN_KV, QC_PLAN_Q, QC_PLAN_WORKSPACE = 1, 2, 4
+QC_STATIC_SCRATCH_BYTES = 4 << 20
 DTYPE_CODE = {"f32": QC_F32, "bf16": QC_BF16}
 MODE_CODE = {"vla": QC_VLA, "gla": QC_GLA}
 
@@ -54,6 +55,8 @@ _PROTOTYPES = {
                              c_void_p]),
     "qc_decode": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                             POINTER(c_int32), POINTER(c_int32), c_float, c_void_p, c_size_t, c_void_p]),
+    "qc_decode_static": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+                                   POINTER(c_int32), POINTER(c_int32), c_float, c_void_p]),
     "qc_decode_graph_create": (c_int32, [c_void_p, c_void_p, POINTER(c_void_p), POINTER(c_void_p), POINTER(c_void_p),
                                          POINTER(c_void_p), c_float, c_void_p, c_size_t, POINTER(c_void_p)]),
     "qc_decode_graph_launch": (c_int32, [c_void_p, c_void_p]),
@@ -198,6 +201,11 @@ def qc_decode(kv, qc, layer, is_lazy, q, k, v, out, vis_start, vis_len, softmax_
     return _check(load_library().qc_decode(kv, qc, layer, int(is_lazy), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
                                           _i32(vis_start), _i32(vis_len), softmax_scale, _ptr(workspace),
                                           workspace_bytes, stream))
+
+
+def qc_decode_static(kv, qc, layer, is_lazy, q, k, v, out, vis_start, vis_len, softmax_scale=0.0, stream=None):
+    return _check(load_library().qc_decode_static(kv, qc, layer, int(is_lazy), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
+                                                 _i32(vis_start), _i32(vis_len), softmax_scale, stream))
 
 
 def _ptr_array(xs):

@@ -480,7 +480,8 @@ struct GraphGeom {
 static qc_status decode_impl(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_lazy, const void* q,
                              const void* k, const void* v, void* out, const int32_t* vis_start,
                              const int32_t* vis_len, float softmax_scale, void* workspace,
-                             size_t workspace_bytes, void* stream, const GraphGeom* geom) {
+                             size_t workspace_bytes, void* stream, const GraphGeom* geom,
+                             bool static_scratch = false) {
   if (!kv) return fail(QC_EINVAL, "qc_decode: null handle");
   const Config& c = kv->cfg;
   // Visual Lazy Attention never touches the Q Cache while decoding; Global Lazy Attention does.
@@ -526,7 +527,9 @@ static qc_status decode_impl(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32
   }
   size_t need = (size_t)kv->batch * c.H * max_chunks * (c.D + 2) * 4;
   if (c.gla()) need = (size_t)(partial_bytes(c) + score_bytes(c));
-  if (workspace_bytes < need) return fail(QC_ECAPACITY, "qc_decode: workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+  if (workspace_bytes < need)
+    return static_scratch ? fail(QC_ECAPACITY, "qc_decode_static: the call needs %zu bytes of scratch, the library's array holds %zu; use qc_decode with a workspace", need, workspace_bytes)
+                          : fail(QC_ECAPACITY, "qc_decode: workspace holds %zu bytes, %zu needed", workspace_bytes, need);
   if (qk_unused && kv->score_workspace != workspace)
     return fail(QC_EINVAL, "qc_decode: layer %d needs the workspace its block's first layer was called with", layer);
 
@@ -578,6 +581,18 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
                     size_t workspace_bytes, void* stream) {
   return decode_impl(kv, qc, layer, is_lazy, q, k, v, out, vis_start, vis_len, softmax_scale, workspace,
                      workspace_bytes, stream, nullptr);
+}
+
+qc_status qc_decode_static(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_lazy, const void* q,
+                           const void* k, const void* v, void* out, const int32_t* vis_start,
+                           const int32_t* vis_len, float softmax_scale, void* stream) {
+  static_assert(QC_STATIC_SCRATCH_BYTES == qc::kStaticScratchBytes, "header and library disagree on the scratch size");
+  void* scratch_ptr = nullptr;
+  size_t scratch_bytes = 0;
+  hipError_t e = qc::decode_static_scratch(&scratch_ptr, &scratch_bytes);
+  if (e != hipSuccess) return fail(QC_EDEVICE, "qc_decode_static: %s", hipGetErrorString(e));
+  return decode_impl(kv, qc, layer, is_lazy, q, k, v, out, vis_start, vis_len, softmax_scale, scratch_ptr,
+                     scratch_bytes, stream, nullptr, true);
 }
 
 // ---- one whole decode step as a replayable graph -------------------------------------------------

@@ -18,9 +18,38 @@
 // split partials and its query at row `len` of the Q Cache; a lazy layer (SHARED instantiation)
 // reads those scores instead of any key row: it streams V only, half the bytes, and gets
 // bit-identical scores.  It appends its v row only.
+#include <atomic>
+
 #include "qc_device.h"
 
 namespace qc {
+
+// ---- scratch memory for callers that cannot allocate ----------------------------------------------
+// The split partials (and, under Global Lazy Attention, the score rows) of a decode call normally
+// live in a workspace the caller allocates.  For callers that cannot allocate, the same kernels are
+// handed this array instead.  Every GPU the library runs on holds its own copy at its own address:
+// in host code the array's name is only a stand-in, so the device address is looked up once per
+// device and that pointer is what reaches the kernels.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+hipError_t decode_static_scratch(void** ptr, size_t* bytes) {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<void*> per_device[kMaxDevices];
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* p = per_device[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));  // address of the current device's copy
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    per_device[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  *bytes = kStaticScratchBytes;
+  return hipSuccess;
+}
 
 // Cache rows are read once per step: load them with the non-temporal hint (measurably faster HBM
 // streaming than ordinary loads on this part).

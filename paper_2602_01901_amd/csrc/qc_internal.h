@@ -192,6 +192,10 @@ hipError_t launch_counter_update(int32_t* counter, int32_t value, int32_t add, h
 hipError_t launch_meta_upload(int32_t* meta_dev, int32_t max_batch, int32_t first, int32_t count, int32_t rows,
                               const MetaChunk& chunk, hipStream_t stream);
 hipError_t launch_prefill(const PrefillArgs& a, int dtype, hipStream_t stream, KernelTimer* timer);
+// Size of the library's own decode scratch array (one per GPU, held until the process ends).
+constexpr size_t kStaticScratchBytes = 4u << 20;
+// Device address and size of that array on the current device; allocates nothing.
+hipError_t decode_static_scratch(void** ptr, size_t* bytes);
 hipError_t launch_decode(const DecodeArgs& a, const DecodeGlaArgs& g, int dtype, hipStream_t stream, KernelTimer* timer);
 hipError_t launch_last_row_attention(const SelectArgs& a, int dtype, int max_len, hipStream_t stream);
 hipError_t launch_js(const float* pm, const float* pn, int64_t stride, int first, int count, const JsChunk& c,
