@@ -99,7 +99,7 @@ def test_cfg4_highres_prefill_sampled():
     """Batch 8 x 3008 tokens (2880 visual), 32 heads: the 256-row prefill kernel, first 8 layers
     (two ordinary layers, then two blocks of one ordinary + two lazy layers)."""
     w = workloads.config(3)
-    worst, sess = run_sampled(w, 8, [(0, 0), (3, 17), (7, 31)])
+    worst, sess = run_sampled(w, 8, [(0, 0), (1, 9), (3, 17), (4, 30), (6, 1), (7, 31)])
     print("cfg4 sampled max abs err %.3g" % worst, flush=True)
     assert worst <= TOL["bf16"]
     rk, rv = B.qc_layer_rows(sess.kv, 3)
@@ -109,7 +109,7 @@ def test_cfg4_highres_prefill_sampled():
 def test_cfg3_batched_decode_sampled():
     """Batch 32 with unequal lengths: full 32-layer prefill then 3 decode steps, sampled heads."""
     w = workloads.config(2)
-    worst, sess = run_sampled(w, w.n_layers, [(0, 5), (13, 0), (31, 31)], decode_steps=3)
+    worst, sess = run_sampled(w, w.n_layers, [(0, 5), (7, 16), (13, 0), (20, 31), (26, 11), (31, 31)], decode_steps=3)
     print("cfg3 sampled max abs err %.3g" % worst, flush=True)
     assert worst <= TOL["bf16"]
     st = sess.stats()
@@ -120,16 +120,31 @@ def test_cfg3_batched_decode_sampled():
 def test_cfg5_video_shape_sampled():
     """13B-shaped video workload: 40 heads, 4864-token prompts; first 5 layers of prefill."""
     w = workloads.config(4)
-    worst, _ = run_sampled(w, 5, [(0, 39), (3, 7)])
+    worst, _ = run_sampled(w, 5, [(0, 39), (0, 0), (1, 20), (2, 33), (3, 7), (3, 39)])
     print("cfg5 sampled max abs err %.3g" % worst, flush=True)
     assert worst <= TOL["bf16"]
+
+
+def test_cfg5_decode_sampled():
+    """13B-shaped video workload as bench.py times it: the full 40-layer prefill of 4 x 4864 tokens, then
+    3 decode steps (7 key chunks per (sequence, head), merged), sampled heads including the last one."""
+    w = workloads.config(4)
+    pairs = [(0, 0), (0, 39), (1, 17), (2, 39), (3, 5), (3, 39)]
+    worst, sess = run_sampled(w, w.n_layers, pairs, decode_steps=3, seed=5)
+    print("cfg5 prefill + decode sampled max abs err %.3g" % worst, flush=True)
+    assert worst <= TOL["bf16"]
+    st = sess.stats()
+    per_row = 40 * 128 * 2
+    assert st["tokens"] == 4 * (4864 + 3) and st["generated"] == 3
+    assert st["k_bytes"] == sum((4864 + 3 - lz * 4608) for _ in range(4) for lz in w.lazy_mask) * per_row
+    assert st["v_bytes"] == 40 * 4 * (4864 + 3) * per_row
 
 
 def test_long_prompt_32k():
     """One 32768-token prompt (32000 visual), 8 heads: 256 query tiles per head and key walks of up to
     512 tiles; an ordinary layer then a lazy one, sampled rows."""
     w = workloads.custom("long", 2, 8, 128, "bf16", [256], [32000], [32768], 0, [0, 1])
-    worst, sess = run_sampled(w, 2, [(0, 0), (0, 7)])
+    worst, sess = run_sampled(w, 2, [(0, 0), (0, 1), (0, 3), (0, 4), (0, 6), (0, 7)])
     print("long prompt sampled max abs err %.3g" % worst, flush=True)
     assert worst <= TOL["bf16"]
     assert B.qc_layer_rows(sess.kv, 1) == (768, 32768)
@@ -139,7 +154,7 @@ def test_gla_cfg4_highres_prefill_sampled():
     """Global Lazy Attention at batch 8 x 3008 tokens: every row of a lazy layer comes from the Q Cache and
     from the K cache of its block's first layer; first 8 layers."""
     w = workloads.config(3)
-    worst, sess = run_sampled(w, 8, [(0, 0), (3, 17), (7, 31)], mode="gla")
+    worst, sess = run_sampled(w, 8, [(0, 0), (1, 9), (3, 17), (4, 30), (6, 1), (7, 31)], mode="gla")
     print("gla cfg4 sampled max abs err %.3g" % worst, flush=True)
     assert worst <= TOL["bf16"]
     assert B.qc_layer_rows(sess.kv, 3) == (0, 8 * 3008)   # a lazy layer keeps no keys at all
@@ -149,7 +164,7 @@ def test_gla_cfg3_batched_decode_sampled():
     """Global Lazy Attention, batch 32 with unequal lengths: full prefill then 3 decode steps in which the
     lazy layers reuse their block's scores."""
     w = workloads.config(2)
-    worst, sess = run_sampled(w, w.n_layers, [(0, 5), (13, 0), (31, 31)], decode_steps=3, mode="gla")
+    worst, sess = run_sampled(w, w.n_layers, [(0, 5), (7, 16), (13, 0), (20, 31), (26, 11), (31, 31)], decode_steps=3, mode="gla")
     print("gla cfg3 sampled max abs err %.3g" % worst, flush=True)
     assert worst <= TOL["bf16"]
     st = sess.stats()
@@ -163,7 +178,7 @@ def test_cfg2_headline_decode_graph_sampled():
     """The headline configuration as bench.py times it: 32 layers, batch 1, 640-token prompt, decode steps
     replayed from the HIP graph (one replay per step), sampled heads against the oracle at every step."""
     w = workloads.config(1)
-    pairs = [(0, 0), (0, 13), (0, 31)]
+    pairs = [(0, 0), (0, 7), (0, 13), (0, 18), (0, 26), (0, 31)]
     sess = P.Session.for_workload(w)
     sess.reset(w.vis_start, w.vis_len, zero_fill=False)
     oracles = {p: LazyStackOracle(w.n_layers, 1, w.head_dim, w.lazy_mask, w.vis_start[0], w.vis_len[0]) for p in pairs}
@@ -205,7 +220,7 @@ def test_cfg3_pruned_decode_sampled():
     w = workloads.config(2)
     first_late, rank_layer = 2, 1
     keep = [v // 2 for v in w.vis_len]
-    pairs = [(0, 5), (13, 0), (31, 31)]
+    pairs = [(0, 5), (7, 16), (13, 0), (20, 31), (26, 11), (31, 31)]
     rng = np.random.default_rng(4)
     sess = P.Session.for_workload(w)
     sess.reset(w.vis_start, w.vis_len, zero_fill=False)
