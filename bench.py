@@ -6,10 +6,10 @@ prefill every layer of the stack (ordinary and lazy layers in order), then run t
 decode steps, each of which visits every layer.  Inputs are seeded N(0,1) tensors resident in
 HBM before the timed region starts; every call goes through the C ABI (qc_prefill / qc_decode).
 
-The headline line is measured on the LLaVA-1.5-7B-shaped configuration (batch 1).  Because that
-shape is launch/latency bound on a 256-CU part, the same JSON line also carries, under
-"workloads", the batched-decode configuration (HBM roofline) and the high-resolution prefill
-configuration (MFMA roofline), each timed in this same run.
+The headline line is measured on the largest single-GPU configuration, the 13B-shaped video workload
+(40 layers x 40 heads, batch 4, 4864-token prompts of which 4608 visual, 1024 generated tokens).  The
+other configurations (batch-1 7B shape, batched decode, high-resolution prefill) and the widened
+entry points are timed in the same run and reported under "workloads".
 
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
@@ -22,7 +22,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
@@ -85,9 +84,29 @@ class Runner:
                 q = k = None
             s.prefill(l, q, k, v, w.cu_seqlens, out=self.out_pre)
 
-    def decode_steps_run(self, steps):
+    def decode_steps_run(self, steps, time_every=0, timed_steps=None):
+        """time_every > 0: the library's per-kernel HIP events are switched on for one decode step in
+        every `time_every` (ordinary calls only); the index of each such step (= tokens generated
+        before it) is appended to timed_steps."""
         w, s = self.w, self.sess
         stream = self.torch.cuda.current_stream(s.device).cuda_stream
+        if time_every and not self.use_graph:
+            from paper_2602_01901_amd import binding as B
+            g0 = s.stats()["generated"]
+            for t in range(steps):
+                on = t % time_every == time_every // 2
+                if on:
+                    B.qc_timing_enable(s.kv, 1)
+                    timed_steps.append(g0 + t)
+                row = self.dec[t % len(self.dec)]
+                for l in range(w.n_layers):
+                    q, k, v = row[l]
+                    if self.no_qk[l]:
+                        q = k = None
+                    s.decode(l, q, k, v, out=self.out_dec, stream=stream)
+                if on:
+                    B.qc_timing_enable(s.kv, 0)
+            return
         if self.use_graph:
             if self.graph is None:
                 row = self.dec[0]
@@ -144,16 +163,16 @@ def timed(torch, fn, reps):
 
 
 def bench_cfg2(args):
+    """Batch-1 7B shape (640-token prompt, 256 decode steps): launch- and latency-bound on a 256-CU part;
+    decode steps are replayed from one HIP graph."""
     import torch
     import workloads
     w = workloads.config(1)
     r = Runner(w, w.decode_steps, graph=not args.no_graph)
-    log("cfg2: warmup %d" % args.warmup)
-    for _ in range(args.warmup):
-        r.step()
+    r.step()
     torch.cuda.synchronize()
     # whole steps
-    wall, _ = timed(torch, r.step, args.steps)
+    wall, _ = timed(torch, r.step, 3)
     # split of the same step into its two phases (extra passes, not part of `value`)
     pre_wall, pre_ev = timed(torch, r.prefill_stack, max(args.steps, 3))
     r.prefill_stack()
@@ -174,6 +193,8 @@ def bench_cfg2(args):
     achieved = mean_bytes / (dec_us * 1e-6) / 1e9
     pf = prefill_flops_per_layer(w) * w.n_layers
     res = {
+        "workload": w.name, "batch": w.batch,
+        "decode_launch": "ordinary qc_decode calls" if args.no_graph else "one replay of a HIP graph of the 32 layer calls per decode step",
         "ms_per_step": wall * 1e3,
         "decode_tokens_per_s": w.batch * w.decode_steps / dec_ev,
         "decode_ms_per_token_step": dec_ev / w.decode_steps * 1e3,
@@ -182,16 +203,23 @@ def bench_cfg2(args):
         "k_cache_bytes_per_token": stats["k_bytes"] / stats["tokens"],
         "k_cache_bytes_per_token_standard": w.n_layers * w.n_heads * w.head_dim * w.elem_bytes,
         "k_cache_bytes_per_token_after_prefill": stats_prefill["k_bytes"] / stats_prefill["tokens"],
-        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<bf16,128>", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+        # kernels of a few microseconds: an event pair also brackets the dispatch gap, so the figure that
+        # fits inside the step is the whole replayed decode phase (all bytes of a step over its duration)
+        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<bf16,128> + decode_merge_kernel (whole replayed decode phase)",
+                     "achieved": mean_bytes * w.n_layers * w.decode_steps / dec_ev / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": mean_bytes * w.n_layers * w.decode_steps / dec_ev / 1e9 / HBM_PEAK_GBS,
                      "traffic": measured_traffic("decode_cfg2"),
-                     "avg_launch_us": dec_us, "launches_timed": dec_n, "algorithmic_bytes_per_launch": mean_bytes},
+                     "avg_launch_us": dec_ev / (w.n_layers * w.decode_steps) * 1e6,
+                     "launches_timed": w.n_layers * w.decode_steps, "algorithmic_bytes_per_launch": mean_bytes,
+                     "event_pair_around_split_kernel_us": dec_us, "event_pair_GBps": achieved,
+                     "note": "latency-bound shape: 12.6 MB per layer call would take 1.6 us at the HBM peak"},
         "prefill_kernel": {"kernel": "prefill_mfma_kernel", "avg_launch_us": pre_us, "launches_timed": pre_n,
                            "tflops": prefill_flops_per_layer(w) / (pre_us * 1e-6) / 1e12 if pre_us else None},
     }
     del r
     torch.cuda.empty_cache()
-    return w, res
+    return res
 
 
 def bench_decode_batched(args):
@@ -663,38 +691,92 @@ def bench_ragged_arena(args):
     return res
 
 
-def bench_video(args):
-    """13B-shaped video workload (batch 4, 4864-token prompts, 40 heads): prefill, then decode steps."""
+def bench_headline(args):
+    """13B-shaped video workload (cfg5): the line's headline.  A step = reset + 40-layer prefill of
+    4 x 4864 tokens + 1024 decode steps x 40 layers, through ordinary qc_prefill / qc_decode calls
+    (65 us kernels: replaying a graph gains nothing here).  Inside the timed region HIP events on the
+    launch stream mark the two phases of every step; the library's own event pairs around the dominant
+    kernels are on for every prefill launch and for one decode step in every 32 (1280 of 40960 decode
+    launches per step), so that they do not slow the step they measure."""
     import torch
     import workloads
     w = workloads.config(4)
-    steps = 8
-    r = Runner(w, steps, distinct_decode_inputs=2)     # 68 us kernels: graph replay gains nothing here (measured)
-    r.prefill_stack()
+    r = Runner(w, w.decode_steps, distinct_decode_inputs=4)
+    from paper_2602_01901_amd import binding as B
+    kv = r.sess.kv
+    for i in range(args.warmup):
+        r.step()
+        log("headline: warmup step %d done" % (i + 1))
     torch.cuda.synchronize()
-    _, pre_s = timed(torch, r.prefill_stack, 1)
-    kp = r.kernel_times(r.prefill_stack)["prefill"]
-    r.decode_steps_run(2)
+    for which in (0, 1, 2):
+        B.qc_timing_read(kv, which)
+    timed_steps, phases = [], []
+    stats_prefill = {}
     torch.cuda.synchronize()
-    _, dec_s = timed(torch, lambda: r.decode_steps_run(steps), 1)
-    g = r.sess.stats()["generated"]
-    kd = r.kernel_times(lambda: r.decode_steps_run(2))["decode"]
-    flops_layer = prefill_flops_per_layer(w)
-    bytes_call = sum(decode_bytes_per_layer(w, g + t) for t in range(2)) / 2
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev[0].record()
+        B.qc_timing_enable(kv, 1)
+        r.prefill_stack()
+        B.qc_timing_enable(kv, 0)
+        ev[1].record()
+        if i == 0:
+            stats_prefill.update(r.sess.stats())
+        r.decode_steps_run(w.decode_steps, time_every=32, timed_steps=timed_steps)
+        ev[2].record()
+        phases.append(ev)
+        if (i + 1) % 4 == 0:
+            log("headline: timed step %d enqueued" % (i + 1))
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / args.steps
+    pre_s = sum(e[0].elapsed_time(e[1]) for e in phases) * 1e-3 / args.steps
+    dec_s = sum(e[1].elapsed_time(e[2]) for e in phases) * 1e-3 / args.steps
+    pre_ms, pre_n = B.qc_timing_read(kv, 0)
+    dec_ms, dec_n = B.qc_timing_read(kv, 1)
+    assert dec_n == len(timed_steps) * w.n_layers, (dec_n, len(timed_steps))
+    pre_us, dec_us = pre_ms * 1e3 / pre_n, dec_ms * 1e3 / dec_n
     stats = r.sess.stats()
+    flops_layer = prefill_flops_per_layer(w)
+    bytes_call = sum(decode_bytes_per_layer(w, g) for g in timed_steps) / len(timed_steps)
+    bytes_phase = sum(decode_bytes_per_layer(w, g) for g in range(w.decode_steps)) * w.n_layers
+    launches_per_step = w.decode_steps * w.n_layers
+    # Dominant kernel: the streaming decode kernel, launched once per layer call.  Its duration is taken
+    # as the decode phase's HIP-event time divided by the number of layer calls: that charges the small
+    # merge pass and every launch gap to it (a lower bound on its bandwidth) and by construction fits
+    # inside the step.  The event pairs the library records around the kernel alone, on sampled steps,
+    # are given beside it; a pair also brackets the dispatch of the kernel it surrounds.
+    call_us = dec_s / launches_per_step * 1e6
+    bytes_mean = bytes_phase / launches_per_step
+    achieved = bytes_mean / (call_us * 1e-6) / 1e9
     res = {
-        "workload": w.name, "batch": w.batch, "seq_len": w.seq_len[0], "layers": w.n_layers, "heads": w.n_heads,
-        "prefill_ms": pre_s * 1e3, "prefill_tflops": flops_layer * w.n_layers / pre_s / 1e12,
-        "prefill_kernel_avg_us": kp[0], "prefill_kernel_tflops": flops_layer / (kp[0] * 1e-6) / 1e12,
-        "decode_tokens_per_s": w.batch * steps / dec_s, "decode_ms_per_step": dec_s / steps * 1e3,
-        "decode_kernel_avg_us": kd[0], "decode_kernel_GBps": bytes_call / (kd[0] * 1e-6) / 1e9,
-        "decode_note": "7 key chunks per (sequence, head): the figure is the streaming kernel, the merge pass is extra",
+        "ms_per_step": wall * 1e3,
+        "decode_tokens_per_s": w.batch * w.decode_steps / dec_s,
+        "tokens_per_s_whole_step": w.batch * w.decode_steps / wall,
+        "decode_ms_per_token_step": dec_s / w.decode_steps * 1e3,
+        "decode_phase_ms": dec_s * 1e3,
+        "prefill_ms": pre_s * 1e3,
+        "prefill_tflops": flops_layer * w.n_layers / pre_s / 1e12,
         "k_cache_bytes_per_token": stats["k_bytes"] / stats["tokens"],
+        "k_cache_bytes_per_token_after_prefill": stats_prefill["k_bytes"] / stats_prefill["tokens"],
         "k_cache_bytes_per_token_standard": w.n_layers * w.n_heads * w.head_dim * w.elem_bytes,
+        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<bf16,128> (7 key chunks per (sequence, head); duration = decode "
+                     "phase / layer calls, so the merge pass and the launch gaps are charged to it)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic("decode_cfg5"),
+                     "avg_launch_us": call_us, "launches_timed": launches_per_step * args.steps,
+                     "algorithmic_bytes_per_launch": bytes_mean, "launches_per_step": launches_per_step,
+                     "event_pairs_around_kernel": {"avg_us": dec_us, "launches": dec_n, "algorithmic_bytes_per_launch": bytes_call,
+                                                   "GBps": bytes_call / (dec_us * 1e-6) / 1e9}},
+        "prefill_kernel": {"bound": "mfma", "kernel": "prefill_mfma_kernel (attention + fused cache writes: whole layer call)",
+                           "achieved": flops_layer / (pre_us * 1e-6) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                           "frac": flops_layer / (pre_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                           "traffic": measured_traffic("prefill_cfg5"), "avg_launch_us": pre_us, "launches_timed": pre_n,
+                           "algorithmic_flops_per_launch": flops_layer},
     }
     del r
     torch.cuda.empty_cache()
-    return res
+    return w, res
 
 
 def bench_prefill_long(args):
@@ -705,46 +787,94 @@ def bench_prefill_long(args):
     return bench_prefill_highres(args, w=w, traffic_key="prefill_long")
 
 
-def cpu_baseline(budget_s=20.0):
-    """The fp64 oracle on the host cores, on a bounded sample of the headline workload."""
-    import torch
+def host_threads():
+    """Threads the oracle's numpy routines actually use (its matrix products run in the BLAS pool)."""
+    try:
+        from threadpoolctl import threadpool_info
+        n = [p.get("num_threads", 0) for p in threadpool_info() if p.get("user_api") == "blas"]
+        if n:
+            return max(n)
+    except Exception:
+        pass
+    return os.cpu_count() or 1
+
+
+def cpu_baseline_sample(w, heads, seq=0):
+    """The fp64 oracle as it stands, on the host cores, on a bounded sample of workload `w`: sequence
+    `seq`, the first `heads` heads (sequences and heads are independent instances of the method), fed
+    the very inputs the GPU run uses.  Timed: ONE prefill layer (layer 0, every query row) and ONE decode
+    step (all layers, caches filled by an untimed pass that stores every layer's rows).  Rates are what
+    was run divided by its time; the decode rate is expressed in the metric's unit by the share of the
+    batch's (sequence, head) pairs the sample covers.  Nothing is extrapolated across layers."""
     import workloads
-    from stack_runner import new_oracles, oracle_decode_layer, oracle_prefill_layer
+    from oracle.lazy_stack import LazyStackOracle
+    cu = w.cu_seqlens
+    L = w.seq_len[seq]
+    st = LazyStackOracle(w.n_layers, heads, w.head_dim, w.lazy_mask, w.vis_start[seq], w.vis_len[seq])
+
+    def sample(t):
+        return workloads.to_f64(t[cu[seq]:cu[seq + 1], :heads])
+    q, k, v = (sample(t) for t in workloads.prefill_qkv(w, 0, device="cuda"))
+    t0 = time.perf_counter()
+    st.prefill(0, q, k, v)
+    t_pre = time.perf_counter() - t0
+    for l in range(1, w.n_layers):
+        q, k, v = (sample(t) for t in workloads.prefill_qkv(w, l, device="cuda"))
+        st.prefill(l, q, k, v, rows=[0])
+    ins = [[workloads.to_f64(t[seq, :heads]) for t in workloads.decode_qkv(w, l, 0, device="cuda")] for l in range(w.n_layers)]
+    t1 = time.perf_counter()
+    for l in range(w.n_layers):
+        st.decode(l, *ins[l])
+    t_dec = time.perf_counter() - t1
+    flops = heads * 4 * w.head_dim * L * (L + 1) // 2
+    share = heads / (w.batch * w.n_heads)           # of the batch's (sequence, head) pairs
+    return {"value": w.batch * share / t_dec, "unit": "tokens/s", "cores": host_threads(), "kind": "oracle",
+            "sample": "%s, sequence %d (%d tokens), heads 0..%d of %d: one prefill layer in full (%.2f s) and one decode "
+                      "step over all %d layers (%.3f s); tokens/s = batch x (sample's share of the batch's (sequence, head) "
+                      "pairs) / decode-step time" % (w.name, seq, L, heads - 1, w.n_heads, t_pre, w.n_layers, t_dec),
+            "prefill_tflops_fp64": flops / t_pre / 1e12, "prefill_layer_s": t_pre, "decode_step_s": t_dec,
+            "pairs_share": share}
+
+
+def cpu_baseline_cfg2(budget_s=8.0):
+    """The batch-1 7B shape is small enough for the oracle to run whole: the full 32-layer prefill, then
+    as many 32-layer decode steps as fit the budget."""
+    import workloads
+    from oracle.lazy_stack import LazyStackOracle
     w = workloads.config(1)
-    stacks = new_oracles(w)
-    inputs = [workloads.prefill_qkv(w, l) for l in range(w.n_layers)]
+    st = LazyStackOracle(w.n_layers, w.n_heads, w.head_dim, w.lazy_mask, w.vis_start[0], w.vis_len[0])
+    inputs = [[workloads.to_f64(t) for t in workloads.prefill_qkv(w, l, device="cuda")] for l in range(w.n_layers)]
     t0 = time.perf_counter()
     for l in range(w.n_layers):
-        oracle_prefill_layer(w, stacks, l, *inputs[l])
+        st.prefill(l, *inputs[l])
     t_pre = time.perf_counter() - t0
+    del inputs
     steps = 0
     t1 = time.perf_counter()
     while steps < w.decode_steps and (time.perf_counter() - t1) < budget_s:
         for l in range(w.n_layers):
-            oracle_decode_layer(w, stacks, l, *workloads.decode_qkv(w, l, steps))
+            st.decode(l, *[workloads.to_f64(t[0]) for t in workloads.decode_qkv(w, l, steps, device="cuda")])
         steps += 1
     t_dec = time.perf_counter() - t1
-    return {"value": w.batch * steps / t_dec, "unit": "tokens/s", "cores": torch.get_num_threads(),
-            "kind": "oracle",
-            "sample": "%s: full 32-layer prefill (%.2f s, %.4f TFLOP/s fp64) then %d decode steps of 32 layers"
-                      % (w.name, t_pre, prefill_flops_per_layer(w) * w.n_layers / t_pre / 1e12, steps),
-            "prefill_s": t_pre}
+    return {"value": w.batch * steps / t_dec, "unit": "tokens/s", "cores": host_threads(), "kind": "oracle",
+            "sample": "%s: full 32-layer prefill (%.2f s) then %d decode steps of 32 layers (%.2f s)" % (w.name, t_pre, steps, t_dec),
+            "prefill_tflops_fp64": prefill_flops_per_layer(w) * w.n_layers / t_pre / 1e12}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--decode-batched-steps", type=int, default=16)
     ap.add_argument("--prefill-reps", type=int, default=3)
     ap.add_argument("--skip-extra", action="store_true", help="headline workload only")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
-                    help="headline workload: ordinary qc_decode calls instead of one HIP-graph replay per decode step")
-    ap.add_argument("--only", choices=["decode_batched", "prefill_highres", "gla_decode_batched", "selection", "projection", "pruning",
-                                      "capacity", "video"],
-                    help="profiling aid: run just this extra workload and print its object")
+                    help="batch-1 workload: ordinary qc_decode calls instead of one HIP-graph replay per decode step")
+    ap.add_argument("--only", choices=["headline", "cfg2", "decode_batched", "prefill_highres", "gla_decode_batched", "selection",
+                                      "projection", "pruning", "capacity", "prefill_long"],
+                    help="profiling aid: run just this workload and print its object")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profiling aid: run plain 1 GiB device copies (known HBM traffic) and exit")
     args = ap.parse_args()
@@ -755,6 +885,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the library has no CPU path")
     import paper_2602_01901_amd as P
+    import workloads
     P.load_library()
 
     if args.copy_calibration:
@@ -768,24 +899,27 @@ def main():
                                                "launches": 5}}))
         return
     if args.only:
-        fn = {"decode_batched": bench_decode_batched, "prefill_highres": bench_prefill_highres,
+        fn = {"headline": lambda a: bench_headline(a)[1], "cfg2": bench_cfg2,
+              "decode_batched": bench_decode_batched, "prefill_highres": bench_prefill_highres,
               "gla_decode_batched": bench_gla_decode_batched, "selection": bench_selection,
-              "projection": bench_projection, "pruning": bench_pruning, "capacity": bench_capacity, "video": bench_video}[args.only]
+              "projection": bench_projection, "pruning": bench_pruning, "capacity": bench_capacity,
+              "prefill_long": bench_prefill_long}[args.only]
         print(json.dumps({args.only: fn(args)}))
         return
 
-    w, r = bench_cfg2(args)
-    log("cfg2 done: %.1f tok/s decode, prefill %.2f TFLOP/s" % (r["decode_tokens_per_s"], r["prefill_tflops"]))
+    w, r = bench_headline(args)
+    log("cfg5 done: %.1f tok/s decode (%.0f GB/s in the streaming kernel), prefill %.1f TFLOP/s"
+        % (r["decode_tokens_per_s"], r["roofline"]["achieved"], r["prefill_tflops"]))
     extra = {}
     if not args.skip_extra:
+        extra["llava15_7b_b1"] = bench_cfg2(args)
+        log("cfg2 done: %.1f tok/s decode, prefill %.2f TFLOP/s" % (extra["llava15_7b_b1"]["decode_tokens_per_s"],
+                                                                   extra["llava15_7b_b1"]["prefill_tflops"]))
         extra["decode_batched"] = bench_decode_batched(args)
         log("cfg3 done: %.1f tok/s, %.0f GB/s" % (extra["decode_batched"]["decode_tokens_per_s"],
                                                  extra["decode_batched"]["roofline"]["achieved"]))
         extra["prefill_highres"] = bench_prefill_highres(args)
         log("cfg4 done: %.1f TFLOP/s" % extra["prefill_highres"]["prefill_tflops"])
-        extra["video_13b"] = bench_video(args)
-        log("cfg5 done: prefill %.1f TFLOP/s, decode %.1f tok/s" % (extra["video_13b"]["prefill_tflops"],
-                                                                 extra["video_13b"]["decode_tokens_per_s"]))
         extra["prefill_long_32k"] = bench_prefill_long(args)
         log("32k prompt done: %.1f TFLOP/s" % extra["prefill_long_32k"]["prefill_tflops"])
         extra["gla_decode_batched"] = bench_gla_decode_batched(args)
@@ -802,7 +936,15 @@ def main():
         log("pruning done: %.1f -> %.1f tok/s" % (extra["pruning"]["unpruned"]["decode_tokens_per_s"],
                                                 extra["pruning"]["pruned"]["decode_tokens_per_s"]))
         extra["capacity"] = bench_capacity(args)
-    cpu = None if args.skip_cpu else cpu_baseline()
+    cpu = None
+    if not args.skip_cpu:
+        cpu = cpu_baseline_sample(w, heads=8)
+        log("oracle on cfg5 sample: %.3f tok/s, prefill %.4f TFLOP/s fp64" % (cpu["value"], cpu["prefill_tflops_fp64"]))
+        if not args.skip_extra:
+            extra["llava15_7b_b1"]["cpu_baseline"] = cpu_baseline_cfg2()
+            extra["decode_batched"]["cpu_baseline"] = cpu_baseline_sample(workloads.config(2), heads=8)
+            extra["prefill_highres"]["cpu_baseline"] = cpu_baseline_sample(workloads.config(3), heads=8)
+            log("oracle on cfg2/cfg3/cfg4 samples done")
     line = {
         "metric": "decode_tokens_per_s", "value": r["decode_tokens_per_s"], "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
@@ -810,13 +952,12 @@ def main():
         "config": {"workload": w.name, "layers": w.n_layers, "heads": w.n_heads, "head_dim": w.head_dim,
                    "batch": w.batch, "visual_tokens": w.vis_len[0], "text_tokens": w.seq_len[0] - w.vis_len[0],
                    "decode_steps": w.decode_steps, "lazy_layers": w.n_lazy,
-                   "step": "reset + 32-layer prefill + 256 decode steps x 32 layers",
-                   "decode_launch": "ordinary qc_decode calls" if args.no_graph else
-                                    "one replay of a HIP graph of the 32 layer calls per decode step"},
+                   "step": "reset + 40-layer prefill of 4 x 4864 tokens + 1024 decode steps x 40 layers",
+                   "value_is": "tokens generated / time of the decode phases inside the timed steps (HIP events on the launch stream)",
+                   "decode_launch": "ordinary qc_decode calls"},
+        "tokens_per_s_whole_step": r["tokens_per_s_whole_step"],
         "prefill_tflops": r["prefill_tflops"], "prefill_ms": r["prefill_ms"],
-        # the headline shape's prompt (one sequence of 640 tokens) is latency-bound; the prefill-dominated
-        # configuration (batch 8 x 3008 tokens) timed in this run:
-        "prefill_tflops_highres": extra.get("prefill_highres", {}).get("prefill_tflops"),
+        "decode_phase_ms": r["decode_phase_ms"],
         "decode_ms_per_token_step": r["decode_ms_per_token_step"],
         "k_cache_bytes_per_token": r["k_cache_bytes_per_token"],
         "k_cache_bytes_per_token_after_prefill": r["k_cache_bytes_per_token_after_prefill"],
@@ -829,7 +970,7 @@ def main():
                           "kv_cache_saving": "35 % (GLA and VLA)", "max_batch": "21 -> 32",
                           "decode_throughput": "1.6x (GLA), 1.5x (VLA) over the unmodified model",
                           "efficiency_table_with_FastV": "prefill 30.88 -> 18.49 TFLOPs, 142.60 -> 67.21 ms, KV cache 1.01 -> 0.36 GB (VLA)"},
-        # the workloads that can approach a roofline on a 256-CU part, each timed in this run (details under "workloads")
+        # every workload timed in this run with a roofline figure of its own (details under "workloads")
         "roofline_summary": {k: {"bound": v["roofline"]["bound"], "frac": v["roofline"]["frac"],
                                  "achieved": v["roofline"]["achieved"], "unit": v["roofline"]["unit"]}
                              for k, v in extra.items() if isinstance(v, dict) and "roofline" in v},

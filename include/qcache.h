@@ -374,7 +374,7 @@ qc_status qc_plan_max_batch(const qc_config* cfg, size_t budget_bytes, int32_t w
  * not the small merge pass).  qc_timing_read waits for the recorded events of one kind (which = 0
  * prefill, 1 decode, 2 decode calls of lazy layers under QC_GLA, which run the score-sharing
  * variant of the kernel and are not counted under 1), returns the sum of their durations and the
- * number of launches, and starts over.  At most 16384 launches are kept between reads; further ones are not timed.  Event
+ * number of launches, and starts over.  At most 131072 launches are kept between reads; further ones are not timed.  Event
  * creation allocates: leave this off on paths that must not. */
 qc_status qc_timing_enable(qc_kvcache* kv, int32_t enable);
 qc_status qc_timing_read(qc_kvcache* kv, int32_t which, double* total_ms, int64_t* launches);

@@ -146,7 +146,7 @@ struct MetaChunk {        // by-value payload of the metadata upload kernel: up 
 // Optional instrumentation: HIP events recorded on the call's stream around the dominant kernel
 // of a layer call (prefill: the attention kernel; decode: the streaming kernel, not the merge).
 struct KernelTimer {
-  static constexpr size_t kMaxPairs = 16384;
+  static constexpr size_t kMaxPairs = 131072;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
   size_t used = 0;
   int64_t dropped = 0;
