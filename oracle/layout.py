@@ -4,22 +4,16 @@
 The paper fixes what is stored ("Efficiency Analysis", KV Cache paragraph: a
 lazy layer keeps only its text keys; every layer keeps all values; the Q Cache
 is one layer's worth of visual queries) but not where.  This module states the
-layout the library is specified to use, in closed form, so that cache contents
-can be compared byte for byte:
+row layout the library is specified to use, in closed form, so that cache contents
+can be compared byte for byte.  It covers the K and V row regions and the Q arena
+and nothing else: whatever a library keeps behind the V region for its own
+bookkeeping (per-sequence integers for its kernels, counters) is that library's
+private matter, is not described here and is checked through its queries
+(sequence lengths, row counts, row locations), never through this image.
 
   K region   layers in order; layer l holds [max_batch][H][capK(l)][D] elements,
              capK(l) = max_text for a lazy layer, max_seq otherwise.
   V region   follows the K region; layer l holds [max_batch][H][max_seq][D].
-  meta       follows the V region (256-byte aligned): int32 [2][4][max_batch].
-             Block 0: first token index in the packed prompt, prompt length,
-             vis_start, vis_len of every sequence.  Block 1: the same four rows
-             as the layers after a token-pruning boundary see them (all zero
-             when no pruning took place).  Then 256 bytes of counters: int32 [0]
-             is the number of decode steps a replayed decode graph has counted
-             (zero if none was used).  Then int32 [6][max_batch]: cap_seq,
-             base_seq, cap_text, base_text, cap_vis, base_vis of every sequence
-             when capacities are per sequence (all zero otherwise).  Total
-             rounded up to 256 bytes.
   Q arena    [max_batch][H][max_vis][D].
 
 Row maps: V row = position.  K row = position in a normal layer.  In a lazy
@@ -35,7 +29,6 @@ sequences before b, row r of head h sits at row index base[b]*H + h*cap[b] + r
 of the region.  Equal capacities (cap_seq = max_seq, ...) give back the layout
 above; the sums must fit the pools max_batch*max_seq, max_batch*max_text and
 max_batch*max_vis.  The arena then wastes nothing on a batch of unequal lengths.
-The capacities live in a third block of the meta region (below).
 
 Separately sized late layers (`late`): when a token-pruning boundary is known
 as the arena is sized, the layers from the boundary on hold max_seq_late
@@ -108,11 +101,9 @@ class ArenaLayout:
     def off_v(self, l):
         return self.off_k(self.N) + sum(self.v_layer_bytes(i) for i in range(l))
 
-    def off_meta(self):
-        return _round_up(self.off_v(self.N), 256)
-
-    def meta_bytes(self):
-        return _round_up(2 * 4 * 4 * self.max_batch + 256 + 6 * 4 * self.max_batch, 256)
+    def rows_bytes(self):
+        """Bytes of the K and V row regions together: everything this module describes of the K/V arena."""
+        return self.off_v(self.N)
 
     def _row_index(self, kind, uniform_cap, b, h, row):
         """Row index inside a region of `kind` rows ("seq", "text" or "vis")."""
@@ -124,9 +115,6 @@ class ArenaLayout:
 
     def _k_kind(self, l):
         return "text" if (self.lazy[l] and self.mode == "vla") else "seq"
-
-    def kv_arena_bytes(self):
-        return self.off_meta() + self.meta_bytes()
 
     def q_arena_bytes(self):
         return self.max_batch * self.H * self.cap_q() * self.D * self.e
@@ -177,13 +165,10 @@ def encode_rows(x, dtype):
     return (bits >> 16).astype(np.uint16).view(np.uint8)
 
 
-def kv_arena_image(layout, stacks, tok0=None, graph_steps=0):
-    """Expected bytes of the whole K/V arena given one stack oracle (of the layout's mode) per sequence.
-
-    Unwritten bytes are zero.  `tok0[b]` is the first packed-prompt token index
-    of sequence b (default: prompts packed back to back in batch order).
-    """
-    img = np.zeros(layout.kv_arena_bytes(), dtype=np.uint8)
+def kv_rows_image(layout, stacks):
+    """Expected bytes of the K and V row regions (the first rows_bytes() bytes of the K/V arena) given one
+    stack oracle (of the layout's mode) per sequence.  Unwritten bytes are zero."""
+    img = np.zeros(layout.rows_bytes(), dtype=np.uint8)
     rowb = layout.D * layout.e
     for b, st in enumerate(stacks):
         for l in range(layout.N):
@@ -194,33 +179,6 @@ def kv_arena_image(layout, stacks, tok0=None, graph_steps=0):
                 vr = st.Vc[l][h]
                 o = layout.v_offset(l, b, h, 0)
                 img[o:o + vr.shape[0] * rowb] = encode_rows(vr, layout.dtype).reshape(-1)
-    meta = np.zeros((2, 4, layout.max_batch), dtype=np.int32)
-    start = start_late = 0
-    for b, st in enumerate(stacks):
-        meta[0, 0, b] = start if tok0 is None else tok0[b]
-        meta[0, 1, b] = st.prefill_len
-        meta[0, 2, b] = st.s
-        meta[0, 3, b] = st.Vn
-        start += st.prefill_len
-        late = getattr(st, "late", None)          # a stack pruned between two layers (oracle.pruning)
-        if late is not None and late.prefill_len:
-            meta[1, 0, b] = start_late
-            meta[1, 1, b] = late.prefill_len
-            meta[1, 2, b] = late.s
-            meta[1, 3, b] = late.Vn
-            start_late += late.prefill_len
-    o = layout.off_meta()
-    img[o:o + meta.nbytes] = meta.view(np.uint8).reshape(-1)
-    # the device-side step counter (graph_steps: its value if a decode graph has been replayed)
-    img[o + meta.nbytes:o + meta.nbytes + 4] = np.array([graph_steps], dtype=np.int32).view(np.uint8)
-    if layout.ragged is not None:
-        caps = np.zeros((6, layout.max_batch), dtype=np.int32)
-        for i, kind in enumerate(("seq", "text", "vis")):
-            cap, base = layout.ragged[kind]
-            caps[2 * i, :len(cap)] = cap
-            caps[2 * i + 1, :len(base)] = base
-        o2 = o + meta.nbytes + 256
-        img[o2:o2 + caps.nbytes] = caps.view(np.uint8).reshape(-1)
     return img
 
 
@@ -273,14 +231,17 @@ def q_cache_share_closed_form(n_layers):
 
 
 def max_batch_within(budget_bytes, n_layers, n_heads, head_dim, dtype, max_seq, max_vis, max_text, lazy_mask,
-                     mode="vla", count_q=False):
-    """Largest batch whose K/V arena (plus the Q arena with count_q) fits the budget: the comparison
-    behind the maximum-batch figures of the "Efficiency Evaluation" paragraph.  Plain search upward."""
+                     mode="vla", count_q=False, overhead=None):
+    """Largest batch whose K and V rows (plus the Q arena with count_q) fit the budget: the comparison
+    behind the maximum-batch figures of the "Efficiency Evaluation" paragraph.  Plain search upward.
+    `overhead(batch, rows_bytes)` -> bytes an implementation keeps beside the rows (default: none)."""
     batch = 0
     while True:
         lay = ArenaLayout(n_layers, n_heads, head_dim, dtype, batch + 1, max_seq, max_vis, max_text, lazy_mask,
                           mode=mode)
-        need = lay.kv_arena_bytes() + (lay.q_arena_bytes() if count_q else 0)
+        need = lay.rows_bytes() + (lay.q_arena_bytes() if count_q else 0)
+        if overhead is not None:
+            need += overhead(batch + 1, lay.rows_bytes())
         if need > budget_bytes:
             return batch
         batch += 1

@@ -48,6 +48,25 @@ def oracle_decode_layer(w, stacks, layer, q, k, v):
     return np.stack([stacks[b].decode(layer, q64[b], k64[b], v64[b]) for b in range(w.batch)], axis=0)
 
 
+def check_kv_rows(session, lay, stacks):
+    """The K and V row regions byte for byte against the oracle's image, and what the library keeps of
+    each sequence beside them through its own queries (the oracle does not describe those bytes)."""
+    want = olayout.kv_rows_image(lay, stacks)
+    got = session.kv_arena[: lay.rows_bytes()].cpu().numpy()
+    assert got.shape == want.shape
+    assert np.array_equal(got, want), "K/V rows differ from the oracle's image"
+    from paper_2602_01901_amd import binding as B
+    for b, st in enumerate(stacks):
+        late = getattr(st, "late", None)        # a stack pruned between two layers keeps its unpruned length in `early`
+        want_len = (st.early.len if late is not None and hasattr(st, "early") else st.len)
+        if want_len:
+            assert B.qc_seq_len(session.kv, b) == want_len, b
+    for l in range(lay.N):
+        rk, rv = B.qc_layer_rows(session.kv, l)
+        assert rk == sum(st.Kc[l].shape[1] for st in stacks), l
+        assert rv == sum(st.Vc[l].shape[1] for st in stacks), l
+
+
 def max_abs_err(gpu_tensor, ref64):
     return float(np.max(np.abs(workloads.to_f64(gpu_tensor) - ref64)))
 
@@ -96,10 +115,7 @@ def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=Tru
     torch.cuda.synchronize()
     if check_arena:
         lay = oracle_layout(w, mode, caps)
-        want_kv = olayout.kv_arena_image(lay, stacks)
-        got_kv = session.kv_arena.cpu().numpy()
-        assert got_kv.shape == want_kv.shape
-        assert np.array_equal(got_kv, want_kv), "K/V arena differs from the oracle's image"
+        check_kv_rows(session, lay, stacks)
         want_q = olayout.q_arena_image(lay, stacks)
         got_q = session.q_arena.cpu().numpy()[: lay.q_arena_bytes()]
         assert np.array_equal(got_q, want_q), "Q Cache arena differs from the oracle's image"

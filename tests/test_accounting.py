@@ -67,7 +67,7 @@ def test_max_batch_figures_of_the_paper_follow_from_the_cache_layout():
     H, D, L = 32, 128, 2048
     mask = [0] * (N_ - n) + [1] * n
     mask = [0] + mask[1:] if mask[0] else mask          # layer 0 stays ordinary
-    per_seq = lambda m, mode: (layout.ArenaLayout(N_, H, D, "bf16", 1, L, L, L, m, mode=mode).off_meta())
+    per_seq = lambda m, mode: (layout.ArenaLayout(N_, H, D, "bf16", 1, L, L, L, m, mode=mode).rows_bytes())
     budget = b0 * per_seq([0] * N_, "vla")
     assert budget // per_seq(mask, "gla") == b1
     assert (b0 + 1) * per_seq([0] * N_, "vla") > budget   # 22 plain sequences do not fit

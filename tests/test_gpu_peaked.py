@@ -70,7 +70,7 @@ def test_peaked_graph_replays(mode):
     g = s.decode_graph(*bufs)
     assert workloads.PEAK_STEP == 1
     worst = run_steps(w, s, stacks, mode, g, bufs, "egg")
-    check_caches(w, s, stacks, mode, graph_steps=3)
+    check_caches(w, s, stacks, mode)
     print("peaked graph %s: worst %.3g" % (mode, worst), flush=True)
     s.close()
 

@@ -75,7 +75,7 @@ def test_ragged_capacities_with_graph_replays_and_pruning(mode):
     bufs = step_buffers(w, mode)
     g = s.decode_graph(*bufs)
     run_steps(w, s, stacks, mode, g, bufs, "gegg")
-    check_caches(w, s, stacks, mode, graph_steps=4, caps=caps)
+    check_caches(w, s, stacks, mode, caps=caps)
     s.close()
     assert run_pruned_parity(w, 3, [40, 20, 5], mode, 3, caps=caps) <= TOL[dtype]
 

@@ -64,7 +64,7 @@ def test_random_configuration(seed):
         schedule = "".join(str(rng.choice(["g", "e"])) for _ in range(w.decode_steps))
         run_steps(w, s, stacks, mode, g, bufs, schedule)
         last_g = max([i for i, c in enumerate(schedule) if c == "g"], default=-1)
-        check_caches(w, s, stacks, mode, graph_steps=last_g + 1)
+        check_caches(w, s, stacks, mode)
         s.close()
     else:                                                # pruning boundary before a random ordinary layer
         candidates = [l for l in range(1, w.n_layers) if not w.lazy_mask[l]]

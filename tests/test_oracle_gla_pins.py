@@ -251,12 +251,12 @@ def test_gla_layout_sizes_and_row_map():
     assert lay.off_k(4) == 2 * 3 * 2 * 20 * row                  # two ordinary layers only
     assert lay.off_v(1) - lay.off_v(0) == 3 * 2 * 20 * row
     assert lay.q_arena_bytes() == 3 * 2 * 20 * row               # every position, not only the span
-    assert lay.kv_arena_bytes() == lay.off_meta() + 512           # 2 x 48 bytes of per-sequence integers + 256 of counters, rounded up
+    assert lay.rows_bytes() == lay.off_k(4) + 4 * 3 * 2 * 20 * row  # K rows of two layers, V rows of all four
     for pos in (0, 7, 19):
         assert lay.locate_k(2, 1, 1, pos, 3, 5) == (0, lay.k_offset(0, 1, 1, pos))
         assert lay.locate_k(3, 1, 1, pos, 3, 5) == (3, lay.k_offset(3, 1, 1, pos))
     vla = layout.ArenaLayout(4, 2, 64, "bf16", 3, 20, 12, 9, [0, 1, 1, 0])
-    assert vla.kv_arena_bytes() - lay.kv_arena_bytes() == 2 * 3 * 2 * 9 * row
+    assert vla.rows_bytes() - lay.rows_bytes() == 2 * 3 * 2 * 9 * row
 
 
 def test_arena_images_hold_the_oracles_rows():
@@ -270,7 +270,7 @@ def test_arena_images_hold_the_oracles_rows():
         for l in range(N):
             st.prefill(l, *ins[l])
         sts.append((st, ins))
-    img = layout.kv_arena_image(lay, [s for s, _ in sts])
+    img = layout.kv_rows_image(lay, [s for s, _ in sts])
     qimg = layout.q_arena_image(lay, [s for s, _ in sts])
     st, ins = sts[1]
     o = lay.v_offset(1, 1, 1, 2)
@@ -278,5 +278,3 @@ def test_arena_images_hold_the_oracles_rows():
     o = lay.q_offset(1, 0, 2)
     np.testing.assert_array_equal(qimg[o:o + D * 4].view(np.float32), np.float32(ins[0][0][2, 0]))
     assert lay.off_k(2) == lay.off_k(1)                           # the lazy layer owns no K bytes
-    meta = img[lay.off_meta():lay.off_meta() + 32].view(np.int32).reshape(4, 2)
-    assert meta.tolist() == [[0, L], [L, L - 1], [1, 1], [2, 2]]

@@ -384,9 +384,9 @@ def test_kv_saving_matches_paper_closed_form(N, n, V, T, want):
 
 
 def test_layout_offsets_are_a_dense_non_overlapping_tiling():
-    """Enumerate every element slot of a small arena: K rows, V rows, meta tile [0, size) exactly once."""
+    """Enumerate every element slot of a small arena: K rows and V rows tile [0, rows_bytes) exactly once."""
     lay = layout.ArenaLayout(3, 2, 4, "bf16", 2, 6, 3, 4, [0, 1, 0])
-    seen = np.zeros(lay.kv_arena_bytes(), dtype=np.int32)
+    seen = np.zeros(lay.rows_bytes(), dtype=np.int32)
     rowb = lay.D * lay.e
     for l in range(3):
         for b in range(2):
@@ -397,9 +397,8 @@ def test_layout_offsets_are_a_dense_non_overlapping_tiling():
                 for r in range(lay.max_seq):
                     o = lay.v_offset(l, b, h, r)
                     seen[o:o + rowb] += 1
-    assert lay.off_meta() % 256 == 0
-    seen[lay.off_meta():] += 1
-    assert np.all(seen[:lay.off_v(3)] == 1) and np.all(seen[lay.off_meta():] == 1)
+    assert lay.rows_bytes() == lay.off_v(3)
+    assert np.all(seen == 1)
     assert lay.cap_k(1) == 4 and lay.cap_k(0) == 6
     # lazy layers allocate fewer bytes, not just fewer resident rows
     assert lay.k_layer_bytes(1) * 6 == lay.k_layer_bytes(0) * 4
@@ -418,7 +417,8 @@ def test_arena_image_places_rows_where_locate_says():
             st.prefill(l, *x[l])
         stacks.append(st)
         inputs.append(x)
-    img = layout.kv_arena_image(lay, stacks)
+    img = layout.kv_rows_image(lay, stacks)
+    assert img.shape == (lay.rows_bytes(),)
     for b in range(2):
         for l in range(N):
             for h in range(H):
@@ -431,8 +431,6 @@ def test_arena_image_places_rows_where_locate_says():
                     _, off = lay.locate_v(l, b, h, pos)
                     assert np.array_equal(img[off:off + D * 4].view(np.float32),
                                           inputs[b][l][2][pos, h].astype(np.float32))
-    meta = img[lay.off_meta():lay.off_meta() + 32].view(np.int32).reshape(4, 2)
-    assert meta.tolist() == [[0, L], [L, L], [s, s], [Vn, Vn]]
 
 
 def test_encode_rows_bf16_is_exact_or_refuses():

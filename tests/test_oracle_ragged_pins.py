@@ -27,7 +27,7 @@ def test_equal_capacities_give_back_the_uniform_layout(mode):
     args = (4, 3, 64, "f32", 3, 20, 12, 9, [0, 1, 1, 0])
     a = ArenaLayout(*args, mode=mode)
     b = ArenaLayout(*args, mode=mode, ragged=([20] * 3, [9] * 3, [12] * 3))
-    assert a.kv_arena_bytes() == b.kv_arena_bytes() and a.q_arena_bytes() == b.q_arena_bytes()
+    assert a.rows_bytes() == b.rows_bytes() and a.q_arena_bytes() == b.q_arena_bytes()
     for l in range(4):
         for s in range(3):
             for h in range(3):
@@ -46,7 +46,7 @@ def test_rows_are_disjoint_and_inside_their_regions(mode):
     caps = ([24, 8, 40, 8], [16, 0, 8, 8], [10, 8, 30, 0])
     lay = ArenaLayout(3, 2, 64, "bf16", 4, 20, 12, 8, [0, 1, 0], mode=mode, ragged=caps)
     rowb = 128
-    owner = np.full(lay.off_meta() // rowb, -1, dtype=np.int64)
+    owner = np.full(lay.rows_bytes() // rowb, -1, dtype=np.int64)
     tag = 0
     for l in range(3):
         k_caps = caps[0] if lay._k_kind(l) == "seq" else caps[1]
@@ -93,5 +93,5 @@ def test_smaller_late_layers_worked_by_hand_and_against_the_uniform_layout():
     # a late capacity equal to max_seq changes nothing
     a = ArenaLayout(4, 2, 64, "bf16", 3, 20, 12, 9, [0, 0, 1, 0])
     b = ArenaLayout(4, 2, 64, "bf16", 3, 20, 12, 9, [0, 0, 1, 0], late=(1, 20))
-    assert a.kv_arena_bytes() == b.kv_arena_bytes()
+    assert a.rows_bytes() == b.rows_bytes()
     assert all(a.v_offset(l, 2, 1, 19) == b.v_offset(l, 2, 1, 19) and a.off_k(l) == b.off_k(l) for l in range(4))
