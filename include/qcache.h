@@ -308,8 +308,9 @@ qc_status qc_project_qk(const void* x, int64_t x_stride, const void* w_q, const 
  *   workspace: DEVICE, at least qc_select_workspace_bytes(cfg).  Requires a finished prefill pass, or
  *   an open one in which `layer` has already run (QC_EORDER otherwise; not between the layers of a
  *   decode step), and an ordinary `layer` (QC_EINVAL: a lazy layer does not hold all its keys).
- * qc_attention_similarity: js_out[i] = JS(probs_m row i, probs_n row i) over lens[i] entries, in bits
- *   (JS = (KL(p||m) + KL(q||m))/2, m = (p+q)/2, terms with zero probability contribute zero), and
+ * qc_attention_similarity: js_out[i] = JS(probs_m row i, probs_n row i) over lens[i] entries, in nats
+ *   (JS = (KL(p||m) + KL(q||m))/2, m = (p+q)/2, natural logarithm so that JS <= ln 2, terms with zero
+ *   probability contribute zero), and
  *   *s_out = their mean over the n_samples rows = S(l_m, l_n) of Eq. 3.  probs_m, probs_n, js_out,
  *   s_out: DEVICE fp32; lens: HOST, n_samples entries, each 1..stride.
  * qc_lazy_mask_from_similarity (host only): Eq. 4.  adjacent[i] = S(l_i, l_i+1), i = 0..n_layers-2;

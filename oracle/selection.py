@@ -9,11 +9,12 @@ Follows the paper's "Lazy Attention" subsection:
   S(l_i, l_i+1) < epsilon, 0 < epsilon <= 1; its first layer stays an ordinary layer, the others
   become lazy layers.
 
-Readings taken where the paper is silent (also listed in the design notes): "we average results
-across all attention heads" is applied to the attention rows (a^l is the mean over heads of the
-per-head last rows, as in the token-pruning work the paper cites for the last-row idea);
-logarithms are base 2, which is what bounds JS by 1 and matches the stated range of epsilon;
-terms with zero probability contribute zero; blocks are maximal runs.
+Readings taken where the paper is silent (also listed in the design notes): the averaging over
+attention heads that the paragraph before Eq. 3 mentions is applied to the attention rows (a^l is
+the mean over heads of the per-head last rows, as in the token-pruning work the paper cites for the
+last-row idea); logarithms are natural, so that JS <= ln 2 (the appendix on similarity inside the
+language model plots ln 2 - S, which fixes the unit; the stated range 0 < epsilon <= 1 is then a
+loose bound); terms with zero probability contribute zero; blocks are maximal runs.
 
 All arithmetic is fp64.
 """
@@ -30,12 +31,12 @@ def last_row_attention(q_last, K, scale):
     return attention.softmax_lastaxis(scores).mean(axis=0)
 
 
-def kl_divergence_bits(p, m):
-    """KL(p || m) in bits; entries with p = 0 contribute nothing."""
+def kl_divergence(p, m):
+    """KL(p || m) in nats; entries with p = 0 contribute nothing."""
     p = np.asarray(p, dtype=np.float64)
     m = np.asarray(m, dtype=np.float64)
     nz = p > 0
-    return float(np.sum(p[nz] * (np.log2(p[nz]) - np.log2(m[nz]))))
+    return float(np.sum(p[nz] * (np.log(p[nz]) - np.log(m[nz]))))
 
 
 def js_divergence(p, q):
@@ -43,7 +44,7 @@ def js_divergence(p, q):
     p = np.asarray(p, dtype=np.float64)
     q = np.asarray(q, dtype=np.float64)
     m = (p + q) / 2.0
-    return 0.5 * (kl_divergence_bits(p, m) + kl_divergence_bits(q, m))
+    return 0.5 * (kl_divergence(p, m) + kl_divergence(q, m))
 
 
 def similarity(rows_m, rows_n):

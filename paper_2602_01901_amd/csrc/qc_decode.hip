@@ -22,6 +22,13 @@
 
 #include "qc_device.h"
 
+#ifndef QC_U_SHARED
+#define QC_U_SHARED 8
+#endif
+#ifndef QC_U_PLAIN
+#define QC_U_PLAIN 4
+#endif
+
 namespace qc {
 
 // ---- scratch memory for callers that cannot allocate ----------------------------------------------
@@ -92,7 +99,7 @@ __device__ __forceinline__ void decode_split_body(const DecodeArgs& a, const Dec
   constexpr int LPR = D / EPL;                // lanes per row
   constexpr int GPW = 64 / LPR;               // row groups per wave
   constexpr int GROUPS = 4 * GPW;             // row groups per workgroup
-  constexpr int U = SHARED ? 8 : 4;           // rows in flight per group
+  constexpr int U = SHARED ? QC_U_SHARED : QC_U_PLAIN;   // rows in flight per group
   constexpr int ROWB = D * (int)sizeof(T);
 
   const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;

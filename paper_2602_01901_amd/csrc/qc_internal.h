@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <utility>
 #include <vector>
 
@@ -186,6 +187,19 @@ struct KernelTimer {
     for (auto& p : pool) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
   }
 };
+
+// Raises a kernel's dynamic-LDS limit once per device (the attribute belongs to the device's copy of the
+// kernel).  `done` holds one bit per device; concurrent callers at worst both set the same value.
+inline hipError_t ensure_dynamic_lds(const void* kernel, int bytes, std::atomic<unsigned long long>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < 64;
+  if (tracked && ((done.load(std::memory_order_acquire) >> dev) & 1ull)) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && tracked) done.fetch_or(1ull << dev, std::memory_order_release);
+  return e;
+}
 
 hipError_t launch_fill_zero(void* dev, size_t bytes, hipStream_t stream);
 hipError_t launch_counter_update(int32_t* counter, int32_t value, int32_t add, hipStream_t stream);

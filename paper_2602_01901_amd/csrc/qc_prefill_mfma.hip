@@ -365,13 +365,9 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
 }
 
 hipError_t launch_prefill_mfma_bf16_d128(const PrefillArgs& a, hipStream_t stream, KernelTimer* timer) {
-  static bool attr_set = false;
+  static std::atomic<unsigned long long> attr_set{0};
   constexpr int lds_bytes = pf::STAGES * pf::STAGE;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)prefill_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  if (hipError_t e = ensure_dynamic_lds((const void*)prefill_mfma_kernel, lds_bytes, attr_set); e != hipSuccess) return e;
   const int n_qt = (a.max_len + pf::BM - 1) / pf::BM;
   const int nbh = a.batch * a.n_heads;
   if (timer) timer->begin(stream);

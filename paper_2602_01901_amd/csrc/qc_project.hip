@@ -464,12 +464,8 @@ __global__ __launch_bounds__(256) void project_qk_skinny_staged_kernel(ProjectAr
 }
 
 template <int D> static hipError_t launch_skinny_staged_t(const ProjectArgs& a, int n_rows, hipStream_t stream) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)project_qk_skinny_staged_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, sk::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<unsigned long long> attr_set{0};
+  if (hipError_t e = ensure_dynamic_lds((const void*)project_qk_skinny_staged_kernel<D>, sk::LDS_BYTES, attr_set); e != hipSuccess) return e;
   hipLaunchKernelGGL(project_qk_skinny_staged_kernel<D>, dim3(a.n_heads * (D / 32), 2), dim3(256), sk::LDS_BYTES, stream, a, n_rows);
   return hipGetLastError();
 }
@@ -487,13 +483,9 @@ hipError_t launch_project_qk_skinny(const ProjectArgs& a, int n_rows, hipStream_
 
 template <int D, int MB>
 static hipError_t launch_project_qk_t(const ProjectArgs& a, int rows, hipStream_t stream) {
-  static bool attr_set = false;
+  static std::atomic<unsigned long long> attr_set{0};
   constexpr int lds_bytes = pj::Shape<MB>::LDS_BYTES;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)project_qk_kernel<D, MB>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  if (hipError_t e = ensure_dynamic_lds((const void*)project_qk_kernel<D, MB>, lds_bytes, attr_set); e != hipSuccess) return e;
   const int m_tiles = (rows + pj::Shape<MB>::BM - 1) / pj::Shape<MB>::BM;
   const int nt2 = 2 * (a.n_heads * a.head_dim / pj::BN);
   hipLaunchKernelGGL((project_qk_kernel<D, MB>), dim3(m_tiles * nt2), dim3(512), lds_bytes, stream, a, m_tiles);

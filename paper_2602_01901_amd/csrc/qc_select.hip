@@ -6,7 +6,7 @@
 //                            prompt token against every cached key, plus the row's (max, sum).
 //   last_row_probs_kernel  : one thread per position: mean over heads of exp2(s - max) / sum.
 //   js_kernel / mean_kernel: one workgroup per sample, fixed-order tree reductions (bitwise
-//                            reproducible), base-2 logarithms, 0 log 0 = 0.
+//                            reproducible), natural logarithms (JS <= ln 2), 0 log 0 = 0.
 #include "qc_device.h"
 
 namespace qc {
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void js_kernel(const float* pm, const float* p
     if (y > 0.f) acc += y * (__log2f(y) - lm);
   }
   const float tot = block_sum_256(acc, lds);
-  if (threadIdx.x == 0) js_out[first + i] = 0.5f * tot;
+  if (threadIdx.x == 0) js_out[first + i] = 0.5f * 0.6931471805599453f * tot;   // base-2 logarithms above: to nats
 }
 
 __global__ __launch_bounds__(256) void mean_kernel(const float* x, int n, float* out) {

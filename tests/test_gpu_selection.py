@@ -2,7 +2,7 @@
 
 Tolerances (fp32 kernels against fp64): a probability is exp2 of a 64..128-term fp32 dot product
 divided by a sum of such terms, so its relative error is a few 1e-6 times the score magnitude;
-the bar is |err| <= 1e-5 + 1e-4*|p|.  JS and S are sums of p*log2 terms bounded by 1: bar 1e-4.
+the bar is |err| <= 1e-5 + 1e-4*|p|.  JS and S are sums of p*ln terms bounded by ln 2: bar 1e-4.
 The block decision of Eq. 4 is taken from the same fp32 similarities on both sides."""
 import numpy as np
 import pytest
@@ -111,7 +111,7 @@ def test_similarity_special_cases_and_many_samples():
         if i % 3 == 1:
             assert got[i] == 0.0
         if i % 3 == 0 and L > 1:
-            assert abs(got[i] - 1.0) < 1e-5
+            assert abs(got[i] - np.log(2.0)) < 1e-5       # disjoint supports: the upper bound ln 2
     assert abs(float(sim.item()) - want.mean()) <= 1e-4
 
 
@@ -148,5 +148,5 @@ def test_selection_pipeline_at_the_7b_shape_finds_planted_blocks():
     inside = [a for a, f in zip(adjacent, planted[1:]) if f]
     across = [a for a, f in zip(adjacent, planted[1:]) if not f]
     print("similarity inside blocks max %.3g, across blocks min %.3g" % (max(inside), min(across)), flush=True)
-    assert max(inside) == 0.0 and min(across) > 0.01      # head averaging flattens unrelated rows: about 0.018 bits
+    assert max(inside) == 0.0 and min(across) > 0.007     # head averaging flattens unrelated rows: about 0.012 nats
     assert B.qc_lazy_mask_from_similarity(adjacent, 0.005) == planted
