@@ -581,6 +581,21 @@ def bench_pruning(args):
         del r
         torch.cuda.empty_cache()
     out["decode_speedup"] = out["pruned"]["decode_tokens_per_s"] / out["unpruned"]["decode_tokens_per_s"]
+    # survivor selection alone at the spans of the other configurations (half of every span kept): one
+    # workgroup per sequence, O(span) work, latency-bound
+    sizes = {}
+    for name, cfg_i in (("cfg2_576x1", 1), ("cfg4_2880x8", 3), ("cfg5_4608x4", 4)):
+        wc = workloads.config(cfg_i)
+        stride = max(wc.seq_len)
+        g = torch.Generator(device="cuda").manual_seed(0x51C0 + 99)
+        sc = torch.rand((wc.batch, stride), generator=g, device="cuda", dtype=torch.float32)
+        keep = [v // 2 for v in wc.vis_len]
+        rm = torch.zeros(sum(L - v + k for L, v, k in zip(wc.seq_len, wc.vis_len, keep)), dtype=torch.int32, device="cuda")
+        run = lambda: B.qc_prune_select(sc, stride, wc.batch, wc.cu_seqlens, wc.vis_start, wc.vis_len, keep, rm)
+        run()
+        _, sel_s = timed(torch, run, 20)
+        sizes[name] = {"visual_tokens": wc.vis_len[0], "batch": wc.batch, "select_us": sel_s * 1e6}
+    out["select_by_span"] = sizes
     return out
 
 

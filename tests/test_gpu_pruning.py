@@ -57,6 +57,53 @@ def test_survivor_selection_matches_oracle(case):
     assert np.array_equal(got, want)
 
 
+def adversarial_scores(kind, V, rng):
+    """Finite score vectors that stress a selection: every key byte pattern the radix passes can meet."""
+    if kind == "all_equal":
+        return np.full(V, 0.25, dtype=np.float32)
+    if kind == "two_values":
+        return rng.choice(np.array([0.5, 0.5000001], dtype=np.float32), size=V)          # differ in the last key byte only
+    if kind == "ascending":
+        return np.arange(V, dtype=np.float32) * np.float32(1e-4)
+    if kind == "descending":
+        return (V - np.arange(V, dtype=np.float32)) * np.float32(1e-4)
+    if kind == "softmax_like":                                                             # what the ranking really sees
+        x = rng.standard_normal(V).astype(np.float32) * 4
+        e = np.exp(x - x.max())
+        return (e / e.sum()).astype(np.float32)
+    if kind == "mixed_signs_and_denormals":
+        x = rng.standard_normal(V).astype(np.float32)
+        x[::7] = 0.0
+        x[3::7] = -0.0
+        x[5::11] = np.float32(1e-41)                                                       # denormal
+        x[6::13] = -np.float32(3e38)
+        return x
+    if kind == "shared_prefix":                                                            # equal top three key bytes, random last byte
+        base = np.float32(1.0).view(np.uint32)
+        return (base + rng.integers(0, 256, size=V).astype(np.uint32)).view(np.float32)
+    raise ValueError(kind)
+
+
+@pytest.mark.parametrize("V", [576, 2880, 4608, 32000])
+@pytest.mark.parametrize("kind", ["all_equal", "two_values", "ascending", "descending", "softmax_like",
+                                  "mixed_signs_and_denormals", "shared_prefix"])
+def test_survivor_selection_large_spans_and_adversarial_scores(V, kind):
+    """The span sizes of the benchmark configurations (one image, five tiles, eight frames) and one far
+    beyond them, with keep at both ends, in the middle and next to the ends."""
+    rng = np.random.default_rng(V + len(kind))
+    keeps = [0, 1, V // 2, V - 1, V, V // 3 + 1]
+    lens = [V + 40 + 3 * i for i in range(len(keeps))]
+    vs = [7 + i for i in range(len(keeps))]
+    vl = [V] * len(keeps)
+    stride = max(lens) + 5
+    sc = rng.random((len(keeps), stride)).astype(np.float32)
+    for b in range(len(keeps)):
+        sc[b, vs[b]: vs[b] + V] = adversarial_scores(kind, V, rng)
+    got, _ = select_on_gpu(torch.from_numpy(sc).cuda(), lens, vs, vl, keeps)
+    kept = [kept_visual_positions(sc[b], vs[b], vl[b], keeps[b]) for b in range(len(keeps))]
+    assert np.array_equal(got, packed_row_map(lens, vs, vl, kept))
+
+
 def test_survivor_selection_stays_in_bounds_with_nan_scores():
     lens, vs, vl, keep = [50, 60], [4, 0], [40, 60], [10, 30]
     sc = np.random.default_rng(3).random((2, 64)).astype(np.float32)
