@@ -712,10 +712,39 @@ def bench_ragged_arena(args):
         _, ev_s = timed(torch, lambda: run(steps), 1)
         res[name] = {"kv_arena_bytes": s.kv_bytes, "q_arena_bytes": s.q_bytes, "max_seq": w.max_seq, "max_text": w.max_text,
                      "decode_tokens_per_s": w.batch * steps / ev_s}
+        if caps:
+            # Four pairs of neighbouring slots leave and come back, the second of each pair first (qc_seq_leave /
+            # qc_seq_join): first-fit then fills each pair's hole in the other order, so slot order and row
+            # order differ (the arena has no spare rows, so this is the reordering that is sure to fit).
+            # Prefill pass over the eight, then the same timed decode steps for the whole batch.
+            pairs = [(b, b + 1) for b in range(2, w.batch - 1, 8)]
+            movers = sorted(b for pr in pairs for b in pr)
+            B = P.binding
+            for b in movers:
+                s.seq_leave(b)
+            for lo, hi in pairs:
+                for b in (hi, lo):
+                    s.seq_join(b, w.vis_start[b], w.vis_len[b], caps[0][b], caps[1][b])
+            moved = sum(B.qc_seq_extent(s.kv, b)[1] != sum(caps[0][:b]) for b in movers)
+            cu = [0]
+            for b in range(w.batch):
+                cu.append(cu[-1] + (w.seq_len[b] if b in movers else 0))
+            rows = torch.cat([torch.arange(w.cu_seqlens[b], w.cu_seqlens[b + 1], device=s.device) for b in movers])
+            qj, kj, vj = q[rows], k[rows], v[rows]
+            oj = torch.empty_like(vj)
+            for l in range(w.n_layers):
+                s.prefill(l, qj, kj, vj, cu, out=oj)
+            run(2)
+            _, ev_j = timed(torch, lambda: run(steps), 1)
+            res["after_leave_and_join"] = {"sequences_moved": len(movers), "extents_at_new_rows": int(moved),
+                                           "decode_tokens_per_s": w.batch * steps / ev_j}
+            del qj, kj, vj, oj
         s.close()
         del s, q, k, v, o
         torch.cuda.empty_cache()
     res["arena_bytes_ratio"] = res["per_sequence_capacities"]["kv_arena_bytes"] / res["one_capacity_for_all"]["kv_arena_bytes"]
+    res["decode_rate_vs_one_capacity"] = {k: res[k]["decode_tokens_per_s"] / res["one_capacity_for_all"]["decode_tokens_per_s"]
+                                          for k in ("per_sequence_capacities", "after_leave_and_join")}
     return res
 
 

@@ -158,8 +158,8 @@ qc_status qc_reset(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* 
  * head h start at row (sum of the capacities before b)*n_heads + h*cap[b]; the Q arena is split by
  * vis_len[b] in the same way), so nothing is reserved for lengths a sequence cannot reach.
  * Equal capacities reproduce the layout described under "sizes".
- *   cap_seq, cap_text: HOST, `batch` entries; cap_seq[b] a positive multiple of 8, cap_text[b] >= 0
- *   (QC_EINVAL otherwise).  QC_ECAPACITY unless sum cap_seq <= max_batch*max_seq and, under QC_VLA,
+ *   cap_seq, cap_text: HOST, `batch` entries; cap_seq[b] a positive multiple of 8 (or 0: a free slot,
+ *   see qc_seq_join), cap_text[b] >= 0 (QC_EINVAL otherwise).  QC_ECAPACITY unless sum cap_seq <= max_batch*max_seq and, under QC_VLA,
  *   sum cap_text <= max_batch*max_text and sum vis_len <= max_batch*max_vis; batch <= max_batch.
  * The capacities are written to the arena's meta region on `stream` (the call is never host-only).
  * A workspace from qc_decode_workspace_bytes / qc_select_workspace_bytes is large enough for any
@@ -167,6 +167,37 @@ qc_status qc_reset(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* 
 qc_status qc_reset_ragged(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* vis_start,
                           const int32_t* vis_len, const int32_t* cap_seq, const int32_t* cap_text,
                           int32_t zero_fill, void* stream);
+
+/* ---- sequences joining and leaving a running batch ----------------------------------------------
+ * The paper's Table 5 measures the largest batch that fits at a fixed prompt length; a server also
+ * has to take a finished sequence out of a running batch and put a new one in its place.  On a batch
+ * set up by qc_reset_ragged, `batch` is a number of slots: a slot holds a sequence or is free
+ * (cap_seq[b] = 0 at qc_reset_ragged makes slot b free from the start; its other entries are
+ * ignored).  Every call that takes per-sequence arrays or [batch]-shaped tensors keeps taking one
+ * entry or row per slot; the entries and rows of a free slot are ignored and its `out` rows are
+ * left untouched.
+ *
+ * qc_seq_leave: slot b becomes free and its rows in the three pools can be given to a later join.
+ *   Allowed between two decode steps (QC_EORDER otherwise).  Nothing is cleared.
+ * qc_seq_join: puts a new sequence into free slot b (QC_EINVAL if taken), with its span and its
+ *   capacities as in qc_reset_ragged.  Its rows are placed first-fit: at the lowest row index of
+ *   each pool (positions: max_batch*max_seq rows per head-layer; text rows: max_batch*max_text; Q
+ *   Cache rows: max_batch*max_vis) where a run of the wanted length is free; QC_ECAPACITY if a pool
+ *   has no such run (nothing is moved to make one).  Allowed between two decode steps, and between
+ *   qc_reset_ragged and the first qc_prefill.  After joins between decode steps the next calls must
+ *   be one prefill pass, qc_prefill for layers 0..n_layers-1, in which the sequences that are
+ *   already decoding take no part: their slots have no tokens in cu_seqlens (QC_EINVAL otherwise)
+ *   and their caches and lengths stay as they are; decoding then goes on with everybody.
+ *   Not available on a batch with a qc_prune boundary, and qc_prune is not available on a batch with
+ *   free or later-joined slots (QC_EORDER).  qc_stats_t.generated keeps counting the batch's steps.
+ * Both calls enqueue a small metadata write on `stream`, ordered like every other call.
+ * qc_seq_extent: where slot b's rows start in the three pools (first row index as used in the
+ *   formula under qc_reset_ragged), and whether the slot holds a sequence; HOST outputs. */
+qc_status qc_seq_leave(qc_kvcache* kv, qc_qcache* qc, int32_t b, void* stream);
+qc_status qc_seq_join(qc_kvcache* kv, qc_qcache* qc, int32_t b, int32_t vis_start, int32_t vis_len,
+                      int32_t cap_seq, int32_t cap_text, void* stream);
+qc_status qc_seq_extent(const qc_kvcache* kv, int32_t b, int32_t* live, int32_t* base_seq,
+                        int32_t* base_text, int32_t* base_vis);
 
 /* ---- prefill: one layer over the packed prompts (paper Eq. 1; Eq. 7 in a lazy layer) -----------
  * q, k, v, out: DEVICE, element (token t, head h, dim d) at t*token_stride + h*head_stride + d

@@ -30,6 +30,15 @@ of the region.  Equal capacities (cap_seq = max_seq, ...) give back the layout
 above; the sums must fit the pools max_batch*max_seq, max_batch*max_text and
 max_batch*max_vis.  The arena then wastes nothing on a batch of unequal lengths.
 
+Slots and extents: a batch with per-sequence capacities is a list of slots, each
+holding a sequence or free (capacity 0, no rows).  The run of cap[b] rows-per-head
+that slot b owns in a pool, [base[b], base[b] + cap[b]), is its extent; the rule
+above assigns the extents of a fresh batch back to back in slot order.  A
+sequence that joins later gets, in each pool, the lowest base at which its
+capacity fits between the extents of the sequences then present (`first_fit`);
+nobody else moves, and a leaving sequence's rows keep their bytes until a later
+extent covers them.  `ragged` then carries the bases explicitly.
+
 Separately sized late layers (`late`): when a token-pruning boundary is known
 as the arena is sized, the layers from the boundary on hold max_seq_late
 positions per sequence instead of max_seq; their K blocks (ordinary layers) and V
@@ -53,7 +62,9 @@ def _round_up(x, m):
 class ArenaLayout:
     def __init__(self, n_layers, n_heads, head_dim, dtype, max_batch, max_seq, max_vis, max_text,
                  lazy_mask, mode="vla", ragged=None, late=None):
-        """ragged: None, or (cap_seq, cap_text, cap_vis) lists with one entry per sequence of the batch.
+        """ragged: None, or (cap_seq, cap_text, cap_vis) lists with one entry per slot of the batch (0 for a
+        free slot), optionally followed by (base_seq, base_text, base_vis) when the extents were not
+        assigned back to back (sequences joined later).
         late: None, or (first late layer, max_seq_late): the layers from there on hold max_seq_late
         positions per sequence instead of max_seq (a pruning boundary known when the arena is sized)."""
         self.late = late
@@ -61,14 +72,19 @@ class ArenaLayout:
         assert mode in ("vla", "gla")
         self.ragged = None
         if ragged is not None:
-            cap_seq, cap_text, cap_vis = ([int(x) for x in r] for r in ragged)
+            cap_seq, cap_text, cap_vis = ([int(x) for x in r] for r in ragged[:3])
             assert len(cap_seq) == len(cap_text) == len(cap_vis) <= max_batch
-            assert sum(cap_seq) <= max_batch * max_seq
-            if mode == "vla":
-                assert sum(cap_text) <= max_batch * max_text and sum(cap_vis) <= max_batch * max_vis
-            base = lambda caps: [sum(caps[:b]) for b in range(len(caps))]
-            self.ragged = {"seq": (cap_seq, base(cap_seq)), "text": (cap_text, base(cap_text)),
-                           "vis": (cap_vis, base(cap_vis))}
+            pools = {"seq": max_batch * max_seq, "text": max_batch * max_text, "vis": max_batch * max_vis}
+            caps = {"seq": cap_seq, "text": cap_text, "vis": cap_vis}
+            if len(ragged) == 3:
+                bases = {k: [sum(c[:b]) for b in range(len(c))] for k, c in caps.items()}
+            else:
+                bases = dict(zip(("seq", "text", "vis"), ([int(x) for x in r] for r in ragged[3:6])))
+            for kind in (("seq", "text", "vis") if mode == "vla" else ("seq",)):
+                ext = sorted((b0, c) for b0, c in zip(bases[kind], caps[kind]) if c > 0)
+                assert all(a0 + a1 <= b0 for (a0, a1), (b0, _) in zip(ext, ext[1:])), "extents overlap"
+                assert not ext or (ext[0][0] >= 0 and ext[-1][0] + ext[-1][1] <= pools[kind])
+            self.ragged = {k: (caps[k], bases[k]) for k in caps}
         self.mode = mode
         self.N, self.H, self.D = n_layers, n_heads, head_dim
         self.dtype = dtype
@@ -152,6 +168,17 @@ class ArenaLayout:
         return l, self.v_offset(l, b, h, pos)
 
 
+def first_fit(extents, want, pool):
+    """Lowest base at which `want` rows fit into a pool of `pool` rows beside the extents (base, rows) in
+    use; None if no gap is wide enough.  A request for no rows sits at 0."""
+    if want == 0:
+        return 0
+    for base in range(pool - want + 1):
+        if all(base + want <= b0 or b0 + n <= base for b0, n in extents if n > 0):
+            return base
+    return None
+
+
 def encode_rows(x, dtype):
     """fp64 rows -> raw bytes of the storage type; refuses values the type cannot hold exactly."""
     x32 = np.ascontiguousarray(x, dtype=np.float32)
@@ -165,12 +192,15 @@ def encode_rows(x, dtype):
     return (bits >> 16).astype(np.uint16).view(np.uint8)
 
 
-def kv_rows_image(layout, stacks):
+def kv_rows_image(layout, stacks, onto=None):
     """Expected bytes of the K and V row regions (the first rows_bytes() bytes of the K/V arena) given one
-    stack oracle (of the layout's mode) per sequence.  Unwritten bytes are zero."""
-    img = np.zeros(layout.rows_bytes(), dtype=np.uint8)
+    stack oracle (of the layout's mode) per slot (None for a free slot).  Unwritten bytes are zero, or keep
+    what `onto` holds: an earlier image of the same arena (rows of sequences that have left stay behind)."""
+    img = np.zeros(layout.rows_bytes(), dtype=np.uint8) if onto is None else onto.copy()
     rowb = layout.D * layout.e
     for b, st in enumerate(stacks):
+        if st is None:
+            continue
         for l in range(layout.N):
             for h in range(layout.H):
                 kr = st.Kc[l][h]
@@ -182,11 +212,11 @@ def kv_rows_image(layout, stacks):
     return img
 
 
-def q_arena_image(layout, stacks):
-    img = np.zeros(layout.q_arena_bytes(), dtype=np.uint8)
+def q_arena_image(layout, stacks, onto=None):
+    img = np.zeros(layout.q_arena_bytes(), dtype=np.uint8) if onto is None else onto.copy()
     rowb = layout.D * layout.e
     for b, st in enumerate(stacks):
-        if st.q_owner < 0:
+        if st is None or st.q_owner < 0:
             continue
         for h in range(layout.H):
             o = layout.q_offset(b, h, 0)
@@ -199,6 +229,8 @@ def resident_bytes(layout, stacks):
     per_row = layout.H * layout.D * layout.e
     k = v = q = tokens = 0
     for st in stacks:
+        if st is None:
+            continue
         rk, rv, rq = st.resident_rows()
         k += rk * per_row
         v += rv * per_row

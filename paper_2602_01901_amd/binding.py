@@ -50,6 +50,10 @@ _PROTOTYPES = {
     "qc_reset": (c_int32, [c_void_p, c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32), c_int32, c_void_p]),
     "qc_reset_ragged": (c_int32, [c_void_p, c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32),
                                   POINTER(c_int32), c_int32, c_void_p]),
+    "qc_seq_leave": (c_int32, [c_void_p, c_void_p, c_int32, c_void_p]),
+    "qc_seq_join": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, c_void_p]),
+    "qc_seq_extent": (c_int32, [c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32),
+                                POINTER(c_int32)]),
     "qc_prefill": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                              POINTER(c_int32), c_int64, c_int64, POINTER(c_int32), POINTER(c_int32), c_float,
                              c_void_p]),
@@ -187,6 +191,21 @@ def qc_reset(kv, qc, batch, vis_start, vis_len, zero_fill=1, stream=None):
 def qc_reset_ragged(kv, qc, batch, vis_start, vis_len, cap_seq, cap_text, zero_fill=1, stream=None):
     return _check(load_library().qc_reset_ragged(kv, qc, batch, _i32(vis_start), _i32(vis_len), _i32(cap_seq),
                                                 _i32(cap_text), int(zero_fill), stream))
+
+
+def qc_seq_leave(kv, qc, b, stream=None):
+    return _check(load_library().qc_seq_leave(kv, qc, b, stream))
+
+
+def qc_seq_join(kv, qc, b, vis_start, vis_len, cap_seq, cap_text, stream=None):
+    return _check(load_library().qc_seq_join(kv, qc, b, vis_start, vis_len, cap_seq, cap_text, stream))
+
+
+def qc_seq_extent(kv, b):
+    """(live, base_seq, base_text, base_vis) of slot b."""
+    out = [c_int32() for _ in range(4)]
+    _check(load_library().qc_seq_extent(kv, b, *[byref(x) for x in out]))
+    return tuple(x.value for x in out)
 
 
 def qc_prefill(kv, qc, layer, is_lazy, q, k, v, out, cu_seqlens, token_stride, head_stride, vis_start, vis_len,

@@ -145,6 +145,19 @@ struct qc_kvcache {
     if (ragged) for (int b = 0; b < batch; ++b) m = std::max<int64_t>(m, cap_seq[b]);
     return m;
   }
+  // Slots of the batch (qc_seq_join / qc_seq_leave): live[b] = slot b holds a sequence; joining[b] =
+  // it is (to be) filled by the prefill pass that is open or about to open; joined_at[b] = value of
+  // `generated` when its prefill pass ended.  Without joins and leaves every slot is live, every
+  // sequence belongs to the one pass after qc_reset and joined_at is 0 throughout.
+  std::vector<uint8_t> live, joining;
+  std::vector<int32_t> joined_at;
+  bool join_pass = false;   // the open (or pending) prefill pass fills joining slots beside settled sequences
+  bool settled(int b) const { return live[b] && !joining[b]; }
+  int32_t steps_of(int b) const { return generated - joined_at[b]; }
+  // value the kernels add the step counter to: prompt length less the steps that ran before the sequence joined
+  int32_t len_base(int layer, int b) const { return live[b] ? len_of(layer, b) - joined_at[b] : kFreeSlotLen; }
+  bool all_live() const { for (int b = 0; b < batch; ++b) if (!live[b]) return false; return true; }
+  static constexpr int32_t kFreeSlotLen = -(1 << 30);   // a free slot's length stays negative for any step count
   // Value the device-side step counter holds once everything enqueued so far has run (-1: not set).
   int64_t dev_generated = -1;
   bool timing = false;
@@ -266,6 +279,7 @@ static qc_status reset_impl(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const 
   if (ragged && c.late_from > 0) return fail(QC_EINVAL, "qc_reset_ragged: per-sequence capacities cannot be combined with a configuration that sizes the layers behind a pruning boundary separately");
   int64_t sum_seq = 0, sum_text = 0, sum_vis = 0;
   for (int b = 0; b < batch; ++b) {
+    if (ragged && cap_seq[b] == 0) continue;
     if (vis_start[b] < 0 || vis_len[b] < 0) return fail(QC_EINVAL, "qc_reset: negative span for sequence %d", b);
     if (!ragged) {
       if (!c.gla() && vis_len[b] > c.max_vis) return fail(QC_ECAPACITY, "qc_reset: sequence %d has %d visual tokens, max_vis %d", b, vis_len[b], c.max_vis);
@@ -273,7 +287,7 @@ static qc_status reset_impl(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const 
       continue;
     }
     if (cap_seq[b] < 8 || cap_seq[b] % 8 || cap_text[b] < 0)
-      return fail(QC_EINVAL, "qc_reset_ragged: cap_seq[%d] must be a positive multiple of 8, cap_text[%d] not negative", b, b);
+      return fail(QC_EINVAL, "qc_reset_ragged: cap_seq[%d] must be 0 (a free slot) or a positive multiple of 8, cap_text[%d] not negative", b, b);
     if ((int64_t)vis_start[b] + vis_len[b] > cap_seq[b]) return fail(QC_ECAPACITY, "qc_reset_ragged: span of sequence %d exceeds its %d positions", b, cap_seq[b]);
     sum_seq += cap_seq[b];
     sum_text += cap_text[b];
@@ -303,16 +317,29 @@ static qc_status reset_impl(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const 
   kv->dev_generated = -1;
   qc->owner = -1;
   kv->ragged = ragged;
+  kv->live.assign(batch, 1);
+  kv->joining.assign(batch, 1);
+  kv->joined_at.assign(batch, 0);
+  kv->join_pass = false;
   if (ragged) {
     kv->cap_seq.assign(cap_seq, cap_seq + batch);
     kv->cap_text.assign(cap_text, cap_text + batch);
     kv->base_seq.assign(batch, 0);
     kv->base_text.assign(batch, 0);
     kv->base_vis.assign(batch, 0);
-    for (int b = 1; b < batch; ++b) {
-      kv->base_seq[b] = kv->base_seq[b - 1] + cap_seq[b - 1];
-      kv->base_text[b] = kv->base_text[b - 1] + cap_text[b - 1];
-      kv->base_vis[b] = kv->base_vis[b - 1] + vis_len[b - 1];
+    int64_t next_seq = 0, next_text = 0, next_vis = 0;
+    for (int b = 0; b < batch; ++b) {
+      if (cap_seq[b] == 0) {   // free slot: no rows, nothing to fill
+        kv->live[b] = kv->joining[b] = 0;
+        kv->cap_text[b] = kv->vis_start[b] = kv->vis_len[b] = 0;
+        continue;
+      }
+      kv->base_seq[b] = (int32_t)next_seq;
+      kv->base_text[b] = c.gla() ? 0 : (int32_t)next_text;   // Global Lazy Attention keeps nothing in these two pools
+      kv->base_vis[b] = c.gla() ? 0 : (int32_t)next_vis;
+      next_seq += cap_seq[b];
+      next_text += cap_text[b];
+      next_vis += vis_len[b];
     }
     // the capacity rows the kernels read (after the optional clear above, on the same stream)
     for (int first = 0; first < batch; first += qc::MetaChunk::N) {
@@ -321,11 +348,11 @@ static qc_status reset_impl(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const 
       const int count = batch - first < qc::MetaChunk::N ? batch - first : qc::MetaChunk::N;
       for (int i = 0; i < count; ++i) {
         const int b = first + i;
-        mc.v[qc::CAP_SEQ][i] = cap_seq[b];
+        mc.v[qc::CAP_SEQ][i] = kv->cap_seq[b];
         mc.v[qc::BASE_SEQ][i] = kv->base_seq[b];
-        mc.v[qc::CAP_TEXT][i] = cap_text[b];
+        mc.v[qc::CAP_TEXT][i] = kv->cap_text[b];
         mc.v[qc::BASE_TEXT][i] = kv->base_text[b];
-        mc.v[qc::CAP_VIS][i] = vis_len[b];
+        mc.v[qc::CAP_VIS][i] = kv->vis_len[b];
         mc.v[qc::BASE_VIS][i] = kv->base_vis[b];
       }
       hipError_t e = qc::launch_meta_upload((int32_t*)(kv->arena + c.off_caps()), c.max_batch, first, count, qc::CAPS_ROWS, mc, (hipStream_t)stream);
@@ -366,12 +393,34 @@ static qc::LayerView make_view(const qc_kvcache* kv, const qc_qcache* qc, int la
   return lv;
 }
 
-static qc_status check_spans(const char* who, const qc_kvcache* kv, int layer, const int32_t* vis_start, const int32_t* vis_len) {
+static qc_status check_spans(const char* who, const qc_kvcache* kv, int layer, const int32_t* vis_start, const int32_t* vis_len, bool prefill) {
   if (!vis_start || !vis_len) return fail(QC_EINVAL, "%s: null span arrays", who);
   for (int b = 0; b < kv->batch; ++b)
-    if (vis_start[b] != kv->vis_start[b] || vis_len[b] != kv->vis_len_of(layer, b))
+    if ((prefill ? kv->joining[b] : kv->live[b]) && (vis_start[b] != kv->vis_start[b] || vis_len[b] != kv->vis_len_of(layer, b)))
       return fail(QC_EINVAL, "%s: span of sequence %d differs from the one given to %s", who, b,
                   kv->late(layer) ? "qc_reset and qc_prune" : "qc_reset");
+  return QC_OK;
+}
+
+// Per-sequence integers as the decode kernels want them, for slots [first, first + count): a
+// sequence's length is its entry plus the step counter; a free slot's stays negative.
+static qc_status upload_decode_meta(qc_kvcache* kv, int first, int count, hipStream_t st) {
+  const Config& c = kv->cfg;
+  int32_t* meta = (int32_t*)(kv->arena + c.off_meta());
+  for (int f = first; f < first + count; f += qc::MetaChunk::N) {
+    qc::MetaChunk mc;
+    memset(&mc, 0, sizeof(mc));
+    const int n = first + count - f < qc::MetaChunk::N ? first + count - f : qc::MetaChunk::N;
+    for (int i = 0; i < n; ++i) {
+      const int b = f + i;
+      mc.v[qc::META_TOK0][i] = kv->tok0[b];
+      mc.v[qc::META_LEN0][i] = kv->len_base(0, b);
+      mc.v[qc::META_VIS_START][i] = kv->vis_start[b];
+      mc.v[qc::META_VIS_LEN][i] = kv->vis_len[b];
+    }
+    hipError_t e = qc::launch_meta_upload(meta, c.max_batch, f, n, qc::META_ROWS, mc, st);
+    if (e != hipSuccess) return fail(QC_EDEVICE, "metadata upload: %s", hipGetErrorString(e));
+  }
   return QC_OK;
 }
 
@@ -397,13 +446,19 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
   if (kv->phase != PH_RESET && kv->phase != PH_PREFILL)
     return fail(QC_EORDER, "qc_prefill: no prefill pass is open (call qc_reset first)");
   if (layer != kv->next_layer) return fail(QC_EORDER, "qc_prefill: expected layer %d, got %d", kv->next_layer, layer);
-  if (qc_status s = check_spans("qc_prefill", kv, layer, vis_start, vis_len)) return s;
+  if (qc_status s = check_spans("qc_prefill", kv, layer, vis_start, vis_len, true)) return s;
   // The first layer of the pass, and the first layer after a pruning boundary, fix the packing.
   const bool opens = layer == 0 || layer == kv->first_late;
   if (cu_seqlens[0] != 0) return fail(QC_EINVAL, "qc_prefill: cu_seqlens[0] must be 0");
   int32_t max_len = 0;
+  int participants = 0;
   for (int b = 0; b < kv->batch; ++b) {
     int64_t len = (int64_t)cu_seqlens[b + 1] - cu_seqlens[b];
+    if (!kv->joining[b]) {   // a free slot, or a sequence that is already decoding: not part of this pass
+      if (len != 0) return fail(QC_EINVAL, "qc_prefill: slot %d is not filled by this pass, it must have no tokens in cu_seqlens", b);
+      continue;
+    }
+    ++participants;
     if (len < 1) return fail(QC_EINVAL, "qc_prefill: sequence %d is empty", b);
     const int32_t vn = kv->vis_len_of(layer, b);
     if (layer > 0 && len != kv->len_of(layer, b))
@@ -415,6 +470,7 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
       return fail(QC_EINVAL, "qc_prefill: cu_seqlens changed between layers");
     if (len > max_len) max_len = (int32_t)len;
   }
+  if (participants == 0) return fail(QC_EORDER, "qc_prefill: no slot of the batch is waiting to be filled");
   if ((int64_t)max_len * token_stride * e >= ((int64_t)1 << 31))
     return fail(QC_EINVAL, "qc_prefill: one sequence spans %lld bytes of the input tensors, the limit is 2 GiB", (long long)((int64_t)max_len * token_stride * e));
   if (c.lazy[layer] && qc->owner != c.anchor[layer])
@@ -430,7 +486,7 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
       for (int i = 0; i < count; ++i) {
         int b = first + i;
         mc.v[qc::META_TOK0][i] = cu_seqlens[b];
-        mc.v[qc::META_LEN0][i] = cu_seqlens[b + 1] - cu_seqlens[b];
+        mc.v[qc::META_LEN0][i] = cu_seqlens[b + 1] - cu_seqlens[b];   // 0 outside the pass: the kernels skip the slot
         mc.v[qc::META_VIS_START][i] = kv->vis_start[b];
         mc.v[qc::META_VIS_LEN][i] = kv->vis_len_of(layer, b);
       }
@@ -452,12 +508,13 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
   hipError_t err = qc::launch_prefill(a, c.dtype, st, kv->timing ? &kv->prefill_timer : nullptr);
   if (err != hipSuccess) return fail(QC_EDEVICE, "qc_prefill: %s", hipGetErrorString(err));
 
-  if (layer == 0)
-    for (int b = 0; b < kv->batch; ++b) {
-      kv->tok0[b] = cu_seqlens[b];
-      kv->len0[b] = cu_seqlens[b + 1] - cu_seqlens[b];
-    }
-  else if (opens) {
+  if (layer == 0) {
+    for (int b = 0; b < kv->batch; ++b)
+      if (kv->joining[b]) {
+        kv->tok0[b] = cu_seqlens[b];
+        kv->len0[b] = cu_seqlens[b + 1] - cu_seqlens[b];
+      }
+  } else if (opens) {
     for (int b = 0; b < kv->batch; ++b) kv->tok1[b] = cu_seqlens[b];
     kv->late_known = true;
   }
@@ -465,9 +522,115 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
   kv->next_layer = layer + 1;
   kv->phase = PH_PREFILL;
   if (kv->next_layer == c.N) {
+    // The pass is over: its sequences decode from the next step on.  When slots are free, or sequences
+    // that were decoding already sat the pass out, the per-sequence integers the decode kernels read
+    // are written again: the pass had the lengths of the slots outside it at zero.
+    const bool rewrite = kv->join_pass || !kv->all_live();
+    for (int b = 0; b < kv->batch; ++b)
+      if (kv->joining[b]) {
+        kv->joining[b] = 0;
+        kv->joined_at[b] = kv->generated;
+      }
+    kv->join_pass = false;
     kv->phase = PH_READY;
     kv->next_layer = 0;
+    if (rewrite)
+      if (qc_status s = upload_decode_meta(kv, 0, kv->batch, st)) return s;
   }
+  return QC_OK;
+}
+
+// ---- sequences joining and leaving a running batch ----------------------------------------------
+// Lowest start of `want` free rows in a pool of `pool` rows, given the extents (start, rows) in use;
+// -1 when no gap is wide enough.  A request for no rows is placed at 0.
+static int64_t first_fit(std::vector<std::pair<int64_t, int64_t>> used, int64_t want, int64_t pool) {
+  if (want == 0) return 0;
+  std::sort(used.begin(), used.end());
+  int64_t at = 0;
+  for (const auto& u : used) {
+    if (u.second == 0) continue;
+    if (u.first - at >= want) return at;
+    at = std::max(at, u.first + u.second);
+  }
+  return pool - at >= want ? at : -1;
+}
+
+qc_status qc_seq_leave(qc_kvcache* kv, qc_qcache* qc, int32_t b, void* stream) {
+  if (!kv || !qc) return fail(QC_EINVAL, "qc_seq_leave: null handle");
+  if (!kv->ragged) return fail(QC_EORDER, "qc_seq_leave: needs a batch set up with per-sequence capacities (qc_reset_ragged)");
+  if (b < 0 || b >= kv->batch) return fail(QC_EINVAL, "qc_seq_leave: slot %d out of range", b);
+  if (kv->phase != PH_READY) return fail(QC_EORDER, "qc_seq_leave: allowed between two decode steps only");
+  if (!kv->live[b]) return fail(QC_EINVAL, "qc_seq_leave: slot %d holds no sequence", b);
+  kv->live[b] = 0;
+  kv->cap_seq[b] = kv->cap_text[b] = 0;
+  kv->base_seq[b] = kv->base_text[b] = kv->base_vis[b] = 0;
+  kv->vis_start[b] = kv->vis_len[b] = 0;
+  kv->len0[b] = kv->tok0[b] = kv->joined_at[b] = 0;
+  return upload_decode_meta(kv, b, 1, (hipStream_t)stream);
+}
+
+qc_status qc_seq_join(qc_kvcache* kv, qc_qcache* qc, int32_t b, int32_t vis_start, int32_t vis_len,
+                      int32_t cap_seq, int32_t cap_text, void* stream) {
+  if (!kv || !qc) return fail(QC_EINVAL, "qc_seq_join: null handle");
+  const Config& c = kv->cfg;
+  if (!kv->ragged) return fail(QC_EORDER, "qc_seq_join: needs a batch set up with per-sequence capacities (qc_reset_ragged)");
+  if (b < 0 || b >= kv->batch) return fail(QC_EINVAL, "qc_seq_join: slot %d out of range", b);
+  // between two decode steps, or before the prefill pass that follows (more joins, or the reset) has begun
+  if (kv->phase != PH_READY && kv->phase != PH_RESET) return fail(QC_EORDER, "qc_seq_join: allowed between two decode steps, or before a prefill pass has begun");
+  if (kv->first_late >= 0) return fail(QC_EORDER, "qc_seq_join: not available on a batch with a pruning boundary");
+  if (kv->live[b]) return fail(QC_EINVAL, "qc_seq_join: slot %d is taken", b);
+  if (vis_start < 0 || vis_len < 0) return fail(QC_EINVAL, "qc_seq_join: negative span");
+  if (cap_seq < 8 || cap_seq % 8 || cap_text < 0) return fail(QC_EINVAL, "qc_seq_join: cap_seq must be a positive multiple of 8, cap_text not negative");
+  if ((int64_t)vis_start + vis_len > cap_seq) return fail(QC_ECAPACITY, "qc_seq_join: the span exceeds the sequence's %d positions", cap_seq);
+  std::vector<std::pair<int64_t, int64_t>> seq, text, vis;
+  for (int i = 0; i < kv->batch; ++i)
+    if (kv->live[i]) {
+      seq.emplace_back(kv->base_seq[i], kv->cap_seq[i]);
+      text.emplace_back(kv->base_text[i], kv->cap_text[i]);
+      vis.emplace_back(kv->base_vis[i], kv->vis_len[i]);
+    }
+  const int64_t at_seq = first_fit(seq, cap_seq, (int64_t)c.max_batch * c.max_seq);
+  const int64_t at_text = c.gla() ? 0 : first_fit(text, cap_text, (int64_t)c.max_batch * c.max_text);
+  const int64_t at_vis = c.gla() ? 0 : first_fit(vis, vis_len, (int64_t)c.max_batch * c.max_vis);
+  if (at_seq < 0) return fail(QC_ECAPACITY, "qc_seq_join: no run of %d free positions among max_batch*max_seq = %lld", cap_seq, (long long)c.max_batch * c.max_seq);
+  if (at_text < 0) return fail(QC_ECAPACITY, "qc_seq_join: no run of %d free text rows among max_batch*max_text = %lld", cap_text, (long long)c.max_batch * c.max_text);
+  if (at_vis < 0) return fail(QC_ECAPACITY, "qc_seq_join: no run of %d free Q Cache rows among max_batch*max_vis = %lld", vis_len, (long long)c.max_batch * c.max_vis);
+  qc::MetaChunk mc;
+  memset(&mc, 0, sizeof(mc));
+  mc.v[qc::CAP_SEQ][0] = cap_seq;
+  mc.v[qc::BASE_SEQ][0] = (int32_t)at_seq;
+  mc.v[qc::CAP_TEXT][0] = cap_text;
+  mc.v[qc::BASE_TEXT][0] = (int32_t)at_text;
+  mc.v[qc::CAP_VIS][0] = vis_len;
+  mc.v[qc::BASE_VIS][0] = (int32_t)at_vis;
+  hipError_t e = qc::launch_meta_upload((int32_t*)(kv->arena + c.off_caps()), c.max_batch, b, 1, qc::CAPS_ROWS, mc, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(QC_EDEVICE, "qc_seq_join: %s", hipGetErrorString(e));
+  kv->live[b] = kv->joining[b] = 1;
+  kv->joined_at[b] = 0;
+  kv->cap_seq[b] = cap_seq;
+  kv->cap_text[b] = cap_text;
+  kv->base_seq[b] = (int32_t)at_seq;
+  kv->base_text[b] = (int32_t)at_text;
+  kv->base_vis[b] = (int32_t)at_vis;
+  kv->vis_start[b] = vis_start;
+  kv->vis_len[b] = vis_len;
+  kv->len0[b] = kv->tok0[b] = 0;
+  if (kv->phase == PH_READY) {   // opens a pass of its own: the sequences that are decoding sit it out
+    kv->join_pass = true;
+    kv->phase = PH_RESET;
+    kv->next_layer = 0;
+  }
+  return QC_OK;
+}
+
+qc_status qc_seq_extent(const qc_kvcache* kv, int32_t b, int32_t* live, int32_t* base_seq, int32_t* base_text, int32_t* base_vis) {
+  if (!kv || !live || !base_seq || !base_text || !base_vis) return fail(QC_EINVAL, "qc_seq_extent: null argument");
+  if (!kv->ragged) return fail(QC_EORDER, "qc_seq_extent: needs a batch set up with per-sequence capacities (qc_reset_ragged)");
+  if (b < 0 || b >= kv->batch) return fail(QC_EINVAL, "qc_seq_extent: slot %d out of range", b);
+  *live = kv->live[b];
+  *base_seq = kv->base_seq[b];
+  *base_text = kv->base_text[b];
+  *base_vis = kv->base_vis[b];
   return QC_OK;
 }
 
@@ -500,10 +663,11 @@ static qc_status decode_impl(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32
   if (kv->phase != PH_READY && kv->phase != PH_DECODE) return fail(QC_EORDER, "qc_decode: prefill has not finished");
   if (layer != kv->next_layer) return fail(QC_EORDER, "qc_decode: expected layer %d, got %d", kv->next_layer, layer);
   if (!geom)
-    if (qc_status s = check_spans("qc_decode", kv, layer, vis_start, vis_len)) return s;
+    if (qc_status s = check_spans("qc_decode", kv, layer, vis_start, vis_len, false)) return s;
   int32_t max_len = 0;
   for (int b = 0; b < kv->batch; ++b) {
-    int64_t len = (int64_t)kv->len_of(layer, b) + kv->generated;
+    if (!kv->live[b]) continue;
+    int64_t len = (int64_t)kv->len_of(layer, b) + kv->steps_of(b);
     const int32_t vn = kv->vis_len_of(layer, b);
     if (len + 1 > kv->cap_of(layer, b)) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld positions, its capacity in layer %d is %lld", b, (long long)(len + 1), layer, (long long)kv->cap_of(layer, b));
     if (!c.gla() && len + 1 - vn > kv->cap_text_of(b)) return fail(QC_ECAPACITY, "qc_decode: sequence %d would reach %lld text rows, its capacity is %lld", b, (long long)(len + 1 - vn), (long long)kv->cap_text_of(b));
@@ -553,7 +717,7 @@ static qc_status decode_impl(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32
   a.inline_meta = (!geom && kv->batch <= qc::DecodeArgs::kInlineSeqs) ? 1 : 0;
   for (int b = 0; b < qc::DecodeArgs::kInlineSeqs; ++b) {
     const bool ok = a.inline_meta && b < kv->batch;
-    a.len0_inline[b] = ok ? kv->len_of(layer, b) : 0;
+    a.len0_inline[b] = ok ? kv->len_base(layer, b) : 0;
     a.vis_start_inline[b] = ok ? kv->vis_start[b] : 0;
     a.vis_len_inline[b] = ok ? kv->vis_len_of(layer, b) : 0;
   }
@@ -603,7 +767,8 @@ static qc_status step_fits(const char* who, const qc_kvcache* kv) {
     const int layer = stage ? (kv->first_late >= 0 ? kv->first_late : (c.late_from > 0 ? c.late_from : -1)) : 0;
     if (layer < 0) break;
     for (int b = 0; b < kv->batch; ++b) {
-      const int64_t len = (int64_t)kv->len_of(layer, b) + kv->generated;
+      if (!kv->live[b]) continue;
+      const int64_t len = (int64_t)kv->len_of(layer, b) + kv->steps_of(b);
       if (len + 1 > kv->cap_of(layer, b)) return fail(QC_ECAPACITY, "%s: sequence %d would reach %lld positions, its capacity in layer %d is %lld", who, b, (long long)(len + 1), layer, (long long)kv->cap_of(layer, b));
       if (!c.gla() && len + 1 - kv->vis_len_of(layer, b) > kv->cap_text_of(b))
         return fail(QC_ECAPACITY, "%s: sequence %d would reach %lld text rows, its capacity is %lld", who, b, (long long)(len + 1 - kv->vis_len_of(layer, b)), (long long)kv->cap_text_of(b));
@@ -716,13 +881,9 @@ void qc_decode_graph_destroy(qc_decode_graph* g) {
 static void rows_of(const qc_kvcache* kv, int layer, int b, int64_t* rk, int64_t* rv) {
   const Config& c = kv->cfg;
   int64_t len = 0;
-  switch (kv->phase) {
-    case PH_EMPTY:
-    case PH_RESET: len = 0; break;
-    case PH_PREFILL: len = layer < kv->next_layer ? kv->len_of(layer, b) : 0; break;
-    case PH_READY: len = (int64_t)kv->len_of(layer, b) + kv->generated; break;
-    case PH_DECODE: len = (int64_t)kv->len_of(layer, b) + kv->generated + (layer < kv->next_layer ? 1 : 0); break;
-  }
+  if (kv->phase == PH_EMPTY || !kv->live[b]) len = 0;
+  else if (kv->joining[b]) len = (kv->phase == PH_PREFILL && layer < kv->next_layer) ? kv->len_of(layer, b) : 0;
+  else len = (int64_t)kv->len_of(layer, b) + kv->steps_of(b) + ((kv->phase == PH_DECODE && layer < kv->next_layer) ? 1 : 0);
   *rv = len;
   if (c.gla()) *rk = c.lazy[layer] ? 0 : len;
   else *rk = len ? len - (c.lazy[layer] ? kv->vis_len_of(layer, b) : 0) : 0;
@@ -740,17 +901,21 @@ qc_status qc_stats(const qc_kvcache* kv, const qc_qcache* qc, qc_stats_t* out) {
       out->k_bytes += rk * per_row;
       out->v_bytes += rv * per_row;
     }
-    if (qc && qc->owner >= 0) {
+    if (!kv->live[b]) continue;
+    // a sequence waiting for a pass that has not reached layer 0 yet has nothing resident
+    const bool started = !kv->joining[b] || kv->phase == PH_PREFILL;
+    if (qc && qc->owner >= 0 && started) {
       // rows of the layer that wrote the Q Cache last (after a pruning boundary: of the shortened sequence)
       int64_t q_rows = kv->vis_len_of(qc->owner, b);
       if (c.gla()) {  // one row per position; the row of the token in flight once a block's first layer has run
-        q_rows = (int64_t)kv->len_of(qc->owner, b) + kv->generated;
+        q_rows = kv->len_of(qc->owner, b);
+        if (!kv->joining[b]) q_rows += kv->steps_of(b);
         if (kv->phase == PH_DECODE && qc->owner < kv->next_layer) q_rows += 1;
       }
       out->q_bytes += q_rows * per_row;
     }
-    if (kv->phase == PH_PREFILL) out->tokens += kv->len0[b];
-    else if (kv->phase >= PH_READY) out->tokens += (int64_t)kv->len0[b] + kv->generated;
+    if (kv->joining[b]) out->tokens += kv->phase == PH_PREFILL ? kv->len0[b] : 0;
+    else out->tokens += (int64_t)kv->len0[b] + kv->steps_of(b);
   }
   out->batch = kv->batch;
   out->q_owner = qc ? qc->owner : -1;
@@ -851,8 +1016,10 @@ qc_status qc_last_row_attention(qc_kvcache* kv, int32_t layer, const void* q_las
   if (kv->phase != PH_READY && !(kv->phase == PH_PREFILL && layer < kv->next_layer))
     return fail(QC_EORDER, "qc_last_row_attention: needs a prefill pass in which layer %d has run and no decode step in flight", layer);
   int32_t max_len = 0;
+  // inside a prefill pass the kernels see the prompts of the pass; afterwards every live sequence
   for (int b = 0; b < kv->batch; ++b) {
-    int32_t len = kv->len_of(layer, b) + kv->generated;
+    if (kv->phase == PH_PREFILL ? !kv->joining[b] : !kv->live[b]) continue;
+    int32_t len = kv->len_of(layer, b) + (kv->phase == PH_PREFILL ? 0 : kv->steps_of(b));
     if (len > max_len) max_len = len;
   }
   if (probs_stride < max_len) return fail(QC_EINVAL, "qc_last_row_attention: probs_stride %lld is shorter than the longest sequence (%d)", (long long)probs_stride, max_len);
@@ -867,7 +1034,7 @@ qc_status qc_last_row_attention(qc_kvcache* kv, int32_t layer, const void* q_las
   a.probs_stride = probs_stride;
   a.score_stride = (int32_t)select_score_stride(c);
   a.batch = kv->batch; a.n_heads = c.H; a.head_dim = c.D;
-  a.generated = kv->generated;
+  a.generated = kv->phase == PH_PREFILL ? 0 : kv->generated;
   a.scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)c.D);
   hipError_t e = qc::launch_last_row_attention(a, c.dtype, max_len, (hipStream_t)stream);
   if (e != hipSuccess) return fail(QC_EDEVICE, "qc_last_row_attention: %s", hipGetErrorString(e));
@@ -962,6 +1129,7 @@ qc_status qc_prune(qc_kvcache* kv, qc_qcache* qc, const int32_t* keep) {
   if (!c.same(qc->cfg)) return fail(QC_EINVAL, "qc_prune: handles were created with different configurations");
   if (kv->phase != PH_PREFILL) return fail(QC_EORDER, "qc_prune: allowed only inside a prefill pass, between two layers");
   if (kv->first_late >= 0) return fail(QC_EORDER, "qc_prune: this pass already has a pruning boundary (before layer %d)", kv->first_late);
+  if (kv->join_pass || !kv->all_live()) return fail(QC_EORDER, "qc_prune: not available on a batch with free slots or with sequences that joined later");
   if (c.lazy[kv->next_layer]) return fail(QC_EINVAL, "qc_prune: layer %d is lazy: a boundary cannot fall inside a lazy block", kv->next_layer);
   if (c.late_from > 0 && kv->next_layer != c.late_from) return fail(QC_EINVAL, "qc_prune: the configuration sizes the layers from %d on for a boundary there, not before layer %d", c.late_from, kv->next_layer);
   for (int b = 0; b < kv->batch; ++b) {
@@ -1034,7 +1202,7 @@ qc_status qc_layer_rows(const qc_kvcache* kv, int32_t layer, int64_t* rows_k, in
 qc_status qc_seq_len(const qc_kvcache* kv, int32_t b, int32_t* len) {
   if (!kv || !len) return fail(QC_EINVAL, "qc_seq_len: null argument");
   if (b < 0 || b >= kv->batch) return fail(QC_EINVAL, "qc_seq_len: sequence %d out of range", b);
-  *len = kv->phase >= PH_READY ? kv->len0[b] + kv->generated : 0;
+  *len = kv->settled(b) ? kv->len0[b] + kv->steps_of(b) : 0;
   return QC_OK;
 }
 
@@ -1046,6 +1214,7 @@ qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t 
   if (layer < 0 || layer >= c.N || b < 0 || b >= kv->batch || h < 0 || h >= c.H || pos < 0)
     return fail(QC_EINVAL, "qc_locate: index out of range");
   if (!kv->ragged && pos >= c.max_seq) return fail(QC_EINVAL, "qc_locate: index out of range");
+  if (!kv->live[b]) return fail(QC_EINVAL, "qc_locate: slot %d holds no sequence", b);
   const int64_t rb = c.row_bytes();
   // row index of (b, h, row 0) in a region of full-length rows / of a lazy layer's text rows
   auto seq0_of = [&](int l) {

@@ -263,6 +263,7 @@ template <typename T, int D, bool INLINE>
 __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
   const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
   const int len = decode_meta<INLINE>(a, b).len0 + decode_generated(a);
+  if (len < 0) return;   // a free slot of the batch: nothing was computed, nothing is written
   const int n = (len + a.chunk_keys) / a.chunk_keys;  // ceil((len + 1) / chunk_keys)
   const int64_t bh = (int64_t)b * a.n_heads + h;
   const float* w = a.workspace + bh * a.max_chunks * (D + 2);

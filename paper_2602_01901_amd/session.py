@@ -64,6 +64,21 @@ class Session:
         else:
             B.qc_reset(self.kv, self.qc, self.batch, self.vis_start, self.vis_len, int(zero_fill), self._stream())
 
+    def _set_span(self, b, vis_start, vis_len):
+        self.vis_start[b], self.vis_len[b] = vis_start, vis_len
+        self._vs_c, self._vl_c = B._i32(self.vis_start), B._i32(self.vis_len)
+        self._vl_by_layer = [(self.vis_len, self._vl_c)] * self.n_layers
+
+    def seq_leave(self, b):
+        """Slot b of a batch with per-sequence capacities becomes free (between two decode steps)."""
+        B.qc_seq_leave(self.kv, self.qc, b, self._stream())
+        self._set_span(b, 0, 0)
+
+    def seq_join(self, b, vis_start, vis_len, cap_seq, cap_text):
+        """A new sequence takes free slot b; the next calls are a prefill pass over the joined slots only."""
+        B.qc_seq_join(self.kv, self.qc, b, vis_start, vis_len, cap_seq, cap_text, self._stream())
+        self._set_span(b, vis_start, vis_len)
+
     def prune(self, next_layer, keep):
         """Token pruning boundary before `next_layer` (the layer the prefill pass runs next): from there on
         sequence b keeps keep[b] of its visual tokens.  Later prefill calls take the shortened prompts."""

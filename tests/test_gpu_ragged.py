@@ -86,7 +86,7 @@ def test_reset_ragged_validation():
     st = torch.cuda.current_stream().cuda_stream
     ok = dict(kv=s.kv, qc=s.qc, batch=2, vis_start=[0, 0], vis_len=[8, 8], cap_seq=list(caps[0]), cap_text=list(caps[1]),
               zero_fill=0, stream=st)
-    cases = [(dict(cap_seq=[41, 16]), B.QC_EINVAL), (dict(cap_seq=[0, 16]), B.QC_EINVAL), (dict(cap_text=[-1, 10]), B.QC_EINVAL),
+    cases = [(dict(cap_seq=[41, 16]), B.QC_EINVAL), (dict(cap_seq=[4, 16]), B.QC_EINVAL), (dict(cap_text=[-1, 10]), B.QC_EINVAL),
              (dict(cap_seq=[4096, 16]), B.QC_ECAPACITY), (dict(cap_text=[4096, 10]), B.QC_ECAPACITY),
              (dict(vis_len=[48, 8]), B.QC_ECAPACITY), (dict(batch=3, vis_start=[0] * 3, vis_len=[0] * 3, cap_seq=[8] * 3, cap_text=[8] * 3), B.QC_ECAPACITY),
              (dict(cap_seq=None), B.QC_EINVAL)]

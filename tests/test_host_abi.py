@@ -374,7 +374,7 @@ def test_reset_ragged_validation_happens_before_any_launch():
     cfg, kv, qc = make_handles(c)
     ok = dict(kv=kv, qc=qc, batch=2, vis_start=[0, 4], vis_len=[20, 8], cap_seq=[200, 40], cap_text=[180, 32], zero_fill=0)
     cases = [(dict(cap_seq=[201, 40]), B.QC_EINVAL),          # not a multiple of 8
-             (dict(cap_seq=[0, 40]), B.QC_EINVAL),
+             (dict(cap_seq=[4, 40]), B.QC_EINVAL),            # below 8 and not 0 (0 would be a free slot)
              (dict(cap_text=[-1, 32]), B.QC_EINVAL),
              (dict(cap_seq=None), B.QC_EINVAL),
              (dict(cap_text=None), B.QC_EINVAL),
@@ -387,6 +387,21 @@ def test_reset_ragged_validation_happens_before_any_launch():
         with pytest.raises(P.QcError) as e:
             B.qc_reset_ragged(**dict(ok, **change))
         assert e.value.status == status, change
+
+
+def test_join_leave_need_per_sequence_capacities():
+    cfg, kv, qc = make_handles(CONFIGS[1])
+    for call in (lambda: B.qc_seq_leave(None, qc, 0), lambda: B.qc_seq_join(kv, None, 0, 0, 0, 8, 8),
+                 lambda: B.qc_seq_extent(None, 0)):
+        with pytest.raises(P.QcError) as e:
+            call()
+        assert e.value.status == B.QC_EINVAL
+    B.qc_reset(kv, qc, 2, [0, 0], [0, 0], zero_fill=0)       # equal capacities: host-only
+    for call in (lambda: B.qc_seq_leave(kv, qc, 0), lambda: B.qc_seq_join(kv, qc, 0, 0, 0, 8, 8),
+                 lambda: B.qc_seq_extent(kv, 0)):
+        with pytest.raises(P.QcError) as e:
+            call()
+        assert e.value.status == B.QC_EORDER
 
 
 def test_smaller_late_layers_sizes_match_oracle_layout():

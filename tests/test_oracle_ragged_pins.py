@@ -95,3 +95,40 @@ def test_smaller_late_layers_worked_by_hand_and_against_the_uniform_layout():
     b = ArenaLayout(4, 2, 64, "bf16", 3, 20, 12, 9, [0, 0, 1, 0], late=(1, 20))
     assert a.rows_bytes() == b.rows_bytes()
     assert all(a.v_offset(l, 2, 1, 19) == b.v_offset(l, 2, 1, 19) and a.off_k(l) == b.off_k(l) for l in range(4))
+
+
+def test_first_fit_by_hand():
+    """Extents in a pool of 30 rows: [4, 10) and [15, 20) in use.  Gaps: [0, 4), [10, 15), [20, 30)."""
+    from oracle.layout import first_fit
+    used = [(15, 5), (4, 6)]
+    assert first_fit(used, 4, 30) == 0          # exactly the first gap
+    assert first_fit(used, 5, 30) == 10         # too long for the first, exactly the second
+    assert first_fit(used, 6, 30) == 20
+    assert first_fit(used, 10, 30) == 20        # to the pool's last row
+    assert first_fit(used, 11, 30) is None
+    assert first_fit(used, 0, 30) == 0          # nothing wanted
+    assert first_fit([], 30, 30) == 0 and first_fit([], 31, 30) is None
+    assert first_fit([(0, 0), (7, 0)], 30, 30) == 0     # free slots hold no rows
+
+
+def test_explicit_extents_by_hand():
+    """Two slots of a VLA stack [normal, lazy], H = 2, D = 64, bf16 (128-byte rows), max_batch 2, max_seq 16,
+    max_vis 6, max_text 8.  Slot 0 sits at position base 16 (cap 8), text base 5 (cap 4), Q base 2 (cap 3);
+    slot 1 at 0 (cap 16), 0 (cap 5), 0 (cap 2): the order of the extents need not be the order of the slots."""
+    lay = ArenaLayout(2, 2, 64, "bf16", 2, 16, 6, 8, [0, 1], ragged=([8, 16], [4, 5], [3, 2], [16, 0], [5, 0], [2, 0]))
+    rb = 128
+    k1 = 2 * 2 * 16 * rb                        # layer 0's K block holds max_batch*H*max_seq rows
+    v0 = k1 + 2 * 2 * 8 * rb                    # layer 1 (lazy) holds max_batch*H*max_text rows
+    # V, layer 0: slot 0 head 1 row 3 -> row index 16*2 + 1*8 + 3 = 43
+    assert lay.v_offset(0, 0, 1, 3) == v0 + 43 * rb
+    # lazy layer's K: slot 0 head 1 row 2 -> 5*2 + 1*4 + 2 = 16; slot 1 head 1 row 4 -> 0*2 + 1*5 + 4 = 9
+    assert lay.k_offset(1, 0, 1, 2) == k1 + 16 * rb
+    assert lay.k_offset(1, 1, 1, 4) == k1 + 9 * rb
+    # Q arena: slot 0 head 0 row 0 -> 2*2 = 4; slot 1 head 1 row 1 -> 0 + 1*2 + 1 = 3
+    assert lay.q_offset(0, 0, 0) == 4 * rb and lay.q_offset(1, 1, 1) == 3 * rb
+    # a key inside the span of a lazy layer resolves to the first layer's row of the same position
+    assert lay.locate_k(1, 0, 1, 2, 1, 3) == (0, (16 * 2 + 8 + 2) * rb)
+    with pytest.raises(AssertionError):         # overlapping extents: [0, 16) and [8, 16)
+        ArenaLayout(2, 2, 64, "bf16", 2, 16, 6, 8, [0, 1], ragged=([8, 16], [4, 5], [3, 2], [8, 0], [5, 0], [2, 0]))
+    with pytest.raises(AssertionError):         # past the pool's end: 28 + 8 > 32
+        ArenaLayout(2, 2, 64, "bf16", 2, 16, 6, 8, [0, 1], ragged=([8, 16], [4, 5], [3, 2], [28, 0], [5, 0], [2, 0]))
