@@ -222,11 +222,12 @@ def bench_cfg2(args):
     return res
 
 
-def bench_decode_batched(args):
-    """Batch-32 decode (HBM-bound): caches filled by an untimed prefill, then timed decode steps."""
+def bench_decode_batched(args, w=None, traffic_key="decode_cfg3"):
+    """Batch-32 decode (HBM-bound): caches filled by an untimed prefill, then timed decode steps.  Also used
+    (as a profiling aid) for the decode phase of the headline workload alone."""
     import torch
     import workloads
-    w = workloads.config(2)
+    w = w or workloads.config(2)
     steps = args.decode_batched_steps
     r = Runner(w, steps, distinct_decode_inputs=4)
     r.prefill_stack()
@@ -255,7 +256,7 @@ def bench_decode_batched(args):
         "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<bf16,128> (no split at this batch: one launch per layer call; "
                      "duration = decode phase / layer calls)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic("decode_cfg3"), "avg_launch_us": call_phase_us, "launches_timed": calls,
+                     "traffic": measured_traffic(traffic_key), "avg_launch_us": call_phase_us, "launches_timed": calls,
                      "algorithmic_bytes_per_launch": bytes_mean,
                      "event_pairs_around_kernel": {"avg_us": call_us, "launches": call_n, "algorithmic_bytes_per_launch": bytes_call,
                                                    "GBps": bytes_call / (call_us * 1e-6) / 1e9}},
@@ -930,7 +931,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true",
                     help="batch-1 workload: ordinary qc_decode calls instead of one HIP-graph replay per decode step")
     ap.add_argument("--only", choices=["headline", "cfg2", "decode_batched", "prefill_highres", "gla_decode_batched", "selection",
-                                      "projection", "pruning", "capacity", "prefill_long"],
+                                      "projection", "pruning", "capacity", "prefill_long", "prefill_cfg5", "decode_cfg5"],
                     help="profiling aid: run just this workload and print its object")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profiling aid: run plain 1 GiB device copies (known HBM traffic) and exit")
@@ -960,7 +961,9 @@ def main():
               "decode_batched": bench_decode_batched, "prefill_highres": bench_prefill_highres,
               "gla_decode_batched": bench_gla_decode_batched, "selection": bench_selection,
               "projection": bench_projection, "pruning": bench_pruning, "capacity": bench_capacity,
-              "prefill_long": bench_prefill_long}[args.only]
+              "prefill_long": bench_prefill_long,
+              "prefill_cfg5": lambda a: bench_prefill_highres(a, w=workloads.config(4), traffic_key="prefill_cfg5"),
+              "decode_cfg5": lambda a: bench_decode_batched(a, w=workloads.config(4), traffic_key="decode_cfg5")}[args.only]
         print(json.dumps({args.only: fn(args)}))
         return
 
