@@ -190,12 +190,19 @@ qc_status qc_reset_ragged(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const in
  *   and their caches and lengths stay as they are; decoding then goes on with everybody.
  *   Not available on a batch with a qc_prune boundary, and qc_prune is not available on a batch with
  *   free or later-joined slots (QC_EORDER).  qc_stats_t.generated keeps counting the batch's steps.
- * Both calls enqueue a small metadata write on `stream`, ordered like every other call.
+ * qc_seq_grow: gives the sequence in slot b other capacities (larger, or smaller down to what it
+ *   holds: QC_ECAPACITY below that), between two decode steps.  A pool whose capacity changes gets a new
+ *   extent for the sequence, placed first-fit beside every extent in use including the old one, and
+ *   the rows the sequence holds are copied there on `stream` (every layer's K and V rows, under QC_GLA
+ *   also its Q Cache rows); the old extent is then free.  QC_ECAPACITY if no gap is wide enough; nothing
+ *   changes then.  Not available on a batch with a qc_prune boundary.
+ * The three calls enqueue their device work on `stream`, ordered like every other call.
  * qc_seq_extent: where slot b's rows start in the three pools (first row index as used in the
  *   formula under qc_reset_ragged), and whether the slot holds a sequence; HOST outputs. */
 qc_status qc_seq_leave(qc_kvcache* kv, qc_qcache* qc, int32_t b, void* stream);
 qc_status qc_seq_join(qc_kvcache* kv, qc_qcache* qc, int32_t b, int32_t vis_start, int32_t vis_len,
                       int32_t cap_seq, int32_t cap_text, void* stream);
+qc_status qc_seq_grow(qc_kvcache* kv, qc_qcache* qc, int32_t b, int32_t cap_seq, int32_t cap_text, void* stream);
 qc_status qc_seq_extent(const qc_kvcache* kv, int32_t b, int32_t* live, int32_t* base_seq,
                         int32_t* base_text, int32_t* base_vis);
 

@@ -52,6 +52,7 @@ _PROTOTYPES = {
                                   POINTER(c_int32), c_int32, c_void_p]),
     "qc_seq_leave": (c_int32, [c_void_p, c_void_p, c_int32, c_void_p]),
     "qc_seq_join": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, c_void_p]),
+    "qc_seq_grow": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_void_p]),
     "qc_seq_extent": (c_int32, [c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32),
                                 POINTER(c_int32)]),
     "qc_prefill": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
@@ -199,6 +200,10 @@ def qc_seq_leave(kv, qc, b, stream=None):
 
 def qc_seq_join(kv, qc, b, vis_start, vis_len, cap_seq, cap_text, stream=None):
     return _check(load_library().qc_seq_join(kv, qc, b, vis_start, vis_len, cap_seq, cap_text, stream))
+
+
+def qc_seq_grow(kv, qc, b, cap_seq, cap_text, stream=None):
+    return _check(load_library().qc_seq_grow(kv, qc, b, cap_seq, cap_text, stream))
 
 
 def qc_seq_extent(kv, b):

@@ -623,6 +623,78 @@ qc_status qc_seq_join(qc_kvcache* kv, qc_qcache* qc, int32_t b, int32_t vis_star
   return QC_OK;
 }
 
+qc_status qc_seq_grow(qc_kvcache* kv, qc_qcache* qc, int32_t b, int32_t cap_seq, int32_t cap_text, void* stream) {
+  if (!kv || !qc) return fail(QC_EINVAL, "qc_seq_grow: null handle");
+  const Config& c = kv->cfg;
+  if (!kv->ragged) return fail(QC_EORDER, "qc_seq_grow: needs a batch set up with per-sequence capacities (qc_reset_ragged)");
+  if (b < 0 || b >= kv->batch) return fail(QC_EINVAL, "qc_seq_grow: slot %d out of range", b);
+  if (kv->phase != PH_READY) return fail(QC_EORDER, "qc_seq_grow: allowed between two decode steps only");
+  if (!kv->live[b]) return fail(QC_EINVAL, "qc_seq_grow: slot %d holds no sequence", b);
+  if (kv->first_late >= 0) return fail(QC_EORDER, "qc_seq_grow: not available on a batch with a pruning boundary");
+  const int64_t len = (int64_t)kv->len0[b] + kv->steps_of(b), text = len - kv->vis_len[b];
+  if (cap_seq < 8 || cap_seq % 8 || cap_text < 0) return fail(QC_EINVAL, "qc_seq_grow: cap_seq must be a positive multiple of 8, cap_text not negative");
+  if (cap_seq < len || (!c.gla() && cap_text < text))
+    return fail(QC_ECAPACITY, "qc_seq_grow: the sequence already holds %lld positions and %lld text rows", (long long)len, (long long)text);
+  // New extents beside everybody's current ones, the sequence's own included: rows are copied, never
+  // shifted in place.  A pool whose capacity does not change keeps its extent.
+  std::vector<std::pair<int64_t, int64_t>> seq, txt;
+  for (int i = 0; i < kv->batch; ++i)
+    if (kv->live[i]) {
+      seq.emplace_back(kv->base_seq[i], kv->cap_seq[i]);
+      txt.emplace_back(kv->base_text[i], kv->cap_text[i]);
+    }
+  const bool move_seq = cap_seq != kv->cap_seq[b], move_text = !c.gla() && cap_text != kv->cap_text[b];
+  const int64_t at_seq = move_seq ? first_fit(seq, cap_seq, (int64_t)c.max_batch * c.max_seq) : kv->base_seq[b];
+  const int64_t at_text = move_text ? first_fit(txt, cap_text, (int64_t)c.max_batch * c.max_text) : kv->base_text[b];
+  if (at_seq < 0) return fail(QC_ECAPACITY, "qc_seq_grow: no run of %d free positions among max_batch*max_seq = %lld", cap_seq, (long long)c.max_batch * c.max_seq);
+  if (at_text < 0) return fail(QC_ECAPACITY, "qc_seq_grow: no run of %d free text rows among max_batch*max_text = %lld", cap_text, (long long)c.max_batch * c.max_text);
+  const int64_t rb = c.row_bytes();
+  qc::MoveChunk mc;
+  int n = 0;
+  auto flush = [&]() -> hipError_t {
+    hipError_t e = qc::launch_move_rows(kv->arena, qc->arena, (int32_t)rb, c.H, n, mc, (hipStream_t)stream);
+    n = 0;
+    return e;
+  };
+  auto add = [&](int arena, int64_t region, int64_t base_old, int64_t cap_old, int64_t base_new, int64_t cap_new, int64_t rows) -> hipError_t {
+    if (rows == 0) return hipSuccess;
+    mc.arena[n] = arena;
+    mc.src[n] = region + base_old * c.H * rb;
+    mc.dst[n] = region + base_new * c.H * rb;
+    mc.src_stride[n] = cap_old * rb;
+    mc.dst_stride[n] = cap_new * rb;
+    mc.rows[n] = (int32_t)rows;
+    return ++n == qc::MoveChunk::N ? flush() : hipSuccess;
+  };
+  hipError_t e = hipSuccess;
+  for (int l = 0; l < c.N && e == hipSuccess; ++l) {
+    if (move_seq) e = add(0, c.off_v(l), kv->base_seq[b], kv->cap_seq[b], at_seq, cap_seq, len);
+    if (e != hipSuccess) break;
+    const bool text_rows = c.lazy[l] && !c.gla();
+    if (text_rows) { if (move_text) e = add(0, c.off_k(l), kv->base_text[b], kv->cap_text[b], at_text, cap_text, text); }
+    else if (c.cap_k(l) > 0 && move_seq) e = add(0, c.off_k(l), kv->base_seq[b], kv->cap_seq[b], at_seq, cap_seq, len);
+  }
+  // Global Lazy Attention: the Q Cache holds one row per position, laid out like the position rows
+  if (e == hipSuccess && c.gla() && move_seq && qc->owner >= 0) e = add(1, 0, kv->base_seq[b], kv->cap_seq[b], at_seq, cap_seq, len);
+  if (e == hipSuccess) e = flush();
+  if (e != hipSuccess) return fail(QC_EDEVICE, "qc_seq_grow: %s", hipGetErrorString(e));
+  qc::MetaChunk caps;
+  memset(&caps, 0, sizeof(caps));
+  caps.v[qc::CAP_SEQ][0] = cap_seq;
+  caps.v[qc::BASE_SEQ][0] = (int32_t)at_seq;
+  caps.v[qc::CAP_TEXT][0] = c.gla() ? kv->cap_text[b] : cap_text;
+  caps.v[qc::BASE_TEXT][0] = (int32_t)at_text;
+  caps.v[qc::CAP_VIS][0] = kv->vis_len[b];
+  caps.v[qc::BASE_VIS][0] = kv->base_vis[b];
+  e = qc::launch_meta_upload((int32_t*)(kv->arena + c.off_caps()), c.max_batch, b, 1, qc::CAPS_ROWS, caps, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(QC_EDEVICE, "qc_seq_grow: %s", hipGetErrorString(e));
+  kv->cap_seq[b] = cap_seq;
+  kv->base_seq[b] = (int32_t)at_seq;
+  if (!c.gla()) kv->cap_text[b] = cap_text;
+  kv->base_text[b] = (int32_t)at_text;
+  return QC_OK;
+}
+
 qc_status qc_seq_extent(const qc_kvcache* kv, int32_t b, int32_t* live, int32_t* base_seq, int32_t* base_text, int32_t* base_vis) {
   if (!kv || !live || !base_seq || !base_text || !base_vis) return fail(QC_EINVAL, "qc_seq_extent: null argument");
   if (!kv->ragged) return fail(QC_EORDER, "qc_seq_extent: needs a batch set up with per-sequence capacities (qc_reset_ragged)");

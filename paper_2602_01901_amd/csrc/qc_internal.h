@@ -139,6 +139,14 @@ struct PruneChunk {       // by-value payload of the survivor selection kernel: 
   int32_t out0[N];        // first entry of the sequence in the row map
 };
 
+struct MoveChunk {        // by-value payload of the row relocation kernel: up to N regions
+  enum { N = 32 };
+  int64_t src[N], dst[N];             // byte offsets of head 0's rows inside the arena
+  int64_t src_stride[N], dst_stride[N];   // bytes from one head's rows to the next
+  int32_t rows[N];                    // rows per head to move
+  int32_t arena[N];                   // 0: K/V arena, 1: Q arena
+};
+
 struct MetaChunk {        // by-value payload of the metadata upload kernel: up to ROWS rows of N sequences
   enum { N = 64, ROWS = 6 };
   int32_t v[ROWS][N];
@@ -205,6 +213,8 @@ hipError_t launch_fill_zero(void* dev, size_t bytes, hipStream_t stream);
 hipError_t launch_counter_update(int32_t* counter, int32_t value, int32_t add, hipStream_t stream);
 hipError_t launch_meta_upload(int32_t* meta_dev, int32_t max_batch, int32_t first, int32_t count, int32_t rows,
                               const MetaChunk& chunk, hipStream_t stream);
+hipError_t launch_move_rows(void* arena0, void* arena1, int32_t row_bytes, int32_t n_heads, int32_t count,
+                            const MoveChunk& chunk, hipStream_t stream);
 hipError_t launch_prefill(const PrefillArgs& a, int dtype, hipStream_t stream, KernelTimer* timer);
 // Size of the library's own decode scratch array (one per GPU, held until the process ends).
 constexpr size_t kStaticScratchBytes = 4u << 20;

@@ -47,4 +47,25 @@ hipError_t launch_meta_upload(int32_t* meta_dev, int32_t max_batch, int32_t firs
   return hipGetLastError();
 }
 
+// Moves the rows of one sequence inside up to MoveChunk::N regions (qc_seq_grow): region i holds, per
+// head, `rows[i]` rows of row_bytes at src[i] + h*src_stride[i] that go to dst[i] + h*dst_stride[i]
+// (byte offsets from `base`).  One workgroup per (region, head), 16 bytes per lane.  Source and
+// destination never overlap.
+__global__ __launch_bounds__(256) void move_rows_kernel(char* base0, char* base1, int32_t row_bytes, MoveChunk c) {
+  const int i = blockIdx.x, h = blockIdx.y;
+  char* base = c.arena[i] ? base1 : base0;
+  const int64_t n16 = (int64_t)c.rows[i] * row_bytes / 16;
+  const uint4* src = (const uint4*)(base + c.src[i] + (int64_t)h * c.src_stride[i]);
+  uint4* dst = (uint4*)(base + c.dst[i] + (int64_t)h * c.dst_stride[i]);
+  for (int64_t j = threadIdx.x; j < n16; j += 256) dst[j] = src[j];
+}
+
+hipError_t launch_move_rows(void* arena0, void* arena1, int32_t row_bytes, int32_t n_heads, int32_t count,
+                            const MoveChunk& chunk, hipStream_t stream) {
+  if (count == 0) return hipSuccess;
+  hipLaunchKernelGGL(move_rows_kernel, dim3(count, n_heads), dim3(256), 0, stream, (char*)arena0, (char*)arena1,
+                     row_bytes, chunk);
+  return hipGetLastError();
+}
+
 }  // namespace qc

@@ -79,6 +79,10 @@ class Session:
         B.qc_seq_join(self.kv, self.qc, b, vis_start, vis_len, cap_seq, cap_text, self._stream())
         self._set_span(b, vis_start, vis_len)
 
+    def seq_grow(self, b, cap_seq, cap_text):
+        """Other capacities for the sequence in slot b; its rows move to a new extent where a pool's capacity changes."""
+        B.qc_seq_grow(self.kv, self.qc, b, cap_seq, cap_text, self._stream())
+
     def prune(self, next_layer, keep):
         """Token pruning boundary before `next_layer` (the layer the prefill pass runs next): from there on
         sequence b keeps keep[b] of its visual tokens.  Later prefill calls take the shortened prompts."""

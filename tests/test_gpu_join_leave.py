@@ -99,6 +99,22 @@ class Driver:
         for kind in range(3):
             self.caps[kind][slot] = self.bases[kind][slot] = 0
 
+    def grow(self, slot, cap_seq, cap_text):
+        """New capacities: a pool whose capacity changes gives the sequence a new first-fit extent beside all
+        extents in use, its own old one included; the rows move, the old extent is free afterwards."""
+        w = self.w
+        want = (cap_seq, cap_text)
+        pools = (len(self.slots) * w.max_seq, len(self.slots) * w.max_text)
+        for kind in range(2):
+            if want[kind] == self.caps[kind][slot] or (self.mode == "gla" and kind == 1):
+                continue
+            used = [(self.bases[kind][s], self.caps[kind][s]) for s in range(len(self.slots)) if self.slots[s] is not None]
+            base = olayout.first_fit(used, want[kind], pools[kind])
+            assert base is not None
+            self.bases[kind][slot], self.caps[kind][slot] = base, want[kind]
+        self.session.seq_grow(slot, cap_seq, cap_text)
+        self.check_extents()
+
     def check_extents(self):
         for s, i in enumerate(self.slots):
             live, b_seq, b_text, b_vis = B.qc_seq_extent(self.session.kv, s)
@@ -214,18 +230,36 @@ def test_join_leave_schedule(mode, dtype, D):
     d.decode_step()
     d.check_state()
 
+    # C (capacity 88 positions and 45 text rows, 79 and 39 in use) is given more room: 104 positions do not
+    # fit the 16 free rows between D and B, so C moves behind B (144 + 160 = 304); 56 text rows do not fit
+    # the 25 free rows before B's either and go behind D's (136 + 40 = 176)
+    with pytest.raises(B.QcError):
+        d.session.seq_grow(0, 72, 45)       # below the 79 positions it holds
+    d.grow(0, 104, 56)
+    assert (d.bases[0][0], d.bases[1][0]) == ((304, 176) if mode == "vla" else (304, 0))
+    d.check_state()
     d.leave(1)
     d.decode_step()
     d.check_state()
 
     d.join(1, E)
-    # positions: behind C and D (everything from 128 on is free once B has left); text rows: the 91-row gap
-    # between C and D takes E's 90; Q Cache rows: behind C's 40
-    assert (d.bases[0][1], d.bases[1][1], d.bases[2][1]) == ((128, 45, 40) if mode == "vla" else (128, 0, 0))
+    # positions: C sits at 304..408 now and D at 88..128: the first gap of 224 rows is behind C; text rows: the
+    # 136 rows before D's are free; Q Cache rows: behind C's 40
+    assert (d.bases[0][1], d.bases[1][1], d.bases[2][1]) == ((408, 0, 40) if mode == "vla" else (408, 0, 0))
     d.prefill_pass([1])
     d.decode_step()
     d.check_state()
     assert d.steps == {A: 2, Bq: 4, C: 4, Dq: 4, E: 1}
+    # C alone runs on to 92 positions and 52 text rows, beyond the 88 and 45 it joined with
+    d.leave(1)
+    d.leave(2)
+    for _ in range(11):
+        d.decode_step()
+    d.check_state()
+    assert d.steps[C] == 15
+    with pytest.raises(B.QcError):          # the new limits: 56 text rows (the fifth step from here), 104 positions under GLA
+        for _ in range(20):
+            d.decode_step()
     print("join/leave %s %s: worst error %.2e" % (mode, dtype, d.worst))
     d.session.close()
 

@@ -392,13 +392,13 @@ def test_reset_ragged_validation_happens_before_any_launch():
 def test_join_leave_need_per_sequence_capacities():
     cfg, kv, qc = make_handles(CONFIGS[1])
     for call in (lambda: B.qc_seq_leave(None, qc, 0), lambda: B.qc_seq_join(kv, None, 0, 0, 0, 8, 8),
-                 lambda: B.qc_seq_extent(None, 0)):
+                 lambda: B.qc_seq_grow(kv, None, 0, 8, 8), lambda: B.qc_seq_extent(None, 0)):
         with pytest.raises(P.QcError) as e:
             call()
         assert e.value.status == B.QC_EINVAL
     B.qc_reset(kv, qc, 2, [0, 0], [0, 0], zero_fill=0)       # equal capacities: host-only
     for call in (lambda: B.qc_seq_leave(kv, qc, 0), lambda: B.qc_seq_join(kv, qc, 0, 0, 0, 8, 8),
-                 lambda: B.qc_seq_extent(kv, 0)):
+                 lambda: B.qc_seq_grow(kv, qc, 0, 8, 8), lambda: B.qc_seq_extent(kv, 0)):
         with pytest.raises(P.QcError) as e:
             call()
         assert e.value.status == B.QC_EORDER
