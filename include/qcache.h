@@ -196,7 +196,9 @@ qc_status qc_reset_ragged(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const in
  *   the rows the sequence holds are copied there on `stream` (every layer's K and V rows, under QC_GLA
  *   also its Q Cache rows); the old extent is then free.  QC_ECAPACITY if no gap is wide enough; nothing
  *   changes then.  Not available on a batch with a qc_prune boundary.
- * The three calls enqueue their device work on `stream`, ordered like every other call.
+ * The three calls enqueue their device work on `stream`, ordered like every other call.  A decode
+ * graph (qc_decode_graph_create) recorded on the batch stays valid across them: it reads lengths,
+ * spans, extents and the step count from device memory.
  * qc_seq_extent: where slot b's rows start in the three pools (first row index as used in the
  *   formula under qc_reset_ragged), and whether the slot holds a sequence; HOST outputs. */
 qc_status qc_seq_leave(qc_kvcache* kv, qc_qcache* qc, int32_t b, void* stream);

@@ -174,6 +174,47 @@ class Driver:
             if i is not None:
                 self.steps[i] += 1
 
+    def decode_step_graph(self):
+        """The same step through one replay of a decode graph recorded once over fixed input and output buffers."""
+        w, n = self.w, len(self.slots)
+        gla = self.mode == "gla"
+        dt = workloads.TORCH_DTYPE[w.dtype]
+        if getattr(self, "graph", None) is None:
+            mk = lambda: [torch.zeros(n, w.n_heads, w.head_dim, dtype=dt, device=self.dev) for _ in range(w.n_layers)]
+            self.gq, self.gk, self.gv, self.go = mk(), mk(), mk(), mk()
+            no_qk = [gla and w.lazy_mask[l] for l in range(w.n_layers)]
+            self.graph = self.session.decode_graph([None if no_qk[l] else self.gq[l] for l in range(w.n_layers)],
+                                                   [None if no_qk[l] else self.gk[l] for l in range(w.n_layers)],
+                                                   self.gv, self.go)
+        refs = []
+        for l in range(w.n_layers):
+            q = torch.full((n, w.n_heads, w.head_dim), float("nan"), dtype=dt)
+            k, v = q.clone(), q.clone()
+            ref = {}
+            for s, i in enumerate(self.slots):
+                if i is None:
+                    continue
+                qa, ka, va = workloads.decode_qkv(w, l, self.steps[i])
+                q[s], k[s], v[s] = qa[i], ka[i], va[i]
+                ref[s] = self.stacks[s].decode(l, *(workloads.to_f64(t[i]) for t in (qa, ka, va)))
+            refs.append(ref)
+            self.gq[l].copy_(q); self.gk[l].copy_(k); self.gv[l].copy_(v)
+            self.go[l].fill_(1024.0)
+        self.session.graph_launch(self.graph)
+        torch.cuda.synchronize()
+        for l in range(w.n_layers):
+            got = workloads.to_f64(self.go[l])
+            for s, i in enumerate(self.slots):
+                if i is None:
+                    assert np.all(got[s] == 1024.0), ("free slot written", s, l)
+                else:
+                    err = float(np.max(np.abs(got[s] - refs[l][s])))
+                    assert err <= TOL[w.dtype], ("graph decode", l, s, err)
+                    self.worst = max(self.worst, err)
+        for i in self.slots:
+            if i is not None:
+                self.steps[i] += 1
+
     def check_state(self):
         """Arena images (rows of departed sequences stay behind), lengths, row counts, row locations."""
         torch.cuda.synchronize()
@@ -261,6 +302,33 @@ def test_join_leave_schedule(mode, dtype, D):
         for _ in range(20):
             d.decode_step()
     print("join/leave %s %s: worst error %.2e" % (mode, dtype, d.worst))
+    d.session.close()
+
+
+@pytest.mark.parametrize("mode", ["vla", "gla"])
+def test_graph_replays_across_leave_join_and_growth(mode):
+    """A decode graph recorded before any change of the batch keeps serving it: it reads every per-sequence
+    integer, extent and the step count from device memory.  Replays alternate with ordinary steps."""
+    w = population("bf16", 128)
+    d = Driver(w, mode, slots=3)
+    d.reset([A, Bq, None])
+    d.decode_step_graph()
+    d.decode_step()
+    d.check_state()                      # the image is carried along: rows of departed sequences stay behind
+    d.leave(0)
+    d.join(0, C)
+    d.join(2, Dq)
+    d.prefill_pass([0, 2])
+    d.decode_step_graph()
+    d.decode_step_graph()
+    d.check_state()
+    d.grow(0, 104, 56)
+    d.leave(1)
+    d.decode_step_graph()
+    d.decode_step()
+    d.decode_step_graph()
+    d.check_state()
+    assert d.steps == {A: 2, Bq: 4, C: 5, Dq: 5}
     d.session.close()
 
 
