@@ -31,12 +31,12 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def measured_traffic(key):
+def measured_traffic(key, field="bytes_per_launch"):
     """HBM bytes per launch from committed rocprofv3 --pmc runs (profiles/hbm_traffic.json), or None."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(key, {}).get("bytes_per_launch")
+            return json.load(f).get(key, {}).get(field)
     except (OSError, ValueError):
         return None
 
@@ -822,6 +822,8 @@ def bench_headline(args):
                      "phase / layer calls, so the merge pass and the launch gaps are charged to it)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic("decode_cfg5"),
+                     "traffic_measured_at": "the first 22 decode steps (lengths 4865..4886: 399.7 MB algorithmic per launch there; "
+                                            "the timed region's mean over 1024 steps is algorithmic_bytes_per_launch)",
                      "avg_launch_us": call_us, "launches_timed": launches_per_step * args.steps,
                      "algorithmic_bytes_per_launch": bytes_mean, "launches_per_step": launches_per_step,
                      "event_pairs_around_kernel": {"avg_us": dec_us, "launches": dec_n, "algorithmic_bytes_per_launch": bytes_call,
