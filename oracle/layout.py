@@ -39,6 +39,17 @@ capacity fits between the extents of the sequences then present (`first_fit`);
 nobody else moves, and a leaving sequence's rows keep their bytes until a later
 extent covers them.  `ragged` then carries the bases explicitly.
 
+Pages (`paged`): the regions keep their sizes (max_seq, max_text and max_vis are then multiples of
+PAGE_ROWS = 64), but each is cut into pages of 64 rows for every head, [page][H][64][D], and a sequence
+owns a list of pages per pool instead of one run of rows: row r of head h sits at row index
+(pages[r // 64]*H + h)*64 + r % 64 of the region.  One list per sequence and pool serves every layer and
+head: "seq" pages hold the V rows of every layer and the K rows of ordinary layers (and, under Global Lazy
+Attention, the Q Cache rows), "text" pages the K rows of lazy layers, "vis" pages the Q Cache rows.  Pages
+are handed out lowest free number first (`PagePools`), one pool after the other for each sequence in
+slot order, when a sequence's rows first need them: at the start of its prefill pass for the prompt, and
+before the decode step whose new row opens a page.  A sequence that leaves gives all its pages back; the
+bytes stay until another sequence's rows cover them.
+
 Separately sized late layers (`late`): when a token-pruning boundary is known
 as the arena is sized, the layers from the boundary on hold max_seq_late
 positions per sequence instead of max_seq; their K blocks (ordinary layers) and V
@@ -53,6 +64,7 @@ position in the block's first layer, and the Q arena is
 import numpy as np
 
 ELEM_BYTES = {"f32": 4, "bf16": 2}
+PAGE_ROWS = 64
 
 
 def _round_up(x, m):
@@ -61,7 +73,7 @@ def _round_up(x, m):
 
 class ArenaLayout:
     def __init__(self, n_layers, n_heads, head_dim, dtype, max_batch, max_seq, max_vis, max_text,
-                 lazy_mask, mode="vla", ragged=None, late=None):
+                 lazy_mask, mode="vla", ragged=None, late=None, paged=None):
         """ragged: None, or (cap_seq, cap_text, cap_vis) lists with one entry per slot of the batch (0 for a
         free slot), optionally followed by (base_seq, base_text, base_vis) when the extents were not
         assigned back to back (sequences joined later).
@@ -69,6 +81,18 @@ class ArenaLayout:
         positions per sequence instead of max_seq (a pruning boundary known when the arena is sized)."""
         self.late = late
         assert late is None or (ragged is None and 1 <= late[0] < n_layers and 1 <= late[1] <= max_seq)
+        # paged: None, or {"seq": [pages of slot 0, pages of slot 1, ...], "text": [...], "vis": [...]}
+        self.paged = None
+        if paged is not None:
+            assert ragged is None and late is None
+            assert max_seq % PAGE_ROWS == 0 and (mode == "gla" or (max_text % PAGE_ROWS == 0 and max_vis % PAGE_ROWS == 0))
+            pools = {"seq": max_batch * max_seq // PAGE_ROWS, "text": max_batch * max_text // PAGE_ROWS,
+                     "vis": max_batch * max_vis // PAGE_ROWS}
+            for kind in (("seq", "text", "vis") if mode == "vla" else ("seq",)):
+                held = [pg for lst in paged[kind] for pg in lst]
+                assert len(set(held)) == len(held), "a page is held twice"
+                assert all(0 <= pg < pools[kind] for pg in held), "page outside its pool"
+            self.paged = {k: [list(lst) for lst in v] for k, v in paged.items()}
         assert mode in ("vla", "gla")
         self.ragged = None
         if ragged is not None:
@@ -123,6 +147,10 @@ class ArenaLayout:
 
     def _row_index(self, kind, uniform_cap, b, h, row):
         """Row index inside a region of `kind` rows ("seq", "text" or "vis")."""
+        if self.paged is not None:
+            pages = self.paged[kind][b]
+            assert 0 <= row < len(pages) * PAGE_ROWS, "row on a page the sequence does not hold"
+            return (pages[row // PAGE_ROWS] * self.H + h) * PAGE_ROWS + row % PAGE_ROWS
         if self.ragged is None:
             return (b * self.H + h) * uniform_cap + row
         cap, base = self.ragged[kind]
@@ -192,6 +220,67 @@ def encode_rows(x, dtype):
     return (bits >> 16).astype(np.uint16).view(np.uint8)
 
 
+def _write_rows(img, layout, rows, offset_of_row):
+    """Rows 0..n-1 of one (sequence, head) into the image: one run, or one run per page."""
+    n, rowb = rows.shape[0], layout.D * layout.e
+    step = PAGE_ROWS if layout.paged is not None else max(n, 1)
+    raw = encode_rows(rows, layout.dtype).reshape(n, rowb) if n else None
+    for r0 in range(0, n, step):
+        r1 = min(r0 + step, n)
+        o = offset_of_row(r0)
+        img[o:o + (r1 - r0) * rowb] = raw[r0:r1].reshape(-1)
+
+
+class PagePools:
+    """Who holds which page, under the rule stated in the module's header: lowest free number first, the
+    pools in the order seq, text, vis for each sequence in slot order."""
+
+    def __init__(self, max_batch, max_seq, max_vis, max_text, mode="vla", any_lazy=True):
+        self.mode = mode
+        self.any_lazy = any_lazy
+        size = {"seq": max_batch * max_seq // PAGE_ROWS, "text": max_batch * max_text // PAGE_ROWS,
+                "vis": max_batch * max_vis // PAGE_ROWS}
+        self.free = {k: list(range(n)) for k, n in size.items()}
+        self.held = {k: [[] for _ in range(max_batch)] for k in size}
+
+    def _kinds(self):
+        return ("seq", "text", "vis") if (self.mode == "vla" and self.any_lazy) else ("seq",)
+
+    def _grow_to(self, kind, b, rows):
+        need = (rows + PAGE_ROWS - 1) // PAGE_ROWS - len(self.held[kind][b])
+        if need > len(self.free[kind]):
+            raise MemoryError("pool %s has %d free pages, %d wanted" % (kind, len(self.free[kind]), need))
+        for _ in range(max(need, 0)):
+            self.held[kind][b].append(self.free[kind].pop(0))
+
+    def rows_of(self, length, vis_len):
+        return {"seq": length, "text": length - vis_len, "vis": vis_len}
+
+    def prefill(self, slots, lens, vis_lens):
+        """The prompts of `slots` (in slot order) get their pages."""
+        for b in sorted(slots):
+            want = self.rows_of(lens[b], vis_lens[b])
+            for kind in self._kinds():
+                self._grow_to(kind, b, want[kind])
+
+    def decode_step(self, slots, lens, vis_lens):
+        """Before a decode step: every sequence of `slots` is about to store row lens[b] (and text row
+        lens[b] - vis_lens[b])."""
+        for b in sorted(slots):
+            want = self.rows_of(lens[b] + 1, vis_lens[b])
+            for kind in self._kinds():
+                if kind != "vis":
+                    self._grow_to(kind, b, want[kind])
+
+    def leave(self, b):
+        for kind in self.free:
+            self.free[kind] = sorted(self.free[kind] + self.held[kind][b])
+            self.held[kind][b] = []
+
+    def tables(self):
+        return {k: [list(x) for x in v] for k, v in self.held.items()}
+
+
 def kv_rows_image(layout, stacks, onto=None):
     """Expected bytes of the K and V row regions (the first rows_bytes() bytes of the K/V arena) given one
     stack oracle (of the layout's mode) per slot (None for a free slot).  Unwritten bytes are zero, or keep
@@ -203,12 +292,8 @@ def kv_rows_image(layout, stacks, onto=None):
             continue
         for l in range(layout.N):
             for h in range(layout.H):
-                kr = st.Kc[l][h]
-                o = layout.k_offset(l, b, h, 0)
-                img[o:o + kr.shape[0] * rowb] = encode_rows(kr, layout.dtype).reshape(-1)
-                vr = st.Vc[l][h]
-                o = layout.v_offset(l, b, h, 0)
-                img[o:o + vr.shape[0] * rowb] = encode_rows(vr, layout.dtype).reshape(-1)
+                for rows, offset_of in ((st.Kc[l][h], layout.k_offset), (st.Vc[l][h], layout.v_offset)):
+                    _write_rows(img, layout, rows, lambda r: offset_of(l, b, h, r))
     return img
 
 
@@ -219,8 +304,7 @@ def q_arena_image(layout, stacks, onto=None):
         if st is None or st.q_owner < 0:
             continue
         for h in range(layout.H):
-            o = layout.q_offset(b, h, 0)
-            img[o:o + st.Qc.shape[1] * rowb] = encode_rows(st.Qc[h], layout.dtype).reshape(-1)
+            _write_rows(img, layout, st.Qc[h], lambda r: layout.q_offset(b, h, r))
     return img
 
 
