@@ -208,6 +208,45 @@ qc_status qc_seq_grow(qc_kvcache* kv, qc_qcache* qc, int32_t b, int32_t cap_seq,
 qc_status qc_seq_extent(const qc_kvcache* kv, int32_t b, int32_t* live, int32_t* base_seq,
                         int32_t* base_text, int32_t* base_vis);
 
+/* ---- paged batches ("Efficiency Evaluation", the maximum-batch paragraph: what limits the batch is the
+ * memory the caches of all sequences take together) ------------------------------------------------
+ * On a batch set up by qc_reset_paged the rows of a sequence live on pages of QC_PAGE_ROWS rows that it
+ * is handed as it needs them, so the arena holds whatever mix of lengths fits in total, a sequence grows
+ * without a copy, and a page freed by one sequence serves any other.  The regions keep their sizes and
+ * places; each is read as [page][head][QC_PAGE_ROWS][head_dim], and row r of head h of a sequence sits at
+ * row index (list[r / QC_PAGE_ROWS]*n_heads + h)*QC_PAGE_ROWS + r % QC_PAGE_ROWS, where `list` is the
+ * sequence's page list of the pool the region belongs to: QC_POOL_SEQ (one row per position: V rows of
+ * every layer, K rows of ordinary layers, Q Cache rows under QC_GLA; max_batch*max_seq/QC_PAGE_ROWS
+ * pages), QC_POOL_TEXT (K rows of lazy layers under QC_VLA; max_batch*max_text/QC_PAGE_ROWS pages) and
+ * QC_POOL_VIS (Q Cache rows under QC_VLA; max_batch*max_vis/QC_PAGE_ROWS pages).  One list per sequence
+ * and pool serves every layer and head.  The last two pools are in use only under QC_VLA with at least
+ * one lazy layer.  Pages are handed out lowest free number first, for the slots in order and for each
+ * slot in the order of the pools above: by qc_prefill of layer 0 for the prompts of its pass, and by
+ * qc_decode of layer 0 when the row the step appends opens a page (QC_ECAPACITY, and nothing changed,
+ * when a pool has too few free pages).  A sequence may hold at most max_seq positions, max_text text
+ * rows and max_vis visual rows, as without pages.
+ *   The configuration must have max_seq, max_text and max_vis multiples of QC_PAGE_ROWS, max_seq at
+ *   most 65536 and no prune_before_layer (QC_EINVAL; qc_page_table_bytes returns 0).
+ *   page_lists: DEVICE, 16-byte aligned, at least qc_page_table_bytes(cfg) bytes, owned by the caller and
+ *   left alone by it until the next qc_reset*: the lists as the kernels read them.
+ *   present: HOST, `batch` flags or NULL (every slot holds a sequence); 0 makes slot b free from the start.
+ * Slots work as after qc_reset_ragged: qc_seq_leave gives the sequence's pages back (lowest numbers are
+ * handed out first again; nothing is cleared), qc_seq_join takes no capacities (pass 0 for both) and
+ * its sequence gets pages when its prefill pass begins.  Not available on a paged batch (QC_EORDER):
+ * qc_seq_grow and qc_seq_extent (nothing to grow or to place), qc_prune, qc_last_row_attention and
+ * qc_decode_graph_create (a step may hand out pages, which is host work).  qc_locate answers through the
+ * lists.  qc_reset and qc_reset_ragged return to rows in runs.
+ * qc_seq_pages: HOST query: *count = pages slot b holds in `pool`; the first min(capacity, *count) page
+ *   numbers are written to `pages` if it is not NULL. */
+#define QC_PAGE_ROWS 64
+enum { QC_POOL_SEQ = 0, QC_POOL_TEXT = 1, QC_POOL_VIS = 2 };
+size_t qc_page_table_bytes(const qc_config* cfg);
+qc_status qc_reset_paged(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* vis_start,
+                         const int32_t* vis_len, const uint8_t* present, void* page_lists,
+                         size_t page_list_bytes, int32_t zero_fill, void* stream);
+qc_status qc_seq_pages(const qc_kvcache* kv, int32_t b, int32_t pool, int32_t* pages, int32_t capacity,
+                       int32_t* count);
+
 /* ---- prefill: one layer over the packed prompts (paper Eq. 1; Eq. 7 in a lazy layer) -----------
  * q, k, v, out: DEVICE, element (token t, head h, dim d) at t*token_stride + h*head_stride + d
  *   (strides in elements, shared by all four tensors; head_stride >= head_dim, 16-byte aligned

@@ -50,6 +50,10 @@ _PROTOTYPES = {
     "qc_reset": (c_int32, [c_void_p, c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32), c_int32, c_void_p]),
     "qc_reset_ragged": (c_int32, [c_void_p, c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32),
                                   POINTER(c_int32), c_int32, c_void_p]),
+    "qc_page_table_bytes": (c_size_t, [POINTER(qc_config)]),
+    "qc_reset_paged": (c_int32, [c_void_p, c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32), POINTER(c_uint8),
+                                 c_void_p, c_size_t, c_int32, c_void_p]),
+    "qc_seq_pages": (c_int32, [c_void_p, c_int32, c_int32, POINTER(c_int32), c_int32, POINTER(c_int32)]),
     "qc_seq_leave": (c_int32, [c_void_p, c_void_p, c_int32, c_void_p]),
     "qc_seq_join": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, c_void_p]),
     "qc_seq_grow": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_void_p]),
@@ -192,6 +196,25 @@ def qc_reset(kv, qc, batch, vis_start, vis_len, zero_fill=1, stream=None):
 def qc_reset_ragged(kv, qc, batch, vis_start, vis_len, cap_seq, cap_text, zero_fill=1, stream=None):
     return _check(load_library().qc_reset_ragged(kv, qc, batch, _i32(vis_start), _i32(vis_len), _i32(cap_seq),
                                                 _i32(cap_text), int(zero_fill), stream))
+
+
+def qc_page_table_bytes(cfg):
+    return load_library().qc_page_table_bytes(byref(cfg))
+
+
+def qc_reset_paged(kv, qc, batch, vis_start, vis_len, present, page_lists, page_list_bytes, zero_fill=1, stream=None):
+    flags = None if present is None else (c_uint8 * len(present))(*[int(bool(x)) for x in present])
+    return _check(load_library().qc_reset_paged(kv, qc, batch, _i32(vis_start), _i32(vis_len), flags, _ptr(page_lists),
+                                               page_list_bytes, int(zero_fill), stream))
+
+
+def qc_seq_pages(kv, b, pool):
+    """The pages slot b holds in `pool` (0 positions, 1 text rows, 2 visual rows), in row order."""
+    n = c_int32()
+    _check(load_library().qc_seq_pages(kv, b, pool, None, 0, byref(n)))
+    buf = (c_int32 * max(n.value, 1))()
+    _check(load_library().qc_seq_pages(kv, b, pool, buf, n.value, byref(n)))
+    return [buf[i] for i in range(n.value)]
 
 
 def qc_seq_leave(kv, qc, b, stream=None):

@@ -4,6 +4,7 @@
 #include "qcache.h"
 
 #include <algorithm>
+#include <array>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -69,6 +70,25 @@ struct Config {
   int64_t kv_bytes() const { return off_meta() + meta_bytes(); }
   int64_t q_bytes() const { return (int64_t)max_batch * H * cap_q() * D * e(); }
   int64_t row_bytes() const { return (int64_t)D * e(); }
+  // Paged batches: page lists per sequence and pool (POOL_SEQ positions, POOL_TEXT text rows of lazy layers,
+  // POOL_VIS Q Cache rows under Visual Lazy Attention).  The last two exist only where rows are kept in them.
+  int n_lazy() const { int n = 0; for (auto f : lazy) n += f ? 1 : 0; return n; }
+  bool pool_used(int pool) const { return pool == 0 || (!gla() && n_lazy() > 0); }
+  int32_t pool_stride(int pool) const {   // entries of one sequence's list = pages it may hold at most
+    if (!pool_used(pool)) return 0;
+    return (pool == 0 ? max_seq : pool == 1 ? max_text : max_vis) / qc::kPageRows;
+  }
+  int64_t pool_pages(int pool) const { return (int64_t)max_batch * pool_stride(pool); }
+  int64_t table_off(int pool) const {     // first entry of the pool's lists in the page-list buffer
+    int64_t o = 0;
+    for (int i = 0; i < pool; ++i) o += pool_pages(i);
+    return o;
+  }
+  int64_t table_entries() const { return table_off(3); }
+  bool pageable() const {
+    return late_from == 0 && max_seq % qc::kPageRows == 0 && max_seq / qc::kPageRows <= qc::kMaxPagesPerSeq &&
+           (gla() || (max_text % qc::kPageRows == 0 && max_vis % qc::kPageRows == 0));
+  }
   bool same(const Config& o) const {
     return N == o.N && H == o.H && D == o.D && dtype == o.dtype && max_batch == o.max_batch &&
            max_seq == o.max_seq && max_vis == o.max_vis && max_text == o.max_text && mode == o.mode &&
@@ -145,6 +165,14 @@ struct qc_kvcache {
     if (ragged) for (int b = 0; b < batch; ++b) m = std::max<int64_t>(m, cap_seq[b]);
     return m;
   }
+  // Paged batches (qc_reset_paged): rows live on pages of kPageRows rows.  pages[pool][b] = the pages slot b
+  // holds, in row order; free_pages[pool] ascending (the lowest free page is handed out first); `tables` is
+  // the caller's device buffer the kernels read the lists from.
+  bool paged = false;
+  int32_t* tables = nullptr;
+  std::vector<std::vector<int32_t>> pages[3];
+  std::vector<int32_t> free_pages[3];
+  bool slots() const { return ragged || paged; }   // sequences may join and leave
   // Slots of the batch (qc_seq_join / qc_seq_leave): live[b] = slot b holds a sequence; joining[b] =
   // it is (to be) filled by the prefill pass that is open or about to open; joined_at[b] = value of
   // `generated` when its prefill pass ended.  Without joins and leaves every slot is live, every
@@ -265,9 +293,15 @@ qc_status qc_qcache_create(const qc_config* cfg, void* dev_arena, size_t arena_b
 void qc_kvcache_destroy(qc_kvcache* kv) { delete kv; }
 void qc_qcache_destroy(qc_qcache* qc) { delete qc; }
 
+struct PagedInit {
+  const uint8_t* present;   // batch flags (0 = the slot starts free), or null: every slot holds a sequence
+  void* tables;             // device buffer for the page lists
+  size_t table_bytes;
+};
+
 static qc_status reset_impl(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* vis_start,
                             const int32_t* vis_len, const int32_t* cap_seq, const int32_t* cap_text,
-                            int32_t zero_fill, void* stream) {
+                            int32_t zero_fill, void* stream, const PagedInit* paged = nullptr) {
   if (!kv || !qc) return fail(QC_EINVAL, "qc_reset: null handle");
   if (!kv->cfg.same(qc->cfg)) return fail(QC_EINVAL, "qc_reset: K/V cache and Q Cache were created with different configurations");
   if (!vis_start || !vis_len) return fail(QC_EINVAL, "qc_reset: null span arrays");
@@ -276,10 +310,16 @@ static qc_status reset_impl(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const 
   if (batch > c.max_batch) return fail(QC_ECAPACITY, "qc_reset: batch %d exceeds max_batch %d", batch, c.max_batch);
   const bool ragged = cap_seq != nullptr;
   if (ragged && !cap_text) return fail(QC_EINVAL, "qc_reset_ragged: null capacity array");
+  if (paged) {
+    if (!c.pageable()) return fail(QC_EINVAL, "qc_reset_paged: the configuration cannot be paged (max_seq, max_text and max_vis must be multiples of %d, max_seq at most %d, no separately sized late layers)", qc::kPageRows, qc::kPageRows * qc::kMaxPagesPerSeq);
+    if (!paged->tables || ((uintptr_t)paged->tables & 15)) return fail(QC_EINVAL, "qc_reset_paged: page-list buffer null or not 16-byte aligned");
+    if ((int64_t)paged->table_bytes < c.table_entries() * 4) return fail(QC_ECAPACITY, "qc_reset_paged: page-list buffer holds %zu bytes, %lld needed", paged->table_bytes, (long long)c.table_entries() * 4);
+  }
   if (ragged && c.late_from > 0) return fail(QC_EINVAL, "qc_reset_ragged: per-sequence capacities cannot be combined with a configuration that sizes the layers behind a pruning boundary separately");
   int64_t sum_seq = 0, sum_text = 0, sum_vis = 0;
   for (int b = 0; b < batch; ++b) {
     if (ragged && cap_seq[b] == 0) continue;
+    if (paged && paged->present && !paged->present[b]) continue;
     if (vis_start[b] < 0 || vis_len[b] < 0) return fail(QC_EINVAL, "qc_reset: negative span for sequence %d", b);
     if (!ragged) {
       if (!c.gla() && vis_len[b] > c.max_vis) return fail(QC_ECAPACITY, "qc_reset: sequence %d has %d visual tokens, max_vis %d", b, vis_len[b], c.max_vis);
@@ -321,6 +361,20 @@ static qc_status reset_impl(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const 
   kv->joining.assign(batch, 1);
   kv->joined_at.assign(batch, 0);
   kv->join_pass = false;
+  kv->paged = paged != nullptr;
+  kv->tables = paged ? (int32_t*)paged->tables : nullptr;
+  for (int pool = 0; pool < 3; ++pool) {
+    kv->pages[pool].assign(paged ? batch : 0, std::vector<int32_t>());
+    kv->free_pages[pool].clear();
+    if (paged)
+      for (int64_t pg = 0; pg < c.pool_pages(pool); ++pg) kv->free_pages[pool].push_back((int32_t)pg);
+  }
+  if (paged && paged->present)
+    for (int b = 0; b < batch; ++b)
+      if (!paged->present[b]) {   // free slot: no rows, nothing to fill
+        kv->live[b] = kv->joining[b] = 0;
+        kv->vis_start[b] = kv->vis_len[b] = 0;
+      }
   if (ragged) {
     kv->cap_seq.assign(cap_seq, cap_seq + batch);
     kv->cap_text.assign(cap_text, cap_text + batch);
@@ -374,6 +428,66 @@ qc_status qc_reset_ragged(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const in
   return reset_impl(kv, qc, batch, vis_start, vis_len, cap_seq, cap_text, zero_fill, stream);
 }
 
+static_assert(QC_PAGE_ROWS == qc::kPageRows, "header and library disagree on the page size");
+
+size_t qc_page_table_bytes(const qc_config* cfg) {
+  Config c;
+  if (!parse_config(cfg, &c) || !c.pageable()) return 0;
+  return (size_t)round_up(c.table_entries() * 4, 256);
+}
+
+qc_status qc_reset_paged(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int32_t* vis_start,
+                         const int32_t* vis_len, const uint8_t* present, void* page_lists,
+                         size_t page_list_bytes, int32_t zero_fill, void* stream) {
+  const PagedInit init = {present, page_lists, page_list_bytes};
+  return reset_impl(kv, qc, batch, vis_start, vis_len, nullptr, nullptr, zero_fill, stream, &init);
+}
+
+// Pages the sequences need beyond what they hold.  want[b][pool] = rows slot b must be able to hold in the
+// pool (negative: leave the slot's list of that pool alone).  Checks every pool first (QC_ECAPACITY, nothing
+// changed), then hands pages out lowest number first, slot after slot and pool after pool, and enqueues
+// the new list entries for the kernels.
+static qc_status paged_reserve(qc_kvcache* kv, const std::vector<std::array<int64_t, 3>>& want, const char* who, hipStream_t st) {
+  const Config& c = kv->cfg;
+  int64_t need[3] = {0, 0, 0};
+  for (int b = 0; b < kv->batch; ++b)
+    for (int pool = 0; pool < 3; ++pool) {
+      if (want[b][pool] < 0 || !c.pool_used(pool)) continue;
+      const int64_t pages = (want[b][pool] + qc::kPageRows - 1) / qc::kPageRows;
+      if (pages > c.pool_stride(pool)) return fail(QC_ECAPACITY, "%s: sequence %d needs %lld pages of pool %d, a sequence may hold %d", who, b, (long long)pages, pool, c.pool_stride(pool));
+      need[pool] += std::max<int64_t>(0, pages - (int64_t)kv->pages[pool][b].size());
+    }
+  for (int pool = 0; pool < 3; ++pool)
+    if (need[pool] > (int64_t)kv->free_pages[pool].size())
+      return fail(QC_ECAPACITY, "%s: %lld pages of pool %d needed, %zu free", who, (long long)need[pool], pool, kv->free_pages[pool].size());
+  qc::TableChunk tc;
+  int n = 0;
+  size_t taken[3] = {0, 0, 0};
+  for (int b = 0; b < kv->batch; ++b)
+    for (int pool = 0; pool < 3; ++pool) {
+      if (want[b][pool] < 0 || !c.pool_used(pool)) continue;
+      const int64_t pages = (want[b][pool] + qc::kPageRows - 1) / qc::kPageRows;
+      while ((int64_t)kv->pages[pool][b].size() < pages) {
+        const int32_t pg = kv->free_pages[pool][taken[pool]++];
+        tc.at[n] = (int32_t)(c.table_off(pool) + (int64_t)b * c.pool_stride(pool) + (int64_t)kv->pages[pool][b].size());
+        tc.page[n] = pg;
+        kv->pages[pool][b].push_back(pg);
+        if (++n == qc::TableChunk::N) {
+          hipError_t e = qc::launch_table_upload(kv->tables, n, tc, st);
+          if (e != hipSuccess) return fail(QC_EDEVICE, "%s: page-list upload: %s", who, hipGetErrorString(e));
+          n = 0;
+        }
+      }
+    }
+  for (int pool = 0; pool < 3; ++pool)
+    kv->free_pages[pool].erase(kv->free_pages[pool].begin(), kv->free_pages[pool].begin() + taken[pool]);
+  if (n > 0) {
+    hipError_t e = qc::launch_table_upload(kv->tables, n, tc, st);
+    if (e != hipSuccess) return fail(QC_EDEVICE, "%s: page-list upload: %s", who, hipGetErrorString(e));
+  }
+  return QC_OK;
+}
+
 static qc::LayerView make_view(const qc_kvcache* kv, const qc_qcache* qc, int layer) {
   const Config& c = kv->cfg;
   qc::LayerView lv;
@@ -389,7 +503,18 @@ static qc::LayerView make_view(const qc_kvcache* kv, const qc_qcache* qc, int la
   lv.meta = (const int32_t*)(kv->arena + c.off_meta()) + (kv->late(layer) ? qc::META_ROWS * c.max_batch : 0);
   lv.max_batch = c.max_batch;
   lv.flags = (kv->ragged ? qc::LV_RAGGED : 0) | ((c.lazy[layer] && !c.gla()) ? qc::LV_K_TEXT : 0) |
-             (c.gla() ? 0 : qc::LV_Q_VIS) | (kv->late(layer) ? qc::LV_LATE : 0);
+             (c.gla() ? 0 : qc::LV_Q_VIS) | (kv->late(layer) ? qc::LV_LATE : 0) | (kv->paged ? qc::LV_PAGED : 0);
+  lv.pt_seq = lv.pt_k = lv.pt_q = nullptr;
+  lv.pt_seq_stride = lv.pt_k_stride = lv.pt_q_stride = 0;
+  if (kv->paged) {
+    const int k_pool = (c.lazy[layer] && !c.gla()) ? 1 : 0, q_pool = c.gla() ? 0 : 2;
+    lv.pt_seq = kv->tables + c.table_off(0);
+    lv.pt_seq_stride = c.pool_stride(0);
+    lv.pt_k = kv->tables + c.table_off(k_pool);
+    lv.pt_k_stride = c.pool_stride(k_pool);
+    lv.pt_q = kv->tables + c.table_off(q_pool);
+    lv.pt_q_stride = c.pool_stride(q_pool);
+  }
   return lv;
 }
 
@@ -477,6 +602,15 @@ qc_status qc_prefill(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_la
     return fail(QC_EORDER, "qc_prefill: Q Cache belongs to layer %d, layer %d inherits from %d", qc->owner, layer, c.anchor[layer]);
 
   hipStream_t st = (hipStream_t)stream;
+  if (kv->paged && layer == 0) {   // the prompts of this pass get their pages
+    std::vector<std::array<int64_t, 3>> want(kv->batch, std::array<int64_t, 3>{-1, -1, -1});
+    for (int b = 0; b < kv->batch; ++b)
+      if (kv->joining[b]) {
+        const int64_t len = (int64_t)cu_seqlens[b + 1] - cu_seqlens[b];
+        want[b] = {len, len - kv->vis_len[b], kv->vis_len[b]};
+      }
+    if (qc_status s = paged_reserve(kv, want, "qc_prefill", st)) return s;
+  }
   qc::LayerView lv = make_view(kv, qc, layer);
   if (opens) {
     for (int first = 0; first < kv->batch; first += qc::MetaChunk::N) {
@@ -557,13 +691,22 @@ static int64_t first_fit(std::vector<std::pair<int64_t, int64_t>> used, int64_t 
 
 qc_status qc_seq_leave(qc_kvcache* kv, qc_qcache* qc, int32_t b, void* stream) {
   if (!kv || !qc) return fail(QC_EINVAL, "qc_seq_leave: null handle");
-  if (!kv->ragged) return fail(QC_EORDER, "qc_seq_leave: needs a batch set up with per-sequence capacities (qc_reset_ragged)");
+  if (!kv->slots()) return fail(QC_EORDER, "qc_seq_leave: needs a batch set up with per-sequence capacities (qc_reset_ragged) or with pages (qc_reset_paged)");
   if (b < 0 || b >= kv->batch) return fail(QC_EINVAL, "qc_seq_leave: slot %d out of range", b);
   if (kv->phase != PH_READY) return fail(QC_EORDER, "qc_seq_leave: allowed between two decode steps only");
   if (!kv->live[b]) return fail(QC_EINVAL, "qc_seq_leave: slot %d holds no sequence", b);
   kv->live[b] = 0;
-  kv->cap_seq[b] = kv->cap_text[b] = 0;
-  kv->base_seq[b] = kv->base_text[b] = kv->base_vis[b] = 0;
+  if (kv->paged) {   // its pages are free again (lowest numbers first at the next hand-out)
+    for (int pool = 0; pool < 3; ++pool) {
+      auto& fr = kv->free_pages[pool];
+      fr.insert(fr.end(), kv->pages[pool][b].begin(), kv->pages[pool][b].end());
+      std::sort(fr.begin(), fr.end());
+      kv->pages[pool][b].clear();
+    }
+  } else {
+    kv->cap_seq[b] = kv->cap_text[b] = 0;
+    kv->base_seq[b] = kv->base_text[b] = kv->base_vis[b] = 0;
+  }
   kv->vis_start[b] = kv->vis_len[b] = 0;
   kv->len0[b] = kv->tok0[b] = kv->joined_at[b] = 0;
   return upload_decode_meta(kv, b, 1, (hipStream_t)stream);
@@ -573,13 +716,29 @@ qc_status qc_seq_join(qc_kvcache* kv, qc_qcache* qc, int32_t b, int32_t vis_star
                       int32_t cap_seq, int32_t cap_text, void* stream) {
   if (!kv || !qc) return fail(QC_EINVAL, "qc_seq_join: null handle");
   const Config& c = kv->cfg;
-  if (!kv->ragged) return fail(QC_EORDER, "qc_seq_join: needs a batch set up with per-sequence capacities (qc_reset_ragged)");
+  if (!kv->slots()) return fail(QC_EORDER, "qc_seq_join: needs a batch set up with per-sequence capacities (qc_reset_ragged) or with pages (qc_reset_paged)");
   if (b < 0 || b >= kv->batch) return fail(QC_EINVAL, "qc_seq_join: slot %d out of range", b);
   // between two decode steps, or before the prefill pass that follows (more joins, or the reset) has begun
   if (kv->phase != PH_READY && kv->phase != PH_RESET) return fail(QC_EORDER, "qc_seq_join: allowed between two decode steps, or before a prefill pass has begun");
   if (kv->first_late >= 0) return fail(QC_EORDER, "qc_seq_join: not available on a batch with a pruning boundary");
   if (kv->live[b]) return fail(QC_EINVAL, "qc_seq_join: slot %d is taken", b);
   if (vis_start < 0 || vis_len < 0) return fail(QC_EINVAL, "qc_seq_join: negative span");
+  if (kv->paged) {   // pages are handed out when the sequence's prefill pass begins; capacities are not used
+    if (cap_seq != 0 || cap_text != 0) return fail(QC_EINVAL, "qc_seq_join: a paged batch takes no capacities (pass 0)");
+    if (!c.gla() && vis_len > c.max_vis) return fail(QC_ECAPACITY, "qc_seq_join: %d visual tokens, max_vis %d", vis_len, c.max_vis);
+    if ((int64_t)vis_start + vis_len > c.max_seq) return fail(QC_ECAPACITY, "qc_seq_join: the span exceeds max_seq");
+    kv->live[b] = kv->joining[b] = 1;
+    kv->joined_at[b] = 0;
+    kv->vis_start[b] = vis_start;
+    kv->vis_len[b] = vis_len;
+    kv->len0[b] = kv->tok0[b] = 0;
+    if (kv->phase == PH_READY) {
+      kv->join_pass = true;
+      kv->phase = PH_RESET;
+      kv->next_layer = 0;
+    }
+    return QC_OK;
+  }
   if (cap_seq < 8 || cap_seq % 8 || cap_text < 0) return fail(QC_EINVAL, "qc_seq_join: cap_seq must be a positive multiple of 8, cap_text not negative");
   if ((int64_t)vis_start + vis_len > cap_seq) return fail(QC_ECAPACITY, "qc_seq_join: the span exceeds the sequence's %d positions", cap_seq);
   std::vector<std::pair<int64_t, int64_t>> seq, text, vis;
@@ -626,6 +785,7 @@ qc_status qc_seq_join(qc_kvcache* kv, qc_qcache* qc, int32_t b, int32_t vis_star
 qc_status qc_seq_grow(qc_kvcache* kv, qc_qcache* qc, int32_t b, int32_t cap_seq, int32_t cap_text, void* stream) {
   if (!kv || !qc) return fail(QC_EINVAL, "qc_seq_grow: null handle");
   const Config& c = kv->cfg;
+  if (kv->paged) return fail(QC_EORDER, "qc_seq_grow: a paged batch grows page by page on its own");
   if (!kv->ragged) return fail(QC_EORDER, "qc_seq_grow: needs a batch set up with per-sequence capacities (qc_reset_ragged)");
   if (b < 0 || b >= kv->batch) return fail(QC_EINVAL, "qc_seq_grow: slot %d out of range", b);
   if (kv->phase != PH_READY) return fail(QC_EORDER, "qc_seq_grow: allowed between two decode steps only");
@@ -695,8 +855,20 @@ qc_status qc_seq_grow(qc_kvcache* kv, qc_qcache* qc, int32_t b, int32_t cap_seq,
   return QC_OK;
 }
 
+qc_status qc_seq_pages(const qc_kvcache* kv, int32_t b, int32_t pool, int32_t* pages, int32_t capacity, int32_t* count) {
+  if (!kv || !count) return fail(QC_EINVAL, "qc_seq_pages: null argument");
+  if (!kv->paged) return fail(QC_EORDER, "qc_seq_pages: needs a paged batch (qc_reset_paged)");
+  if (b < 0 || b >= kv->batch || pool < 0 || pool > 2) return fail(QC_EINVAL, "qc_seq_pages: slot or pool out of range");
+  const auto& list = kv->pages[pool][b];
+  *count = (int32_t)list.size();
+  if (pages)
+    for (int i = 0; i < capacity && i < (int)list.size(); ++i) pages[i] = list[i];
+  return QC_OK;
+}
+
 qc_status qc_seq_extent(const qc_kvcache* kv, int32_t b, int32_t* live, int32_t* base_seq, int32_t* base_text, int32_t* base_vis) {
   if (!kv || !live || !base_seq || !base_text || !base_vis) return fail(QC_EINVAL, "qc_seq_extent: null argument");
+  if (kv->paged) return fail(QC_EORDER, "qc_seq_extent: a paged batch has no extents (see qc_seq_pages)");
   if (!kv->ragged) return fail(QC_EORDER, "qc_seq_extent: needs a batch set up with per-sequence capacities (qc_reset_ragged)");
   if (b < 0 || b >= kv->batch) return fail(QC_EINVAL, "qc_seq_extent: slot %d out of range", b);
   *live = kv->live[b];
@@ -769,6 +941,15 @@ static qc_status decode_impl(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32
   if (qk_unused && kv->score_workspace != workspace)
     return fail(QC_EINVAL, "qc_decode: layer %d needs the workspace its block's first layer was called with", layer);
 
+  if (kv->paged && layer == 0) {   // the row this step appends may open a page
+    std::vector<std::array<int64_t, 3>> want(kv->batch, std::array<int64_t, 3>{-1, -1, -1});
+    for (int b = 0; b < kv->batch; ++b)
+      if (kv->live[b]) {
+        const int64_t len = (int64_t)kv->len_of(0, b) + kv->steps_of(b);
+        want[b] = {len + 1, len + 1 - kv->vis_len[b], -1};
+      }
+    if (qc_status s = paged_reserve(kv, want, "qc_decode", (hipStream_t)stream)) return s;
+  }
   qc::DecodeArgs a;
   a.lv = make_view(kv, c.gla() ? qc : nullptr, layer);
   a.q = q; a.k = k; a.v = v; a.out = out;
@@ -786,7 +967,7 @@ static qc_status decode_impl(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32
   a.max_chunks = max_chunks;
   a.scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)c.D);
   // a recorded launch reads everything per-sequence from device memory: it then serves any batch of this size
-  a.inline_meta = (!geom && kv->batch <= qc::DecodeArgs::kInlineSeqs) ? 1 : 0;
+  a.inline_meta = (!geom && !kv->paged && kv->batch <= qc::DecodeArgs::kInlineSeqs) ? 1 : 0;
   for (int b = 0; b < qc::DecodeArgs::kInlineSeqs; ++b) {
     const bool ok = a.inline_meta && b < kv->batch;
     a.len0_inline[b] = ok ? kv->len_base(layer, b) : 0;
@@ -855,6 +1036,7 @@ qc_status qc_decode_graph_create(qc_kvcache* kv, qc_qcache* qc, const void* cons
   if (!out_graph) return fail(QC_EINVAL, "qc_decode_graph_create: out_graph is null");
   *out_graph = nullptr;
   if (!kv || !qc || !q || !k || !v || !out) return fail(QC_EINVAL, "qc_decode_graph_create: null argument");
+  if (kv->paged) return fail(QC_EORDER, "qc_decode_graph_create: not available on a paged batch (a step may hand out pages, which is host work)");
   const Config& c = kv->cfg;
   if (!c.same(qc->cfg)) return fail(QC_EINVAL, "qc_decode_graph_create: handles were created with different configurations");
   if (kv->phase != PH_READY) return fail(QC_EORDER, "qc_decode_graph_create: needs a finished prefill pass and no decode step in flight");
@@ -1081,6 +1263,7 @@ qc_status qc_last_row_attention(qc_kvcache* kv, int32_t layer, const void* q_las
   const Config& c = kv->cfg;
   if (layer < 0 || layer >= c.N) return fail(QC_EINVAL, "qc_last_row_attention: layer %d out of range", layer);
   if (c.lazy[layer]) return fail(QC_EINVAL, "qc_last_row_attention: layer %d is lazy and does not hold all of its keys", layer);
+  if (kv->paged) return fail(QC_EORDER, "qc_last_row_attention: not available on a paged batch");
   if (!q_last || !probs || !workspace) return fail(QC_EINVAL, "qc_last_row_attention: null tensor or workspace");
   if (((uintptr_t)q_last | (uintptr_t)workspace) & 15) return fail(QC_EINVAL, "qc_last_row_attention: q_last and workspace must be 16-byte aligned");
   if ((uintptr_t)probs & 3) return fail(QC_EINVAL, "qc_last_row_attention: probs must be 4-byte aligned");
@@ -1199,6 +1382,7 @@ qc_status qc_prune(qc_kvcache* kv, qc_qcache* qc, const int32_t* keep) {
   if (!kv || !qc || !keep) return fail(QC_EINVAL, "qc_prune: null argument");
   const Config& c = kv->cfg;
   if (!c.same(qc->cfg)) return fail(QC_EINVAL, "qc_prune: handles were created with different configurations");
+  if (kv->paged) return fail(QC_EORDER, "qc_prune: not available on a paged batch");
   if (kv->phase != PH_PREFILL) return fail(QC_EORDER, "qc_prune: allowed only inside a prefill pass, between two layers");
   if (kv->first_late >= 0) return fail(QC_EORDER, "qc_prune: this pass already has a pruning boundary (before layer %d)", kv->first_late);
   if (kv->join_pass || !kv->all_live()) return fail(QC_EORDER, "qc_prune: not available on a batch with free slots or with sequences that joined later");
@@ -1288,6 +1472,32 @@ qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t 
   if (!kv->ragged && pos >= c.max_seq) return fail(QC_EINVAL, "qc_locate: index out of range");
   if (!kv->live[b]) return fail(QC_EINVAL, "qc_locate: slot %d holds no sequence", b);
   const int64_t rb = c.row_bytes();
+  if (kv->paged) {
+    auto on_page = [&](int pool, int64_t row, int64_t* index) {
+      const auto& list = kv->pages[pool][b];
+      if (row / qc::kPageRows >= (int64_t)list.size()) return false;
+      *index = ((int64_t)list[row / qc::kPageRows] * c.H + h) * qc::kPageRows + row % qc::kPageRows;
+      return true;
+    };
+    int64_t index = 0;
+    if (which == QC_V) {
+      if (!on_page(0, pos, &index)) return fail(QC_ECAPACITY, "qc_locate: position %d lies on no page of the sequence", pos);
+      *src_layer = layer;
+      *byte_offset = c.off_v(layer) + index * rb;
+      return QC_OK;
+    }
+    const int32_t s = kv->vis_start[b], vn = kv->vis_len[b];
+    int src = layer;
+    int64_t row = pos;
+    if (c.lazy[layer]) {
+      if (c.gla() || (pos >= s && pos < s + vn)) src = c.anchor[layer];
+      else if (pos >= s + vn) row = pos - vn;
+    }
+    if (!on_page((c.lazy[src] && !c.gla()) ? 1 : 0, row, &index)) return fail(QC_ECAPACITY, "qc_locate: position %d lies on no page of the sequence", pos);
+    *src_layer = src;
+    *byte_offset = c.off_k(src) + index * rb;
+    return QC_OK;
+  }
   // row index of (b, h, row 0) in a region of full-length rows / of a lazy layer's text rows
   auto seq0_of = [&](int l) {
     return kv->ragged ? (int64_t)kv->base_seq[b] * c.H + (int64_t)h * kv->cap_seq[b] : ((int64_t)b * c.H + h) * c.cap_v(l);

@@ -92,7 +92,9 @@ __device__ __forceinline__ int decode_generated(const DecodeArgs& a) {
 // MODE 0: ordinary and Visual Lazy Attention layers.  MODE 1: first layer of a Global Lazy Attention
 // block (also stores its scores and its query).  MODE 2: lazy layer under Global Lazy Attention
 // (reuses the stored scores, streams V only).
-template <typename T, int D, int MODE, bool INLINE>
+// PAGED: rows live on pages; the workgroup stages the sequence's two page lists (positions, and the
+// pool its own K rows live in) in LDS before it streams.
+template <typename T, int D, int MODE, bool INLINE, bool PAGED>
 __device__ __forceinline__ void decode_split_body(const DecodeArgs& a, const DecodeGlaArgs& g) {
   constexpr bool SHARED = MODE == 2, STORE = MODE == 1;
   constexpr int EPL = ElemTraits<T>::kPer16;  // elements per lane (16 bytes)
@@ -115,10 +117,34 @@ __device__ __forceinline__ void decode_split_body(const DecodeArgs& a, const Dec
   const int li = lane % LPR, gid = wave * GPW + lane / LPR;
   const int64_t bh = (int64_t)b * a.n_heads + h;
 
-  const RowBase rb = row_bases(a.lv, b, h, a.n_heads);
+  __shared__ int32_t s_pg_seq[PAGED ? kMaxPagesPerSeq : 1], s_pg_k[PAGED ? kMaxPagesPerSeq : 1];
+  RowBase rb = {0, 0, 0, 0};
+  if constexpr (PAGED) {
+    const int n_seq = (len >> 6) + 1;                                   // pages holding positions 0 .. len
+    const int n_k = (((lazy && !SHARED) ? len - sm.vis_len : len) >> 6) + 1;   // pages holding its own K rows
+    for (int i = threadIdx.x; i < n_seq; i += 256) s_pg_seq[i] = a.lv.pt_seq[(int64_t)b * a.lv.pt_seq_stride + i];
+    if (!SHARED)
+      for (int i = threadIdx.x; i < n_k; i += 256) s_pg_k[i] = a.lv.pt_k[(int64_t)b * a.lv.pt_k_stride + i];
+    __syncthreads();
+  } else {
+    rb = row_bases(a.lv, b, h, a.n_heads);
+  }
+  // addresses of this lane's 16 bytes of a row: own K row r, the first layer's K row of a position, own V row
   char* kown = a.lv.k_own + rb.k * ROWB + li * 16;
   const char* kanc = lazy ? a.lv.k_anchor + rb.anchor * ROWB + li * 16 : nullptr;
   char* vown = a.lv.v_own + rb.v * ROWB + li * 16;
+  auto k_own_at = [&](int r) -> char* {
+    if constexpr (PAGED) return kown + paged_row(s_pg_k, r, h, a.n_heads) * ROWB;
+    else return kown + (int64_t)r * ROWB;
+  };
+  auto k_anchor_at = [&](int pos) -> const char* {
+    if constexpr (PAGED) return kanc + paged_row(s_pg_seq, pos, h, a.n_heads) * ROWB;
+    else return kanc + (int64_t)pos * ROWB;
+  };
+  auto v_own_at = [&](int pos) -> char* {
+    if constexpr (PAGED) return vown + paged_row(s_pg_seq, pos, h, a.n_heads) * ROWB;
+    else return vown + (int64_t)pos * ROWB;
+  };
   const char* knew = (const char*)a.k + bh * ROWB + li * 16;
   const char* vnew = (const char*)a.v + bh * ROWB + li * 16;
 
@@ -157,21 +183,24 @@ __device__ __forceinline__ void decode_split_body(const DecodeArgs& a, const Dec
       if (pos < kend) {
         if (pos == len) {  // the token being decoded: read the inputs, append to the caches
           vr[u] = *(const uint4*)vnew;
-          *(uint4*)(vown + (int64_t)len * ROWB) = vr[u];
+          *(uint4*)v_own_at(len) = vr[u];
           if (!SHARED) {
             kr[u] = *(const uint4*)knew;
             const int krow = lazy ? len - sm.vis_len : len;
-            *(uint4*)(kown + (int64_t)krow * ROWB) = kr[u];
-            if (STORE) *(uint4*)(a.lv.q_cache + (rb.q + len) * ROWB + li * 16) = qraw;
+            *(uint4*)k_own_at(krow) = kr[u];
+            if (STORE) {   // Global Lazy Attention: the Q Cache row of a position lives like its V row
+              if constexpr (PAGED) *(uint4*)(a.lv.q_cache + paged_row(s_pg_seq, len, h, a.n_heads) * ROWB + li * 16) = qraw;
+              else *(uint4*)(a.lv.q_cache + (rb.q + len) * ROWB + li * 16) = qraw;
+            }
           }
         } else {
           if (!SHARED) {
             const char* kp;
-            if (lazy && pos >= s) kp = pos < e ? kanc + (int64_t)pos * ROWB : kown + (int64_t)(pos - sm.vis_len) * ROWB;
-            else kp = kown + (int64_t)pos * ROWB;
+            if (lazy && pos >= s) kp = pos < e ? k_anchor_at(pos) : k_own_at(pos - sm.vis_len);
+            else kp = k_own_at(pos);
             kr[u] = stream_load16(kp);
           }
-          vr[u] = stream_load16(vown + (int64_t)pos * ROWB);
+          vr[u] = stream_load16(v_own_at(pos));
         }
       }
     }
@@ -246,13 +275,13 @@ __device__ __forceinline__ void decode_split_body(const DecodeArgs& a, const Dec
   }
 }
 
-template <typename T, int D, bool INLINE>
+template <typename T, int D, bool INLINE, bool PAGED>
 __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
-  decode_split_body<T, D, 0, INLINE>(a, DecodeGlaArgs{nullptr, 0, 0});
+  decode_split_body<T, D, 0, INLINE, PAGED>(a, DecodeGlaArgs{nullptr, 0, 0});
 }
-template <typename T, int D, int MODE, bool INLINE>
+template <typename T, int D, int MODE, bool INLINE, bool PAGED>
 __global__ __launch_bounds__(256) void decode_split_gla_kernel(DecodeArgs a, DecodeGlaArgs g) {
-  decode_split_body<T, D, MODE, INLINE>(a, g);
+  decode_split_body<T, D, MODE, INLINE, PAGED>(a, g);
 }
 
 // Merge the chunk partials of one (sequence, head) in chunk order.  Partials are loaded in batches
@@ -296,13 +325,25 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
   store_elem((T*)a.out + bh * D + d, o / l);
 }
 
+template <typename T, int D, bool INLINE, bool PAGED>
+static void launch_split(const DecodeArgs& a, const DecodeGlaArgs& g, hipStream_t stream) {
+  dim3 grid(a.max_chunks, a.n_heads, a.batch);
+  if (g.mode == 2) hipLaunchKernelGGL((decode_split_gla_kernel<T, D, 2, INLINE, PAGED>), grid, dim3(256), 0, stream, a, g);
+  else if (g.mode == 1) hipLaunchKernelGGL((decode_split_gla_kernel<T, D, 1, INLINE, PAGED>), grid, dim3(256), 0, stream, a, g);
+  else hipLaunchKernelGGL((decode_split_kernel<T, D, INLINE, PAGED>), grid, dim3(256), 0, stream, a);
+}
+
 template <typename T, int D, bool INLINE>
 static hipError_t launch_decode_t(const DecodeArgs& a, const DecodeGlaArgs& g, hipStream_t stream, KernelTimer* timer) {
-  dim3 grid(a.max_chunks, a.n_heads, a.batch);
+  const bool paged = (a.lv.flags & LV_PAGED) != 0;
+  if (paged && INLINE) return hipErrorInvalidValue;   // paged batches read their per-sequence integers from memory
   if (timer) timer->begin(stream);
-  if (g.mode == 2) hipLaunchKernelGGL((decode_split_gla_kernel<T, D, 2, INLINE>), grid, dim3(256), 0, stream, a, g);
-  else if (g.mode == 1) hipLaunchKernelGGL((decode_split_gla_kernel<T, D, 1, INLINE>), grid, dim3(256), 0, stream, a, g);
-  else hipLaunchKernelGGL((decode_split_kernel<T, D, INLINE>), grid, dim3(256), 0, stream, a);
+  if constexpr (!INLINE) {
+    if (paged) launch_split<T, D, false, true>(a, g, stream);
+    else launch_split<T, D, false, false>(a, g, stream);
+  } else {
+    launch_split<T, D, true, false>(a, g, stream);
+  }
   if (timer) timer->end(stream);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.max_chunks == 1) return e;

@@ -103,6 +103,13 @@ __device__ __forceinline__ SeqMeta load_meta(const LayerView& lv, int b, int inh
   return m;
 }
 
+// Paged regions: index of row r of head h, given the sequence's page list of the pool (in global memory or
+// staged in LDS).
+template <typename PageList>
+__device__ __forceinline__ int64_t paged_row(PageList pages, int r, int h, int n_heads) {
+  return ((int64_t)pages[r >> 6] * n_heads + h) * kPageRows + (r & (kPageRows - 1));
+}
+
 // Index of row 0 of (sequence b, head h) in each cache region a layer call touches, in rows.
 struct RowBase {
   int64_t k, v, anchor, q;   // k_own, v_own, k_anchor, q_cache
@@ -130,6 +137,35 @@ __device__ __forceinline__ RowBase row_bases(const LayerView& lv, int b, int h, 
                                     (int64_t)h * uniform_load(caps + CAP_VIS * lv.max_batch + b)
                               : seq;
   return r;
+}
+
+// Row indices of one (sequence, head) in either layout, chosen at run time (for the paths that are
+// not tuned; the tuned kernels take the layout as a template parameter).
+struct RowIndex {
+  RowBase rb;
+  const int32_t *pk, *pv, *pq;   // page lists of this sequence: k_own's pool, positions, q_cache's pool
+  int32_t h, n_heads;
+  bool paged;
+  __device__ __forceinline__ int64_t k(int r) const { return paged ? paged_row(pk, r, h, n_heads) : rb.k + r; }
+  __device__ __forceinline__ int64_t v(int r) const { return paged ? paged_row(pv, r, h, n_heads) : rb.v + r; }
+  __device__ __forceinline__ int64_t anchor(int r) const { return paged ? paged_row(pv, r, h, n_heads) : rb.anchor + r; }
+  __device__ __forceinline__ int64_t q(int r) const { return paged ? paged_row(pq, r, h, n_heads) : rb.q + r; }
+};
+__device__ __forceinline__ RowIndex row_index(const LayerView& lv, int b, int h, int n_heads) {
+  RowIndex x;
+  x.paged = (lv.flags & LV_PAGED) != 0;
+  x.h = h;
+  x.n_heads = n_heads;
+  x.pk = x.pv = x.pq = nullptr;
+  x.rb = RowBase{0, 0, 0, 0};
+  if (x.paged) {
+    x.pk = lv.pt_k + (int64_t)b * lv.pt_k_stride;
+    x.pv = lv.pt_seq + (int64_t)b * lv.pt_seq_stride;
+    x.pq = lv.pt_q + (int64_t)b * lv.pt_q_stride;
+  } else {
+    x.rb = row_bases(lv, b, h, n_heads);
+  }
+  return x;
 }
 
 }  // namespace qc

@@ -22,7 +22,14 @@ enum { META_COUNTER_WORDS = 64 };
 enum { LV_RAGGED = 1,    // capacities are per sequence: row bases come from the capacity rows
        LV_K_TEXT = 2,    // k_own holds text rows only (lazy layer, Visual Lazy Attention)
        LV_Q_VIS = 4,     // q_cache holds visual rows only (Visual Lazy Attention)
-       LV_LATE = 8 };    // meta points at block 1 (layer behind a pruning boundary)
+       LV_LATE = 8,      // meta points at block 1 (layer behind a pruning boundary)
+       LV_PAGED = 16 };  // rows live on pages of kPageRows rows; the page lists below say which
+
+// Paged batches: every region is [page][head][kPageRows][D]; a sequence holds a list of pages per pool
+// (positions: V rows, K rows of ordinary layers, Q Cache rows under Global Lazy Attention; text rows: K rows
+// of lazy layers; visual rows: Q Cache rows under Visual Lazy Attention).  Row r of head h sits at row
+// index (list[r / kPageRows] * H + h) * kPageRows + r % kPageRows of its region.
+enum { kPageRows = 64, kMaxPagesPerSeq = 1024 };
 
 // Device addresses of everything one layer call touches.  Cache regions are
 // [batch][head][cap][D] with the element type of the configuration (with per-sequence capacities:
@@ -39,6 +46,11 @@ struct LayerView {
   int32_t cap_q;
   int32_t max_batch;
   int32_t flags;
+  // page lists (LV_PAGED): sequence b's list of a pool starts at pt_x + b * pt_x_stride
+  const int32_t* pt_seq;  // positions: v_own, k_anchor, k_own of an ordinary layer
+  const int32_t* pt_k;    // the pool k_own's rows live in (pt_seq, or the text-row lists in a lazy layer)
+  const int32_t* pt_q;    // the pool q_cache's rows live in
+  int32_t pt_seq_stride, pt_k_stride, pt_q_stride;
 };
 
 struct PrefillArgs {
@@ -147,6 +159,12 @@ struct MoveChunk {        // by-value payload of the row relocation kernel: up t
   int32_t arena[N];                   // 0: K/V arena, 1: Q arena
 };
 
+struct TableChunk {       // by-value payload of the page-list upload kernel: up to N entries
+  enum { N = 128 };
+  int32_t at[N];          // index into the page-list buffer
+  int32_t page[N];
+};
+
 struct MetaChunk {        // by-value payload of the metadata upload kernel: up to ROWS rows of N sequences
   enum { N = 64, ROWS = 6 };
   int32_t v[ROWS][N];
@@ -213,6 +231,7 @@ hipError_t launch_fill_zero(void* dev, size_t bytes, hipStream_t stream);
 hipError_t launch_counter_update(int32_t* counter, int32_t value, int32_t add, hipStream_t stream);
 hipError_t launch_meta_upload(int32_t* meta_dev, int32_t max_batch, int32_t first, int32_t count, int32_t rows,
                               const MetaChunk& chunk, hipStream_t stream);
+hipError_t launch_table_upload(int32_t* tables, int32_t count, const TableChunk& chunk, hipStream_t stream);
 hipError_t launch_move_rows(void* arena0, void* arena1, int32_t row_bytes, int32_t n_heads, int32_t count,
                             const MoveChunk& chunk, hipStream_t stream);
 hipError_t launch_prefill(const PrefillArgs& a, int dtype, hipStream_t stream, KernelTimer* timer);

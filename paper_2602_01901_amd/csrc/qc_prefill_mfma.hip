@@ -55,14 +55,22 @@ constexpr float kRescaleThreshold = 8.0f;  // log2 units
 // consecutive LDS addresses), so the swizzle is applied on the global side: lane i of an
 // instruction that fills rows r0..r0+3 fetches logical chunk (i % 16) ^ swz(row).
 
-__device__ __forceinline__ const char* pf_q_row(const PrefillArgs& a, const SeqMeta& sm, const RowBase& rb, int h, int pos) {
-  if (a.is_lazy && pos >= sm.vis_start && pos < sm.vis_start + sm.vis_len)
-    return a.lv.q_cache + (rb.q + (pos - sm.vis_start)) * pf::ROWB;
+// Page lists of one sequence (paged batches; null otherwise): positions, k_own's pool, q_cache's pool.
+struct PfPages {
+  const int32_t *seq, *k, *q;
+};
+template <bool PAGED>
+__device__ __forceinline__ const char* pf_q_row(const PrefillArgs& a, const SeqMeta& sm, const RowBase& rb, const PfPages& pg, int h, int pos) {
+  if (a.is_lazy && pos >= sm.vis_start && pos < sm.vis_start + sm.vis_len) {
+    const int r = pos - sm.vis_start;
+    return a.lv.q_cache + (PAGED ? paged_row(pg.q, r, h, a.n_heads) : rb.q + r) * pf::ROWB;
+  }
   return (const char*)a.q + ((int64_t)(sm.tok0 + pos) * a.token_stride + (int64_t)h * a.head_stride) * 2;
 }
-__device__ __forceinline__ const char* pf_k_row(const PrefillArgs& a, const SeqMeta& sm, const RowBase& rb, int h, int pos) {
+template <bool PAGED>
+__device__ __forceinline__ const char* pf_k_row(const PrefillArgs& a, const SeqMeta& sm, const RowBase& rb, const PfPages& pg, int h, int pos) {
   if (a.is_lazy && pos >= sm.vis_start && pos < sm.vis_start + sm.vis_len)
-    return a.lv.k_anchor + (rb.anchor + pos) * pf::ROWB;
+    return a.lv.k_anchor + (PAGED ? paged_row(pg.seq, pos, h, a.n_heads) : rb.anchor + pos) * pf::ROWB;
   return (const char*)a.k + ((int64_t)(sm.tok0 + pos) * a.token_stride + (int64_t)h * a.head_stride) * 2;
 }
 
@@ -108,7 +116,11 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {  // at most N ve
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// PAGED: cache rows live on pages of 64 rows, which is also the key tile: a key tile read from the first
+// layer's K cache and the tiles a workgroup stores are one page each.
+template <bool PAGED>
 __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArgs a, int n_qt, int xcd_map) {
+  static_assert(pf::BN == kPageRows, "a key tile is one page");
   using namespace pf;
   extern __shared__ __attribute__((aligned(16))) char lds[];
 
@@ -131,7 +143,13 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
   const int len = sm.len0;
   const int q0 = qt * BM;
   if (q0 >= len) return;
-  const RowBase rb = row_bases(a.lv, b, h, a.n_heads);
+  const RowBase rb = PAGED ? RowBase{0, 0, 0, 0} : row_bases(a.lv, b, h, a.n_heads);
+  PfPages pg = {nullptr, nullptr, nullptr};
+  if constexpr (PAGED) {
+    pg.seq = a.lv.pt_seq + (int64_t)b * a.lv.pt_seq_stride;
+    pg.k = a.lv.pt_k + (int64_t)b * a.lv.pt_k_stride;
+    pg.q = a.lv.pt_q + (int64_t)b * a.lv.pt_q_stride;
+  }
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
@@ -155,7 +173,8 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
   const uint32_t ts2 = (uint32_t)(a.token_stride * 2);
   const char* kin_base = uniform_ptr((const char*)a.k + ((int64_t)sm.tok0 * a.token_stride + (int64_t)h * a.head_stride) * 2);
   const char* vin_base = uniform_ptr((const char*)a.v + ((int64_t)sm.tok0 * a.token_stride + (int64_t)h * a.head_stride) * 2);
-  const char* kanc_base = uniform_ptr(a.is_lazy ? a.lv.k_anchor + rb.anchor * ROWB : nullptr);
+  const char* kanc_base = uniform_ptr(a.is_lazy ? a.lv.k_anchor + (PAGED ? (int64_t)h * kPageRows : rb.anchor) * ROWB : nullptr);
+  const int64_t page_bytes = (int64_t)a.n_heads * kPageRows * ROWB;   // one page of a region, all heads
   uint32_t off_kin[LPT], off_kanc[LPT], off_v[LPT];
 #pragma unroll
   for (int p = 0; p < LPT; ++p) {
@@ -165,7 +184,8 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
     off_v[p] = r * ts2 + ((lchunk ^ ((r & 3) << 2)) * 16);
   }
   const int span_lo = a.is_lazy ? sm.vis_start : 0, span_hi = a.is_lazy ? sm.vis_start + sm.vis_len : 0;
-  auto load_tile = [&](int t) {
+  // `page`: paged batches, lazy layer: the page of the sequence that holds positions t*64 .. t*64+63
+  auto load_tile = [&](int t, int page) {
     const uint32_t kb = __builtin_amdgcn_readfirstlane(lds_base + (t % STAGES) * STAGE + wave * (4 * LPT) * ROWB);
     const uint32_t vb = kb + TILE;
     const int k0 = __builtin_amdgcn_readfirstlane(t * BN);
@@ -174,7 +194,7 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
     if (k0 + BN <= len && (inside || outside)) {
       const char* vsrc = vin_base + (uint64_t)k0 * ts2;
       if (inside) {
-        const char* ksrc = kanc_base + (uint64_t)k0 * ROWB;
+        const char* ksrc = PAGED ? kanc_base + (uint64_t)page * page_bytes : kanc_base + (uint64_t)k0 * ROWB;
 #pragma unroll
         for (int p = 0; p < LPT; ++p) {
           async_copy16_sv(ksrc, off_kanc[p], kb + p * 4 * ROWB);
@@ -193,24 +213,32 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
       for (int p = 0; p < LPT; ++p) {
         const int r = lrow + 4 * p;
         const int pos = min(k0 + r, len - 1);  // rows past the end repeat the last row; their scores are masked
-        async_copy16(pf_k_row(a, sm, rb, h, pos) + ((lchunk ^ (r & 15)) * 16), kb + p * 4 * ROWB);
+        async_copy16(pf_k_row<PAGED>(a, sm, rb, pg, h, pos) + ((lchunk ^ (r & 15)) * 16), kb + p * 4 * ROWB);
         async_copy16(vin_base + (int64_t)pos * ts2 + ((lchunk ^ ((r & 3) << 2)) * 16), vb + p * 4 * ROWB);
       }
     }
   };
 
-  load_tile(0);  // issued before the Q loads below so that the two latencies overlap
+  // Paged lazy layers: the page of a key tile is fetched (a scalar load) one tile before its loads are issued.
+  auto page_of_tile = [&](int t) -> int {
+    if constexpr (PAGED) return a.is_lazy ? uniform_load(pg.seq + min(t, n_tiles - 1)) : 0;
+    else return 0;
+  };
+  int page_ahead = page_of_tile(0);
+  load_tile(0, page_ahead);  // issued before the Q loads below so that the two latencies overlap
+  page_ahead = page_of_tile(1);
 
   // ---- Q fragments (B operand of S^T = K Q^T): query qi, dims ks*16 + hf*8 .. +8
   bf16x8 qf[8];
   {
-    const char* qp = pf_q_row(a, sm, rb, h, min(qi, len - 1));
+    const char* qp = pf_q_row<PAGED>(a, sm, rb, pg, h, min(qi, len - 1));
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + (ks * 16 + hf * 8) * 2));
     // Q Cache write (ordinary layer followed by a lazy one): the span rows of Q, straight from the
     // fragments this lane holds (the two lane halves of a row write alternate 16-byte pieces).
     if (a.write_q && qi < len && qi >= sm.vis_start && qi < sm.vis_start + sm.vis_len) {
-      char* qc = a.lv.q_cache + (rb.q + (qi - sm.vis_start)) * ROWB;
+      const int qr = qi - sm.vis_start;
+      char* qc = a.lv.q_cache + (PAGED ? paged_row(pg.q, qr, h, a.n_heads) : rb.q + qr) * ROWB;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) *(uint4*)(qc + (ks * 16 + hf * 8) * 2) = __builtin_bit_cast(uint4, qf[ks]);
     }
@@ -237,6 +265,9 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
     const int k0 = t * BN;
     char* kdst = a.lv.k_own + rb.k * ROWB;
     char* vdst = a.lv.v_own + rb.v * ROWB;
+    // row index of a row of this (sequence, head) in the region: run of rows, or page by page
+    auto v_row = [&](int r) -> int64_t { if constexpr (PAGED) return paged_row(pg.seq, r, h, a.n_heads); else return r; };
+    auto k_row = [&](int r) -> int64_t { if constexpr (PAGED) return paged_row(pg.k, r, h, a.n_heads); else return r; };
     const int s0 = sm.vis_start, s1 = sm.vis_start + sm.vis_len;
 #pragma unroll
     for (int p = 0; p < BN * 16 / (NW * 64); ++p) {
@@ -245,12 +276,12 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
       const int pos = k0 + r;
       if (pos < len) {
         const uint4 vv = *(const uint4*)(vb + r * ROWB + cp * 16);
-        *(uint4*)(vdst + (int64_t)pos * ROWB + ((cp ^ ((r & 3) << 2)) * 16)) = vv;
+        *(uint4*)(vdst + v_row(pos) * ROWB + ((cp ^ ((r & 3) << 2)) * 16)) = vv;
         const bool in_span = a.is_lazy && pos >= s0 && pos < s1;
         if (!in_span) {
           const int row = (a.is_lazy && pos >= s1) ? pos - sm.vis_len : pos;
           const uint4 kv = *(const uint4*)(kb + r * ROWB + cp * 16);
-          *(uint4*)(kdst + (int64_t)row * ROWB + ((cp ^ (r & 15)) * 16)) = kv;
+          *(uint4*)(kdst + k_row(row) * ROWB + ((cp ^ (r & 15)) * 16)) = kv;
         }
       }
     }
@@ -261,7 +292,10 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
     // wave is done with tile t-1, whose buffer is refilled next.
     wait_vmcnt<0>();
     __syncthreads();
-    if (t + 1 < n_tiles) load_tile(t + 1);
+    if (t + 1 < n_tiles) {
+      load_tile(t + 1, page_ahead);
+      page_ahead = page_of_tile(t + 2);
+    }
     const int k0 = t * BN;
     if (k0 >= q0) store_tile_to_caches(t);
     if (k0 <= wrow0 + 31) {  // wave-uniform: otherwise every key of the tile is above the diagonal
@@ -365,13 +399,18 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
 }
 
 hipError_t launch_prefill_mfma_bf16_d128(const PrefillArgs& a, hipStream_t stream, KernelTimer* timer) {
-  static std::atomic<unsigned long long> attr_set{0};
+  static std::atomic<unsigned long long> attr_set{0}, attr_set_paged{0};
   constexpr int lds_bytes = pf::STAGES * pf::STAGE;
-  if (hipError_t e = ensure_dynamic_lds((const void*)prefill_mfma_kernel, lds_bytes, attr_set); e != hipSuccess) return e;
+  const bool paged = (a.lv.flags & LV_PAGED) != 0;
+  if (hipError_t e = paged ? ensure_dynamic_lds((const void*)prefill_mfma_kernel<true>, lds_bytes, attr_set_paged)
+                           : ensure_dynamic_lds((const void*)prefill_mfma_kernel<false>, lds_bytes, attr_set);
+      e != hipSuccess)
+    return e;
   const int n_qt = (a.max_len + pf::BM - 1) / pf::BM;
   const int nbh = a.batch * a.n_heads;
   if (timer) timer->begin(stream);
-  hipLaunchKernelGGL(prefill_mfma_kernel, dim3(n_qt * nbh), dim3(pf::NW * 64), lds_bytes, stream, a, n_qt, (nbh % 8 == 0) ? 1 : 0);
+  if (paged) hipLaunchKernelGGL(prefill_mfma_kernel<true>, dim3(n_qt * nbh), dim3(pf::NW * 64), lds_bytes, stream, a, n_qt, (nbh % 8 == 0) ? 1 : 0);
+  else hipLaunchKernelGGL(prefill_mfma_kernel<false>, dim3(n_qt * nbh), dim3(pf::NW * 64), lds_bytes, stream, a, n_qt, (nbh % 8 == 0) ? 1 : 0);
   if (timer) timer->end(stream);
   return hipGetLastError();
 }

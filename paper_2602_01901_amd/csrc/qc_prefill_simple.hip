@@ -13,15 +13,15 @@ namespace qc {
 // Row address of query/key `pos` of sequence `sm`, head h, honouring the lazy substitution:
 // inside the visual span a lazy layer reads the Q Cache / the anchor layer's K rows.
 template <typename T, int D>
-__device__ __forceinline__ const T* q_row_ptr(const PrefillArgs& a, const SeqMeta& sm, const RowBase& rb, int h, int pos) {
+__device__ __forceinline__ const T* q_row_ptr(const PrefillArgs& a, const SeqMeta& sm, const RowIndex& rb, int h, int pos) {
   if (a.is_lazy && pos >= sm.vis_start && pos < sm.vis_start + sm.vis_len)
-    return (const T*)a.lv.q_cache + (rb.q + (pos - sm.vis_start)) * D;
+    return (const T*)a.lv.q_cache + rb.q(pos - sm.vis_start) * D;
   return (const T*)a.q + (int64_t)(sm.tok0 + pos) * a.token_stride + (int64_t)h * a.head_stride;
 }
 template <typename T, int D>
-__device__ __forceinline__ const T* k_row_ptr(const PrefillArgs& a, const SeqMeta& sm, const RowBase& rb, int h, int pos) {
+__device__ __forceinline__ const T* k_row_ptr(const PrefillArgs& a, const SeqMeta& sm, const RowIndex& rb, int h, int pos) {
   if (a.is_lazy && pos >= sm.vis_start && pos < sm.vis_start + sm.vis_len)
-    return (const T*)a.lv.k_anchor + (rb.anchor + pos) * D;
+    return (const T*)a.lv.k_anchor + rb.anchor(pos) * D;
   return (const T*)a.k + (int64_t)(sm.tok0 + pos) * a.token_stride + (int64_t)h * a.head_stride;
 }
 
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void prefill_simple_kernel(PrefillArgs a) {
   const int len = sm.len0;
   const int q0 = blockIdx.x * BQ;
   if (q0 >= len) return;
-  const RowBase rb = row_bases(a.lv, b, h, a.n_heads);
+  const RowIndex rb = row_index(a.lv, b, h, a.n_heads);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float c = a.scale * kLog2e;
 
@@ -142,20 +142,20 @@ __global__ __launch_bounds__(256) void prefill_cache_write_kernel(PrefillArgs a)
   const SeqMeta sm = load_meta(a.lv, b, a.inherit_all);
   const int r0 = blockIdx.x * ROWS;
   if (r0 >= sm.len0) return;
-  const RowBase rb = row_bases(a.lv, b, h, a.n_heads);
+  const RowIndex rb = row_index(a.lv, b, h, a.n_heads);
   const int ch = threadIdx.x % CPR;
   const int s = sm.vis_start, e = s + sm.vis_len;
   for (int pos = r0 + threadIdx.x / CPR; pos < min(r0 + ROWS, sm.len0); pos += 256 / CPR) {
     const int64_t in = (int64_t)(sm.tok0 + pos) * a.token_stride + (int64_t)h * a.head_stride + ch * EPL;
     const bool in_span = pos >= s && pos < e;
-    *(uint4*)((T*)a.lv.v_own + (rb.v + pos) * D + ch * EPL) = *(const uint4*)((const T*)a.v + in);
+    *(uint4*)((T*)a.lv.v_own + rb.v(pos) * D + ch * EPL) = *(const uint4*)((const T*)a.v + in);
     if (!a.is_lazy) {
-      *(uint4*)((T*)a.lv.k_own + (rb.k + pos) * D + ch * EPL) = *(const uint4*)((const T*)a.k + in);
+      *(uint4*)((T*)a.lv.k_own + rb.k(pos) * D + ch * EPL) = *(const uint4*)((const T*)a.k + in);
       if (a.write_q && in_span)
-        *(uint4*)((T*)a.lv.q_cache + (rb.q + (pos - s)) * D + ch * EPL) = *(const uint4*)((const T*)a.q + in);
+        *(uint4*)((T*)a.lv.q_cache + rb.q(pos - s) * D + ch * EPL) = *(const uint4*)((const T*)a.q + in);
     } else if (!in_span) {
       const int row = pos < s ? pos : pos - sm.vis_len;
-      *(uint4*)((T*)a.lv.k_own + (rb.k + row) * D + ch * EPL) = *(const uint4*)((const T*)a.k + in);
+      *(uint4*)((T*)a.lv.k_own + rb.k(row) * D + ch * EPL) = *(const uint4*)((const T*)a.k + in);
     }
   }
 }

@@ -47,6 +47,17 @@ hipError_t launch_meta_upload(int32_t* meta_dev, int32_t max_batch, int32_t firs
   return hipGetLastError();
 }
 
+__global__ void table_upload_kernel(int32_t* tables, int32_t count, TableChunk c) {
+  const int i = threadIdx.x;
+  if (i < count) tables[c.at[i]] = c.page[i];
+}
+
+hipError_t launch_table_upload(int32_t* tables, int32_t count, const TableChunk& chunk, hipStream_t stream) {
+  if (count == 0) return hipSuccess;
+  hipLaunchKernelGGL(table_upload_kernel, dim3(1), dim3(TableChunk::N), 0, stream, tables, count, chunk);
+  return hipGetLastError();
+}
+
 // Moves the rows of one sequence inside up to MoveChunk::N regions (qc_seq_grow): region i holds, per
 // head, `rows[i]` rows of row_bytes at src[i] + h*src_stride[i] that go to dst[i] + h*dst_stride[i]
 // (byte offsets from `base`).  One workgroup per (region, head), 16 bytes per lane.  Source and

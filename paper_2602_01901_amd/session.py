@@ -40,6 +40,7 @@ class Session:
         self._lib = B.load_library()
         self._ws_ptr = self.workspace.data_ptr()
         self._graphs = []
+        self.page_lists = None
 
     @classmethod
     def for_workload(cls, w, device="cuda:0", mode="vla", prune_before_layer=0, max_seq_late=0):
@@ -50,15 +51,24 @@ class Session:
     def _stream(self):
         return torch.cuda.current_stream(self.device).cuda_stream
 
-    def reset(self, vis_start, vis_len, zero_fill=True, cap_seq=None, cap_text=None):
-        """cap_seq / cap_text: optional per-sequence capacities (qc_reset_ragged)."""
+    def reset(self, vis_start, vis_len, zero_fill=True, cap_seq=None, cap_text=None, paged=False, present=None):
+        """cap_seq / cap_text: optional per-sequence capacities (qc_reset_ragged).  paged: rows on pages
+        (qc_reset_paged; `present` flags the slots that hold a sequence from the start, default all)."""
         self.vis_start, self.vis_len = list(vis_start), list(vis_len)
         self.batch = len(self.vis_start)
         # marshalled once per batch: the span arrays every later call repeats
         self._vs_c, self._vl_c = B._i32(self.vis_start), B._i32(self.vis_len)
         self.first_late, self.keep = None, None
         self._vl_by_layer = [(self.vis_len, self._vl_c)] * self.n_layers   # span lengths each layer's calls repeat
-        if cap_seq is not None:
+        if paged:
+            nbytes = B.qc_page_table_bytes(self.cfg)
+            if nbytes == 0:
+                raise B.QcError(B.QC_EINVAL, "the configuration cannot be paged")
+            if self.page_lists is None:
+                self.page_lists = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            B.qc_reset_paged(self.kv, self.qc, self.batch, self.vis_start, self.vis_len, present, self.page_lists, nbytes,
+                             int(zero_fill), self._stream())
+        elif cap_seq is not None:
             B.qc_reset_ragged(self.kv, self.qc, self.batch, self.vis_start, self.vis_len, cap_seq, cap_text,
                               int(zero_fill), self._stream())
         else:
@@ -74,7 +84,7 @@ class Session:
         B.qc_seq_leave(self.kv, self.qc, b, self._stream())
         self._set_span(b, 0, 0)
 
-    def seq_join(self, b, vis_start, vis_len, cap_seq, cap_text):
+    def seq_join(self, b, vis_start, vis_len, cap_seq=0, cap_text=0):
         """A new sequence takes free slot b; the next calls are a prefill pass over the joined slots only."""
         B.qc_seq_join(self.kv, self.qc, b, vis_start, vis_len, cap_seq, cap_text, self._stream())
         self._set_span(b, vis_start, vis_len)

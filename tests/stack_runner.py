@@ -10,16 +10,32 @@ from oracle.lazy_stack import LazyStackOracle
 TOL = {"f32": 1e-4, "bf16": 3e-2}   # max-abs-error bars for outputs (fp32 / bf16 storage)
 
 
-def oracle_layout(w, mode="vla", caps=None, late=None):
+def oracle_layout(w, mode="vla", caps=None, late=None, paged=None):
     """caps: None, or (cap_seq, cap_text) per sequence (the Q arena is then split by vis_len).
-    late: None, or (first late layer, max_seq_late) of a configuration with smaller late layers."""
+    late: None, or (first late layer, max_seq_late) of a configuration with smaller late layers.
+    paged: None, or the page lists per pool and slot (oracle.layout.PagePools.tables())."""
     ragged = None if caps is None else (caps[0], caps[1], w.vis_len)
     return olayout.ArenaLayout(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.batch, w.max_seq, w.max_vis,
-                               w.max_text, w.lazy_mask, mode=mode, ragged=ragged, late=late)
+                               w.max_text, w.lazy_mask, mode=mode, ragged=ragged, late=late, paged=paged)
 
 
-def reset_session(session, w, caps=None, zero_fill=True):
-    if caps is None:
+def oracle_page_pools(w, mode="vla"):
+    return olayout.PagePools(w.batch, w.max_seq, w.max_vis, w.max_text, mode=mode, any_lazy=any(w.lazy_mask))
+
+
+def check_page_lists(session, pools):
+    """The library hands out the pages the stated rule hands out."""
+    from paper_2602_01901_amd import binding as B
+    want = pools.tables()
+    for pool, kind in enumerate(("seq", "text", "vis")):
+        for b in range(len(want[kind])):
+            assert B.qc_seq_pages(session.kv, b, pool) == want[kind][b], (kind, b)
+
+
+def reset_session(session, w, caps=None, zero_fill=True, paged=False):
+    if paged:
+        session.reset(w.vis_start, w.vis_len, zero_fill=zero_fill, paged=True)
+    elif caps is None:
         session.reset(w.vis_start, w.vis_len, zero_fill=zero_fill)
     else:
         session.reset(w.vis_start, w.vis_len, zero_fill=zero_fill, cap_seq=caps[0], cap_text=caps[1])
@@ -71,7 +87,8 @@ def max_abs_err(gpu_tensor, ref64):
     return float(np.max(np.abs(workloads.to_f64(gpu_tensor) - ref64)))
 
 
-def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=True, caps=None, zero_fill=True):
+def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=True, caps=None, zero_fill=True,
+                    paged=False):
     """Prefill every layer then `decode_steps` decode steps on both sides; returns worst errors.
 
     With poison_span the span rows of q and k handed to lazy layers hold NaN on the GPU side
@@ -83,7 +100,10 @@ def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=Tru
     mode = session.mode
     gla = mode == "gla"
     stacks = new_oracles(w, mode=mode)
-    reset_session(session, w, caps, zero_fill=zero_fill)
+    reset_session(session, w, caps, zero_fill=zero_fill, paged=paged)
+    pools = oracle_page_pools(w, mode) if paged else None
+    if paged:
+        pools.prefill(range(w.batch), w.seq_len, w.vis_len)
     worst_p = worst_d = 0.0
     for l in range(w.n_layers):
         q, k, v = workloads.prefill_qkv(w, l)
@@ -102,6 +122,8 @@ def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=Tru
         assert np.isfinite(err), "layer %d produced non-finite output" % l
         worst_p = max(worst_p, err)
     for t in range(decode_steps):
+        if paged:
+            pools.decode_step(range(w.batch), [n + t for n in w.seq_len], w.vis_len)
         for l in range(w.n_layers):
             q, k, v = workloads.decode_qkv(w, l, t)
             ref = oracle_decode_layer(w, stacks, l, q, k, v)
@@ -113,8 +135,10 @@ def run_full_parity(w, decode_steps, session, poison_span=False, check_arena=Tru
             assert np.isfinite(err)
             worst_d = max(worst_d, err)
     torch.cuda.synchronize()
+    if paged:
+        check_page_lists(session, pools)
     if check_arena:
-        lay = oracle_layout(w, mode, caps)
+        lay = oracle_layout(w, mode, caps, paged=pools.tables() if paged else None)
         check_kv_rows(session, lay, stacks)
         want_q = olayout.q_arena_image(lay, stacks)
         got_q = session.q_arena.cpu().numpy()[: lay.q_arena_bytes()]
