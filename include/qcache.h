@@ -223,10 +223,10 @@ qc_status qc_seq_extent(const qc_kvcache* kv, int32_t b, int32_t* live, int32_t*
  * one lazy layer.  Pages are handed out lowest free number first, for the slots in order and for each
  * slot in the order of the pools above: by qc_prefill of layer 0 for the prompts of its pass, and by
  * qc_decode of layer 0 when the row the step appends opens a page (QC_ECAPACITY, and nothing changed,
- * when a pool has too few free pages).  A sequence may hold at most max_seq positions, max_text text
- * rows and max_vis visual rows, as without pages.
- *   The configuration must have max_seq, max_text and max_vis multiples of QC_PAGE_ROWS, max_seq at
- *   most 65536 and no prune_before_layer (QC_EINVAL; qc_page_table_bytes returns 0).
+ * when a pool has too few free pages).  max_seq, max_text and max_vis only size the pools: a sequence
+ * may hold any share of a pool, up to 1024 pages (65536 rows) of it.
+ *   The configuration must have max_seq, max_text and max_vis multiples of QC_PAGE_ROWS and no
+ *   prune_before_layer (QC_EINVAL; qc_page_table_bytes returns 0).
  *   page_lists: DEVICE, 16-byte aligned, at least qc_page_table_bytes(cfg) bytes, owned by the caller and
  *   left alone by it until the next qc_reset*: the lists as the kernels read them.
  *   present: HOST, `batch` flags or NULL (every slot holds a sequence); 0 makes slot b free from the start.

@@ -74,19 +74,20 @@ struct Config {
   // POOL_VIS Q Cache rows under Visual Lazy Attention).  The last two exist only where rows are kept in them.
   int n_lazy() const { int n = 0; for (auto f : lazy) n += f ? 1 : 0; return n; }
   bool pool_used(int pool) const { return pool == 0 || (!gla() && n_lazy() > 0); }
-  int32_t pool_stride(int pool) const {   // entries of one sequence's list = pages it may hold at most
+  int64_t pool_pages(int pool) const {
     if (!pool_used(pool)) return 0;
-    return (pool == 0 ? max_seq : pool == 1 ? max_text : max_vis) / qc::kPageRows;
+    return (int64_t)max_batch * ((pool == 0 ? max_seq : pool == 1 ? max_text : max_vis) / qc::kPageRows);
   }
-  int64_t pool_pages(int pool) const { return (int64_t)max_batch * pool_stride(pool); }
+  // entries of one sequence's list = pages it may hold at most: the whole pool, up to what the kernels stage
+  int32_t pool_stride(int pool) const { return (int32_t)std::min<int64_t>(pool_pages(pool), qc::kMaxPagesPerSeq); }
   int64_t table_off(int pool) const {     // first entry of the pool's lists in the page-list buffer
     int64_t o = 0;
-    for (int i = 0; i < pool; ++i) o += pool_pages(i);
+    for (int i = 0; i < pool; ++i) o += (int64_t)max_batch * pool_stride(i);
     return o;
   }
   int64_t table_entries() const { return table_off(3); }
   bool pageable() const {
-    return late_from == 0 && max_seq % qc::kPageRows == 0 && max_seq / qc::kPageRows <= qc::kMaxPagesPerSeq &&
+    return late_from == 0 && max_seq % qc::kPageRows == 0 &&
            (gla() || (max_text % qc::kPageRows == 0 && max_vis % qc::kPageRows == 0));
   }
   bool same(const Config& o) const {
@@ -155,11 +156,19 @@ struct qc_kvcache {
   int32_t len_of(int layer, int b) const { return late(layer) ? len0[b] - vis_len[b] + vis_len1[b] : len0[b]; }
   // Per-sequence capacities (qc_reset_ragged): rows sequence b may use, and where they start.
   bool ragged = false;
+  bool paged = false;     // rows on pages (qc_reset_paged), see below
   std::vector<int32_t> cap_seq, cap_text, base_seq, base_text, base_vis;
   int64_t cap_seq_of(int b) const { return ragged ? cap_seq[b] : cfg.max_seq; }
-  // positions sequence b may reach in `layer` (smaller behind a configured pruning boundary)
-  int64_t cap_of(int layer, int b) const { return ragged ? cap_seq[b] : cfg.cap_v(layer); }
-  int64_t cap_text_of(int b) const { return ragged ? cap_text[b] : cfg.max_text; }
+  // positions sequence b may reach in `layer` (smaller behind a configured pruning boundary; on a paged
+  // batch as far as its page list reaches: the pools decide before that)
+  int64_t cap_of(int layer, int b) const {
+    if (paged) return (int64_t)cfg.pool_stride(0) * qc::kPageRows;
+    return ragged ? cap_seq[b] : cfg.cap_v(layer);
+  }
+  int64_t cap_text_of(int b) const {
+    if (paged) return cfg.pool_used(1) ? (int64_t)cfg.pool_stride(1) * qc::kPageRows : (int64_t)1 << 40;
+    return ragged ? cap_text[b] : cfg.max_text;
+  }
   int64_t longest_cap() const {
     int64_t m = ragged ? 0 : cfg.max_seq;
     if (ragged) for (int b = 0; b < batch; ++b) m = std::max<int64_t>(m, cap_seq[b]);
@@ -168,7 +177,6 @@ struct qc_kvcache {
   // Paged batches (qc_reset_paged): rows live on pages of kPageRows rows.  pages[pool][b] = the pages slot b
   // holds, in row order; free_pages[pool] ascending (the lowest free page is handed out first); `tables` is
   // the caller's device buffer the kernels read the lists from.
-  bool paged = false;
   int32_t* tables = nullptr;
   std::vector<std::vector<int32_t>> pages[3];
   std::vector<int32_t> free_pages[3];
@@ -321,6 +329,11 @@ static qc_status reset_impl(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const 
     if (ragged && cap_seq[b] == 0) continue;
     if (paged && paged->present && !paged->present[b]) continue;
     if (vis_start[b] < 0 || vis_len[b] < 0) return fail(QC_EINVAL, "qc_reset: negative span for sequence %d", b);
+    if (paged) {
+      if (c.pool_used(2) && vis_len[b] > (int64_t)c.pool_stride(2) * qc::kPageRows) return fail(QC_ECAPACITY, "qc_reset_paged: sequence %d has %d visual tokens, a sequence may hold %lld", b, vis_len[b], (long long)c.pool_stride(2) * qc::kPageRows);
+      if ((int64_t)vis_start[b] + vis_len[b] > (int64_t)c.pool_stride(0) * qc::kPageRows) return fail(QC_ECAPACITY, "qc_reset_paged: span of sequence %d exceeds what a sequence may hold", b);
+      continue;
+    }
     if (!ragged) {
       if (!c.gla() && vis_len[b] > c.max_vis) return fail(QC_ECAPACITY, "qc_reset: sequence %d has %d visual tokens, max_vis %d", b, vis_len[b], c.max_vis);
       if ((int64_t)vis_start[b] + vis_len[b] > c.max_seq) return fail(QC_ECAPACITY, "qc_reset: span of sequence %d exceeds max_seq", b);
@@ -725,8 +738,8 @@ qc_status qc_seq_join(qc_kvcache* kv, qc_qcache* qc, int32_t b, int32_t vis_star
   if (vis_start < 0 || vis_len < 0) return fail(QC_EINVAL, "qc_seq_join: negative span");
   if (kv->paged) {   // pages are handed out when the sequence's prefill pass begins; capacities are not used
     if (cap_seq != 0 || cap_text != 0) return fail(QC_EINVAL, "qc_seq_join: a paged batch takes no capacities (pass 0)");
-    if (!c.gla() && vis_len > c.max_vis) return fail(QC_ECAPACITY, "qc_seq_join: %d visual tokens, max_vis %d", vis_len, c.max_vis);
-    if ((int64_t)vis_start + vis_len > c.max_seq) return fail(QC_ECAPACITY, "qc_seq_join: the span exceeds max_seq");
+    if (c.pool_used(2) && vis_len > (int64_t)c.pool_stride(2) * qc::kPageRows) return fail(QC_ECAPACITY, "qc_seq_join: %d visual tokens, a sequence may hold %lld", vis_len, (long long)c.pool_stride(2) * qc::kPageRows);
+    if ((int64_t)vis_start + vis_len > (int64_t)c.pool_stride(0) * qc::kPageRows) return fail(QC_ECAPACITY, "qc_seq_join: the span exceeds what a sequence may hold");
     kv->live[b] = kv->joining[b] = 1;
     kv->joined_at[b] = 0;
     kv->vis_start[b] = vis_start;

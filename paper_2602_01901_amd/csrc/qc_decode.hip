@@ -150,6 +150,11 @@ __device__ __forceinline__ void decode_split_body(const DecodeArgs& a, const Dec
 
   // one score per position: rows of score_stride floats, or (per-sequence capacities) laid out like the V rows
   float* score_row = (SHARED || STORE) ? g.scores + ((a.lv.flags & LV_RAGGED) ? rb.v : bh * g.score_stride) : nullptr;
+  // where the score of a position is kept: paged batches lay the scores out like the V rows
+  auto score_at = [&](int pos) -> float* {
+    if constexpr (PAGED) return g.scores + paged_row(s_pg_seq, pos, h, a.n_heads);
+    else return score_row + pos;
+  };
 
   float qf[EPL];
   uint4 qraw = make_uint4(0, 0, 0, 0);
@@ -172,7 +177,7 @@ __device__ __forceinline__ void decode_split_body(const DecodeArgs& a, const Dec
     float mine = -INFINITY;
     if (SHARED) {  // lane li < U of a group fetches the score of the group's row u = li; broadcast below
       const int pos = r0 + li * GROUPS;
-      if (li < U && pos < kend) mine = score_row[pos];
+      if (li < U && pos < kend) mine = *score_at(pos);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -219,7 +224,7 @@ __device__ __forceinline__ void decode_split_body(const DecodeArgs& a, const Dec
         const int pos = r0 + u * GROUPS;
         if (pos < kend) {
           sc[u] = d;
-          if (STORE && li == 0) score_row[pos] = d;
+          if (STORE && li == 0) *score_at(pos) = d;
         }
       }
       mt = fmaxf(mt, sc[u]);

@@ -40,11 +40,11 @@ def arena_rows(sess, which, layer, b, h, pos_list):
     return torch.stack(out).cpu().numpy()
 
 
-def run_sampled(w, n_layers, pairs, decode_steps=0, seed=0, mode="vla"):
+def run_sampled(w, n_layers, pairs, decode_steps=0, seed=0, mode="vla", paged=False):
     rng = np.random.default_rng(seed)
     gla = mode == "gla"
     sess = P.Session.for_workload(w, mode=mode)
-    sess.reset(w.vis_start, w.vis_len, zero_fill=False)
+    sess.reset(w.vis_start, w.vis_len, zero_fill=False, paged=paged)
     if gla:
         oracles = {p: GlobalLazyStackOracle(w.n_layers, 1, w.head_dim, w.lazy_mask) for p in pairs}
     else:
@@ -115,6 +115,33 @@ def test_cfg3_batched_decode_sampled():
     st = sess.stats()
     want_k = sum((L + 3 - lz * 576) for L in w.seq_len for lz in w.lazy_mask) * 32 * 128 * 2
     assert st["k_bytes"] == want_k and st["tokens"] == sum(w.seq_len) + 3 * 32
+
+
+def test_cfg3_batched_decode_sampled_on_pages():
+    """The same on a paged batch, in the launch configuration the benchmark times; the page lists against
+    the hand-out rule (three steps open no page at these lengths except where a length is a multiple of 64)."""
+    import dataclasses
+    from oracle.layout import PagePools
+    w = workloads.config(2)
+    w = dataclasses.replace(w, max_seq=-(-w.max_seq // 64) * 64, max_text=-(-w.max_text // 64) * 64)   # whole pages
+    worst, sess = run_sampled(w, w.n_layers, [(0, 5), (7, 16), (13, 0), (20, 31), (26, 11), (31, 31)], decode_steps=3, paged=True)
+    print("cfg3 paged sampled max abs err %.3g" % worst, flush=True)
+    assert worst <= TOL["bf16"]
+    pools = PagePools(w.batch, w.max_seq, w.max_vis, w.max_text)
+    pools.prefill(range(w.batch), w.seq_len, w.vis_len)
+    for t in range(3):
+        pools.decode_step(range(w.batch), [n + t for n in w.seq_len], w.vis_len)
+    want = pools.tables()
+    for pool, kind in enumerate(("seq", "text", "vis")):
+        for b in range(w.batch):
+            assert B.qc_seq_pages(sess.kv, b, pool) == want[kind][b], (kind, b)
+
+
+def test_cfg4_highres_prefill_sampled_on_pages():
+    w = workloads.config(3)
+    worst, _ = run_sampled(w, 8, [(0, 0), (3, 17), (7, 31), (5, 8)], paged=True)
+    print("cfg4 paged sampled max abs err %.3g" % worst, flush=True)
+    assert worst <= TOL["bf16"]
 
 
 def test_cfg5_video_shape_sampled():
