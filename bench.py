@@ -749,6 +749,94 @@ def bench_ragged_arena(args):
     return res
 
 
+def bench_paged(args):
+    """Pages against runs of rows: the batched-decode configuration (32 prompts of 704..1088 tokens, capacities
+    rounded up to whole pages) decoded from both layouts in the same run, again after a quarter of the batch
+    has left and other sequences have taken the freed pages, and the high-resolution prefill on pages."""
+    import dataclasses
+    import torch
+    import workloads
+    import paper_2602_01901_amd as P
+    base = workloads.config(2)
+    up = lambda x: -(-x // 64) * 64
+    w = dataclasses.replace(base, max_seq=up(base.max_seq), max_text=up(base.max_text))
+    steps = args.decode_batched_steps
+    res = {"workload": w.name + " (capacities in whole pages)", "page_rows": 64}
+    for name, paged in (("rows_in_runs", False), ("pages", True)):
+        s = P.Session.for_workload(w)
+        q, k, v = workloads.prefill_qkv(w, 0, device=s.device)
+        o = torch.empty_like(v)
+        s.reset(w.vis_start, w.vis_len, zero_fill=False, paged=paged)
+
+        def prefill_all(qq, kk, vv, cu, oo):
+            for l in range(w.n_layers):
+                s.prefill(l, qq, kk, vv, cu, out=oo)
+        prefill_all(q, k, v, w.cu_seqlens, o)
+        torch.cuda.synchronize()
+        s.reset(w.vis_start, w.vis_len, zero_fill=False, paged=paged)
+        _, ev_p = timed(torch, lambda: prefill_all(q, k, v, w.cu_seqlens, o), 1)
+        dq, dk, dv = workloads.decode_qkv(w, 0, 0, device=s.device)
+        do = torch.empty_like(dv)
+
+        def run(nsteps):
+            for _ in range(nsteps):
+                for l in range(w.n_layers):
+                    s.decode(l, dq, dk, dv, out=do)
+        run(2)
+        _, ev_s = timed(torch, lambda: run(steps), 1)
+        res[name] = {"prefill_stack_ms": ev_p * 1e3, "decode_tokens_per_s": w.batch * steps / ev_s}
+        if paged:
+            # every fourth sequence leaves; the freed pages go, lowest first, to the same prompts joining in
+            # the reverse order, so a sequence's pages are scattered over the pools
+            movers = list(range(1, w.batch, 4))
+            for b in movers:
+                s.seq_leave(b)
+            for b in reversed(movers):
+                s.seq_join(b, w.vis_start[b], w.vis_len[b])
+            cu = [0]
+            for b in range(w.batch):
+                cu.append(cu[-1] + (w.seq_len[b] if b in movers else 0))
+            rows = torch.cat([torch.arange(w.cu_seqlens[b], w.cu_seqlens[b + 1], device=s.device) for b in movers])
+            qj, kj, vj = q[rows], k[rows], v[rows]
+            prefill_all(qj, kj, vj, cu, torch.empty_like(vj))
+            run(2)
+            _, ev_j = timed(torch, lambda: run(steps), 1)
+            B = P.binding
+            lists = [B.qc_seq_pages(s.kv, b, 0) for b in movers]
+            res["pages_after_leave_and_join"] = {
+                "sequences_moved": len(movers),
+                "page_lists_not_consecutive": sum(any(y != x + 1 for x, y in zip(l, l[1:])) for l in lists),
+                "decode_tokens_per_s": w.batch * steps / ev_j}
+            del qj, kj, vj
+        s.close()
+        del s, q, k, v, o
+        torch.cuda.empty_cache()
+    res["decode_rate_pages_vs_runs"] = res["pages"]["decode_tokens_per_s"] / res["rows_in_runs"]["decode_tokens_per_s"]
+    res["decode_rate_scattered_pages_vs_runs"] = (res["pages_after_leave_and_join"]["decode_tokens_per_s"] /
+                                                  res["rows_in_runs"]["decode_tokens_per_s"])
+    # prefill at the high-resolution shape (8 x 3008 tokens): the matrix-core kernel in both layouts
+    w4 = workloads.config(3)
+    flops = prefill_flops_per_layer(w4)
+    layers = [l for l in range(w4.n_layers)][:8]
+    for name, paged in (("rows_in_runs", False), ("pages", True)):
+        s = P.Session.for_workload(w4)
+        pre = [workloads.prefill_qkv(w4, l, device=s.device) for l in layers]
+        o = torch.empty_like(pre[0][2])
+
+        def run_pre():
+            s.reset(w4.vis_start, w4.vis_len, zero_fill=False, paged=paged)
+            for l in layers:
+                s.prefill(l, *pre[l], w4.cu_seqlens, out=o)
+        run_pre()
+        _, ev = timed(torch, run_pre, args.prefill_reps)
+        res[name]["prefill_highres_tflops"] = flops * len(layers) / ev / 1e12
+        s.close()
+        del s, pre, o
+        torch.cuda.empty_cache()
+    res["prefill_rate_pages_vs_runs"] = res["pages"]["prefill_highres_tflops"] / res["rows_in_runs"]["prefill_highres_tflops"]
+    return res
+
+
 def bench_headline(args):
     """13B-shaped video workload (cfg5): the line's headline.  A step = reset + 40-layer prefill of
     4 x 4864 tokens + 1024 decode steps x 40 layers, through ordinary qc_prefill / qc_decode calls
@@ -933,7 +1021,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true",
                     help="batch-1 workload: ordinary qc_decode calls instead of one HIP-graph replay per decode step")
     ap.add_argument("--only", choices=["headline", "cfg2", "decode_batched", "prefill_highres", "gla_decode_batched", "selection",
-                                      "projection", "pruning", "capacity", "prefill_long", "prefill_cfg5", "decode_cfg5"],
+                                      "projection", "pruning", "capacity", "paged", "prefill_long", "prefill_cfg5", "decode_cfg5"],
                     help="profiling aid: run just this workload and print its object")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profiling aid: run plain 1 GiB device copies (known HBM traffic) and exit")
@@ -963,7 +1051,7 @@ def main():
               "decode_batched": bench_decode_batched, "prefill_highres": bench_prefill_highres,
               "gla_decode_batched": bench_gla_decode_batched, "selection": bench_selection,
               "projection": bench_projection, "pruning": bench_pruning, "capacity": bench_capacity,
-              "prefill_long": bench_prefill_long,
+              "prefill_long": bench_prefill_long, "paged": bench_paged,
               "prefill_cfg5": lambda a: bench_prefill_highres(a, w=workloads.config(4), traffic_key="prefill_cfg5"),
               "decode_cfg5": lambda a: bench_decode_batched(a, w=workloads.config(4), traffic_key="decode_cfg5")}[args.only]
         print(json.dumps({args.only: fn(args)}))
@@ -998,6 +1086,10 @@ def main():
         log("pruning done: %.1f -> %.1f tok/s" % (extra["pruning"]["unpruned"]["decode_tokens_per_s"],
                                                 extra["pruning"]["pruned"]["decode_tokens_per_s"]))
         extra["capacity"] = bench_capacity(args)
+        extra["paged"] = bench_paged(args)
+        log("pages done: decode %.3f x, scattered %.3f x, prefill %.3f x the rate with rows in runs"
+            % (extra["paged"]["decode_rate_pages_vs_runs"], extra["paged"]["decode_rate_scattered_pages_vs_runs"],
+               extra["paged"]["prefill_rate_pages_vs_runs"]))
     cpu = None
     if not args.skip_cpu:
         cpu = cpu_baseline_sample(w, heads=8)

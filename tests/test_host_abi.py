@@ -415,3 +415,64 @@ def test_smaller_late_layers_sizes_match_oracle_layout():
         # the planner sees the smaller arena
         budget = 10 * lay.rows_bytes()
         assert B.qc_plan_max_batch(cfg, budget, B.QC_PLAN_KV) > B.qc_plan_max_batch(P.make_config(*c, mode=mode), budget, B.QC_PLAN_KV)
+
+
+PAGED = (4, 2, 64, "bf16", 3, 192, 64, 128, [0, 1, 1, 0])     # pools of 9 / 6 / 3 pages
+
+
+def test_page_list_buffer_size_and_pageable_configurations():
+    up = lambda x: (x + 255) // 256 * 256
+    cfg = P.make_config(*PAGED)
+    # a sequence's list is as long as its pool: 3 sequences x (9 + 6 + 3) entries of 4 bytes
+    assert B.qc_page_table_bytes(cfg) == up(3 * (9 + 6 + 3) * 4)
+    # Global Lazy Attention keeps everything on the position pages
+    assert B.qc_page_table_bytes(P.make_config(*PAGED, mode="gla")) == up(3 * 9 * 4)
+    # no lazy layer: the other two pools hold nothing
+    assert B.qc_page_table_bytes(P.make_config(*PAGED[:8], [0, 0, 0, 0])) == up(3 * 9 * 4)
+    # capacities must be whole pages; separately sized late layers cannot be paged
+    for bad in ((4, 2, 64, "bf16", 3, 200, 64, 128, [0, 1, 1, 0]), (4, 2, 64, "bf16", 3, 192, 60, 128, [0, 1, 1, 0]),
+                (4, 2, 64, "bf16", 3, 192, 64, 70, [0, 1, 1, 0])):
+        assert B.qc_page_table_bytes(P.make_config(*bad)) == 0
+    assert B.qc_page_table_bytes(P.make_config(*bad, mode="gla")) == B.qc_page_table_bytes(P.make_config(*PAGED, mode="gla"))
+    assert B.qc_page_table_bytes(P.make_config(*PAGED[:8], [0, 1, 0, 0], prune_before_layer=2, max_seq_late=64)) == 0
+    # a list never exceeds what the kernels stage: 1024 pages per sequence
+    big = P.make_config(2, 1, 64, "bf16", 64, 2048, 64, 64, [0, 0])
+    assert B.qc_page_table_bytes(big) == up(64 * 1024 * 4)
+
+
+def test_reset_paged_validation_and_what_a_paged_batch_refuses():
+    cfg, kv, qc = make_handles(PAGED)
+    nbytes = B.qc_page_table_bytes(cfg)
+    ok = dict(kv=kv, qc=qc, batch=3, vis_start=[0, 4, 0], vis_len=[20, 8, 0], present=None, page_lists=FAKE,
+              page_list_bytes=nbytes, zero_fill=0)
+    cases = [(dict(page_lists=None), B.QC_EINVAL), (dict(page_lists=FAKE + 4), B.QC_EINVAL),
+             (dict(page_list_bytes=nbytes - 256), B.QC_ECAPACITY),
+             (dict(batch=4, vis_start=[0] * 4, vis_len=[0] * 4), B.QC_ECAPACITY),
+             (dict(vis_len=[193, 8, 0]), B.QC_ECAPACITY),          # more visual rows than the whole pool (3 pages)
+             (dict(vis_start=[570, 4, 0]), B.QC_ECAPACITY),        # span beyond the position pool (9 pages)
+             (dict(vis_len=[-1, 8, 0]), B.QC_EINVAL)]
+    for change, status in cases:
+        with pytest.raises(P.QcError) as e:
+            B.qc_reset_paged(**dict(ok, **change))
+        assert e.value.status == status, change
+    # a configuration that cannot be paged
+    _, kv2, qc2 = make_handles(CONFIGS[1])
+    with pytest.raises(P.QcError) as e:
+        B.qc_reset_paged(**dict(ok, kv=kv2, qc=qc2))
+    assert e.value.status == B.QC_EINVAL
+    # host-only when nothing is cleared; slot 2 starts free
+    B.qc_reset_paged(**dict(ok, present=[1, 1, 0]))
+    assert [B.qc_seq_pages(kv, b, pool) for b in range(3) for pool in range(3)] == [[]] * 9
+    for call, status in ((lambda: B.qc_seq_grow(kv, qc, 0, 64, 0), B.QC_EORDER), (lambda: B.qc_seq_extent(kv, 0), B.QC_EORDER),
+                         (lambda: B.qc_seq_join(kv, qc, 2, 0, 0, 64, 0), B.QC_EINVAL),     # capacities are not taken
+                         (lambda: B.qc_seq_join(kv, qc, 0, 0, 0, 0, 0), B.QC_EINVAL),      # slot taken
+                         (lambda: B.qc_seq_join(kv, qc, 2, 0, 200, 0, 0), B.QC_ECAPACITY),
+                         (lambda: B.qc_seq_pages(kv, 3, 0), B.QC_EINVAL), (lambda: B.qc_seq_pages(kv, 0, 3), B.QC_EINVAL),
+                         (lambda: B.qc_locate(kv, B.QC_V, 0, 0, 0, 0), B.QC_ECAPACITY)):    # no page held yet
+        with pytest.raises(P.QcError) as e:
+            call()
+        assert e.value.status == status
+    B.qc_seq_join(kv, qc, 2, 3, 10, 0, 0)                      # before the first prefill: host-only
+    with pytest.raises(P.QcError) as e:                        # needs a paged batch
+        B.qc_seq_pages(kv2, 0, 0)
+    assert e.value.status == B.QC_EORDER
