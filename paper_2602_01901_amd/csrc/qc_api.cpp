@@ -1276,7 +1276,6 @@ qc_status qc_last_row_attention(qc_kvcache* kv, int32_t layer, const void* q_las
   const Config& c = kv->cfg;
   if (layer < 0 || layer >= c.N) return fail(QC_EINVAL, "qc_last_row_attention: layer %d out of range", layer);
   if (c.lazy[layer]) return fail(QC_EINVAL, "qc_last_row_attention: layer %d is lazy and does not hold all of its keys", layer);
-  if (kv->paged) return fail(QC_EORDER, "qc_last_row_attention: not available on a paged batch");
   if (!q_last || !probs || !workspace) return fail(QC_EINVAL, "qc_last_row_attention: null tensor or workspace");
   if (((uintptr_t)q_last | (uintptr_t)workspace) & 15) return fail(QC_EINVAL, "qc_last_row_attention: q_last and workspace must be 16-byte aligned");
   if ((uintptr_t)probs & 3) return fail(QC_EINVAL, "qc_last_row_attention: probs must be 4-byte aligned");

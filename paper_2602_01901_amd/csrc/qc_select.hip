@@ -23,10 +23,11 @@ __global__ __launch_bounds__(256) void last_row_scores_kernel(SelectArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int li = lane % LPR, gid = wave * GPW + lane / LPR;
   const int64_t bh = (int64_t)b * a.n_heads + h;
-  const RowBase rb = row_bases(a.lv, b, h, a.n_heads);
-  const char* krows = a.lv.k_own + rb.k * ROWB + li * 16;
-  // score rows: score_stride floats each, or (per-sequence capacities) laid out like the layer's rows
-  float* srow = a.scores + ((a.lv.flags & LV_RAGGED) ? rb.k : bh * a.score_stride);
+  const RowIndex ri = row_index(a.lv, b, h, a.n_heads);
+  const char* krows = a.lv.k_own + li * 16;
+  // score rows: score_stride floats each, or (per-sequence capacities, pages) laid out like the layer's rows
+  const bool like_rows = (a.lv.flags & (LV_RAGGED | LV_PAGED)) != 0;
+  float* srow = a.scores + (like_rows ? 0 : bh * a.score_stride);
 
   float qf[EPL];
   {
@@ -38,14 +39,15 @@ __global__ __launch_bounds__(256) void last_row_scores_kernel(SelectArgs a) {
   }
   float m = -INFINITY, l = 0.f;
   for (int pos = gid; pos < len; pos += GROUPS) {
-    const uint4 raw = *(const uint4*)(krows + (int64_t)pos * ROWB);
+    const int64_t row = ri.k(pos);
+    const uint4 raw = *(const uint4*)(krows + row * ROWB);
     float kf[EPL];
     unpack16(raw, kf, (T*)nullptr);
     float d = 0.f;
 #pragma unroll
     for (int i = 0; i < EPL; ++i) d = fmaf(qf[i], kf[i], d);
     d = group_sum<LPR>(d);
-    if (li == 0) srow[pos] = d;
+    if (li == 0) srow[like_rows ? row : (int64_t)pos] = d;
     const float mn = fmaxf(m, d);
     l = l * __builtin_amdgcn_exp2f(m - mn) + __builtin_amdgcn_exp2f(d - mn);
     m = mn;
@@ -74,7 +76,8 @@ __global__ __launch_bounds__(256) void last_row_probs_kernel(SelectArgs a) {
   float acc = 0.f;
   for (int h = 0; h < a.n_heads; ++h) {
     const int64_t bh = (int64_t)b * a.n_heads + h;
-    const float s = a.scores[((a.lv.flags & LV_RAGGED) ? row_bases(a.lv, b, h, a.n_heads).k : bh * a.score_stride) + pos];
+    const bool like_rows = (a.lv.flags & (LV_RAGGED | LV_PAGED)) != 0;
+    const float s = a.scores[like_rows ? row_index(a.lv, b, h, a.n_heads).k(pos) : bh * a.score_stride + pos];
     acc += __builtin_amdgcn_exp2f(s - a.row_stats[bh * 2]) / a.row_stats[bh * 2 + 1];
   }
   a.probs[(int64_t)b * a.probs_stride + pos] = acc / (float)a.n_heads;

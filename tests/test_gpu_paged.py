@@ -257,3 +257,33 @@ def test_one_sequence_may_take_more_than_its_share(mode):
     want = olayout.kv_rows_image(lay, stacks + [None])
     assert np.array_equal(s.kv_arena[: lay.rows_bytes()].cpu().numpy(), want)
     s.close()
+
+
+@pytest.mark.parametrize("dtype,D", [("f32", 64), ("bf16", 128)])
+def test_last_row_attention_reads_keys_from_pages(dtype, D):
+    """The selection statistic (Eq. 3) of an ordinary layer on a paged batch against the oracle."""
+    from oracle import selection
+    from paper_2602_01901_amd import binding as B
+    lens = [131, 64, 45, 7, 300]
+    w = workloads.custom("select_paged", 3, 3, D, dtype, [0] * 5, [0] * 5, lens, 0, [0, 0, 0], seed_tag=D,
+                         max_seq=192, max_vis=64, max_text=128)      # 300 positions exceed the per-slot share
+    s = _session(w)
+    s.reset(w.vis_start, w.vis_len, paged=True)
+    ws = torch.empty(B.qc_select_workspace_bytes(s.cfg), dtype=torch.uint8, device="cuda")
+    cu, stride, scale = w.cu_seqlens, 304, 1.0 / np.sqrt(D)
+    worst = 0.0
+    for l in range(w.n_layers):
+        q, k, v = (t.cuda() for t in workloads.prefill_qkv(w, l))
+        s.prefill(l, q, k, v, cu)
+        probs = torch.full((w.batch, stride), -1.0, dtype=torch.float32, device="cuda")
+        q_last = torch.stack([q[cu[b + 1] - 1] for b in range(w.batch)]).contiguous()
+        B.qc_last_row_attention(s.kv, l, q_last, probs, stride, 0.0, ws, ws.numel())
+        got = probs.cpu().numpy().astype(np.float64)
+        for b in range(w.batch):
+            K = np.transpose(workloads.to_f64(k[cu[b]:cu[b + 1]]), (1, 0, 2))
+            want = selection.last_row_attention(workloads.to_f64(q[cu[b + 1] - 1]), K, scale)
+            assert np.all(np.abs(got[b, :lens[b]] - want) <= 1e-5 + 1e-4 * want), (l, b)
+            assert np.all(got[b, lens[b]:] == -1.0)
+            worst = max(worst, float(np.max(np.abs(got[b, :lens[b]] - want))))
+    print("paged last-row attention: worst abs err %.3g" % worst, flush=True)
+    s.close()
