@@ -58,14 +58,6 @@ hipError_t decode_static_scratch(void** ptr, size_t* bytes) {
   return hipSuccess;
 }
 
-// Cache rows are read once per step: load them with the non-temporal hint (measurably faster HBM
-// streaming than ordinary loads on this part).
-__device__ __forceinline__ uint4 stream_load16(const char* p) {
-  typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-  const u32x4 t = __builtin_nontemporal_load((const u32x4*)p);
-  return make_uint4(t.x, t.y, t.z, t.w);
-}
-
 // Per-sequence integers: from the kernel arguments for small batches (INLINE), else from the arena's
 // meta region.  Two instantiations rather than a run-time choice: with a choice the compiler selects
 // between the two addresses and issues one per-lane load, a full memory round trip ahead of

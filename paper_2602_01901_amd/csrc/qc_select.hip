@@ -38,19 +38,32 @@ __global__ __launch_bounds__(256) void last_row_scores_kernel(SelectArgs a) {
     for (int i = 0; i < EPL; ++i) qf[i] *= c;
   }
   float m = -INFINITY, l = 0.f;
-  for (int pos = gid; pos < len; pos += GROUPS) {
-    const int64_t row = ri.k(pos);
-    const uint4 raw = *(const uint4*)(krows + row * ROWB);
-    float kf[EPL];
-    unpack16(raw, kf, (T*)nullptr);
-    float d = 0.f;
+  constexpr int U = 8;   // rows in flight per group: the kernel streams every K row of the layer once
+  for (int p0 = gid; p0 < len; p0 += GROUPS * U) {
+    uint4 raw[U];
+    int64_t row[U];
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) d = fmaf(qf[i], kf[i], d);
-    d = group_sum<LPR>(d);
-    if (li == 0) srow[like_rows ? row : (int64_t)pos] = d;
-    const float mn = fmaxf(m, d);
-    l = l * __builtin_amdgcn_exp2f(m - mn) + __builtin_amdgcn_exp2f(d - mn);
-    m = mn;
+    for (int u = 0; u < U; ++u) {
+      const int pos = min(p0 + u * GROUPS, len - 1);   // rows past the end repeat the last one and are dropped below
+      row[u] = ri.k(pos);
+      raw[u] = stream_load16(krows + row[u] * ROWB);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int pos = p0 + u * GROUPS;
+      float kf[EPL];
+      unpack16(raw[u], kf, (T*)nullptr);
+      float d = 0.f;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) d = fmaf(qf[i], kf[i], d);
+      d = group_sum<LPR>(d);
+      if (pos < len) {
+        if (li == 0) srow[like_rows ? row[u] : (int64_t)pos] = d;
+        const float mn = fmaxf(m, d);
+        l = l * __builtin_amdgcn_exp2f(m - mn) + __builtin_amdgcn_exp2f(d - mn);
+        m = mn;
+      }
+    }
   }
   __shared__ float s_m[GROUPS], s_l[GROUPS];
   if (li == 0) {
