@@ -172,6 +172,12 @@ struct qc_kvcache {
   int64_t longest_cap() const {
     int64_t m = ragged ? 0 : cfg.max_seq;
     if (ragged) for (int b = 0; b < batch; ++b) m = std::max<int64_t>(m, cap_seq[b]);
+    // paged: a sequence has no capacity of its own; a recorded launch covers max_seq positions, or, once a
+    // sequence is longer than that, the next multiple of max_seq above the longest one (and is recorded
+    // again when a sequence outgrows it)
+    if (paged)
+      for (int b = 0; b < batch; ++b)
+        if (live[b]) m = std::max<int64_t>(m, ((int64_t)len0[b] + steps_of(b) + 1 + cfg.max_seq - 1) / cfg.max_seq * cfg.max_seq);
     return m;
   }
   // Paged batches (qc_reset_paged): rows live on pages of kPageRows rows.  pages[pool][b] = the pages slot b
@@ -213,6 +219,7 @@ struct qc_decode_graph {
   hipGraphExec_t exec = nullptr;
   int32_t batch = 0, first_late = -1;
   bool ragged = false;                   // recorded with per-sequence capacities
+  bool paged = false;                    // recorded on a paged batch
   int64_t covered = 0;                   // positions the recorded launch grids cover
   int32_t final_owner = -1;              // Q Cache owner after a step (Global Lazy Attention)
   const void* score_workspace = nullptr;
@@ -954,7 +961,7 @@ static qc_status decode_impl(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32
   if (qk_unused && kv->score_workspace != workspace)
     return fail(QC_EINVAL, "qc_decode: layer %d needs the workspace its block's first layer was called with", layer);
 
-  if (kv->paged && layer == 0) {   // the row this step appends may open a page
+  if (kv->paged && layer == 0 && !geom) {   // the row this step appends may open a page (a replayed step: at its launch)
     std::vector<std::array<int64_t, 3>> want(kv->batch, std::array<int64_t, 3>{-1, -1, -1});
     for (int b = 0; b < kv->batch; ++b)
       if (kv->live[b]) {
@@ -1049,7 +1056,6 @@ qc_status qc_decode_graph_create(qc_kvcache* kv, qc_qcache* qc, const void* cons
   if (!out_graph) return fail(QC_EINVAL, "qc_decode_graph_create: out_graph is null");
   *out_graph = nullptr;
   if (!kv || !qc || !q || !k || !v || !out) return fail(QC_EINVAL, "qc_decode_graph_create: null argument");
-  if (kv->paged) return fail(QC_EORDER, "qc_decode_graph_create: not available on a paged batch (a step may hand out pages, which is host work)");
   const Config& c = kv->cfg;
   if (!c.same(qc->cfg)) return fail(QC_EINVAL, "qc_decode_graph_create: handles were created with different configurations");
   if (kv->phase != PH_READY) return fail(QC_EORDER, "qc_decode_graph_create: needs a finished prefill pass and no decode step in flight");
@@ -1108,7 +1114,7 @@ qc_status qc_decode_graph_create(qc_kvcache* kv, qc_qcache* qc, const void* cons
   }
   g->kv = kv; g->qc = qc; g->exec = exec;
   g->batch = kv->batch; g->first_late = kv->first_late;
-  g->ragged = kv->ragged; g->covered = (int64_t)geom.chunk * geom.max_chunks;
+  g->ragged = kv->ragged; g->paged = kv->paged; g->covered = (int64_t)geom.chunk * geom.max_chunks;
   g->final_owner = final_owner; g->score_workspace = final_score_ws;
   *out_graph = g;
   return QC_OK;
@@ -1121,9 +1127,18 @@ qc_status qc_decode_graph_launch(qc_decode_graph* g, void* stream) {
   if (kv->phase != PH_READY) return fail(QC_EORDER, "qc_decode_graph_launch: needs a finished prefill pass and no decode step in flight");
   if (kv->batch != g->batch || kv->first_late != g->first_late)
     return fail(QC_EORDER, "qc_decode_graph_launch: the graph was recorded for %d sequences (pruning boundary %d), the cache now holds %d (%d)", g->batch, g->first_late, kv->batch, kv->first_late);
-  if (kv->ragged != g->ragged || kv->longest_cap() > g->covered)
+  if (kv->ragged != g->ragged || kv->paged != g->paged || kv->longest_cap() > g->covered)
     return fail(QC_EORDER, "qc_decode_graph_launch: the graph was recorded for another kind of capacities, or for at most %lld positions", (long long)g->covered);
   if (qc_status s = step_fits("qc_decode_graph_launch", kv)) return s;
+  if (kv->paged) {   // the row this step appends may open a page: host work ahead of the replay, on its stream
+    std::vector<std::array<int64_t, 3>> want(kv->batch, std::array<int64_t, 3>{-1, -1, -1});
+    for (int b = 0; b < kv->batch; ++b)
+      if (kv->live[b]) {
+        const int64_t len = (int64_t)kv->len_of(0, b) + kv->steps_of(b);
+        want[b] = {len + 1, len + 1 - kv->vis_len[b], -1};
+      }
+    if (qc_status s = paged_reserve(kv, want, "qc_decode_graph_launch", (hipStream_t)stream)) return s;
+  }
   if (kv->dev_generated != kv->generated) {  // first replay, or ordinary qc_decode steps ran in between
     hipError_t e = qc::launch_counter_update((int32_t*)(kv->arena + c.off_counters()), kv->generated, 0, (hipStream_t)stream);
     if (e != hipSuccess) return fail(QC_EDEVICE, "qc_decode_graph_launch: %s", hipGetErrorString(e));

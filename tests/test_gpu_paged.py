@@ -287,3 +287,33 @@ def test_last_row_attention_reads_keys_from_pages(dtype, D):
             worst = max(worst, float(np.max(np.abs(got[b, :lens[b]] - want))))
     print("paged last-row attention: worst abs err %.3g" % worst, flush=True)
     s.close()
+
+
+@pytest.mark.parametrize("mode", ["vla", "gla"])
+def test_decode_graph_replays_on_pages(mode):
+    """Graph replays and ordinary steps alternate on a paged batch; replays open pages (host work ahead of
+    the launch); every step is checked, then the lists and both arenas."""
+    from test_gpu_graph import run_steps, step_buffers
+    w = _bf16_workload(decode_steps=30)
+    s = _session(w, mode)
+    stacks = sr.new_oracles(w, mode=mode)
+    pools = sr.oracle_page_pools(w, mode)
+    sr.reset_session(s, w, zero_fill=True, paged=True)
+    pools.prefill(range(w.batch), w.seq_len, w.vis_len)
+    for l in range(w.n_layers):
+        q, k, v = workloads.prefill_qkv(w, l)
+        sr.oracle_prefill_layer(w, stacks, l, q, k, v)
+        no_qk = mode == "gla" and w.lazy_mask[l]
+        s.prefill(l, None if no_qk else q.cuda(), None if no_qk else k.cuda(), v.cuda(), w.cu_seqlens)
+    bufs = step_buffers(w, mode)
+    graph = s.decode_graph(*bufs)
+    schedule = "gggeg" * 6          # sequence 3 opens a page at step 0, sequence 1 at step 24: both in replays
+    worst = run_steps(w, s, stacks, mode, graph, bufs, schedule)
+    for t in range(len(schedule)):
+        pools.decode_step(range(w.batch), [n + t for n in w.seq_len], w.vis_len)
+    assert worst <= sr.TOL["bf16"]
+    sr.check_page_lists(s, pools)
+    lay = sr.oracle_layout(w, mode, paged=pools.tables())
+    sr.check_kv_rows(s, lay, stacks)
+    assert np.array_equal(s.q_arena.cpu().numpy()[: lay.q_arena_bytes()], olayout.q_arena_image(lay, stacks))
+    s.close()
