@@ -233,7 +233,10 @@ qc_status qc_seq_extent(const qc_kvcache* kv, int32_t b, int32_t* live, int32_t*
  * Slots work as after qc_reset_ragged: qc_seq_leave gives the sequence's pages back (lowest numbers are
  * handed out first again; nothing is cleared), qc_seq_join takes no capacities (pass 0 for both) and
  * its sequence gets pages when its prefill pass begins.  Not available on a paged batch (QC_EORDER):
- * qc_seq_grow and qc_seq_extent (nothing to grow or to place) and qc_prune.  A decode graph recorded on
+ * qc_seq_grow and qc_seq_extent (nothing to grow or to place).  qc_prune works as elsewhere; the layers
+ * behind its boundary use the first rows of the same lists, so the pages keep following the unpruned
+ * lengths (a configuration with prune_before_layer, which sizes those layers apart, cannot be paged).
+ * A decode graph recorded on
  * a paged batch covers max_seq positions (or the next multiple of max_seq above the longest sequence at
  * the time); qc_decode_graph_launch hands out the pages its step opens before it launches the graph, and
  * returns QC_EORDER once a sequence has outgrown what the graph covers (record a new one then).

@@ -1409,7 +1409,6 @@ qc_status qc_prune(qc_kvcache* kv, qc_qcache* qc, const int32_t* keep) {
   if (!kv || !qc || !keep) return fail(QC_EINVAL, "qc_prune: null argument");
   const Config& c = kv->cfg;
   if (!c.same(qc->cfg)) return fail(QC_EINVAL, "qc_prune: handles were created with different configurations");
-  if (kv->paged) return fail(QC_EORDER, "qc_prune: not available on a paged batch");
   if (kv->phase != PH_PREFILL) return fail(QC_EORDER, "qc_prune: allowed only inside a prefill pass, between two layers");
   if (kv->first_late >= 0) return fail(QC_EORDER, "qc_prune: this pass already has a pruning boundary (before layer %d)", kv->first_late);
   if (kv->join_pass || !kv->all_live()) return fail(QC_EORDER, "qc_prune: not available on a batch with free slots or with sequences that joined later");
@@ -1513,7 +1512,7 @@ qc_status qc_locate(const qc_kvcache* kv, int32_t which, int32_t layer, int32_t 
       *byte_offset = c.off_v(layer) + index * rb;
       return QC_OK;
     }
-    const int32_t s = kv->vis_start[b], vn = kv->vis_len[b];
+    const int32_t s = kv->vis_start[b], vn = kv->vis_len_of(layer, b);
     int src = layer;
     int64_t row = pos;
     if (c.lazy[layer]) {

@@ -138,11 +138,16 @@ def test_gather_rows_is_bit_exact(row_elems, dtype, pad):
     assert np.all(got[:, row_elems:] == 0)              # padding of the destination rows untouched
 
 
-def run_pruned_parity(w, first_late, keep, mode, decode_steps, caps=None, max_seq_late=0, use_graph=False):
+def run_pruned_parity(w, first_late, keep, mode, decode_steps, caps=None, max_seq_late=0, use_graph=False, paged=False):
     """Early layers, ranking from the last early layer's last-row attention, pruning, late layers, decode."""
     s = (P.Session.for_workload(w, mode=mode, prune_before_layer=first_late, max_seq_late=max_seq_late) if max_seq_late
          else P.Session.for_workload(w, mode=mode))
-    reset_session(s, w, caps)
+    reset_session(s, w, caps, paged=paged)
+    pools = None
+    if paged:                                   # pages follow the unpruned lengths: one list serves every layer
+        from stack_runner import oracle_page_pools
+        pools = oracle_page_pools(w, mode)
+        pools.prefill(range(w.batch), w.seq_len, w.vis_len)
     stacks = [PrunedStackOracle(w.n_layers, w.n_heads, w.head_dim, w.lazy_mask, w.vis_start[b], w.vis_len[b],
                                 first_late, keep[b], mode=mode) for b in range(w.batch)]
     cu = w.cu_seqlens
@@ -209,6 +214,8 @@ def run_pruned_parity(w, first_late, keep, mode, decode_steps, caps=None, max_se
                 bufs[i] = [None if w.lazy_mask[l] else bufs[i][l] for l in range(w.n_layers)]
         graph = s.decode_graph(*bufs)
     for t in range(decode_steps):
+        if paged:
+            pools.decode_step(range(w.batch), [n + t for n in w.seq_len], w.vis_len)
         ins = [workloads.decode_qkv(w, l, t) for l in range(w.n_layers)]
         if use_graph:
             for l in range(w.n_layers):
@@ -232,7 +239,11 @@ def run_pruned_parity(w, first_late, keep, mode, decode_steps, caps=None, max_se
             assert np.isfinite(err)
             worst = max(worst, err)
     torch.cuda.synchronize()
-    lay = oracle_layout(w, mode, caps, late=(first_late, max_seq_late) if max_seq_late else None)
+    lay = oracle_layout(w, mode, caps, late=(first_late, max_seq_late) if max_seq_late else None,
+                        paged=pools.tables() if paged else None)
+    if paged:
+        from stack_runner import check_page_lists
+        check_page_lists(s, pools)
     assert np.array_equal(s.kv_arena[: lay.rows_bytes()].cpu().numpy(), olayout.kv_rows_image(lay, stacks)), "K/V rows differ"
     assert np.array_equal(s.q_arena.cpu().numpy()[: lay.q_arena_bytes()], olayout.q_arena_image(lay, stacks)), "Q arena differs"
     res = olayout.resident_bytes(lay, stacks)
@@ -249,6 +260,18 @@ def run_pruned_parity(w, first_late, keep, mode, decode_steps, caps=None, max_se
 
 
 MASK6 = [0, 0, 1, 0, 1, 1]
+
+
+@pytest.mark.parametrize("mode", ["vla", "gla"])
+@pytest.mark.parametrize("use_graph", [False, True])
+def test_pruned_stack_on_pages_matches_oracle(mode, use_graph):
+    """Token pruning on a paged batch: the layers behind the boundary use the first rows of the same page
+    lists (pages follow the unpruned lengths); decode steps cross a page boundary."""
+    lens, vs, vl = [150, 97, 64], [5, 0, 20], [100, 80, 0]
+    w = workloads.custom("pruned_paged", 6, 3, 128, "bf16", vs, vl, lens, 3, MASK6, seed_tag=21,
+                         max_seq=192, max_vis=128, max_text=128)
+    worst = run_pruned_parity(w, 3, [37, 80, 0], mode, 3, paged=True, use_graph=use_graph)
+    assert worst <= TOL["bf16"]
 
 
 @pytest.mark.parametrize("mode", ["vla", "gla"])
