@@ -74,3 +74,27 @@ def test_random_configuration(seed):
         keep = [int(rng.integers(0, v + 1)) for v in w.vis_len]
         keep = [max(k, 1 if L == v else 0) for k, L, v in zip(keep, w.seq_len, w.vis_len)]   # every sequence keeps a token
         assert run_pruned_parity(w, first_late, keep, mode, w.decode_steps, use_graph=bool(seed % 2)) <= TOL[w.dtype]
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configuration_on_pages(seed):
+    """The same population on paged batches (capacities rounded up to whole pages): ordinary calls with the
+    arenas and page lists compared, or a pruning boundary with or without graph replays."""
+    import dataclasses
+    w, rng = random_case(seed)
+    up = lambda x: -(-x // 64) * 64
+    w = dataclasses.replace(w, max_seq=up(w.max_seq), max_vis=up(w.max_vis), max_text=up(w.max_text))
+    mode = "gla" if seed % 2 else "vla"
+    if seed % 3 != 2:
+        s = P.Session.for_workload(w, mode=mode)
+        wp, wd = run_full_parity(w, w.decode_steps, s, poison_span=bool(seed % 4 == 0), paged=True)
+        assert max(wp, wd) <= TOL[w.dtype]
+        s.close()
+    else:
+        candidates = [l for l in range(1, w.n_layers) if not w.lazy_mask[l]]
+        if not candidates:
+            pytest.skip("no ordinary layer after layer 0 in this mask")
+        first_late = int(rng.choice(candidates))
+        keep = [int(rng.integers(0, v + 1)) for v in w.vis_len]
+        keep = [max(k, 1 if L == v else 0) for k, L, v in zip(keep, w.seq_len, w.vis_len)]
+        assert run_pruned_parity(w, first_late, keep, mode, w.decode_steps, use_graph=bool(seed % 2), paged=True) <= TOL[w.dtype]
