@@ -317,3 +317,17 @@ def test_decode_graph_replays_on_pages(mode):
     sr.check_kv_rows(s, lay, stacks)
     assert np.array_equal(s.q_arena.cpu().numpy()[: lay.q_arena_bytes()], olayout.q_arena_image(lay, stacks))
     s.close()
+
+
+@pytest.mark.parametrize("mode", ["vla", "gla"])
+@pytest.mark.parametrize("which", ["f32", "bf16"])
+def test_nothing_reads_a_page_row_it_has_not_written(mode, which):
+    """Arenas and workspace start as all-ones bytes (NaN in either element type) and are not cleared: rows
+    of a page behind a sequence's last position, and pages nobody holds, must never reach an output."""
+    w = _f32_workload(decode_steps=5) if which == "f32" else _bf16_workload(decode_steps=5)
+    s = _session(w, mode)
+    for t in (s.kv_arena, s.q_arena, s.workspace):
+        t.fill_(0xFF)
+    wp, wd = sr.run_full_parity(w, w.decode_steps, s, check_arena=False, zero_fill=False, paged=True)
+    assert max(wp, wd) <= sr.TOL[w.dtype]
+    s.close()
