@@ -786,6 +786,13 @@ def bench_paged(args):
         _, ev_s = timed(torch, lambda: run(steps), 1)
         res[name] = {"prefill_stack_ms": ev_p * 1e3, "decode_tokens_per_s": w.batch * steps / ev_s}
         if paged:
+            # what the pools hold now, and what the batch would hold with every sequence decoded to the end:
+            # the admission arithmetic a serving loop does with qc_pages_needed and qc_pool_pages
+            pools = [P.binding.qc_pool_pages(s.kv, pool) for pool in range(3)]
+            at_end = [sum(x) for x in zip(*[P.binding.qc_pages_needed(s.cfg, w.seq_len[b] + w.decode_steps, w.vis_len[b])
+                                            for b in range(w.batch)])]
+            res[name]["pool_pages"] = {"total": [t for t, _ in pools], "held_now": [t - f for t, f in pools],
+                                       "held_after_%d_decode_steps" % w.decode_steps: at_end}
             # every fourth sequence leaves; the freed pages go, lowest first, to the same prompts joining in
             # the reverse order, so a sequence's pages are scattered over the pools
             movers = list(range(1, w.batch, 4))

@@ -242,7 +242,15 @@ qc_status qc_seq_extent(const qc_kvcache* kv, int32_t b, int32_t* live, int32_t*
  * returns QC_EORDER once a sequence has outgrown what the graph covers (record a new one then).
  * qc_locate answers through the lists.  qc_reset and qc_reset_ragged return to rows in runs.
  * qc_seq_pages: HOST query: *count = pages slot b holds in `pool`; the first min(capacity, *count) page
- *   numbers are written to `pages` if it is not NULL. */
+ *   numbers are written to `pages` if it is not NULL.
+ * qc_pool_pages: HOST query: pages of `pool` in all and free at this moment (0 and 0 for a pool the
+ *   configuration does not use).  QC_EORDER unless the batch is paged.
+ * qc_pages_needed: HOST arithmetic, no handle: pages[QC_POOL_*] = pages a sequence holds in each pool once
+ *   `len` positions of it are stored, vis_len of them visual: ceil(len/QC_PAGE_ROWS) of QC_POOL_SEQ,
+ *   ceil((len - vis_len)/QC_PAGE_ROWS) of QC_POOL_TEXT and ceil(vis_len/QC_PAGE_ROWS) of QC_POOL_VIS (0 for
+ *   a pool the configuration does not use).  With qc_pool_pages this is what admission needs: a sequence
+ *   whose prompt and planned decode steps need no more than the free pages can join and will not run dry.
+ *   QC_EINVAL for a configuration that cannot be paged or unless 0 <= vis_len <= len. */
 #define QC_PAGE_ROWS 64
 enum { QC_POOL_SEQ = 0, QC_POOL_TEXT = 1, QC_POOL_VIS = 2 };
 size_t qc_page_table_bytes(const qc_config* cfg);
@@ -251,6 +259,8 @@ qc_status qc_reset_paged(qc_kvcache* kv, qc_qcache* qc, int32_t batch, const int
                          size_t page_list_bytes, int32_t zero_fill, void* stream);
 qc_status qc_seq_pages(const qc_kvcache* kv, int32_t b, int32_t pool, int32_t* pages, int32_t capacity,
                        int32_t* count);
+qc_status qc_pool_pages(const qc_kvcache* kv, int32_t pool, int32_t* total, int32_t* free_pages);
+qc_status qc_pages_needed(const qc_config* cfg, int32_t len, int32_t vis_len, int32_t* pages /* 3 entries */);
 
 /* ---- prefill: one layer over the packed prompts (paper Eq. 1; Eq. 7 in a lazy layer) -----------
  * q, k, v, out: DEVICE, element (token t, head h, dim d) at t*token_stride + h*head_stride + d

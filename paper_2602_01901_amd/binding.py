@@ -54,6 +54,8 @@ _PROTOTYPES = {
     "qc_reset_paged": (c_int32, [c_void_p, c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32), POINTER(c_uint8),
                                  c_void_p, c_size_t, c_int32, c_void_p]),
     "qc_seq_pages": (c_int32, [c_void_p, c_int32, c_int32, POINTER(c_int32), c_int32, POINTER(c_int32)]),
+    "qc_pool_pages": (c_int32, [c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32)]),
+    "qc_pages_needed": (c_int32, [POINTER(qc_config), c_int32, c_int32, POINTER(c_int32)]),
     "qc_seq_leave": (c_int32, [c_void_p, c_void_p, c_int32, c_void_p]),
     "qc_seq_join": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, c_void_p]),
     "qc_seq_grow": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_void_p]),
@@ -215,6 +217,20 @@ def qc_seq_pages(kv, b, pool):
     buf = (c_int32 * max(n.value, 1))()
     _check(load_library().qc_seq_pages(kv, b, pool, buf, n.value, byref(n)))
     return [buf[i] for i in range(n.value)]
+
+
+def qc_pool_pages(kv, pool):
+    """(pages of `pool` in all, pages free at this moment)."""
+    total, free = c_int32(), c_int32()
+    _check(load_library().qc_pool_pages(kv, pool, byref(total), byref(free)))
+    return total.value, free.value
+
+
+def qc_pages_needed(cfg, length, vis_len):
+    """Pages a sequence of `length` stored positions, vis_len of them visual, holds in the three pools."""
+    buf = (c_int32 * 3)()
+    _check(load_library().qc_pages_needed(byref(cfg), length, vis_len, buf))
+    return [buf[0], buf[1], buf[2]]
 
 
 def qc_seq_leave(kv, qc, b, stream=None):

@@ -886,6 +886,27 @@ qc_status qc_seq_pages(const qc_kvcache* kv, int32_t b, int32_t pool, int32_t* p
   return QC_OK;
 }
 
+qc_status qc_pool_pages(const qc_kvcache* kv, int32_t pool, int32_t* total, int32_t* free_pages) {
+  if (!kv || !total || !free_pages) return fail(QC_EINVAL, "qc_pool_pages: null argument");
+  if (!kv->paged) return fail(QC_EORDER, "qc_pool_pages: needs a paged batch (qc_reset_paged)");
+  if (pool < 0 || pool > 2) return fail(QC_EINVAL, "qc_pool_pages: pool out of range");
+  *total = (int32_t)kv->cfg.pool_pages(pool);
+  *free_pages = (int32_t)kv->free_pages[pool].size();
+  return QC_OK;
+}
+
+qc_status qc_pages_needed(const qc_config* cfg, int32_t len, int32_t vis_len, int32_t* pages) {
+  Config c;
+  if (!pages) return fail(QC_EINVAL, "qc_pages_needed: null argument");
+  if (!parse_config(cfg, &c)) return fail(QC_EINVAL, "qc_pages_needed: invalid configuration");
+  if (!c.pageable()) return fail(QC_EINVAL, "qc_pages_needed: the configuration cannot be paged");
+  if (len < 0 || vis_len < 0 || vis_len > len) return fail(QC_EINVAL, "qc_pages_needed: need 0 <= vis_len <= len");
+  const int64_t rows[3] = {len, (int64_t)len - vis_len, vis_len};
+  for (int pool = 0; pool < 3; ++pool)
+    pages[pool] = c.pool_used(pool) ? (int32_t)((rows[pool] + qc::kPageRows - 1) / qc::kPageRows) : 0;
+  return QC_OK;
+}
+
 qc_status qc_seq_extent(const qc_kvcache* kv, int32_t b, int32_t* live, int32_t* base_seq, int32_t* base_text, int32_t* base_vis) {
   if (!kv || !live || !base_seq || !base_text || !base_vis) return fail(QC_EINVAL, "qc_seq_extent: null argument");
   if (kv->paged) return fail(QC_EORDER, "qc_seq_extent: a paged batch has no extents (see qc_seq_pages)");

@@ -30,6 +30,11 @@ def check_page_lists(session, pools):
     for pool, kind in enumerate(("seq", "text", "vis")):
         for b in range(len(want[kind])):
             assert B.qc_seq_pages(session.kv, b, pool) == want[kind][b], (kind, b)
+        if kind in pools._kinds():
+            held = sum(len(x) for x in want[kind])
+            assert B.qc_pool_pages(session.kv, pool) == (held + len(pools.free[kind]), len(pools.free[kind])), kind
+        else:
+            assert B.qc_pool_pages(session.kv, pool) == (0, 0), kind
 
 
 def reset_session(session, w, caps=None, zero_fill=True, paged=False):

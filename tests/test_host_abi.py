@@ -463,6 +463,13 @@ def test_reset_paged_validation_and_what_a_paged_batch_refuses():
     # host-only when nothing is cleared; slot 2 starts free
     B.qc_reset_paged(**dict(ok, present=[1, 1, 0]))
     assert [B.qc_seq_pages(kv, b, pool) for b in range(3) for pool in range(3)] == [[]] * 9
+    assert [B.qc_pool_pages(kv, pool) for pool in range(3)] == [(9, 9), (6, 6), (3, 3)]
+    with pytest.raises(P.QcError) as e:
+        B.qc_pool_pages(kv, 3)
+    assert e.value.status == B.QC_EINVAL
+    with pytest.raises(P.QcError) as e:
+        B.qc_pool_pages(kv2, 0)
+    assert e.value.status == B.QC_EORDER
     for call, status in ((lambda: B.qc_seq_grow(kv, qc, 0, 64, 0), B.QC_EORDER), (lambda: B.qc_seq_extent(kv, 0), B.QC_EORDER),
                          (lambda: B.qc_seq_join(kv, qc, 2, 0, 0, 64, 0), B.QC_EINVAL),     # capacities are not taken
                          (lambda: B.qc_seq_join(kv, qc, 0, 0, 0, 0, 0), B.QC_EINVAL),      # slot taken
@@ -476,3 +483,30 @@ def test_reset_paged_validation_and_what_a_paged_batch_refuses():
     with pytest.raises(P.QcError) as e:                        # needs a paged batch
         B.qc_seq_pages(kv2, 0, 0)
     assert e.value.status == B.QC_EORDER
+
+
+def test_pages_a_sequence_needs():
+    """qc_pages_needed against values worked by hand and against the oracle's page hand-out for one prompt."""
+    from oracle.layout import PagePools
+    cfg = P.make_config(*PAGED)
+    assert B.qc_pages_needed(cfg, 0, 0) == [0, 0, 0]
+    assert B.qc_pages_needed(cfg, 1, 0) == [1, 1, 0]
+    assert B.qc_pages_needed(cfg, 64, 64) == [1, 0, 1]
+    assert B.qc_pages_needed(cfg, 130, 65) == [3, 2, 2]          # 130 positions, 65 text rows, 65 visual rows
+    assert B.qc_pages_needed(cfg, 704, 576) == [11, 2, 9]        # more than the pools hold: arithmetic only
+    gla = P.make_config(*PAGED, mode="gla")
+    assert B.qc_pages_needed(gla, 130, 65) == [3, 0, 0]
+    assert B.qc_pages_needed(P.make_config(*PAGED[:8], [0, 0, 0, 0]), 130, 65) == [3, 0, 0]
+    for length, vis in ((1, 1), (63, 10), (64, 0), (65, 64), (191, 64), (192, 1)):
+        for mode, c in (("vla", cfg), ("gla", gla)):
+            pp = PagePools(1, 192, 192, 192, mode=mode)
+            pp.prefill([0], [length], [vis])
+            held = pp.tables()
+            assert B.qc_pages_needed(c, length, vis) == [len(held[k][0]) for k in ("seq", "text", "vis")], (length, vis, mode)
+    for bad in ((-1, 0), (5, 6), (5, -1)):
+        with pytest.raises(P.QcError) as e:
+            B.qc_pages_needed(cfg, *bad)
+        assert e.value.status == B.QC_EINVAL
+    with pytest.raises(P.QcError) as e:                           # max_seq not a whole number of pages
+        B.qc_pages_needed(P.make_config(4, 2, 64, "bf16", 3, 200, 64, 128, [0, 1, 1, 0]), 10, 0)
+    assert e.value.status == B.QC_EINVAL
