@@ -59,18 +59,39 @@ constexpr float kRescaleThreshold = 8.0f;  // log2 units
 struct PfPages {
   const int32_t *seq, *k, *q;
 };
+// Up to two pages that a run of at most 64 consecutive rows of a pool touches, fetched by scalar loads:
+// rows of page index `first` live on page p0, rows of the next index on p1.
+struct PagePair {
+  int first, p0, p1;
+  __device__ __forceinline__ int64_t row(int r, int h, int n_heads) const {
+    return ((int64_t)((r >> 6) == first ? p0 : p1) * n_heads + h) * kPageRows + (r & (kPageRows - 1));
+  }
+};
+// `first` must be a wave-uniform index; both entries read lie inside the list (entries the sequence does
+// not hold are fetched but never chosen by a row that exists).
+__device__ __forceinline__ PagePair load_page_pair(const int32_t* list, int first, int list_len) {
+  PagePair pp = {first, 0, 0};
+  if (list_len > 0) {
+    pp.first = min(first, list_len - 1);
+    pp.p0 = uniform_load(list + pp.first);
+    pp.p1 = uniform_load(list + min(pp.first + 1, list_len - 1));
+  }
+  return pp;
+}
+// qp: the Q Cache pages of the wave's query rows (paged batches).
 template <bool PAGED>
-__device__ __forceinline__ const char* pf_q_row(const PrefillArgs& a, const SeqMeta& sm, const RowBase& rb, const PfPages& pg, int h, int pos) {
+__device__ __forceinline__ const char* pf_q_row(const PrefillArgs& a, const SeqMeta& sm, const RowBase& rb, const PagePair& qp, int h, int pos) {
   if (a.is_lazy && pos >= sm.vis_start && pos < sm.vis_start + sm.vis_len) {
     const int r = pos - sm.vis_start;
-    return a.lv.q_cache + (PAGED ? paged_row(pg.q, r, h, a.n_heads) : rb.q + r) * pf::ROWB;
+    return a.lv.q_cache + (PAGED ? qp.row(r, h, a.n_heads) : rb.q + r) * pf::ROWB;
   }
   return (const char*)a.q + ((int64_t)(sm.tok0 + pos) * a.token_stride + (int64_t)h * a.head_stride) * 2;
 }
+// page: the page that holds the positions of pos's key tile (paged batches; a tile is one page).
 template <bool PAGED>
-__device__ __forceinline__ const char* pf_k_row(const PrefillArgs& a, const SeqMeta& sm, const RowBase& rb, const PfPages& pg, int h, int pos) {
+__device__ __forceinline__ const char* pf_k_row(const PrefillArgs& a, const SeqMeta& sm, const RowBase& rb, int page, int h, int pos) {
   if (a.is_lazy && pos >= sm.vis_start && pos < sm.vis_start + sm.vis_len)
-    return a.lv.k_anchor + (PAGED ? paged_row(pg.seq, pos, h, a.n_heads) : rb.anchor + pos) * pf::ROWB;
+    return a.lv.k_anchor + (PAGED ? ((int64_t)page * a.n_heads + h) * kPageRows + (pos & (kPageRows - 1)) : rb.anchor + pos) * pf::ROWB;
   return (const char*)a.k + ((int64_t)(sm.tok0 + pos) * a.token_stride + (int64_t)h * a.head_stride) * 2;
 }
 
@@ -213,32 +234,45 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
       for (int p = 0; p < LPT; ++p) {
         const int r = lrow + 4 * p;
         const int pos = min(k0 + r, len - 1);  // rows past the end repeat the last row; their scores are masked
-        async_copy16(pf_k_row<PAGED>(a, sm, rb, pg, h, pos) + ((lchunk ^ (r & 15)) * 16), kb + p * 4 * ROWB);
+        async_copy16(pf_k_row<PAGED>(a, sm, rb, page, h, pos) + ((lchunk ^ (r & 15)) * 16), kb + p * 4 * ROWB);
         async_copy16(vin_base + (int64_t)pos * ts2 + ((lchunk ^ ((r & 3) << 2)) * 16), vb + p * 4 * ROWB);
       }
     }
   };
 
-  // Paged lazy layers: the page of a key tile is fetched (a scalar load) one tile before its loads are issued.
+  // Paged lazy layers: lane i keeps the page of key tile 64*block + i of the sequence, for the current
+  // block of 64 tiles and the next one (one vector load per 64 tiles, long complete when first used);
+  // a tile's page is then a lane read away, with no memory access in the tile loop.
+  int pages_cur = 0, pages_next = 0;
+  auto fetch_pages = [&](int block) -> int {
+    if constexpr (PAGED)
+      if (a.is_lazy) return pg.seq[min(block * 64 + lane, a.lv.pt_seq_stride - 1)];
+    return 0;
+  };
   auto page_of_tile = [&](int t) -> int {
-    if constexpr (PAGED) return a.is_lazy ? uniform_load(pg.seq + min(t, n_tiles - 1)) : 0;
+    if constexpr (PAGED) return __builtin_amdgcn_readlane(pages_cur, t & 63);
     else return 0;
   };
-  int page_ahead = page_of_tile(0);
-  load_tile(0, page_ahead);  // issued before the Q loads below so that the two latencies overlap
-  page_ahead = page_of_tile(1);
+  pages_cur = fetch_pages(0);
+  pages_next = fetch_pages(1);
+  load_tile(0, page_of_tile(0));  // issued before the Q loads below so that the two latencies overlap
 
   // ---- Q fragments (B operand of S^T = K Q^T): query qi, dims ks*16 + hf*8 .. +8
   bf16x8 qf[8];
   {
-    const char* qp = pf_q_row<PAGED>(a, sm, rb, pg, h, min(qi, len - 1));
+    // paged batches: the Q Cache rows of this wave's queries lie on at most two pages
+    PagePair qpages = {0, 0, 0};
+    if constexpr (PAGED)
+      if (a.is_lazy || a.write_q)
+        qpages = load_page_pair(pg.q, max(min(__builtin_amdgcn_readfirstlane(wrow0), len - 1) - sm.vis_start, 0) >> 6, a.lv.pt_q_stride);
+    const char* qp = pf_q_row<PAGED>(a, sm, rb, qpages, h, min(qi, len - 1));
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + (ks * 16 + hf * 8) * 2));
     // Q Cache write (ordinary layer followed by a lazy one): the span rows of Q, straight from the
     // fragments this lane holds (the two lane halves of a row write alternate 16-byte pieces).
     if (a.write_q && qi < len && qi >= sm.vis_start && qi < sm.vis_start + sm.vis_len) {
       const int qr = qi - sm.vis_start;
-      char* qc = a.lv.q_cache + (PAGED ? paged_row(pg.q, qr, h, a.n_heads) : rb.q + qr) * ROWB;
+      char* qc = a.lv.q_cache + (PAGED ? qpages.row(qr, h, a.n_heads) : rb.q + qr) * ROWB;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) *(uint4*)(qc + (ks * 16 + hf * 8) * 2) = __builtin_bit_cast(uint4, qf[ks]);
     }
@@ -259,16 +293,50 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
   // Once such a tile is visible in LDS every thread copies a share of it to the K and V caches
   // (16-byte pieces, swizzle undone).  A lazy layer stores text rows only, moved down by vis_len
   // behind the span; its span rows in LDS are the anchor layer's and are not stored again.
+  // Paged batches: a stored tile is one page of positions (its V rows, an ordinary layer's K rows, a lazy
+  // layer's K rows ahead of the span); a lazy layer's K rows behind the span, moved down by vis_len, lie
+  // on at most two pages of the text pool.  All fetched by scalar loads before the tile loop.
+  struct StorePages {
+    int v, k_pos;
+    PagePair k_text;
+  };
+  auto store_pages = [&](int t) -> StorePages {
+    StorePages sp = {0, 0, {0, 0, 0}};
+    if constexpr (PAGED) {
+      const int tt = min(t, n_tiles - 1);
+      sp.v = uniform_load(pg.seq + tt);
+      if (!a.is_lazy) {
+        sp.k_pos = uniform_load(pg.k + tt);
+      } else if (!a.inherit_all && a.lv.pt_k_stride > 0) {
+        sp.k_pos = uniform_load(pg.k + min(tt, a.lv.pt_k_stride - 1));
+        sp.k_text = load_page_pair(pg.k, max(max(tt * BN, sm.vis_start + sm.vis_len) - sm.vis_len, 0) >> 6, a.lv.pt_k_stride);
+      }
+    }
+    return sp;
+  };
+  const int t_own = q0 / BN;   // the workgroup's own rows are key tiles t_own and t_own + 1
+  const StorePages sp_a = store_pages(t_own), sp_b = store_pages(t_own + 1);
   auto store_tile_to_caches = [&](int t) {
     const char* kb = lds + (t % STAGES) * STAGE;
     const char* vb = kb + TILE;
     const int k0 = t * BN;
     char* kdst = a.lv.k_own + rb.k * ROWB;
     char* vdst = a.lv.v_own + rb.v * ROWB;
-    // row index of a row of this (sequence, head) in the region: run of rows, or page by page
-    auto v_row = [&](int r) -> int64_t { if constexpr (PAGED) return paged_row(pg.seq, r, h, a.n_heads); else return r; };
-    auto k_row = [&](int r) -> int64_t { if constexpr (PAGED) return paged_row(pg.k, r, h, a.n_heads); else return r; };
+    const StorePages sp = t == t_own ? sp_a : sp_b;
     const int s0 = sm.vis_start, s1 = sm.vis_start + sm.vis_len;
+    // row index of a row of this (sequence, head) in the region: run of rows, or page by page
+    auto v_row = [&](int pos) -> int64_t {
+      if constexpr (PAGED) return ((int64_t)sp.v * a.n_heads + h) * kPageRows + (pos & (kPageRows - 1));
+      else return pos;
+    };
+    auto k_row = [&](int row, int pos) -> int64_t {   // row: where position pos is kept (pos, or pos - vis_len)
+      if constexpr (PAGED) {
+        if (a.is_lazy && pos >= s1) return sp.k_text.row(row, h, a.n_heads);
+        return ((int64_t)sp.k_pos * a.n_heads + h) * kPageRows + (row & (kPageRows - 1));
+      } else {
+        return row;
+      }
+    };
 #pragma unroll
     for (int p = 0; p < BN * 16 / (NW * 64); ++p) {
       const int idx = p * (NW * 64) + tid;
@@ -281,7 +349,7 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
         if (!in_span) {
           const int row = (a.is_lazy && pos >= s1) ? pos - sm.vis_len : pos;
           const uint4 kv = *(const uint4*)(kb + r * ROWB + cp * 16);
-          *(uint4*)(kdst + k_row(row) * ROWB + ((cp ^ (r & 15)) * 16)) = kv;
+          *(uint4*)(kdst + k_row(row, pos) * ROWB + ((cp ^ (r & 15)) * 16)) = kv;
         }
       }
     }
@@ -293,8 +361,12 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
     wait_vmcnt<0>();
     __syncthreads();
     if (t + 1 < n_tiles) {
-      load_tile(t + 1, page_ahead);
-      page_ahead = page_of_tile(t + 2);
+      if constexpr (PAGED)
+        if (((t + 1) & 63) == 0) {
+          pages_cur = pages_next;
+          pages_next = fetch_pages(((t + 1) >> 6) + 1);
+        }
+      load_tile(t + 1, page_of_tile(t + 1));
     }
     const int k0 = t * BN;
     if (k0 >= q0) store_tile_to_caches(t);

@@ -152,6 +152,16 @@ def test_cfg5_video_shape_sampled():
     assert worst <= TOL["bf16"]
 
 
+def test_cfg5_video_shape_sampled_on_pages():
+    """The same on a paged batch: 76 key tiles per prompt, 72 of them inside the span, so a lazy layer walks
+    more than 64 pages of the first layer's keys."""
+    w = workloads.config(4)
+    assert w.max_seq % 64 == 0 and w.max_vis % 64 == 0 and w.max_text % 64 == 0
+    worst, _ = run_sampled(w, 5, [(0, 39), (1, 0), (2, 20), (3, 39)], seed=9, paged=True)
+    print("cfg5 paged sampled max abs err %.3g" % worst, flush=True)
+    assert worst <= TOL["bf16"]
+
+
 def test_cfg5_decode_sampled():
     """13B-shaped video workload as bench.py times it: the full 40-layer prefill of 4 x 4864 tokens, then
     3 decode steps (7 key chunks per (sequence, head), merged), sampled heads including the last one."""
