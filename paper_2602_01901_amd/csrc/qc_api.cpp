@@ -480,8 +480,9 @@ static qc_status paged_reserve(qc_kvcache* kv, const std::vector<std::array<int6
   for (int pool = 0; pool < 3; ++pool)
     if (need[pool] > (int64_t)kv->free_pages[pool].size())
       return fail(QC_ECAPACITY, "%s: %lld pages of pool %d needed, %zu free", who, (long long)need[pool], pool, kv->free_pages[pool].size());
-  qc::TableChunk tc;
-  int n = 0;
+  // host side first (complete and consistent whatever the uploads below return), then the new entries
+  // go to the device lists, TableChunk::N per launch
+  std::vector<std::pair<int32_t, int32_t>> entries;   // (index in the page-list buffer, page)
   size_t taken[3] = {0, 0, 0};
   for (int b = 0; b < kv->batch; ++b)
     for (int pool = 0; pool < 3; ++pool) {
@@ -489,19 +490,19 @@ static qc_status paged_reserve(qc_kvcache* kv, const std::vector<std::array<int6
       const int64_t pages = (want[b][pool] + qc::kPageRows - 1) / qc::kPageRows;
       while ((int64_t)kv->pages[pool][b].size() < pages) {
         const int32_t pg = kv->free_pages[pool][taken[pool]++];
-        tc.at[n] = (int32_t)(c.table_off(pool) + (int64_t)b * c.pool_stride(pool) + (int64_t)kv->pages[pool][b].size());
-        tc.page[n] = pg;
+        entries.emplace_back((int32_t)(c.table_off(pool) + (int64_t)b * c.pool_stride(pool) + (int64_t)kv->pages[pool][b].size()), pg);
         kv->pages[pool][b].push_back(pg);
-        if (++n == qc::TableChunk::N) {
-          hipError_t e = qc::launch_table_upload(kv->tables, n, tc, st);
-          if (e != hipSuccess) return fail(QC_EDEVICE, "%s: page-list upload: %s", who, hipGetErrorString(e));
-          n = 0;
-        }
       }
     }
   for (int pool = 0; pool < 3; ++pool)
     kv->free_pages[pool].erase(kv->free_pages[pool].begin(), kv->free_pages[pool].begin() + taken[pool]);
-  if (n > 0) {
+  qc::TableChunk tc;
+  for (size_t first = 0; first < entries.size(); first += qc::TableChunk::N) {
+    const int n = (int)std::min<size_t>(qc::TableChunk::N, entries.size() - first);
+    for (int i = 0; i < n; ++i) {
+      tc.at[i] = entries[first + i].first;
+      tc.page[i] = entries[first + i].second;
+    }
     hipError_t e = qc::launch_table_upload(kv->tables, n, tc, st);
     if (e != hipSuccess) return fail(QC_EDEVICE, "%s: page-list upload: %s", who, hipGetErrorString(e));
   }

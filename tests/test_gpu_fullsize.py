@@ -187,6 +187,19 @@ def test_long_prompt_32k():
     assert B.qc_layer_rows(sess.kv, 1) == (768, 32768)
 
 
+@pytest.mark.parametrize("mode", ["vla", "gla"])
+def test_long_prompt_32k_on_pages(mode):
+    """The same prompt on a paged batch: 512 pages of positions, 500 of visual rows; the lazy layer walks the
+    first layer's keys page by page through eight blocks of 64 pages."""
+    w = workloads.custom("long_paged", 2, 8, 128, "bf16", [256], [32000], [32768], 0, [0, 1],
+                         max_seq=32768, max_vis=32000, max_text=768)
+    worst, sess = run_sampled(w, 2, [(0, 0), (0, 3), (0, 7)], seed=3, mode=mode, paged=True)
+    print("long prompt on pages (%s) sampled max abs err %.3g" % (mode, worst), flush=True)
+    assert worst <= TOL["bf16"]
+    assert B.qc_seq_pages(sess.kv, 0, 0) == list(range(512))
+    assert B.qc_pool_pages(sess.kv, 0) == (512, 0)
+
+
 def test_gla_cfg4_highres_prefill_sampled():
     """Global Lazy Attention at batch 8 x 3008 tokens: every row of a lazy layer comes from the Q Cache and
     from the K cache of its block's first layer; first 8 layers."""
