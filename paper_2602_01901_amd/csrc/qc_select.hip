@@ -39,7 +39,15 @@ __global__ __launch_bounds__(256) void last_row_scores_kernel(SelectArgs a) {
   }
   float m = -INFINITY, l = 0.f;
   constexpr int U = 8;   // rows in flight per group: the kernel streams every K row of the layer once
-  for (int p0 = gid; p0 < len; p0 += GROUPS * U) {
+  // The scores are not stored from inside the row loop (loads and stores share one counter: a store in
+  // flight would hold up the wait for the next rows); kStage of them are collected in LDS and written out
+  // together.
+  constexpr int kStage = 2048;
+  static_assert(kStage % (GROUPS * U) == 0, "a block is a whole number of iterations");
+  __shared__ float s_stage[kStage];
+  for (int block0 = 0; block0 < len; block0 += kStage) {
+  const int block_end = min(block0 + kStage, len);
+  for (int p0 = block0 + gid; p0 < block_end; p0 += GROUPS * U) {
     uint4 raw[U];
     int64_t row[U];
 #pragma unroll
@@ -58,12 +66,16 @@ __global__ __launch_bounds__(256) void last_row_scores_kernel(SelectArgs a) {
       for (int i = 0; i < EPL; ++i) d = fmaf(qf[i], kf[i], d);
       d = group_sum<LPR>(d);
       if (pos < len) {
-        if (li == 0) srow[like_rows ? row[u] : (int64_t)pos] = d;
+        if (li == 0) s_stage[pos - block0] = d;
         const float mn = fmaxf(m, d);
         l = l * __builtin_amdgcn_exp2f(m - mn) + __builtin_amdgcn_exp2f(d - mn);
         m = mn;
       }
     }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < block_end - block0; i += 256) srow[like_rows ? ri.k(block0 + i) : (int64_t)(block0 + i)] = s_stage[i];
+  if (block_end < len) __syncthreads();   // the next block writes the stage again
   }
   __shared__ float s_m[GROUPS], s_l[GROUPS];
   if (li == 0) {
