@@ -510,3 +510,30 @@ def test_pages_a_sequence_needs():
     with pytest.raises(P.QcError) as e:                           # max_seq not a whole number of pages
         B.qc_pages_needed(P.make_config(4, 2, 64, "bf16", 3, 200, 64, 128, [0, 1, 1, 0]), 10, 0)
     assert e.value.status == B.QC_EINVAL
+
+
+def test_plain_c_caller_gets_the_same_answers(tmp_path):
+    """include/qcache.h compiles as C99 and a C program linked against the library gets, from the host-only
+    entry points, what the Python binding gets (tests/c_abi_probe.c)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    here = os.path.dirname(os.path.abspath(__file__))
+    root = os.path.dirname(here)
+    libdir = os.path.dirname(P.LIB_PATH)
+    exe = str(tmp_path / "c_abi_probe")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                    os.path.join(here, "c_abi_probe.c"), "-o", exe, "-L", libdir, "-l:" + os.path.basename(P.LIB_PATH),
+                    "-Wl,-rpath," + libdir, "-Wl,--allow-shlib-undefined"], check=True, capture_output=True, text=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True, timeout=60).stdout
+    got = dict(line.split(" ", 1) for line in out.strip().splitlines())
+    cfg = P.make_config(*PAGED)
+    assert int(got["kv_arena_bytes"]) == B.qc_kv_arena_bytes(cfg)
+    assert int(got["q_arena_bytes"]) == B.qc_q_arena_bytes(cfg)
+    assert int(got["page_table_bytes"]) == B.qc_page_table_bytes(cfg)
+    assert got["pages_needed"].split() == ["0", "3", "2", "2"]
+    assert got["plan_max_batch"].split() == ["0", str(B.qc_plan_max_batch(cfg, 1 << 20, B.QC_PLAN_KV | B.QC_PLAN_Q))]
+    assert got["bad_call"].split(" ", 1) == [str(B.QC_EINVAL), B.qc_status_str(B.QC_EINVAL)]
+    assert "vis_len" in got["last_error"]
