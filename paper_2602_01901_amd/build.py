@@ -57,5 +57,20 @@ def build_library(verbose=False, extra_flags=()):
     return LIB_PATH
 
 
+NATIVE_CALLER_SRC = os.path.join(ROOT, "tests", "c_abi_gpu_probe.cpp")
+NATIVE_CALLER = os.path.join(ROOT, "tests", "c_abi_gpu_probe")
+
+
+def build_native_caller(verbose=False):
+    """The test program that calls the library with nothing but the HIP runtime (tests/c_abi_gpu_probe.cpp):
+    host code only, linked against the library that sits in the package directory."""
+    _run([hipcc(), "-O2", "-std=c++17", "-Wall", "-I", os.path.join(ROOT, "include"), NATIVE_CALLER_SRC,
+          "-o", NATIVE_CALLER + ".tmp", "-L", PKG_DIR, "-l:" + os.path.basename(LIB_PATH),
+          "-Wl,-rpath," + PKG_DIR, "-Wl,-rpath,$ORIGIN/../paper_2602_01901_amd"], verbose)
+    os.replace(NATIVE_CALLER + ".tmp", NATIVE_CALLER)
+    return NATIVE_CALLER
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_native_caller(verbose=True))
