@@ -913,7 +913,7 @@ def bench_headline(args):
         "k_cache_bytes_per_token": stats["k_bytes"] / stats["tokens"],
         "k_cache_bytes_per_token_after_prefill": stats_prefill["k_bytes"] / stats_prefill["tokens"],
         "k_cache_bytes_per_token_standard": w.n_layers * w.n_heads * w.head_dim * w.elem_bytes,
-        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<bf16,128> (7 key chunks per (sequence, head); duration = decode "
+        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<bf16,128> (8 key chunks per (sequence, head): 5 workgroups per compute unit; duration = decode "
                      "phase / layer calls, so the merge pass and the launch gaps are charged to it)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic("decode_cfg5"),

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <array>
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -509,6 +510,19 @@ static qc_status paged_reserve(qc_kvcache* kv, const std::vector<std::array<int6
   return QC_OK;
 }
 
+// Compute units of the current device (cached per device; 256 if the runtime does not say).
+static int compute_units() {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<int> cached[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+  cached[dev].store(n, std::memory_order_relaxed);
+  return n;
+}
+
 static qc::LayerView make_view(const qc_kvcache* kv, const qc_qcache* qc, int layer) {
   const Config& c = kv->cfg;
   qc::LayerView lv;
@@ -961,15 +975,36 @@ static qc_status decode_impl(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32
   }
   if (qk_unused && qc->owner != c.anchor[layer])
     return fail(QC_EORDER, "qc_decode: Q Cache belongs to layer %d, layer %d inherits from %d", qc->owner, layer, c.anchor[layer]);
-  // Split the key axis only as far as needed to give every CU a few workgroups: each extra chunk
-  // costs a partial result and the merge pass.  With many (sequence, head) pairs there is no split
+  // Split the key axis only as far as needed to give every compute unit a few workgroups: each extra
+  // chunk costs a partial result and the merge pass.  With many (sequence, head) pairs there is no split
   // and the kernel writes the output directly.
   constexpr int64_t kTargetGroups = 1024;
   const int64_t pairs = (int64_t)kv->batch * c.H;
   int64_t want = (kTargetGroups + pairs - 1) / pairs;
   if (want < 1) want = 1;
+  // Where the chunks stay long (the bandwidth-bound launches), the number of chunks is the one between
+  // 3 and 6 workgroups per compute unit (all resident at once) that spreads them most evenly: the launch
+  // lasts as long as its fullest unit.  Measured at 160 pairs on 256 units, 5 to 9 chunks: 5.53, 6.11,
+  // 5.88, 6.16, 6.10 TB/s for 3.1, 3.75, 4.4, 5.0, 5.6 workgroups per unit.
+  if (!geom) {
+    const int64_t units = compute_units();
+    int64_t best = 0;
+    double best_ratio = 0.0;
+    for (int64_t n = std::max<int64_t>(1, (3 * units + pairs - 1) / pairs); n * pairs <= 6 * units; ++n) {
+      if ((max_len + 1) / n < 2 * kMinChunkKeys) break;
+      const double per_unit = (double)(n * pairs) / (double)units;
+      const double ratio = std::ceil(per_unit) / per_unit;   // fullest unit against the mean
+      if (best == 0 || ratio < best_ratio - 1e-9) {
+        best = n;
+        best_ratio = ratio;
+      }
+    }
+    if (best > 0) want = best;
+  }
   int64_t per = (max_len + 1 + want - 1) / want;
-  int32_t chunk = (int32_t)round_up(per < kMinChunkKeys ? kMinChunkKeys : per, kMinChunkKeys);
+  // chunks of (nearly) equal length: a chunk rounded up to a multiple of 64 left up to a tenth more rows
+  // in six chunks than in the seventh at cfg5 (+2.5 % time)
+  int32_t chunk = (int32_t)(per < kMinChunkKeys ? kMinChunkKeys : round_up(per, 8));
   int32_t max_chunks = (max_len + 1 + chunk - 1) / chunk;
   if (geom) {
     chunk = geom->chunk;

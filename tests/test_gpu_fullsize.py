@@ -164,7 +164,7 @@ def test_cfg5_video_shape_sampled_on_pages():
 
 def test_cfg5_decode_sampled():
     """13B-shaped video workload as bench.py times it: the full 40-layer prefill of 4 x 4864 tokens, then
-    3 decode steps (7 key chunks per (sequence, head), merged), sampled heads including the last one."""
+    3 decode steps (8 key chunks per (sequence, head), merged), sampled heads including the last one."""
     w = workloads.config(4)
     pairs = [(0, 0), (0, 39), (1, 17), (2, 39), (3, 5), (3, 39)]
     worst, sess = run_sampled(w, w.n_layers, pairs, decode_steps=3, seed=5)
