@@ -150,6 +150,7 @@ struct qc_kvcache {
   // Token pruning: layers >= first_late see sequence b with vis_len1[b] visual tokens and len1[b]
   // prompt tokens, packed from tok1[b] (the last two known once the first such layer has run).
   int32_t first_late = -1;
+  int32_t units = 256;    // compute units of the device the handle was created on
   bool late_known = false;
   std::vector<int32_t> vis_len1, len1, tok1;
   bool late(int layer) const { return first_late >= 0 && layer >= first_late; }
@@ -273,6 +274,19 @@ size_t qc_decode_workspace_bytes(const qc_config* cfg) {
   return (size_t)(partial_bytes(c) + score_bytes(c));
 }
 
+// Compute units of the current device (cached per device; 256 if the runtime does not say).
+static int compute_units() {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<int> cached[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+  cached[dev].store(n, std::memory_order_relaxed);
+  return n;
+}
+
 qc_status qc_kvcache_create(const qc_config* cfg, void* dev_arena, size_t arena_bytes, qc_kvcache** out) {
   if (!out) return fail(QC_EINVAL, "qc_kvcache_create: out is null");
   *out = nullptr;
@@ -285,6 +299,7 @@ qc_status qc_kvcache_create(const qc_config* cfg, void* dev_arena, size_t arena_
   if (!kv) return fail(QC_ECAPACITY, "qc_kvcache_create: out of host memory");
   kv->cfg = c;
   kv->arena = (char*)dev_arena;
+  kv->units = compute_units();   // asked once, here: not from inside a call that a caller may be capturing
   *out = kv;
   return QC_OK;
 }
@@ -508,19 +523,6 @@ static qc_status paged_reserve(qc_kvcache* kv, const std::vector<std::array<int6
     if (e != hipSuccess) return fail(QC_EDEVICE, "%s: page-list upload: %s", who, hipGetErrorString(e));
   }
   return QC_OK;
-}
-
-// Compute units of the current device (cached per device; 256 if the runtime does not say).
-static int compute_units() {
-  constexpr int kMaxDevices = 64;
-  static std::atomic<int> cached[kMaxDevices];
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
-  int n = cached[dev].load(std::memory_order_relaxed);
-  if (n > 0) return n;
-  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-  cached[dev].store(n, std::memory_order_relaxed);
-  return n;
 }
 
 static qc::LayerView make_view(const qc_kvcache* kv, const qc_qcache* qc, int layer) {
@@ -987,7 +989,7 @@ static qc_status decode_impl(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32
   // lasts as long as its fullest unit.  Measured at 160 pairs on 256 units, 5 to 9 chunks: 5.53, 6.11,
   // 5.88, 6.16, 6.10 TB/s for 3.1, 3.75, 4.4, 5.0, 5.6 workgroups per unit.
   if (!geom) {
-    const int64_t units = compute_units();
+    const int64_t units = kv->units;
     int64_t best = 0;
     double best_ratio = 0.0;
     for (int64_t n = std::max<int64_t>(1, (3 * units + pairs - 1) / pairs); n * pairs <= 6 * units; ++n) {
