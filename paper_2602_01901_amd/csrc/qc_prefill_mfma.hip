@@ -370,7 +370,9 @@ __global__ __launch_bounds__(pf::NW * 64, 2) void prefill_mfma_kernel(PrefillArg
     }
     const int k0 = t * BN;
     if (k0 >= q0) store_tile_to_caches(t);
-    if (k0 <= wrow0 + 31) {  // wave-uniform: otherwise every key of the tile is above the diagonal
+    // wave-uniform: otherwise every key of the tile is above the diagonal, or (last query tile of a prompt
+    // whose length is not a multiple of 128) the wave has no query row at all and only helps with the tiles
+    if (k0 <= wrow0 + 31 && wrow0 < len) {
       const char* kb = lds + (t % STAGES) * STAGE;
       const char* vb = kb + TILE;
       f32x16 s[2];
