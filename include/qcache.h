@@ -307,6 +307,14 @@ qc_status qc_decode(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32_t is_laz
                     const int32_t* vis_len, float softmax_scale, void* workspace,
                     size_t workspace_bytes, void* stream);
 
+/* qc_decode_split: HOST arithmetic, no handle: how an ordinary qc_decode call (not a recorded one) divides
+ * the key positions 0..max_len of `pairs` = batch * n_heads (sequence, head) pairs among workgroups on a
+ * device of `compute_units` units: *chunk_keys positions per workgroup, *chunks workgroups for the longest
+ * sequence (1: no split, no merge pass).  Stated here because the decode rate depends on it: the workgroups
+ * are spread as evenly over the compute units as the pair count allows.  QC_EINVAL for non-positive
+ * arguments (max_len may be 0). */
+qc_status qc_decode_split(int32_t pairs, int32_t max_len, int32_t compute_units, int32_t* chunk_keys, int32_t* chunks);
+
 /* ---- decode for callers that cannot allocate ------------------------------------------------------
  * For callers that must not call hipMalloc (code under HIP graph capture, tight serving loops,
  * harnesses that forbid allocation) and therefore cannot bring a workspace: qc_decode with the

@@ -55,6 +55,7 @@ _PROTOTYPES = {
                                  c_void_p, c_size_t, c_int32, c_void_p]),
     "qc_seq_pages": (c_int32, [c_void_p, c_int32, c_int32, POINTER(c_int32), c_int32, POINTER(c_int32)]),
     "qc_pool_pages": (c_int32, [c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32)]),
+    "qc_decode_split": (c_int32, [c_int32, c_int32, c_int32, POINTER(c_int32), POINTER(c_int32)]),
     "qc_pages_needed": (c_int32, [POINTER(qc_config), c_int32, c_int32, POINTER(c_int32)]),
     "qc_seq_leave": (c_int32, [c_void_p, c_void_p, c_int32, c_void_p]),
     "qc_seq_join": (c_int32, [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, c_void_p]),
@@ -217,6 +218,13 @@ def qc_seq_pages(kv, b, pool):
     buf = (c_int32 * max(n.value, 1))()
     _check(load_library().qc_seq_pages(kv, b, pool, buf, n.value, byref(n)))
     return [buf[i] for i in range(n.value)]
+
+
+def qc_decode_split(pairs, max_len, compute_units=256):
+    """(key positions per workgroup, workgroups for the longest sequence) of an ordinary decode call."""
+    chunk, n = c_int32(), c_int32()
+    _check(load_library().qc_decode_split(pairs, max_len, compute_units, byref(chunk), byref(n)))
+    return chunk.value, n.value
 
 
 def qc_pool_pages(kv, pool):

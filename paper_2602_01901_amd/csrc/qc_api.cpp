@@ -936,6 +936,45 @@ qc_status qc_seq_extent(const qc_kvcache* kv, int32_t b, int32_t* live, int32_t*
   return QC_OK;
 }
 
+// How a decode launch splits the key axis of its (sequence, head) pairs: *chunk key positions per workgroup,
+// *max_chunks workgroups for the longest sequence (positions 0 .. max_len).
+// Split only as far as needed to give every compute unit a few workgroups: each extra chunk costs a
+// partial result and the merge pass.  With many pairs there is no split and the kernel writes the output
+// directly.
+static void split_plan(int64_t pairs, int64_t max_len, int64_t units, int32_t* chunk, int32_t* max_chunks) {
+  constexpr int64_t kTargetGroups = 1024;
+  int64_t want = (kTargetGroups + pairs - 1) / pairs;
+  if (want < 1) want = 1;
+  // Where the chunks stay long (the bandwidth-bound launches), the number of chunks is the one between
+  // 3 and 6 workgroups per compute unit (all resident at once) that spreads them most evenly: the launch
+  // lasts as long as its fullest unit.  Measured at 160 pairs on 256 units, 5 to 9 chunks: 5.53, 6.11,
+  // 5.88, 6.16, 6.10 TB/s for 3.1, 3.75, 4.4, 5.0, 5.6 workgroups per unit.
+  int64_t best = 0;
+  double best_ratio = 0.0;
+  for (int64_t n = std::max<int64_t>(1, (3 * units + pairs - 1) / pairs); n * pairs <= 6 * units; ++n) {
+    if ((max_len + 1) / n < 2 * kMinChunkKeys) break;
+    const double per_unit = (double)(n * pairs) / (double)units;
+    const double ratio = std::ceil(per_unit) / per_unit;   // fullest unit against the mean
+    if (best == 0 || ratio < best_ratio - 1e-9) {
+      best = n;
+      best_ratio = ratio;
+    }
+  }
+  if (best > 0) want = best;
+  const int64_t per = (max_len + 1 + want - 1) / want;
+  // chunks of (nearly) equal length: a chunk rounded up to a multiple of 64 left up to a tenth more rows
+  // in six chunks than in the seventh at cfg5 (+2.5 % time)
+  *chunk = (int32_t)(per < kMinChunkKeys ? kMinChunkKeys : round_up(per, 8));
+  *max_chunks = (int32_t)((max_len + 1 + *chunk - 1) / *chunk);
+}
+
+qc_status qc_decode_split(int32_t pairs, int32_t max_len, int32_t compute_units_, int32_t* chunk_keys, int32_t* chunks) {
+  if (!chunk_keys || !chunks) return fail(QC_EINVAL, "qc_decode_split: null argument");
+  if (pairs < 1 || max_len < 0 || compute_units_ < 1) return fail(QC_EINVAL, "qc_decode_split: need pairs >= 1, max_len >= 0, compute_units >= 1");
+  split_plan(pairs, max_len, compute_units_, chunk_keys, chunks);
+  return QC_OK;
+}
+
 // Launch geometry of a decode call that is being recorded into a graph: fixed for every later replay.
 struct GraphGeom {
   int32_t chunk, max_chunks;
@@ -977,37 +1016,9 @@ static qc_status decode_impl(qc_kvcache* kv, qc_qcache* qc, int32_t layer, int32
   }
   if (qk_unused && qc->owner != c.anchor[layer])
     return fail(QC_EORDER, "qc_decode: Q Cache belongs to layer %d, layer %d inherits from %d", qc->owner, layer, c.anchor[layer]);
-  // Split the key axis only as far as needed to give every compute unit a few workgroups: each extra
-  // chunk costs a partial result and the merge pass.  With many (sequence, head) pairs there is no split
-  // and the kernel writes the output directly.
-  constexpr int64_t kTargetGroups = 1024;
   const int64_t pairs = (int64_t)kv->batch * c.H;
-  int64_t want = (kTargetGroups + pairs - 1) / pairs;
-  if (want < 1) want = 1;
-  // Where the chunks stay long (the bandwidth-bound launches), the number of chunks is the one between
-  // 3 and 6 workgroups per compute unit (all resident at once) that spreads them most evenly: the launch
-  // lasts as long as its fullest unit.  Measured at 160 pairs on 256 units, 5 to 9 chunks: 5.53, 6.11,
-  // 5.88, 6.16, 6.10 TB/s for 3.1, 3.75, 4.4, 5.0, 5.6 workgroups per unit.
-  if (!geom) {
-    const int64_t units = kv->units;
-    int64_t best = 0;
-    double best_ratio = 0.0;
-    for (int64_t n = std::max<int64_t>(1, (3 * units + pairs - 1) / pairs); n * pairs <= 6 * units; ++n) {
-      if ((max_len + 1) / n < 2 * kMinChunkKeys) break;
-      const double per_unit = (double)(n * pairs) / (double)units;
-      const double ratio = std::ceil(per_unit) / per_unit;   // fullest unit against the mean
-      if (best == 0 || ratio < best_ratio - 1e-9) {
-        best = n;
-        best_ratio = ratio;
-      }
-    }
-    if (best > 0) want = best;
-  }
-  int64_t per = (max_len + 1 + want - 1) / want;
-  // chunks of (nearly) equal length: a chunk rounded up to a multiple of 64 left up to a tenth more rows
-  // in six chunks than in the seventh at cfg5 (+2.5 % time)
-  int32_t chunk = (int32_t)(per < kMinChunkKeys ? kMinChunkKeys : round_up(per, 8));
-  int32_t max_chunks = (max_len + 1 + chunk - 1) / chunk;
+  int32_t chunk = 0, max_chunks = 0;
+  split_plan(pairs, max_len, kv->units, &chunk, &max_chunks);
   if (geom) {
     chunk = geom->chunk;
     max_chunks = geom->max_chunks;

@@ -537,3 +537,43 @@ def test_plain_c_caller_gets_the_same_answers(tmp_path):
     assert got["plan_max_batch"].split() == ["0", str(B.qc_plan_max_batch(cfg, 1 << 20, B.QC_PLAN_KV | B.QC_PLAN_Q))]
     assert got["bad_call"].split(" ", 1) == [str(B.QC_EINVAL), B.qc_status_str(B.QC_EINVAL)]
     assert "vis_len" in got["last_error"]
+
+
+def test_decode_split_spreads_workgroups_evenly():
+    """qc_decode_split at the benchmark's shapes, and against the rule written out again: among the chunk
+    counts that give 3 to 6 workgroups per compute unit and chunks of at least 128 positions, the one whose
+    fullest unit is closest to the mean (fewest chunks on a tie); otherwise about 1024 workgroups with
+    chunks of at least 64 positions; chunks of equal length rounded up to 8."""
+    from math import ceil
+    # 13B video shape: 4 x 40 pairs -> 8 chunks = 1280 workgroups, 5 per unit, over the whole decode phase
+    for max_len in (4864, 5000, 5887):
+        chunk, n = B.qc_decode_split(160, max_len, 256)
+        assert n == 8 and chunk == -(-ceil((max_len + 1) / 8) // 8) * 8
+    assert B.qc_decode_split(1024, 1599, 256)[1] == 1            # batch 32 x 32 heads: no split, 4 per unit
+    assert B.qc_decode_split(32, 640, 256) == (64, 11)            # batch 1: latency-bound, chunks of 64 positions
+    assert B.qc_decode_split(160, 4864, 256)[0] * 7 < 4865 <= B.qc_decode_split(160, 4864, 256)[0] * 8
+
+    def rule(pairs, max_len, units):
+        want = max(1, ceil(1024 / pairs))
+        best = None
+        n = max(1, ceil(3 * units / pairs))
+        while n * pairs <= 6 * units and (max_len + 1) // n >= 128:
+            x = n * pairs / units
+            r = ceil(x) / x
+            if best is None or r < best[0] - 1e-9:
+                best = (r, n)
+            n += 1
+        if best:
+            want = best[1]
+        per = ceil((max_len + 1) / want)
+        chunk = 64 if per < 64 else -(-per // 8) * 8
+        return chunk, ceil((max_len + 1) / chunk)
+
+    for pairs in (1, 7, 32, 96, 160, 255, 256, 257, 672, 928, 1024, 1440, 1632, 5000):
+        for max_len in (0, 63, 64, 500, 1599, 4864, 32767):
+            for units in (256, 304, 64):
+                assert B.qc_decode_split(pairs, max_len, units) == rule(pairs, max_len, units), (pairs, max_len, units)
+    for bad in ((0, 10, 256), (4, -1, 256), (4, 10, 0)):
+        with pytest.raises(P.QcError) as e:
+            B.qc_decode_split(*bad)
+        assert e.value.status == B.QC_EINVAL
